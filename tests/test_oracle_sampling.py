@@ -1,0 +1,184 @@
+"""Pins for the oracle's sampling-mode acceptance: it must leave the target model's sampling
+distribution unchanged (abstract: "maintaining a consistent sampling distribution").  Checked by
+brute force on a vocab-16 model: the decoder's decisions are piecewise constant in the uniforms,
+so every cell of uniforms is enumerated exactly (cell volume = probability), the real decoder is
+run on one point per cell, and the law of the emitted tokens is compared with the product of the
+target model's conditionals, which are computed from scratch by whole-sequence forwards."""
+import numpy as np
+import pytest
+
+from oracle import kangaroo_oracle as O
+from paper_2404_18911_amd import inputs as I
+
+TINY = I.ModelShape("tiny16", 2, 16, 2, 8, 32, 16, 1, "f32")
+PROMPT = [3, 11, 7]
+
+
+class Need(Exception):
+    def __init__(self, pos, purpose):
+        self.pos, self.purpose = pos, purpose
+
+
+class Uniforms:
+    """Uniforms indexed by (position, purpose); reading one that is not fixed yet raises."""
+
+    def __init__(self, fixed):
+        self.fixed = fixed
+
+    def __getitem__(self, key):
+        if key not in self.fixed:
+            raise Need(*key)
+        return self.fixed[key]
+
+
+@pytest.fixture(scope="module")
+def world():
+    W = I.gen_weights(TINY, seed=7, alpha=0.8, std=0.45)
+    ref = O.OracleModel(TINY, W, 16)
+    cache = {}
+
+    def dists(prefix):
+        """(target p, draft q) for the token following `prefix`, by a whole-sequence forward."""
+        key = tuple(prefix)
+        if key not in cache:
+            f = ref.shallow(list(prefix), 0)
+            p = O.softmax(ref.head(ref.deep(f, 0)[-1:], 0)[0])
+            q = O.softmax(ref.head(ref.adapter(f, 0)[-1:], 1)[0])
+            cache[key] = (p, q)
+        return cache[key]
+
+    return W, dists
+
+
+def test_one_position_identity_for_arbitrary_rows():
+    """sum_d q(d) [a(d) delta_d + (1 - a(d)) r] = p, with the oracle's own a and r."""
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        p = rng.dirichlet(np.full(16, 0.3))
+        q = rng.dirichlet(np.full(16, 0.3)) * 0.999 + 0.001 / 16
+        r = O.residual_distribution(p, q)
+        out = np.zeros(16)
+        for d in range(16):
+            a = O.accept_probability(p, q, d)
+            out[d] += q[d] * a
+            out += q[d] * (1.0 - a) * r
+        np.testing.assert_allclose(out, p, rtol=0, atol=1e-12)
+
+
+def test_inverse_cdf_cells():
+    p = np.array([0.0, 0.25, 0.0, 0.5, 0.25])
+    assert [O.inverse_cdf(p, u) for u in (0.0, 0.2499, 0.25, 0.7499, 0.75, 0.999999)] == [1, 1, 3, 3, 4, 4]
+
+
+def enumerate_law(W, dists, gamma, eta, n_rounds_until, start=None):
+    """Exact law of the tokens emitted after the prefill token, conditional on the uniforms in
+    `start`.  Returns ({tuple(emitted): prob}, {tuple(emitted): one set of uniforms leading there})."""
+    law = {}
+    rep = {}
+    runs = [0]
+
+    def cells(breaks):
+        pts = sorted(set([0.0, 1.0] + [min(1.0, max(0.0, float(b))) for b in breaks]))
+        return [((a + b) / 2, b - a) for a, b in zip(pts[:-1], pts[1:]) if b - a > 0]
+
+    def rec(fixed, prob):
+        state = {}
+        try:
+            runs[0] += 1
+            dec = O.KangarooDecoder(O.OracleModel(TINY, W, 16), gamma=gamma, eta=eta, mode="sample",
+                                    uniforms=Uniforms(fixed))
+            state["dec"] = dec
+            state["out"] = [dec.prefill(PROMPT)]
+            while not n_rounds_until(state["out"][1:], len(dec.S)):
+                state["out"] += dec.round()
+            key = tuple(state["out"][1:])
+            law[key] = law.get(key, 0.0) + prob
+            rep.setdefault(key, dict(fixed))
+            return
+        except Need as e:
+            dec = state["dec"]
+            seq = PROMPT + state.get("out", []) + dec.D
+            p, q = dists(seq[:e.pos])
+            if e.purpose == O.U_DRAFT:
+                br = np.cumsum(q)
+            elif e.purpose == O.U_ACCEPT:
+                br = [O.accept_probability(p, q, seq[e.pos])]
+            else:
+                br = list(np.cumsum(p)) + list(np.cumsum(O.residual_distribution(p, q)))
+            for mid, vol in cells(br):
+                rec({**fixed, (e.pos, e.purpose): mid}, prob * vol)
+
+    rec(dict(start) if start else {(len(PROMPT), O.U_RESAMPLE): 0.37}, 1.0)
+    return law, rep
+
+
+def test_two_tokens_over_two_rounds_gamma1(world):
+    """gamma = 1: enumerate rounds until two tokens are out; joint law == p(a) p(b | a)."""
+    W, dists = world
+    law1, rep = enumerate_law(W, dists, 1, 0.6, lambda out, rounds: rounds >= 1)
+    assert abs(sum(law1.values()) - 1.0) < 1e-12
+    c = O.inverse_cdf(dists(PROMPT)[0], 0.37)
+    p1 = dists(PROMPT + [c])[0]
+    joint = np.zeros((16, 16))
+    law = {}
+    for key, pr in law1.items():
+        if len(key) >= 2:
+            joint[key[0], key[1]] += pr
+            law[key] = pr
+        else:
+            # the state after a one-token round depends on the emitted token only: enumerate the
+            # second round once, from one set of uniforms that leads there
+            law2, _ = enumerate_law(W, dists, 1, 0.6, lambda out, rounds: len(out) >= 2, start=rep[key])
+            assert abs(sum(law2.values()) - 1.0) < 1e-12
+            for k2, pr2 in law2.items():
+                assert k2[0] == key[0]
+                joint[k2[0], k2[1]] += pr * pr2
+                law[k2] = pr * pr2
+    want = np.array([[p1[a] * dists(PROMPT + [c, a])[0][b] for b in range(16)] for a in range(16)])
+    np.testing.assert_allclose(joint, want, rtol=0, atol=1e-12)
+    # both outcomes of a round occurred with real mass
+    lens = {len(k) for k in law}
+    assert lens == {2, 3} or lens == {2}
+
+
+@pytest.mark.parametrize("eta", [0.0, 1.5])
+def test_one_round_gamma2_prefix_laws(world, eta):
+    """gamma = 2, one round (k = 2 with eta = 0, k = 1 with eta > 1): the round's emitted tokens
+    extended by the target's own conditionals reproduce p(a) p(b | a) p(c | a, b)."""
+    W, dists = world
+    law, _ = enumerate_law(W, dists, 2, eta, lambda out, rounds: rounds >= 1)
+    assert abs(sum(law.values()) - 1.0) < 1e-12
+    c0 = O.inverse_cdf(dists(PROMPT)[0], 0.37)
+    base = PROMPT + [c0]
+    kmax = 2 if eta == 0.0 else 1
+    assert max(len(k) for k in law) == kmax + 1
+    first = np.zeros(16)
+    pair = np.zeros((16, 16))
+    for key, pr in law.items():
+        first[key[0]] += pr
+        if len(key) >= 2:
+            pair[key[0], key[1]] += pr
+        else:
+            pair[key[0], :] += pr * dists(base + [key[0]])[0]
+    p1 = dists(base)[0]
+    np.testing.assert_allclose(first, p1, rtol=0, atol=1e-12)
+    want = np.array([p1[a] * dists(base + [a])[0] for a in range(16)])
+    np.testing.assert_allclose(pair, want, rtol=0, atol=1e-12)
+    if kmax == 2:
+        tri = {}
+        for key, pr in law.items():
+            if len(key) == 3:
+                tri[key] = tri.get(key, 0.0) + pr
+        # mass of full acceptance + bonus token c, given the first two tokens (a, b), plus the
+        # mass of shorter rounds continued by the target itself, equals the target's joint law
+        for a in range(0, 16, 5):
+            for b in range(0, 16, 3):
+                got = np.zeros(16)
+                for cc in range(16):
+                    got[cc] = tri.get((a, b, cc), 0.0)
+                short2 = law.get((a, b), 0.0)
+                short1 = law.get((a,), 0.0)
+                p2 = dists(base + [a])[0]
+                p3 = dists(base + [a, b])[0]
+                got += short2 * p3 + short1 * p2[b] * p3
+                np.testing.assert_allclose(got, p1[a] * p2[b] * p3, rtol=0, atol=1e-12)
