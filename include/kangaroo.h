@@ -1,0 +1,195 @@
+/*
+ * libkangaroo — C ABI of the MI355X (gfx950) implementation of Kangaroo's batch-1
+ * draft-and-verify decode loop (arXiv 2404.18911, "Kangaroo: Lossless Self-Speculative
+ * Decoding via Double Early Exiting").
+ *
+ * Conventions for every call
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device; "host" pointers are
+ *     ordinary host addresses.  The library never allocates or frees device memory: the caller
+ *     owns the weight arena, the KV pool and the scratch area it binds, and the HIP stream.
+ *   - Return value: KG_OK (0) or a negative kg_status.  kg_last_error() gives a message for the
+ *     last failing call on that context.  A failing call leaves the sequence state unchanged,
+ *     except after KG_EHIP (device error), after which the context must be reset.
+ *   - A context is not thread-safe; calls on one context must not overlap.
+ *   - Row counts per forward are limited to KG_MAX_ROWS (gamma + 1 <= 8).
+ *
+ * Call order:  kg_create -> kg_workspace_bytes -> kg_bind -> kg_load_tensor (all tensors)
+ *              -> kg_prefill -> { kg_draft_step x (1..gamma) -> kg_verify -> kg_accept }*
+ *              or kg_generate / kg_decode_plain, which run the whole loop.
+ */
+#ifndef KANGAROO_H
+#define KANGAROO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KG_MAX_ROWS 8
+
+typedef enum kg_status {
+    KG_OK = 0,
+    KG_EINVAL = -1, /* bad argument or configuration */
+    KG_ESTATE = -2, /* call-order violation (e.g. verify before any draft step) */
+    KG_ENOSPC = -3, /* the sequence would exceed max_seq, or a buffer is too small */
+    KG_EHIP = -4,   /* a HIP runtime call failed; message holds the HIP error string */
+    KG_ENOMEM = -5  /* host allocation failed */
+} kg_status;
+
+typedef struct kg_ctx kg_ctx; /* opaque */
+
+/* Model and cache shape.  The target model M^b of Section 3 (Notation) is a LLaMA-style decoder
+ * (Section 4.1 uses Vicuna): n_layers pre-norm blocks of RMSNorm, rotary multi-head attention,
+ * SwiGLU feed-forward; exit_layer is the early-exit layer l of Section 3.1 (1 <= l <= n_layers). */
+typedef struct kg_config {
+    int n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    int exit_layer;
+    int dtype;          /* storage type of weights and KV cache: 0 = float32, 1 = bfloat16 */
+    float rms_eps, rope_theta;
+    int max_seq;        /* token capacity of the caches: prompt + generated + gamma_max + 1 */
+    int gamma_max;      /* largest draft length gamma that will be used (<= KG_MAX_ROWS - 1) */
+    int kv_page_tokens; /* tokens per KV page: a power of two in 16..128 */
+} kg_config;
+
+/* Tensors of the model.  Per-layer kinds take layer = 0..n_layers-1, the others layer = -1.
+ * The adapter A of Section 3.1 / Figure 2 / Table 2 (row "Kangaroo") is one bias-free multi-head
+ * attention (KG_A_WQ..KG_A_WO, each [d_model][d_model]) between two RMSNorm gain vectors, and
+ * re-uses the target's LM head. */
+typedef enum kg_tensor_kind {
+    KG_EMBED = 0,       /* [vocab][d_model] */
+    KG_LM_HEAD = 1,     /* [vocab][d_model] */
+    KG_FINAL_NORM = 2,  /* [d_model] */
+    KG_WQ = 3, KG_WK = 4, KG_WV = 5, KG_WO = 6, /* [d_model][d_model] */
+    KG_WG = 7, KG_WU = 8,                        /* [d_ffn][d_model]   */
+    KG_WD = 9,                                   /* [d_model][d_ffn]   */
+    KG_NORM1 = 10, KG_NORM2 = 11,                /* [d_model] */
+    KG_A_WQ = 12, KG_A_WK = 13, KG_A_WV = 14, KG_A_WO = 15,
+    KG_A_NORM_IN = 16, KG_A_NORM_LAST = 17,
+    KG_N_TENSOR_KINDS = 18
+} kg_tensor_kind;
+
+/* Decoding parameters.  gamma and eta are the maximum draft length and the confidence
+ * threshold of Section 3.2 (the paper's setting: gamma = 6, eta = 0.6, Section 4.2); drafting
+ * stops after a token whose top-1 probability is < eta (Eq. 4; eta = 0 gives fixed-step
+ * drafting).  mode 0 accepts drafts while they equal the target's top-1 token; mode 1 is
+ * speculative rejection sampling at the given temperature, which keeps the target's sampling
+ * distribution.  In mode 1 `uniforms` (host, float[n_uniform_positions][3], each in [0,1)) gives,
+ * per absolute token position, the numbers used to draw a draft token [0], to test its
+ * acceptance [1], and to draw a resampled / bonus / first token [2]. */
+typedef struct kg_params {
+    int mode;
+    float temperature;
+    float eta;
+    int gamma;
+    const float *uniforms;
+    int n_uniform_positions;
+} kg_params;
+
+/* Counters of one kg_generate / kg_decode_plain call.  s_hist[s] counts the rounds that emitted
+ * s tokens (the list S of Section 3; compression rate, Eq. 1, is emitted_in_rounds / rounds). */
+typedef struct kg_stats {
+    int rounds, drafted, accepted, emitted;
+    int s_hist[KG_MAX_ROWS + 1];
+    int draft_steps, verify_calls, plain_steps;
+    double t_draft_s, t_verify_s, t_total_s; /* host wall-clock spent in each phase */
+} kg_stats;
+
+/* Create a context for a shape.  Host-only: no device is touched.  *out is NULL on failure. */
+int kg_create(const kg_config *cfg, kg_ctx **out);
+
+/* Bytes the caller must provide to kg_bind: the arena that will hold the re-tiled weights, the KV
+ * pool (n_layers + 1 caches: one per decoder layer plus the adapter's), and scratch. */
+int kg_workspace_bytes(const kg_ctx *ctx, size_t *weight_bytes, size_t *kv_bytes, size_t *scratch_bytes);
+
+/* Bind caller-owned device memory (256-byte aligned, at least the sizes above; all BORROWED until
+ * kg_destroy) and the HIP stream (a hipStream_t, may be NULL for the default stream) every kernel
+ * of this context is launched on.  Clears scratch and resets the sequence. */
+int kg_bind(kg_ctx *ctx, void *weights_dev, size_t weight_bytes, void *kv_dev, size_t kv_bytes,
+            void *scratch_dev, size_t scratch_bytes, void *hip_stream);
+
+/* Load one tensor (Section 3.1: the target's weights and the adapter's; the exit layer was fixed at
+ * kg_create).  src_dev is a row-major device array of n_elements values in the configured dtype;
+ * it is copied into the arena in the library's tiled layout and may be freed when the call returns
+ * (the call synchronises the stream). */
+int kg_load_tensor(kg_ctx *ctx, int kind, int layer, const void *src_dev, size_t n_elements);
+
+/* Optional: order in which physical KV pages are handed out (host, a permutation of 0..n-1 where
+ * n = number of pages = ceil(max_seq / kv_page_tokens)).  Default is the identity.  Resets the
+ * sequence. */
+int kg_set_page_order(kg_ctx *ctx, const int32_t *perm_host, int n);
+
+/* Run the full model and the adapter over the prompt (host, n >= 1 token ids): fills all caches
+ * for positions 0..n-1 and returns the target model's next token, which becomes the pending
+ * token of the first round.  Resets any previous sequence. */
+int kg_prefill(kg_ctx *ctx, const kg_params *p, const int32_t *prompt_host, int n, int32_t *first_token);
+
+/* One drafting step of the self-draft model M^s = A o M^b[:l] (Section 3.1): shallow layers on
+ * the latest token, adapter (on two rows when a lagged feature is pending, Figure 2), shared LM
+ * head with fused arg-max / log-sum-exp.  Outputs the draft token, its top-1 probability, and
+ * *stop = 1 when drafting must end (confidence < eta, Eq. 4, or gamma drafts exist). */
+int kg_draft_step(kg_ctx *ctx, const kg_params *p, int32_t *token, float *confidence, int *stop);
+
+/* Compute the last draft's next early feature, then run the remaining layers M^b[l:] once over
+ * [f_0..f_k] (Figure 2).  target_tokens (host, room for gamma+1) receives the target's greedy
+ * token per row (mode 0) and *k_plus_1 the number of rows. */
+int kg_verify(kg_ctx *ctx, const kg_params *p, int32_t *target_tokens, int *k_plus_1);
+
+/* Acceptance (Section 3: the first rejected draft discards the rest) and cache rollback.
+ * emitted (host, room for gamma+1) receives the 1..k+1 tokens of this round. */
+int kg_accept(kg_ctx *ctx, const kg_params *p, int32_t *emitted, int *n_emitted);
+
+/* prefill + rounds until max_new tokens are out (the first is the prefill's).  out: host, room for
+ * max_new.  Produces exactly the stream the stepwise calls produce.  stats may be NULL. */
+int kg_generate(kg_ctx *ctx, const kg_params *p, const int32_t *prompt_host, int n_prompt, int max_new,
+                int32_t *out, int *n_out, kg_stats *stats);
+
+/* Plain autoregressive decoding of the full model (Section 1), one token per forward. */
+int kg_decode_plain(kg_ctx *ctx, const kg_params *p, const int32_t *prompt_host, int n_prompt, int max_new,
+                    int32_t *out, int *n_out, kg_stats *stats);
+
+/* One plain step after kg_prefill (or after earlier plain steps): feed `token` at the next
+ * position through all layers and return the next token.  Lets a caller force the token stream. */
+int kg_plain_step(kg_ctx *ctx, const kg_params *p, int32_t token, int32_t *next_token);
+
+/* Copy one row of the most recent logits to the host (float[vocab]).  which = 0: draft logits of
+ * draft step `row` of the current round; which = 1: target logits of row `row` of the last
+ * verify / prefill / plain step. */
+int kg_read_logits(kg_ctx *ctx, int which, int row, float *host_out);
+
+/* Copy the early feature f_row of the current round (float[d_model]) to the host. */
+int kg_read_feature(kg_ctx *ctx, int row, float *host_out);
+
+/* Copy the cached key and value vectors (float[d_model] each, widened from the cache type) of
+ * cache `slot` (0..n_layers-1: decoder layers; n_layers: the adapter) at position pos. */
+int kg_read_kv(kg_ctx *ctx, int slot, int pos, float *k_host, float *v_host);
+
+/* Sequence state: committed tokens (`base`), tokens in the adapter's cache, lag flag, drafts so far. */
+int kg_get_state(const kg_ctx *ctx, int *base, int *adapter_len, int *lag, int *n_drafts);
+
+/* Drop the sequence state, keep bindings and weights. */
+int kg_reset(kg_ctx *ctx);
+
+const char *kg_last_error(const kg_ctx *ctx);
+void kg_destroy(kg_ctx *ctx);
+
+/*
+ * Stand-alone weight-streaming product Y[M][N] = X[M][K] . W^T used by every projection of the
+ * decode forwards (Section 1: decoding is bound by reading the weights), exposed for kernel-level
+ * tests and bandwidth measurements.
+ *   kg_op_packed_bytes: bytes of the tiled form of a [N][K] matrix (N % 16 == 0, K % 8 == 0).
+ *   kg_op_pack:   re-tile a row-major dev matrix (dtype 0 f32 / 1 bf16) into packed_dev.
+ *   kg_op_linear: x_dev float[M][K], y_dev float[M][N]; work_dev >= kg_op_work_bytes(K) bytes of
+ *                 device scratch; M <= KG_MAX_ROWS.  Launches on `hip_stream`, does not synchronise.
+ */
+size_t kg_op_packed_bytes(int dtype, int N, int K);
+size_t kg_op_work_bytes(int K);
+int kg_op_pack(int dtype, const void *src_dev, int N, int K, void *packed_dev, void *hip_stream);
+int kg_op_linear(int dtype, const void *packed_dev, int N, int K, const float *x_dev, int M, float *y_dev,
+                 void *work_dev, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KANGAROO_H */

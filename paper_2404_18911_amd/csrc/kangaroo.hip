@@ -1,0 +1,866 @@
+// Host side of libkangaroo: the C ABI declared in include/kangaroo.h.  It owns no device memory;
+// it carves the caller's arena / KV pool / scratch, launches the kernels of kernels.hip.h on the
+// caller's stream, and runs the control flow of the draft-and-verify round (Section 3, Figure 2).
+#include "kernels.hip.h"
+
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "kangaroo.h"
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x, size_t a = ALIGN) { return (x + a - 1) / a * a; }
+
+struct LayerW {
+    size_t qkv, wo, gu, wd, g1, g2; // byte offsets into the arena
+};
+
+struct Phase { enum { NONE = 0, READY = 1, DRAFTING = 2, VERIFIED = 3, PLAIN = 4 }; };
+
+} // namespace
+
+struct kg_ctx {
+    kg_config c;
+    bool bf;
+    int esz;                 // bytes per stored weight / cache element
+    int KSd, KSf;            // k-steps (32 features) of d_model and d_ffn
+    int n_pages, logP;
+    // arena layout
+    std::vector<LayerW> lw;
+    size_t a_qkv, a_wo, a_gin, a_glast, head, embed, gfinal, arena_bytes;
+    size_t kv_bytes, scratch_bytes;
+    // scratch layout (byte offsets)
+    size_t s_x0, s_x1, s_F, s_qkv, s_actX, s_actA, s_actF, s_ssq0, s_ssq1, s_opart, s_mxs, s_sms, s_cnt,
+        s_dlog, s_tlog, s_tok, s_conf, s_pt, s_rope, s_invf, s_misc;
+    // bindings
+    char *arena = nullptr, *kv = nullptr, *scr = nullptr;
+    hipStream_t stream = nullptr;
+    bool bound = false;
+    std::vector<char> loaded; // per (kind, layer) flag
+    std::vector<int> page_order;
+    // pinned host staging
+    int *h_tok = nullptr;
+    float *h_conf = nullptr;
+    // sequence state (see kg_get_state)
+    int phase = Phase::NONE;
+    int base = 0, adapter_len = 0, lag = 0, pending = -1;
+    int n_drafts = 0, stopped = 0;
+    int drafts[KG_MAX_ROWS];
+    float confs[KG_MAX_ROWS];
+    int targets[KG_MAX_ROWS];
+    int n_target_rows = 0;
+    int plain_len = 0;
+    char err[512];
+};
+
+namespace {
+
+int fail(kg_ctx *ctx, int code, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+#define HIPCHK(ctx, call)                                                                            \
+    do {                                                                                             \
+        hipError_t e_ = (call);                                                                      \
+        if (e_ != hipSuccess) return fail(ctx, KG_EHIP, "%s: %s", #call, hipGetErrorString(e_));     \
+    } while (0)
+
+#define KGCHK(call)                 \
+    do {                            \
+        int r_ = (call);            \
+        if (r_ != KG_OK) return r_; \
+    } while (0)
+
+inline size_t act_bytes(int K) { return (size_t)((K + 31) / 32) * 1024; }
+inline size_t packed_bytes(bool bf, int N, int K) { return bf ? (size_t)(N / 16) * ((K + 31) / 32) * 1024 : (size_t)N * K * 4; }
+
+int ilog2(int v)
+{
+    int l = 0;
+    while ((1 << l) < v) l++;
+    return l;
+}
+
+void layout(kg_ctx *x)
+{
+    const kg_config &c = x->c;
+    const int d = c.d_model, f = c.d_ffn, V = c.vocab, L = c.n_layers;
+    size_t o = 0;
+    auto take = [&](size_t b) { size_t r = o; o += up(b); return r; };
+    x->lw.resize(L);
+    for (int i = 0; i < L; i++) {
+        x->lw[i].qkv = take(packed_bytes(x->bf, 3 * d, d));
+        x->lw[i].wo = take(packed_bytes(x->bf, d, d));
+        x->lw[i].gu = take(packed_bytes(x->bf, 2 * f, d));
+        x->lw[i].wd = take(packed_bytes(x->bf, d, f));
+        x->lw[i].g1 = take((size_t)d * 4);
+        x->lw[i].g2 = take((size_t)d * 4);
+    }
+    x->a_qkv = take(packed_bytes(x->bf, 3 * d, d));
+    x->a_wo = take(packed_bytes(x->bf, d, d));
+    x->a_gin = take((size_t)d * 4);
+    x->a_glast = take((size_t)d * 4);
+    x->head = take(packed_bytes(x->bf, V, d));
+    x->embed = take((size_t)V * d * x->esz);
+    x->gfinal = take((size_t)d * 4);
+    x->arena_bytes = o;
+
+    x->kv_bytes = up((size_t)x->n_pages * (L + 1) * c.n_heads * 2 * c.kv_page_tokens * c.head_dim * x->esz);
+
+    o = 0;
+    x->s_x0 = take((size_t)KG_ROWS * d * 4);
+    x->s_x1 = take((size_t)KG_ROWS * d * 4);
+    x->s_F = take((size_t)(KG_ROWS + 1) * d * 4); // row 0: lagged feature, rows 1..8: f_0..f_7
+    x->s_qkv = take((size_t)KG_ROWS * 3 * d * 4);
+    x->s_actX = take(act_bytes(d));
+    x->s_actA = take(act_bytes(d));
+    x->s_actF = take(act_bytes(f));
+    x->s_ssq0 = take((size_t)(d / 16) * KG_ROWS * 4);
+    x->s_ssq1 = take((size_t)(d / 16) * KG_ROWS * 4);
+    x->s_opart = take((size_t)c.n_heads * x->n_pages * KG_ROWS * c.head_dim * 4);
+    x->s_mxs = take((size_t)c.n_heads * x->n_pages * KG_ROWS * 4);
+    x->s_sms = take((size_t)c.n_heads * x->n_pages * KG_ROWS * 4);
+    x->s_cnt = take((size_t)c.n_heads * 4);
+    x->s_dlog = take((size_t)KG_ROWS * V * 4);
+    x->s_tlog = take((size_t)KG_ROWS * V * 4);
+    x->s_tok = take(KG_ROWS * 4);
+    x->s_conf = take(KG_ROWS * 4);
+    x->s_pt = take((size_t)x->n_pages * 4);
+    x->s_rope = take((size_t)c.max_seq * (c.head_dim / 2) * 8);
+    x->s_invf = take((size_t)(c.head_dim / 2) * 8);
+    x->s_misc = take((size_t)2 * d * 4);
+    x->scratch_bytes = o;
+}
+
+template <typename T> inline T *at(char *basep, size_t off) { return reinterpret_cast<T *>(basep + off); }
+
+int check_launch(kg_ctx *x, const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(x, KG_EHIP, "launch %s: %s", what, hipGetErrorString(e));
+    return KG_OK;
+}
+
+// ---- kernel launch helpers ---------------------------------------------------------------------
+
+int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Epi &e)
+{
+    if (N % 16) return fail(x, KG_EINVAL, "projection rows %d not a multiple of 16", N);
+    if (x->bf)
+        hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(256), 0, x->stream,
+                           at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
+    else
+        hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, x->stream, at<const float>(x->arena, w_off),
+                           K, (const float *)act, e);
+    return check_launch(x, "gemv");
+}
+
+int launch_pack_rows(kg_ctx *x, const int *tokens, const float *rows, int M, const float *gain, float *xout,
+                     void *act, float *ssq)
+{
+    Tok8 tk;
+    for (int i = 0; i < KG_ROWS; i++) tk.t[i] = (tokens && i < M) ? tokens[i] : 0;
+    const void *emb = tokens ? (const void *)(x->arena + x->embed) : nullptr;
+    const int d = x->c.d_model;
+    if (x->bf)
+        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(d / 16), dim3(128), 0, x->stream, emb, tk, rows, d, M, gain,
+                           xout, act, ssq);
+    else
+        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(d / 16), dim3(128), 0, x->stream, emb, tk, rows, d, M,
+                           gain, xout, act, ssq);
+    return check_launch(x, "pack_rows");
+}
+
+int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
+{
+    const kg_config &c = x->c;
+    AttnArgs a;
+    a.qkv = at<const float>(x->scr, x->s_qkv);
+    a.d = c.d_model; a.H = c.n_heads; a.M = M; a.pos0 = pos0; a.P = c.kv_page_tokens; a.logP = x->logP;
+    a.page_table = at<const int>(x->scr, x->s_pt);
+    a.kv = x->kv; a.slot = slot; a.n_slots = c.n_layers + 1;
+    a.rope = at<const float2>(x->scr, x->s_rope);
+    a.opart = at<float>(x->scr, x->s_opart); a.mxs = at<float>(x->scr, x->s_mxs); a.sms = at<float>(x->scr, x->s_sms);
+    a.cnt = at<int>(x->scr, x->s_cnt);
+    a.S = (pos0 + M + c.kv_page_tokens - 1) >> x->logP;
+    a.act_out = x->scr + x->s_actA;
+    a.append_only = append_only;
+    dim3 grid(c.n_heads, a.S);
+    if (x->bf) {
+        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<uint16_t, 128, true>), grid, dim3(256), 0, x->stream, a);
+        else hipLaunchKernelGGL((attn_kernel<uint16_t, 64, true>), grid, dim3(256), 0, x->stream, a);
+    } else {
+        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, false>), grid, dim3(256), 0, x->stream, a);
+        else hipLaunchKernelGGL((attn_kernel<float, 64, false>), grid, dim3(256), 0, x->stream, a);
+    }
+    return check_launch(x, "attention");
+}
+
+Epi epi_base(kg_ctx *x, int kind, int M, int N)
+{
+    Epi e;
+    memset(&e, 0, sizeof(e));
+    e.kind = kind; e.M = M; e.N = N;
+    e.inv_d = 1.f / (float)x->c.d_model;
+    e.eps = x->c.rms_eps;
+    e.nt_in = x->c.d_model / 16;
+    return e;
+}
+
+// Attention sub-layer + (optionally) feed-forward sub-layer of one block on M rows at pos0.
+// In:  actX = x_in * g_attn (packed), ssq0 = tile sums of squares of x_in, x_in fp32 rows.
+// Out: x rows in x_out; actX = x_out * next_gain if next_gain, ssq0 = tile sums of x_out.
+int run_block(kg_ctx *x, int slot, size_t qkv_off, size_t wo_off, size_t gu_off, size_t wd_off, const float *g2,
+              int M, int pos0, const float *x_in, float *x_out, const float *next_gain, bool with_ffn)
+{
+    const kg_config &c = x->c;
+    const int d = c.d_model, f = c.d_ffn;
+    float *ssq0 = at<float>(x->scr, x->s_ssq0), *ssq1 = at<float>(x->scr, x->s_ssq1);
+    void *actX = x->scr + x->s_actX, *actA = x->scr + x->s_actA, *actF = x->scr + x->s_actF;
+    float *x_mid = with_ffn ? at<float>(x->scr, x->s_x1) : x_out;
+
+    Epi e = epi_base(x, EPI_PLAIN, M, 3 * d);
+    e.ssq_in = ssq0; e.out = at<float>(x->scr, x->s_qkv);
+    KGCHK(launch_gemv(x, qkv_off, 3 * d, d, actX, e));
+    KGCHK(launch_attn(x, slot, pos0, M, 0));
+
+    e = epi_base(x, EPI_RESID, M, d);
+    e.res = x_in; e.xout = x_mid; e.act_out = actX; e.act_K = d;
+    if (with_ffn) { e.gain = g2; e.ssq_out = ssq1; }
+    else { e.gain = next_gain; e.ssq_out = ssq0; if (!next_gain) e.act_out = nullptr; }
+    KGCHK(launch_gemv(x, wo_off, d, d, actA, e));
+    if (!with_ffn) return KG_OK;
+
+    e = epi_base(x, EPI_SWIGLU, M, 2 * f);
+    e.ssq_in = ssq1; e.act_out = actF; e.act_K = f;
+    KGCHK(launch_gemv(x, gu_off, 2 * f, d, actX, e));
+
+    e = epi_base(x, EPI_RESID, M, d);
+    e.res = x_mid; e.xout = x_out; e.act_out = next_gain ? actX : nullptr; e.act_K = d; e.gain = next_gain;
+    e.ssq_out = ssq0;
+    KGCHK(launch_gemv(x, wd_off, d, f, actF, e));
+    return KG_OK;
+}
+
+// Decoder blocks lo..hi-1.  x_first: fp32 rows feeding block lo (already packed into actX/ssq0
+// with norm1[lo]); the result rows land in x_last; final_gain prepares actX for what follows.
+int run_layers(kg_ctx *x, int lo, int hi, int M, int pos0, const float *x_first, float *x_last,
+               const float *final_gain)
+{
+    float *x0 = at<float>(x->scr, x->s_x0);
+    const float *xin = x_first;
+    for (int i = lo; i < hi; i++) {
+        const LayerW &w = x->lw[i];
+        bool last = (i == hi - 1);
+        float *xout = last ? x_last : x0;
+        const float *ng = last ? final_gain : at<const float>(x->arena, x->lw[i + 1].g1);
+        KGCHK(run_block(x, i, w.qkv, w.wo, w.gu, w.wd, at<const float>(x->arena, w.g2), M, pos0, xin, xout, ng, true));
+        xin = xout;
+    }
+    return KG_OK;
+}
+
+// LM head on the rows packed in actX (+ssq0): logits rows (m + row_shift) of `logits`, then
+// arg-max and top-1 probability of rows 0..n_out-1 into the device tok/conf arrays.
+int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float inv_temp)
+{
+    Epi e = epi_base(x, EPI_PLAIN, M, x->c.vocab);
+    e.ssq_in = at<float>(x->scr, x->s_ssq0); e.out = logits; e.row_shift = row_shift;
+    KGCHK(launch_gemv(x, x->head, x->c.vocab, x->c.d_model, x->scr + x->s_actX, e));
+    hipLaunchKernelGGL(head_reduce_kernel, dim3(n_out), dim3(1024), 0, x->stream, logits, x->c.vocab, n_out,
+                       inv_temp, at<int>(x->scr, x->s_tok), at<float>(x->scr, x->s_conf));
+    return check_launch(x, "head_reduce");
+}
+
+int fetch_results(kg_ctx *x, int n)
+{
+    HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, n * 4, hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipMemcpyAsync(x->h_conf, x->scr + x->s_conf, n * 4, hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    return KG_OK;
+}
+
+float *Frow(kg_ctx *x, int j) { return at<float>(x->scr, x->s_F) + (size_t)(j + 1) * x->c.d_model; } // f_j
+float *Flag(kg_ctx *x) { return at<float>(x->scr, x->s_F); }
+
+// shallow sub-network M^b[:l] on M tokens at pos0; early features go to rows f_j0..f_{j0+M-1}
+int run_shallow(kg_ctx *x, const int *tokens, int M, int pos0, int j0)
+{
+    const kg_config &c = x->c;
+    float *x0 = at<float>(x->scr, x->s_x0);
+    KGCHK(launch_pack_rows(x, tokens, nullptr, M, at<const float>(x->arena, x->lw[0].g1), x0, x->scr + x->s_actX,
+                           at<float>(x->scr, x->s_ssq0)));
+    return run_layers(x, 0, c.exit_layer, M, pos0, x0, Frow(x, j0), nullptr);
+}
+
+// adapter A on rows starting at F-buffer row `frow` (0 = lag slot), positions pos0..; when
+// `full` is false only its K/V are appended (prefill).  Leaves actX/ssq0 ready for the LM head.
+int run_adapter(kg_ctx *x, int frow, int M, int pos0, bool full)
+{
+    const kg_config &c = x->c;
+    const float *rows = at<float>(x->scr, x->s_F) + (size_t)frow * c.d_model;
+    KGCHK(launch_pack_rows(x, nullptr, rows, M, at<const float>(x->arena, x->a_gin), nullptr, x->scr + x->s_actX,
+                           at<float>(x->scr, x->s_ssq0)));
+    if (!full) {
+        Epi e = epi_base(x, EPI_PLAIN, M, 3 * c.d_model);
+        e.ssq_in = at<float>(x->scr, x->s_ssq0); e.out = at<float>(x->scr, x->s_qkv);
+        KGCHK(launch_gemv(x, x->a_qkv, 3 * c.d_model, c.d_model, x->scr + x->s_actX, e));
+        return launch_attn(x, c.n_layers, pos0, M, 1);
+    }
+    return run_block(x, c.n_layers, x->a_qkv, x->a_wo, 0, 0, nullptr, M, pos0, rows, at<float>(x->scr, x->s_x1),
+                     at<const float>(x->arena, x->a_glast), false);
+}
+
+// remaining layers M^b[l:] on early features f_0..f_{M-1} at pos0, then final norm (folded) —
+// leaves actX/ssq0 ready for the LM head.
+int run_deep(kg_ctx *x, int M, int pos0)
+{
+    const kg_config &c = x->c;
+    const float *gf = at<const float>(x->arena, x->gfinal);
+    if (c.exit_layer == c.n_layers)
+        return launch_pack_rows(x, nullptr, Frow(x, 0), M, gf, nullptr, x->scr + x->s_actX, at<float>(x->scr, x->s_ssq0));
+    KGCHK(launch_pack_rows(x, nullptr, Frow(x, 0), M, at<const float>(x->arena, x->lw[c.exit_layer].g1), nullptr,
+                           x->scr + x->s_actX, at<float>(x->scr, x->s_ssq0)));
+    return run_layers(x, c.exit_layer, c.n_layers, M, pos0, Frow(x, 0), at<float>(x->scr, x->s_x0), gf);
+}
+
+int check_ready(kg_ctx *x)
+{
+    if (!x) return KG_EINVAL;
+    if (!x->bound) return fail(x, KG_ESTATE, "kg_bind has not been called");
+    for (size_t i = 0; i < x->loaded.size(); i++)
+        if (!x->loaded[i]) return fail(x, KG_ESTATE, "tensor slot %zu has not been loaded", i);
+    return KG_OK;
+}
+
+int check_params(kg_ctx *x, const kg_params *p)
+{
+    if (!p) return fail(x, KG_EINVAL, "params is NULL");
+    if (p->gamma < 1 || p->gamma > x->c.gamma_max) return fail(x, KG_EINVAL, "gamma %d outside 1..%d", p->gamma, x->c.gamma_max);
+    if (p->mode != 0 && p->mode != 1) return fail(x, KG_EINVAL, "mode %d is neither 0 (greedy) nor 1 (sampling)", p->mode);
+    if (p->mode == 1) {
+        if (!(p->temperature > 0.f)) return fail(x, KG_EINVAL, "temperature must be > 0");
+        if (!p->uniforms) return fail(x, KG_EINVAL, "sampling mode needs uniforms");
+    }
+    if (!(p->eta >= 0.f)) return fail(x, KG_EINVAL, "eta must be >= 0");
+    return KG_OK;
+}
+
+int tensor_slot(const kg_ctx *x, int kind, int layer)
+{
+    // slot index into `loaded`: 3 globals, 9 per layer, 6 adapter
+    if (kind <= KG_FINAL_NORM) return kind;
+    if (kind <= KG_NORM2) return 3 + layer * 9 + (kind - KG_WQ);
+    return 3 + x->c.n_layers * 9 + (kind - KG_A_WQ);
+}
+
+double now_s()
+{
+    return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+} // namespace
+
+// ================================================================================================
+extern "C" {
+
+int kg_create(const kg_config *cfg, kg_ctx **out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return KG_EINVAL;
+    const kg_config &c = *cfg;
+    if (c.n_layers < 1 || c.d_model < 16 || c.n_heads < 1 || c.d_ffn < 8 || c.vocab < 16) return KG_EINVAL;
+    if (c.head_dim != 64 && c.head_dim != 128) return KG_EINVAL;
+    if (c.n_heads * c.head_dim != c.d_model) return KG_EINVAL;
+    if (c.d_model % 16 || c.d_ffn % 8 || c.vocab % 16) return KG_EINVAL;
+    if (c.exit_layer < 1 || c.exit_layer > c.n_layers) return KG_EINVAL;
+    if (c.dtype != 0 && c.dtype != 1) return KG_EINVAL;
+    if (c.gamma_max < 1 || c.gamma_max > KG_MAX_ROWS - 1) return KG_EINVAL;
+    if (c.kv_page_tokens < 16 || c.kv_page_tokens > 128 || (c.kv_page_tokens & (c.kv_page_tokens - 1))) return KG_EINVAL;
+    if (c.max_seq < 2 || !(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return KG_EINVAL;
+    kg_ctx *x = new (std::nothrow) kg_ctx();
+    if (!x) return KG_ENOMEM;
+    x->c = c;
+    x->bf = c.dtype == 1;
+    x->esz = x->bf ? 2 : 4;
+    x->KSd = (c.d_model + 31) / 32;
+    x->KSf = (c.d_ffn + 31) / 32;
+    x->logP = ilog2(c.kv_page_tokens);
+    x->n_pages = (c.max_seq + c.kv_page_tokens - 1) / c.kv_page_tokens;
+    x->err[0] = 0;
+    layout(x);
+    x->loaded.assign(3 + (size_t)c.n_layers * 9 + 6, 0);
+    x->page_order.resize(x->n_pages);
+    for (int i = 0; i < x->n_pages; i++) x->page_order[i] = i;
+    *out = x;
+    return KG_OK;
+}
+
+int kg_workspace_bytes(const kg_ctx *x, size_t *weight_bytes, size_t *kv_bytes, size_t *scratch_bytes)
+{
+    if (!x) return KG_EINVAL;
+    if (weight_bytes) *weight_bytes = x->arena_bytes;
+    if (kv_bytes) *kv_bytes = x->kv_bytes;
+    if (scratch_bytes) *scratch_bytes = x->scratch_bytes;
+    return KG_OK;
+}
+
+static int upload_tables(kg_ctx *x)
+{
+    const kg_config &c = x->c;
+    HIPCHK(x, hipMemsetAsync(x->scr, 0, x->scratch_bytes, x->stream));
+    HIPCHK(x, hipMemcpyAsync(x->scr + x->s_pt, x->page_order.data(), (size_t)x->n_pages * 4, hipMemcpyHostToDevice,
+                             x->stream));
+    std::vector<double> invf(c.head_dim / 2);
+    for (int i = 0; i < c.head_dim / 2; i++) invf[i] = std::pow((double)c.rope_theta, -2.0 * i / c.head_dim);
+    HIPCHK(x, hipMemcpyAsync(x->scr + x->s_invf, invf.data(), invf.size() * 8, hipMemcpyHostToDevice, x->stream));
+    int n = c.max_seq * (c.head_dim / 2);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, x->stream, at<float2>(x->scr, x->s_rope),
+                       c.max_seq, c.head_dim / 2, at<const double>(x->scr, x->s_invf));
+    KGCHK(check_launch(x, "rope_table"));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    return KG_OK;
+}
+
+int kg_bind(kg_ctx *x, void *weights_dev, size_t weight_bytes, void *kv_dev, size_t kv_bytes, void *scratch_dev,
+            size_t scratch_bytes, void *hip_stream)
+{
+    if (!x) return KG_EINVAL;
+    if (!weights_dev || !kv_dev || !scratch_dev) return fail(x, KG_EINVAL, "NULL device buffer");
+    if (((uintptr_t)weights_dev | (uintptr_t)kv_dev | (uintptr_t)scratch_dev) & (ALIGN - 1))
+        return fail(x, KG_EINVAL, "device buffers must be %zu-byte aligned", ALIGN);
+    if (weight_bytes < x->arena_bytes || kv_bytes < x->kv_bytes || scratch_bytes < x->scratch_bytes)
+        return fail(x, KG_ENOSPC, "buffers too small: need %zu/%zu/%zu bytes", x->arena_bytes, x->kv_bytes, x->scratch_bytes);
+    x->arena = (char *)weights_dev; x->kv = (char *)kv_dev; x->scr = (char *)scratch_dev;
+    x->stream = (hipStream_t)hip_stream;
+    if (!x->h_tok) {
+        HIPCHK(x, hipHostMalloc((void **)&x->h_tok, KG_ROWS * 4, hipHostMallocDefault));
+        HIPCHK(x, hipHostMalloc((void **)&x->h_conf, KG_ROWS * 4, hipHostMallocDefault));
+    }
+    x->bound = true;
+    std::fill(x->loaded.begin(), x->loaded.end(), 0);
+    x->phase = Phase::NONE;
+    return upload_tables(x);
+}
+
+int kg_load_tensor(kg_ctx *x, int kind, int layer, const void *src, size_t n_elements)
+{
+    if (!x) return KG_EINVAL;
+    if (!x->bound) return fail(x, KG_ESTATE, "kg_bind has not been called");
+    if (!src) return fail(x, KG_EINVAL, "NULL tensor");
+    const kg_config &c = x->c;
+    const int d = c.d_model, f = c.d_ffn, V = c.vocab;
+    if (kind < 0 || kind >= KG_N_TENSOR_KINDS) return fail(x, KG_EINVAL, "unknown tensor kind %d", kind);
+    bool per_layer = kind >= KG_WQ && kind <= KG_NORM2;
+    if (per_layer ? (layer < 0 || layer >= c.n_layers) : (layer != -1))
+        return fail(x, KG_EINVAL, "bad layer %d for tensor kind %d", layer, kind);
+    int rows = 0, K = 0, row_off = 0, mode = 0;
+    size_t dst = 0;
+    bool is_gain = false;
+    switch (kind) {
+    case KG_EMBED: rows = V; K = d; dst = x->embed; break;
+    case KG_LM_HEAD: rows = V; K = d; dst = x->head; break;
+    case KG_FINAL_NORM: is_gain = true; dst = x->gfinal; break;
+    case KG_WQ: case KG_WK: case KG_WV: rows = d; K = d; dst = x->lw[layer].qkv; row_off = (kind - KG_WQ) * d; break;
+    case KG_WO: rows = d; K = d; dst = x->lw[layer].wo; break;
+    case KG_WG: case KG_WU: rows = f; K = d; dst = x->lw[layer].gu; mode = 1 + (kind - KG_WG); break;
+    case KG_WD: rows = d; K = f; dst = x->lw[layer].wd; break;
+    case KG_NORM1: is_gain = true; dst = x->lw[layer].g1; break;
+    case KG_NORM2: is_gain = true; dst = x->lw[layer].g2; break;
+    case KG_A_WQ: case KG_A_WK: case KG_A_WV: rows = d; K = d; dst = x->a_qkv; row_off = (kind - KG_A_WQ) * d; break;
+    case KG_A_WO: rows = d; K = d; dst = x->a_wo; break;
+    case KG_A_NORM_IN: is_gain = true; dst = x->a_gin; break;
+    case KG_A_NORM_LAST: is_gain = true; dst = x->a_glast; break;
+    }
+    size_t want = is_gain ? (size_t)d : (size_t)rows * K;
+    if (n_elements != want) return fail(x, KG_EINVAL, "tensor kind %d: %zu elements given, %zu expected", kind, n_elements, want);
+    if (is_gain) {
+        hipLaunchKernelGGL(gain_to_f32_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, src, x->bf ? 1 : 0, d,
+                           at<float>(x->arena, dst));
+    } else if (kind == KG_EMBED) {
+        HIPCHK(x, hipMemcpyAsync(x->arena + dst, src, want * x->esz, hipMemcpyDeviceToDevice, x->stream));
+    } else if (x->bf) {
+        if (K % 8) return fail(x, KG_EINVAL, "bf16 tensors need K %% 8 == 0");
+        int KS = (K + 31) / 32;
+        size_t total = (size_t)rows * KS * 4;
+        hipLaunchKernelGGL(pack_w_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, x->stream,
+                           (const uint16_t *)src, rows, K, at<u32x4_t>(x->arena, dst), KS, row_off, mode);
+    } else {
+        size_t total = (size_t)rows * K;
+        hipLaunchKernelGGL(pack_w_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, x->stream,
+                           (const float *)src, rows, K, at<float>(x->arena, dst), row_off, mode);
+    }
+    KGCHK(check_launch(x, "load_tensor"));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    x->loaded[tensor_slot(x, kind, layer)] = 1;
+    return KG_OK;
+}
+
+int kg_set_page_order(kg_ctx *x, const int32_t *perm, int n)
+{
+    if (!x || !perm) return KG_EINVAL;
+    if (n != x->n_pages) return fail(x, KG_EINVAL, "page order has %d entries, the pool has %d pages", n, x->n_pages);
+    std::vector<char> seen(n, 0);
+    for (int i = 0; i < n; i++) {
+        if (perm[i] < 0 || perm[i] >= n || seen[perm[i]]) return fail(x, KG_EINVAL, "page order is not a permutation");
+        seen[perm[i]] = 1;
+    }
+    x->page_order.assign(perm, perm + n);
+    x->phase = Phase::NONE;
+    if (x->bound) {
+        HIPCHK(x, hipMemcpyAsync(x->scr + x->s_pt, x->page_order.data(), (size_t)n * 4, hipMemcpyHostToDevice, x->stream));
+        HIPCHK(x, hipStreamSynchronize(x->stream));
+    }
+    return KG_OK;
+}
+
+int kg_reset(kg_ctx *x)
+{
+    if (!x) return KG_EINVAL;
+    x->phase = Phase::NONE;
+    x->base = x->adapter_len = x->lag = 0;
+    x->n_drafts = x->stopped = 0;
+    x->pending = -1;
+    if (x->bound) {
+        HIPCHK(x, hipMemsetAsync(x->scr + x->s_cnt, 0, (size_t)x->c.n_heads * 4, x->stream));
+        HIPCHK(x, hipStreamSynchronize(x->stream));
+    }
+    return KG_OK;
+}
+
+int kg_prefill(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n, int32_t *first_token)
+{
+    KGCHK(check_ready(x));
+    KGCHK(check_params(x, p));
+    if (!prompt || !first_token || n < 1) return fail(x, KG_EINVAL, "bad prompt");
+    const kg_config &c = x->c;
+    if (n + 1 + p->gamma + 1 > c.max_seq) return fail(x, KG_ENOSPC, "prompt of %d tokens does not fit max_seq %d", n, c.max_seq);
+    for (int i = 0; i < n; i++)
+        if (prompt[i] < 0 || prompt[i] >= c.vocab) return fail(x, KG_EINVAL, "prompt token %d out of range", prompt[i]);
+    KGCHK(kg_reset(x));
+    float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
+    for (int pos0 = 0; pos0 < n; pos0 += KG_ROWS) {
+        int M = std::min(KG_ROWS, n - pos0);
+        KGCHK(run_shallow(x, prompt + pos0, M, pos0, 0));
+        KGCHK(run_adapter(x, 1, M, pos0, false));
+        KGCHK(run_deep(x, M, pos0));
+        if (pos0 + M == n) KGCHK(run_head(x, M, -(M - 1), at<float>(x->scr, x->s_tlog), 1, inv_t));
+    }
+    KGCHK(fetch_results(x, 1));
+    x->base = n; x->adapter_len = n; x->lag = 0;
+    x->n_drafts = 0; x->stopped = 0;
+    x->n_target_rows = 1;
+    x->pending = x->h_tok[0];
+    x->plain_len = n;
+    x->phase = Phase::READY;
+    *first_token = x->pending;
+    return KG_OK;
+}
+
+int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confidence, int *stop)
+{
+    KGCHK(check_ready(x));
+    KGCHK(check_params(x, p));
+    if (!token || !confidence || !stop) return fail(x, KG_EINVAL, "NULL output");
+    if (x->phase != Phase::READY && x->phase != Phase::DRAFTING) return fail(x, KG_ESTATE, "draft_step needs a prefilled sequence and no pending verify");
+    if (x->stopped || x->n_drafts >= p->gamma) return fail(x, KG_ESTATE, "drafting already ended for this round");
+    const int j = x->n_drafts;
+    if (x->base + j + 2 >= x->c.max_seq) return fail(x, KG_ENOSPC, "sequence would exceed max_seq");
+    const int tok = j == 0 ? x->pending : x->drafts[j - 1];
+    const int pos = x->base + j;
+    KGCHK(run_shallow(x, &tok, 1, pos, j));
+    int M = 1;
+    if (j == 0 && x->lag) {                       // adapter catches up on [lagged f, f_0] (Figure 2)
+        M = 2;
+        KGCHK(run_adapter(x, 0, 2, pos - 1, true));
+    } else {
+        KGCHK(run_adapter(x, j + 1, 1, pos, true));
+    }
+    float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
+    float *dl = at<float>(x->scr, x->s_dlog) + (size_t)j * x->c.vocab;
+    KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t));
+    KGCHK(fetch_results(x, 1));
+    x->lag = 0;
+    x->adapter_len = pos + 1;
+    x->drafts[j] = x->h_tok[0];
+    x->confs[j] = x->h_conf[0];
+    x->n_drafts = j + 1;
+    x->stopped = (x->confs[j] < p->eta) || (x->n_drafts == p->gamma);   // Eq. 4
+    x->phase = Phase::DRAFTING;
+    *token = x->drafts[j];
+    *confidence = x->confs[j];
+    *stop = x->stopped;
+    return KG_OK;
+}
+
+int kg_verify(kg_ctx *x, const kg_params *p, int32_t *target_tokens, int *k_plus_1)
+{
+    KGCHK(check_ready(x));
+    KGCHK(check_params(x, p));
+    if (!target_tokens || !k_plus_1) return fail(x, KG_EINVAL, "NULL output");
+    if (x->phase != Phase::DRAFTING || x->n_drafts < 1) return fail(x, KG_ESTATE, "verify needs at least one draft step");
+    const int k = x->n_drafts;
+    if (x->base + k + 1 >= x->c.max_seq) return fail(x, KG_ENOSPC, "sequence would exceed max_seq");
+    const int tok = x->drafts[k - 1];
+    KGCHK(run_shallow(x, &tok, 1, x->base + k, k));            // next early feature f_k; adapter not run
+    KGCHK(run_deep(x, k + 1, x->base));
+    float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
+    KGCHK(run_head(x, k + 1, 0, at<float>(x->scr, x->s_tlog), k + 1, inv_t));
+    KGCHK(fetch_results(x, k + 1));
+    for (int i = 0; i <= k; i++) { x->targets[i] = x->h_tok[i]; target_tokens[i] = x->h_tok[i]; }
+    x->n_target_rows = k + 1;
+    *k_plus_1 = k + 1;
+    x->phase = Phase::VERIFIED;
+    return KG_OK;
+}
+
+int kg_accept(kg_ctx *x, const kg_params *p, int32_t *emitted, int *n_emitted)
+{
+    KGCHK(check_ready(x));
+    KGCHK(check_params(x, p));
+    if (!emitted || !n_emitted) return fail(x, KG_EINVAL, "NULL output");
+    if (x->phase != Phase::VERIFIED) return fail(x, KG_ESTATE, "accept needs a verified round");
+    if (p->mode != 0) return fail(x, KG_EINVAL, "sampling-mode acceptance is not built yet");
+    const int k = x->n_drafts;
+    int n = 0;
+    while (n < k && x->drafts[n] == x->targets[n]) n++;
+    for (int i = 0; i < n; i++) emitted[i] = x->drafts[i];
+    emitted[n] = x->targets[n];
+    *n_emitted = n + 1;
+    // rollback: caches are cut by length; the adapter saw f_0..f_{k-1} only
+    const int old = x->base;
+    x->base = old + n + 1;
+    x->adapter_len = old + std::min(n + 1, k);
+    x->lag = (n == k);
+    if (x->lag) {
+        HIPCHK(x, hipMemcpyAsync(Flag(x), Frow(x, k), (size_t)x->c.d_model * 4, hipMemcpyDeviceToDevice, x->stream));
+    }
+    x->pending = emitted[n];
+    x->n_drafts = 0; x->stopped = 0;
+    x->phase = Phase::READY;
+    return KG_OK;
+}
+
+int kg_generate(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n_prompt, int max_new, int32_t *out,
+                int *n_out, kg_stats *st)
+{
+    KGCHK(check_ready(x));
+    KGCHK(check_params(x, p));
+    if (!out || !n_out || max_new < 1) return fail(x, KG_EINVAL, "bad output arguments");
+    if (n_prompt + max_new + p->gamma + 1 > x->c.max_seq) return fail(x, KG_ENOSPC, "prompt + max_new + gamma + 1 exceeds max_seq");
+    kg_stats s;
+    memset(&s, 0, sizeof(s));
+    int32_t tok;
+    KGCHK(kg_prefill(x, p, prompt, n_prompt, &tok));
+    double t0 = now_s();
+    int n = 0;
+    out[n++] = tok;
+    while (n < max_new) {
+        double ta = now_s();
+        int stop = 0;
+        float conf;
+        while (!stop) { KGCHK(kg_draft_step(x, p, &tok, &conf, &stop)); s.draft_steps++; }
+        double tb = now_s();
+        int32_t tg[KG_MAX_ROWS], em[KG_MAX_ROWS];
+        int kp1 = 0, ne = 0;
+        KGCHK(kg_verify(x, p, tg, &kp1));
+        KGCHK(kg_accept(x, p, em, &ne));
+        double tc = now_s();
+        s.t_draft_s += tb - ta; s.t_verify_s += tc - tb;
+        s.rounds++; s.verify_calls++; s.drafted += kp1 - 1; s.accepted += ne - 1;
+        int room = max_new - n;
+        int take = ne < room ? ne : room;
+        s.s_hist[take]++;
+        for (int i = 0; i < take; i++) out[n++] = em[i];
+    }
+    s.emitted = n;
+    s.t_total_s = now_s() - t0;
+    *n_out = n;
+    if (st) *st = s;
+    return KG_OK;
+}
+
+int kg_plain_step(kg_ctx *x, const kg_params *p, int32_t token, int32_t *next_token)
+{
+    KGCHK(check_ready(x));
+    KGCHK(check_params(x, p));
+    if (!next_token) return fail(x, KG_EINVAL, "NULL output");
+    if (x->phase != Phase::READY && x->phase != Phase::PLAIN) return fail(x, KG_ESTATE, "plain_step needs a prefilled sequence");
+    if (token < 0 || token >= x->c.vocab) return fail(x, KG_EINVAL, "token out of range");
+    if (x->plain_len + 1 >= x->c.max_seq) return fail(x, KG_ENOSPC, "sequence would exceed max_seq");
+    const kg_config &c = x->c;
+    float *x0 = at<float>(x->scr, x->s_x0);
+    const int tok = token;
+    KGCHK(launch_pack_rows(x, &tok, nullptr, 1, at<const float>(x->arena, x->lw[0].g1), x0, x->scr + x->s_actX,
+                           at<float>(x->scr, x->s_ssq0)));
+    KGCHK(run_layers(x, 0, c.n_layers, 1, x->plain_len, x0, x0, at<const float>(x->arena, x->gfinal)));
+    float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
+    KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t));
+    KGCHK(fetch_results(x, 1));
+    x->plain_len++;
+    x->n_target_rows = 1;
+    x->phase = Phase::PLAIN;     // the adapter cache is no longer in step: draft calls are refused
+    *next_token = x->h_tok[0];
+    return KG_OK;
+}
+
+int kg_decode_plain(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n_prompt, int max_new, int32_t *out,
+                    int *n_out, kg_stats *st)
+{
+    KGCHK(check_ready(x));
+    KGCHK(check_params(x, p));
+    if (!out || !n_out || max_new < 1) return fail(x, KG_EINVAL, "bad output arguments");
+    if (n_prompt + max_new + 1 > x->c.max_seq) return fail(x, KG_ENOSPC, "prompt + max_new + 1 exceeds max_seq");
+    kg_stats s;
+    memset(&s, 0, sizeof(s));
+    int32_t tok;
+    KGCHK(kg_prefill(x, p, prompt, n_prompt, &tok));
+    double t0 = now_s();
+    int n = 0;
+    out[n++] = tok;
+    while (n < max_new) {
+        KGCHK(kg_plain_step(x, p, tok, &tok));
+        out[n++] = tok;
+        s.plain_steps++;
+    }
+    s.emitted = n;
+    s.t_total_s = now_s() - t0;
+    *n_out = n;
+    if (st) *st = s;
+    return KG_OK;
+}
+
+int kg_read_logits(kg_ctx *x, int which, int row, float *host_out)
+{
+    if (!x || !host_out) return KG_EINVAL;
+    if (!x->bound) return fail(x, KG_ESTATE, "not bound");
+    size_t off;
+    if (which == 0) {
+        if (row < 0 || row >= x->n_drafts) return fail(x, KG_EINVAL, "draft row %d outside 0..%d", row, x->n_drafts - 1);
+        off = x->s_dlog;
+    } else if (which == 1) {
+        if (row < 0 || row >= x->n_target_rows) return fail(x, KG_EINVAL, "target row %d outside 0..%d", row, x->n_target_rows - 1);
+        off = x->s_tlog;
+    } else return fail(x, KG_EINVAL, "which must be 0 or 1");
+    HIPCHK(x, hipMemcpyAsync(host_out, x->scr + off + (size_t)row * x->c.vocab * 4, (size_t)x->c.vocab * 4,
+                             hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    return KG_OK;
+}
+
+int kg_read_feature(kg_ctx *x, int row, float *host_out)
+{
+    if (!x || !host_out) return KG_EINVAL;
+    if (!x->bound) return fail(x, KG_ESTATE, "not bound");
+    if (row < -1 || row >= KG_ROWS) return fail(x, KG_EINVAL, "feature row out of range");
+    HIPCHK(x, hipMemcpyAsync(host_out, Frow(x, row), (size_t)x->c.d_model * 4, hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    return KG_OK;
+}
+
+int kg_read_kv(kg_ctx *x, int slot, int pos, float *k_host, float *v_host)
+{
+    if (!x || !k_host || !v_host) return KG_EINVAL;
+    if (!x->bound) return fail(x, KG_ESTATE, "not bound");
+    const kg_config &c = x->c;
+    if (slot < 0 || slot > c.n_layers || pos < 0 || pos >= c.max_seq) return fail(x, KG_EINVAL, "slot/pos out of range");
+    float *tmp = at<float>(x->scr, x->s_misc);
+    int n = c.d_model;
+    if (x->bf)
+        hipLaunchKernelGGL(kv_read_kernel<uint16_t>, dim3((n + 255) / 256), dim3(256), 0, x->stream, x->kv,
+                           at<const int>(x->scr, x->s_pt), slot, c.n_layers + 1, c.n_heads, c.head_dim,
+                           c.kv_page_tokens, x->logP, pos, tmp, tmp + n);
+    else
+        hipLaunchKernelGGL(kv_read_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, x->stream, x->kv,
+                           at<const int>(x->scr, x->s_pt), slot, c.n_layers + 1, c.n_heads, c.head_dim,
+                           c.kv_page_tokens, x->logP, pos, tmp, tmp + n);
+    KGCHK(check_launch(x, "kv_read"));
+    HIPCHK(x, hipMemcpyAsync(k_host, tmp, (size_t)n * 4, hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipMemcpyAsync(v_host, tmp + n, (size_t)n * 4, hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    return KG_OK;
+}
+
+int kg_get_state(const kg_ctx *x, int *base, int *adapter_len, int *lag, int *n_drafts)
+{
+    if (!x) return KG_EINVAL;
+    if (base) *base = x->base;
+    if (adapter_len) *adapter_len = x->adapter_len;
+    if (lag) *lag = x->lag;
+    if (n_drafts) *n_drafts = x->n_drafts;
+    return KG_OK;
+}
+
+const char *kg_last_error(const kg_ctx *x) { return x ? x->err : "NULL context"; }
+
+void kg_destroy(kg_ctx *x)
+{
+    if (!x) return;
+    if (x->h_tok) (void)hipHostFree(x->h_tok);
+    if (x->h_conf) (void)hipHostFree(x->h_conf);
+    delete x;
+}
+
+// ---- stand-alone projection ---------------------------------------------------------------------
+
+size_t kg_op_packed_bytes(int dtype, int N, int K) { return packed_bytes(dtype == 1, N, K); }
+size_t kg_op_work_bytes(int K) { return up(act_bytes(K)) ; }
+
+int kg_op_pack(int dtype, const void *src, int N, int K, void *packed, void *hip_stream)
+{
+    if (!src || !packed || N < 16 || N % 16 || K < 8 || K % 8 || (dtype != 0 && dtype != 1)) return KG_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (dtype == 1) {
+        int KS = (K + 31) / 32;
+        size_t total = (size_t)N * KS * 4;
+        hipLaunchKernelGGL(pack_w_bf16_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const uint16_t *)src, N, K, (u32x4_t *)packed, KS, 0, 0);
+    } else {
+        size_t total = (size_t)N * K;
+        hipLaunchKernelGGL(pack_w_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const float *)src, N, K, (float *)packed, 0, 0);
+    }
+    return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
+}
+
+int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, int M, float *yd, void *work,
+                 void *hip_stream)
+{
+    if (!packed || !xd || !yd || !work || N < 16 || N % 16 || K < 16 || K % 16 || M < 1 || M > KG_ROWS ||
+        (dtype != 0 && dtype != 1))
+        return KG_EINVAL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Tok8 tk;
+    memset(&tk, 0, sizeof(tk));
+    Epi e;
+    memset(&e, 0, sizeof(e));
+    e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = yd;
+    if (dtype == 1) {
+        if (hipMemsetAsync(work, 0, act_bytes(K), s) != hipSuccess) return KG_EHIP;
+        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, xd, K, M,
+                           (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
+        hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(256), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
+                           (const u32x4_t *)work, e);
+    } else {
+        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, xd, K, M,
+                           (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
+        hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, s, (const float *)packed, K, (const float *)work, e);
+    }
+    return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
+}
+
+} // extern "C"

@@ -1,0 +1,554 @@
+// Device code of libkangaroo: hand-written HIP kernels for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Every decode forward of Kangaroo (draft step of M^s = A o M^b[:l], verification by M^b[l:],
+// Sections 3.1-3.2 and Figure 2) has at most 8 rows, so each projection is a weight-streaming
+// product bounded by HBM bandwidth (Section 1).  The design here:
+//   * weights are re-tiled once at load time into 1 KB tiles of 16 rows x 32 k in exactly the
+//     register layout of the A operand of v_mfma_f32_16x16x32_bf16, so a wavefront streams
+//     contiguous memory with 16-byte loads straight into MFMA operands (no LDS, no conversion);
+//   * activations stay fp32; a row is split into bf16 hi + bf16 lo parts that occupy columns
+//     m and m+8 of the 16-column B operand, so one MFMA gives fp32-grade products for 8 rows;
+//   * the result for a row never depends on how many other rows are in the batch, which keeps
+//     verification bit-identical to one-token decoding (needed for token-exact losslessness);
+//   * RMSNorm is folded in: the producer's epilogue stores x*g (hi/lo) and per-tile sums of
+//     squares, the consumer's epilogue multiplies by rsqrt(mean square + eps).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+#define KG_ROWS 8
+
+enum { EPI_PLAIN = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+
+// What a projection kernel does with a finished 16-row tile y[16][8].
+struct Epi {
+    int kind;
+    int M;              // live rows (<= 8)
+    int N;              // output features of this projection
+    // RMSNorm scale of the projection's input rows: rsqrt(sum(ssq_in[t][m]) * inv_d + eps); null = 1
+    const float *ssq_in;
+    int nt_in;
+    float inv_d, eps;
+    // EPI_PLAIN: out[(m + row_shift)][n] = y * scale, rows with m + row_shift < 0 are dropped
+    float *out;
+    int row_shift;
+    // EPI_RESID: x = res[m][n] + y; xout[m][n] = x; act_out <- x * gain[n]; ssq_out[tile][m] = sum x^2
+    const float *res;
+    float *xout;
+    // EPI_RESID / EPI_SWIGLU: activation for the next projection (K index = n, or tile*8+i for SwiGLU)
+    void *act_out;
+    int act_K;
+    const float *gain;
+    float *ssq_out;
+};
+
+__device__ __forceinline__ uint16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Store activation value v of row m, feature k, for a consumer projection with K features.
+// BF: bf16 hi/lo parts in B-operand tile layout [k/32][lane = (k%32/8)*16 + col][k%8], col = m (hi), m+8 (lo).
+// else: plain float [m][K].
+template <bool BF>
+__device__ __forceinline__ void store_act(void *buf, int K, int m, int k, float v)
+{
+    if (BF) {
+        uint16_t hi = f2bf(v);
+        uint16_t lo = f2bf(v - bf2f(hi));
+        uint16_t *p = (uint16_t *)buf;
+        size_t base = ((size_t)(k >> 5) * 64 + ((k >> 3) & 3) * 16 + m) * 8 + (k & 7);
+        p[base] = hi;
+        p[base + 64] = lo;
+    } else {
+        ((float *)buf)[(size_t)m * K + k] = v;
+    }
+}
+
+// scale[m] = rsqrt(mean square of the input row + eps), from per-tile partial sums, fixed order.
+// Called by all 256 threads of a block; result valid after the next __syncthreads().
+__device__ __forceinline__ void compute_scale(const Epi &e, float *sc)
+{
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int m = wave; m < e.M; m += 4) {
+        float s = 0.f;
+        if (e.ssq_in) {
+            for (int i = lane; i < e.nt_in; i += 64) s += e.ssq_in[(size_t)i * KG_ROWS + m];
+            for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+            s = rsqrtf(s * e.inv_d + e.eps);
+        } else {
+            s = 1.f;
+        }
+        if (lane == 0) sc[m] = s;
+    }
+}
+
+// Epilogue on a finished tile: yt[16][8] in LDS (row in tile, batch row), all 256 threads call it.
+template <bool BF>
+__device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_ROWS], const float *sc,
+                                         float (*sq)[KG_ROWS])
+{
+    int t = threadIdx.x;
+    if (e.kind == EPI_PLAIN) {
+        if (t < 128) {
+            int row = t >> 3, m = t & 7;
+            int mo = m + e.row_shift;
+            if (m < e.M && mo >= 0) e.out[(size_t)mo * e.N + rt * 16 + row] = yt[row][m] * sc[m];
+        }
+    } else if (e.kind == EPI_RESID) {
+        if (t < 128) {
+            int row = t >> 3, m = t & 7;
+            float v = 0.f;
+            if (m < e.M) {
+                int n = rt * 16 + row;
+                v = e.res[(size_t)m * e.N + n] + yt[row][m];
+                e.xout[(size_t)m * e.N + n] = v;
+                if (e.act_out) store_act<BF>(e.act_out, e.act_K, m, n, e.gain ? v * e.gain[n] : v);
+            }
+            sq[row][m] = v * v;
+        }
+        if (e.ssq_out) {
+            __syncthreads();
+            if (t < KG_ROWS) {
+                float s = 0.f;
+                for (int r = 0; r < 16; r++) s += sq[r][t];
+                e.ssq_out[(size_t)rt * KG_ROWS + t] = s;
+            }
+        }
+    } else { // EPI_SWIGLU: tile rows (2i, 2i+1) = (gate, up) of feed-forward feature rt*8 + i
+        if (t < 64) {
+            int i = t >> 3, m = t & 7;
+            if (m < e.M) {
+                float g = yt[2 * i][m] * sc[m], u = yt[2 * i + 1][m] * sc[m];
+                float a = g / (1.f + __expf(-g)) * u;
+                store_act<BF>(e.act_out, e.act_K, m, rt * 8 + i, a);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Projection, bf16 weights: one block (4 waves) per 16-row tile; the waves split K; each wave
+// streams its 1 KB weight tiles with 16-byte non-temporal loads and issues one MFMA per tile.
+// W: tiles [rt][ks][64 lanes][8 bf16]; act: B-operand tiles [ks][64 lanes][8 bf16].
+__global__ __launch_bounds__(256) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS,
+                                                        const u32x4_t *__restrict__ act, Epi e)
+{
+    __shared__ float part[4][16][KG_ROWS];
+    __shared__ float yt[16][KG_ROWS];
+    __shared__ float sq[16][KG_ROWS];
+    __shared__ float sc[KG_ROWS];
+    const int rt = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int ks0 = (wave * KS) >> 2, ks1 = ((wave + 1) * KS) >> 2;
+    const u32x4_t *wp = W + ((size_t)rt * KS + ks0) * 64 + lane;
+    const u32x4_t *bp = act + (size_t)ks0 * 64 + lane;
+    const bool bact = (lane & 7) < e.M;
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    int n = ks1 - ks0;
+    constexpr int U = 8;
+    while (n >= U) {
+        u32x4_t a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) a[u] = __builtin_nontemporal_load(wp + u * 64);
+#pragma unroll
+        for (int u = 0; u < U; u++) b[u] = bact ? bp[u * 64] : zero;
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u]),
+                                                          __builtin_bit_cast(bf16x8_t, b[u]), acc, 0, 0, 0);
+        wp += U * 64;
+        bp += U * 64;
+        n -= U;
+    }
+    while (n > 0) {
+        u32x4_t a = __builtin_nontemporal_load(wp);
+        u32x4_t b = bact ? bp[0] : zero;
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                      __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
+        wp += 64;
+        bp += 64;
+        n--;
+    }
+    compute_scale(e, sc);
+    // D layout: lane holds column (lane & 15) and tile rows 4*(lane >> 4) + r.  Columns m and m+8
+    // are the hi and lo parts of batch row m: fold them.
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        float v = acc[r] + __shfl_xor(acc[r], 8);
+        if ((lane & 15) < 8) part[wave][4 * (lane >> 4) + r][lane & 7] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        int row = threadIdx.x >> 3, m = threadIdx.x & 7;
+        yt[row][m] = ((part[0][row][m] + part[1][row][m]) + part[2][row][m]) + part[3][row][m];
+    }
+    __syncthreads();
+    epilogue<true>(e, rt, yt, sc, sq);
+}
+
+// Projection, fp32 weights (row-major [N][K]) and fp32 activations [8][K]: 16 threads per row.
+// Only the small fp32 correctness configuration uses it.
+__global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__ W, int K,
+                                                       const float *__restrict__ act, Epi e)
+{
+    __shared__ float yt[16][KG_ROWS];
+    __shared__ float sq[16][KG_ROWS];
+    __shared__ float sc[KG_ROWS];
+    const int rt = blockIdx.x;
+    const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
+    const float *wr = W + (size_t)(rt * 16 + row) * K;
+    float acc[KG_ROWS];
+#pragma unroll
+    for (int m = 0; m < KG_ROWS; m++) acc[m] = 0.f;
+    for (int k = sub; k < K; k += 16) {
+        float w = wr[k];
+#pragma unroll
+        for (int m = 0; m < KG_ROWS; m++)
+            if (m < e.M) acc[m] = fmaf(w, act[(size_t)m * K + k], acc[m]);
+    }
+    compute_scale(e, sc);
+#pragma unroll
+    for (int m = 0; m < KG_ROWS; m++) {
+        float v = acc[m];
+        for (int o = 8; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+        if (sub == 0) yt[row][m] = v;
+    }
+    __syncthreads();
+    epilogue<false>(e, rt, yt, sc, sq);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rows -> activation for the first projection of a stack: x[m] = E[tok[m]] (emb != null) or the
+// given fp32 rows; writes xout (optional), act = x * gain (hi/lo), ssq[tile][m].  One block per
+// 16 features.
+struct Tok8 { int t[KG_ROWS]; };
+
+template <bool BF>
+__global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 tok, const float *rows, int d,
+                                                        int M, const float *gain, float *xout, void *act,
+                                                        float *ssq)
+{
+    __shared__ float sq[16][KG_ROWS];
+    int rt = blockIdx.x, row = threadIdx.x >> 3, m = threadIdx.x & 7;
+    int n = rt * 16 + row;
+    float v = 0.f;
+    if (m < M) {
+        if (emb) {
+            size_t idx = (size_t)tok.t[m] * d + n;
+            v = BF ? bf2f(((const uint16_t *)emb)[idx]) : ((const float *)emb)[idx];
+        } else {
+            v = rows[(size_t)m * d + n];
+        }
+        if (xout) xout[(size_t)m * d + n] = v;
+        store_act<BF>(act, d, m, n, gain ? v * gain[n] : v);
+    }
+    sq[row][m] = v * v;
+    __syncthreads();
+    if (threadIdx.x < KG_ROWS && ssq) {
+        float s = 0.f;
+        for (int r = 0; r < 16; r++) s += sq[r][threadIdx.x];
+        ssq[(size_t)rt * KG_ROWS + threadIdx.x] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight re-tiling.  Destination row of source row r: mode 0: row_off + r; mode 1 (gate): 16*(r/8)
+// + 2*(r%8); mode 2 (up): the same + 1, so a tile holds 8 (gate, up) pairs.
+__device__ __forceinline__ int map_row(int r, int row_off, int mode)
+{
+    return mode == 0 ? row_off + r : 16 * (r >> 3) + 2 * (r & 7) + (mode - 1);
+}
+
+__global__ void pack_w_bf16_kernel(const uint16_t *src, int rows, int K, u32x4_t *dst, int KS, int row_off,
+                                   int mode)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t total = (size_t)rows * KS * 4;
+    if (i >= total) return;
+    int g = (int)(i & 3);
+    int ks = (int)((i >> 2) % KS);
+    int r = (int)((i >> 2) / KS);
+    int k0 = ks * 32 + g * 8;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (k0 + 8 <= K) v = *(const u32x4_t *)(src + (size_t)r * K + k0);
+    int R = map_row(r, row_off, mode);
+    dst[((size_t)(R >> 4) * KS + ks) * 64 + g * 16 + (R & 15)] = v;
+}
+
+__global__ void pack_w_f32_kernel(const float *src, int rows, int K, float *dst, int row_off, int mode)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)rows * K) return;
+    int r = (int)(i / K), k = (int)(i % K);
+    dst[(size_t)map_row(r, row_off, mode) * K + k] = src[i];
+}
+
+__global__ void gain_to_f32_kernel(const void *src, int bf, int n, float *dst)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = bf ? bf2f(((const uint16_t *)src)[i]) : ((const float *)src)[i];
+}
+
+// cos/sin table of the rotary embedding, angle = pos * inv_freq[i] evaluated in double.
+__global__ void rope_table_kernel(float2 *tab, int max_seq, int half, const double *inv_freq)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= max_seq * half) return;
+    double a = (double)(i / half) * inv_freq[i % half];
+    tab[i] = make_float2((float)cos(a), (float)sin(a));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode attention over a paged KV cache for up to 8 query rows at positions pos0..pos0+M-1.
+// grid = (heads, pages in use); block = 256.  A block handles one head and one page of P
+// positions: it rotates q (and k), appends the new k/v rows that fall in its page, computes
+// scores, a page-local softmax and P.V, and stores an unnormalised partial.  The last block to
+// finish for a head merges the partials in page order (so results do not depend on arrival
+// order, nor on how many rows or trailing pages the launch had).
+struct AttnArgs {
+    const float *qkv;   // [M][3d]: q | k | v, already RMS-scaled projections
+    int d, H, M, pos0, P, logP;
+    const int *page_table;
+    void *kv;           // pool: [phys page][slot][head][K|V][P][hd]
+    int slot, n_slots;
+    const float2 *rope; // [max_seq][hd/2]
+    float *opart;       // [H][S][8][hd]
+    float *mxs, *sms;   // [H][S][8]
+    int *cnt;           // [H], zero between launches
+    int S;              // pages covered by this launch = ceil((pos0+M)/P)
+    void *act_out;      // attention output as activation for the output projection (K = d)
+    int append_only;    // 1: only append k/v (prefill of the adapter cache)
+};
+
+template <typename T> __device__ __forceinline__ float kv_ld(const T *p);
+template <> __device__ __forceinline__ float kv_ld<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float kv_ld<uint16_t>(const uint16_t *p) { return bf2f(*p); }
+template <typename T> __device__ __forceinline__ void kv_st(T *p, float v);
+template <> __device__ __forceinline__ void kv_st<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void kv_st<uint16_t>(uint16_t *p, float v) { *p = f2bf(v); }
+
+template <typename T> __device__ __forceinline__ void kv_ld8(const T *p, float *o);
+template <> __device__ __forceinline__ void kv_ld8<float>(const float *p, float *o)
+{
+    float4 a = *(const float4 *)p, b = *(const float4 *)(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+template <> __device__ __forceinline__ void kv_ld8<uint16_t>(const uint16_t *p, float *o)
+{
+    u32x4_t a = *(const u32x4_t *)p;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        o[2 * i] = __uint_as_float(a[i] << 16);
+        o[2 * i + 1] = __uint_as_float(a[i] & 0xFFFF0000u);
+    }
+}
+
+template <typename T, int HD, bool BF>
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
+{
+    constexpr int LPR = HD / 8;        // lanes per cache row (8 elements each)
+    constexpr int NG = 256 / LPR;      // position groups in the block
+    constexpr int GPW = 64 / LPR;      // position groups per wave
+    __shared__ float qs[KG_ROWS][HD];
+    __shared__ float sc[KG_ROWS][128];
+    __shared__ float wpart[4][KG_ROWS][HD];
+    __shared__ float mx_s[KG_ROWS], sm_s[KG_ROWS];
+    __shared__ int last_flag;
+    const int h = blockIdx.x, s = blockIdx.y, t = threadIdx.x;
+    const int wave = t >> 6, lane = t & 63;
+    const int P = a.P, M = a.M, d = a.d;
+    const int p_begin = s << a.logP;
+    const int n_valid = min(P, a.pos0 + M - p_begin);      // positions of this page that hold data
+    T *Kp = (T *)a.kv + ((((size_t)a.page_table[s] * a.n_slots + a.slot) * a.H + h) * 2) * (size_t)P * HD;
+    T *Vp = Kp + (size_t)P * HD;
+    const float qscale = rsqrtf((float)HD);
+
+    // rotate q into LDS; rotate and append the new k, v rows that live in this page
+    for (int i = t; i < M * (HD / 2); i += 256) {
+        int m = i / (HD / 2), j = i % (HD / 2);
+        int pos = a.pos0 + m;
+        float2 cs = a.rope[(size_t)pos * (HD / 2) + j];
+        const float *q = a.qkv + (size_t)m * 3 * d + h * HD;
+        float x0 = q[j], x1 = q[j + HD / 2];
+        qs[m][j] = (x0 * cs.x - x1 * cs.y) * qscale;
+        qs[m][j + HD / 2] = (x1 * cs.x + x0 * cs.y) * qscale;
+        if (pos >= p_begin && pos < p_begin + P) {
+            const float *k = q + d, *v = q + 2 * d;
+            float k0 = k[j], k1 = k[j + HD / 2];
+            int pl = pos - p_begin;
+            kv_st<T>(Kp + (size_t)pl * HD + j, k0 * cs.x - k1 * cs.y);
+            kv_st<T>(Kp + (size_t)pl * HD + j + HD / 2, k1 * cs.x + k0 * cs.y);
+            kv_st<T>(Vp + (size_t)pl * HD + j, v[j]);
+            kv_st<T>(Vp + (size_t)pl * HD + j + HD / 2, v[j + HD / 2]);
+        }
+    }
+    if (a.append_only) return;
+    __syncthreads();
+
+    const int c = t % LPR;             // 8-element chunk of the head dimension
+    const int grp = t / LPR;           // position group: handles positions grp, grp+NG, ...
+    // scores
+    for (int pl = grp; pl < P; pl += NG) {
+        float part[KG_ROWS];
+#pragma unroll
+        for (int m = 0; m < KG_ROWS; m++) part[m] = 0.f;
+        if (pl < n_valid) {
+            float kk[8];
+            kv_ld8<T>(Kp + (size_t)pl * HD + c * 8, kk);
+#pragma unroll
+            for (int m = 0; m < KG_ROWS; m++)
+                if (m < M) {
+#pragma unroll
+                    for (int i = 0; i < 8; i++) part[m] = fmaf(kk[i], qs[m][c * 8 + i], part[m]);
+                }
+        }
+#pragma unroll
+        for (int m = 0; m < KG_ROWS; m++) {
+            float v = part[m];
+#pragma unroll
+            for (int o = LPR / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+            if (c == 0 && m < M) sc[m][pl] = (pl < n_valid && p_begin + pl <= a.pos0 + m) ? v : -INFINITY;
+        }
+    }
+    __syncthreads();
+    // page-local softmax statistics: wave w handles rows w, w+4
+    for (int m = wave; m < M; m += 4) {
+        float mx = -INFINITY;
+        for (int pl = lane; pl < P; pl += 64) mx = fmaxf(mx, sc[m][pl]);
+        for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float sum = 0.f;
+        for (int pl = lane; pl < P; pl += 64) {
+            float pr = (mx == -INFINITY) ? 0.f : __expf(sc[m][pl] - mx);
+            sc[m][pl] = pr;
+            sum += pr;
+        }
+        for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+        if (lane == 0) { mx_s[m] = mx; sm_s[m] = sum; }
+    }
+    __syncthreads();
+    // P.V: thread accumulates its chunk over its positions, then fixed-order reduction
+    float acc[KG_ROWS][8];
+#pragma unroll
+    for (int m = 0; m < KG_ROWS; m++)
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[m][i] = 0.f;
+    for (int pl = grp; pl < n_valid; pl += NG) {
+        float vv[8];
+        kv_ld8<T>(Vp + (size_t)pl * HD + c * 8, vv);
+#pragma unroll
+        for (int m = 0; m < KG_ROWS; m++)
+            if (m < M) {
+                float pr = sc[m][pl];
+#pragma unroll
+                for (int i = 0; i < 8; i++) acc[m][i] = fmaf(pr, vv[i], acc[m][i]);
+            }
+    }
+#pragma unroll
+    for (int m = 0; m < KG_ROWS; m++)
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            float v = acc[m][i];
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o);
+            if ((lane / LPR) == 0 && m < M) wpart[wave][m][c * 8 + i] = v;
+        }
+    __syncthreads();
+    float *op = a.opart + ((size_t)h * a.S + s) * KG_ROWS * HD;
+    for (int i = t; i < M * HD; i += 256) {
+        int m = i / HD, e = i % HD;
+        op[m * HD + e] = ((wpart[0][m][e] + wpart[1][m][e]) + wpart[2][m][e]) + wpart[3][m][e];
+    }
+    if (t < M) {
+        a.mxs[((size_t)h * a.S + s) * KG_ROWS + t] = mx_s[t];
+        a.sms[((size_t)h * a.S + s) * KG_ROWS + t] = sm_s[t];
+    }
+    // last block of this head merges
+    __threadfence();
+    __syncthreads();
+    if (t == 0) {
+        int old = atomicAdd(&a.cnt[h], 1);
+        last_flag = (old == a.S - 1);
+    }
+    __syncthreads();
+    if (!last_flag) return;
+    __threadfence();
+    for (int i = t; i < M * HD; i += 256) {
+        int m = i / HD, e = i % HD;
+        float gm = -INFINITY;
+        for (int ss = 0; ss < a.S; ss++)
+            gm = fmaxf(gm, __builtin_nontemporal_load(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]));
+        float num = 0.f, den = 0.f;
+        for (int ss = 0; ss < a.S; ss++) {
+            float mxv = __builtin_nontemporal_load(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]);
+            if (mxv == -INFINITY) continue;
+            float w = __expf(mxv - gm);
+            num += w * __builtin_nontemporal_load(&a.opart[(((size_t)h * a.S + ss) * KG_ROWS + m) * HD + e]);
+            den += w * __builtin_nontemporal_load(&a.sms[((size_t)h * a.S + ss) * KG_ROWS + m]);
+        }
+        store_act<BF>(a.act_out, d, m, h * HD + e, num / den);
+    }
+    if (t == 0) a.cnt[h] = 0;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row statistics of logits: arg-max (lowest index among equal maxima), top-1 probability of
+// softmax(z / T) = 1 / sum exp((z - max) / T).  One block per row.
+__global__ __launch_bounds__(1024) void head_reduce_kernel(const float *logits, int V, int M, float inv_temp,
+                                                           int *tok_out, float *conf_out)
+{
+    __shared__ float bv[16];
+    __shared__ int bi[16];
+    __shared__ float bs[16];
+    int m = blockIdx.x, t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const float *z = logits + (size_t)m * V;
+    float best = -INFINITY;
+    int idx = 0x7FFFFFFF;
+    for (int i = t; i < V; i += 1024) {
+        float v = z[i];
+        if (v > best) { best = v; idx = i; }
+    }
+    for (int o = 32; o >= 1; o >>= 1) {
+        float ov = __shfl_xor(best, o);
+        int oi = __shfl_xor(idx, o);
+        if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+    }
+    if (lane == 0) { bv[wave] = best; bi[wave] = idx; }
+    __syncthreads();
+    best = bv[0]; idx = bi[0];
+    for (int w = 1; w < 16; w++)
+        if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
+    float sum = 0.f;
+    for (int i = t; i < V; i += 1024) sum += __expf((z[i] - best) * inv_temp);
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) bs[wave] = sum;
+    __syncthreads();
+    if (t == 0) {
+        float s = 0.f;
+        for (int w = 0; w < 16; w++) s += bs[w];
+        tok_out[m] = idx;
+        conf_out[m] = 1.f / s;
+    }
+}
+
+// Copy cached k and v rows of one position, widened to float (test / debug access).
+template <typename T>
+__global__ void kv_read_kernel(const void *kv, const int *page_table, int slot, int n_slots, int H, int hd,
+                               int P, int logP, int pos, float *k_out, float *v_out)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= H * hd) return;
+    int h = i / hd, e = i % hd;
+    const T *Kp = (const T *)kv + ((((size_t)page_table[pos >> logP] * n_slots + slot) * H + h) * 2) * (size_t)P * hd;
+    int pl = pos & (P - 1);
+    k_out[i] = kv_ld<T>(Kp + (size_t)pl * hd + e);
+    v_out[i] = kv_ld<T>(Kp + (size_t)P * hd + (size_t)pl * hd + e);
+}

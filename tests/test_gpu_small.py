@@ -1,0 +1,143 @@
+"""GPU parity on the small configurations (fp32 toy = BASELINE config 1; bf16 variants of it):
+the HIP path through the C ABI against the CPU oracle, element by element on logits and
+features, token by token (near-ties adjudicated by the oracle's logits), plus the properties
+that hold on the GPU alone: greedy Kangaroo == plain decoding, generate == stepwise calls,
+rollback == fresh prefill, page order irrelevant."""
+import ctypes
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2404_18911_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # max-abs logit tolerance (benchmark spec)
+
+
+def _oracle(shape, W, max_seq):
+    from oracle import kangaroo_oracle as O
+    return O.OracleModel(shape, W, max_seq)
+
+
+def _linear_case(dtype, N, K, M, seed):
+    from oracle import kangaroo_oracle as O
+    from paper_2404_18911_amd import binding as B
+    rng = np.random.default_rng(seed)
+    Wf = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    Wh = I.f32_to_bf16_bits(Wf) if dtype == "bf16" else Wf
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    y = B.op_linear(Wh, x)
+    x64 = x.astype(np.float64)
+    ref = np.empty((M, N))
+    dp = ctypes.POINTER(ctypes.c_double)
+    O.lib().ko_matvec(Wh.ctypes.data, 1 if dtype == "bf16" else 0, N, K, x64.ctypes.data_as(dp), M,
+                      ref.ctypes.data_as(dp))
+    Wabs = np.abs(I.bf16_bits_to_f32(Wh) if dtype == "bf16" else Wf).astype(np.float64)
+    bound = (np.abs(x64) @ Wabs.T) * 2.0 ** -15 + 1e-7     # hi+lo activation split keeps ~16 bits; fp32 sums
+    assert np.all(np.abs(y - ref) <= bound), float(np.max(np.abs(y - ref) / bound))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("N,K,M", [(16, 32, 1), (64, 64, 3), (1024, 688, 8), (4096, 4096, 7), (2000 * 16, 512, 2),
+                                   (1376, 11008, 5)])
+def test_projection_kernel_matches_oracle_matvec(dtype, N, K, M):
+    """Weight-streaming product vs the oracle's fp64 loop: several tiles, ragged K (688 is not a
+    multiple of 32), every row count class."""
+    _linear_case(dtype, N, K, M, seed=N + K + M)
+
+
+@pytest.mark.parametrize("name,gamma,eta,alpha,hs,page", [
+    ("toy", 6, 0.6, 0.1, 1.0, 128),          # BASELINE config 1
+    ("toy", 6, 0.6, 0.05, 25.0, 16),         # sharpened head: draft length varies; several KV pages
+    ("toy", 6, 0.0, 0.05, 25.0, 32),         # fixed-step drafting (eta = 0): 7-row verification
+    ("toy_bf16", 6, 0.6, 0.05, 25.0, 16),
+    ("small_bf16", 5, 0.6, 0.05, 16.0, 64),  # head_dim 128, exit layer 2
+])
+def test_stepwise_kangaroo_follows_oracle(name, gamma, eta, alpha, hs, page):
+    from tests import parity as P
+    shape = I.SHAPES[name]
+    W = I.gen_weights(shape, seed=1, alpha=alpha, head_scale=hs)
+    prompt = I.gen_prompt(shape.vocab, 16)
+    kg = P.load_model(shape, W, 96, gamma_max=6, kv_page_tokens=page)
+    fol = P.Follow(TOL[shape.dtype])
+    out, rounds = P.follow_kangaroo(kg, _oracle(shape, W, 96), prompt, 32, gamma, eta, fol)
+    assert all(1 <= k <= gamma and 0 <= n <= k for k, n in rounds)
+    if eta == 0.0:
+        assert all(k == gamma for k, _ in rounds)
+    if hs > 1.0 and eta > 0:
+        assert len({k for k, _ in rounds}) > 1          # the stop rule really fired at different lengths
+    assert any(n == k for k, n in rounds) and any(n < k for k, n in rounds)
+    print(f"{name}: max logit err {fol.max_logit_err:.3e}, near-tie exceptions {fol.exceptions}/{fol.decisions}")
+    kg.close()
+
+
+@pytest.mark.parametrize("name", ["toy", "toy_bf16"])
+def test_plain_decoding_follows_oracle(name):
+    from tests import parity as P
+    shape = I.SHAPES[name]
+    W = I.gen_weights(shape, seed=1, alpha=0.1)
+    kg = P.load_model(shape, W, 64, kv_page_tokens=16)
+    fol = P.Follow(TOL[shape.dtype])
+    P.follow_plain(kg, _oracle(shape, W, 64), I.gen_prompt(shape.vocab, 16), 32, fol)
+    kg.close()
+
+
+@pytest.mark.parametrize("name,exit_layer", [("toy", 1), ("toy", 4), ("toy_bf16", 2), ("small_bf16", 2)])
+@pytest.mark.parametrize("gamma,eta,hs", [(6, 0.6, 1.0), (6, 0.6, 25.0), (6, 0.0, 25.0), (3, 0.3, 25.0), (1, 0.6, 25.0)])
+def test_gpu_kangaroo_is_token_identical_to_gpu_plain_decoding(name, exit_layer, gamma, eta, hs):
+    """Losslessness on the GPU itself, exact: verification rows are bit-identical to one-token
+    decoding, so no tie can flip.  generate must also equal the stepwise calls."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = dataclasses.replace(I.SHAPES[name], exit_layer=exit_layer)
+    W = I.gen_weights(shape, seed=3, alpha=0.05, head_scale=hs)
+    prompt = I.gen_prompt(shape.vocab, 19, seed=4)
+    kg = P.load_model(shape, W, 128, kv_page_tokens=32)
+    p, _ = B.make_params(eta=eta, gamma=gamma)
+    plain, _ = kg.decode_plain(p, prompt, 64)
+    out, st = kg.generate(p, prompt, 64)
+    assert out == plain
+    assert st.emitted == 64 and sum(s * c for s, c in enumerate(st.s_hist)) == 63
+    assert all(st.s_hist[s] == 0 for s in range(gamma + 2, 9)) and st.s_hist[0] == 0
+    # stepwise
+    t = [kg.prefill(p, prompt)]
+    while len(t) < 64:
+        while not kg.draft_step(p)[2]:
+            pass
+        kg.verify(p)
+        t += kg.accept(p)
+    assert t[:64] == out
+    kg.close()
+
+
+def test_rollback_equals_fresh_prefill_and_page_order_is_irrelevant():
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["toy_bf16"]
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=25.0)
+    prompt = list(I.gen_prompt(shape.vocab, 13))
+    p, _ = B.make_params(eta=0.6, gamma=4)
+    kg = P.load_model(shape, W, 128, kv_page_tokens=16)
+    ref, _ = kg.generate(p, prompt, 40)
+    kg.set_page_order(np.random.default_rng(0).permutation(8))
+    seq = prompt + [kg.prefill(p, prompt)]
+    fresh = P.load_model(shape, W, 128, kv_page_tokens=16)
+    for _ in range(8):
+        while not kg.draft_step(p)[2]:
+            pass
+        kg.verify(p)
+        seq += kg.accept(p)
+        base, alen, lag, _ = kg.state()
+        assert base == len(seq) - 1
+        fresh.prefill(p, seq[:base])
+        for slot in range(shape.n_layers + 1):
+            upto = alen if slot == shape.n_layers else base
+            for pos in range(upto):
+                a, b = kg.read_kv(slot, pos), fresh.read_kv(slot, pos)
+                np.testing.assert_array_equal(a[0], b[0])
+                np.testing.assert_array_equal(a[1], b[1])
+    assert seq[len(prompt):] == ref[: len(seq) - len(prompt)]
+    kg.close()
+    fresh.close()
