@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the Kangaroo decode loop on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic request of the Vicuna-7B-shaped
+configuration: prefill of a 256-token prompt, then draft-and-verify rounds until 256 new tokens
+are out (eta = 0.6, gamma = 6, greedy).  `value` is new tokens per second of the decode loop
+(prefill excluded, host synchronisations included), summed over the timed steps; `ms_per_step`
+is the wall-clock of a whole step, prefill included.  Weights are random-init (see
+paper_2404_18911_amd/inputs.py) and are resident in HBM before the timed region.
+
+Prints ONE JSON line.  Extra legs (not part of `value`): plain decoding, eta = 0, the second
+alpha of the configuration, a per-launch-timed pass for the roofline figure, and the CPU oracle
+timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def forward_bytes(shape):
+    """Algorithmic HBM bytes (weights once) of each forward type."""
+    b = shape.bytes_per_weight()
+    d, f, V = shape.d_model, shape.d_ffn, shape.vocab
+    layer = (4 * d * d + 3 * d * f) * b
+    head = d * V * b
+    adapter = 4 * d * d * b
+    l, L = shape.exit_layer, shape.n_layers
+    return dict(layer=layer, head=head, adapter=adapter, plain=L * layer + head, draft=l * layer + adapter + head,
+                shallow=l * layer, verify=(L - l) * layer + head)
+
+
+def reload_alpha(kg, shape, alpha, threads):
+    """Re-draw the tensors that depend on alpha (deep o_proj / down_proj, adapter output projection)."""
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2404_18911_amd import inputs as I
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        for kind, layer, rows, cols in I.tensor_list(shape):
+            if (kind in (I.KIND_WO, I.KIND_WD) and layer >= shape.exit_layer) or kind == I.KIND_A_WO:
+                kg.load_tensor(kind, layer, I.gen_tensor(shape, kind, layer, rows, cols, seed=1, alpha=alpha, pool=pool))
+
+
+def cpu_baseline(shape, W, prompt, threads, n_prompt=32, n_new=8):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    from oracle import kangaroo_oracle as O
+    os.environ.setdefault("OMP_NUM_THREADS", str(threads))
+    m = O.OracleModel(shape, W, n_prompt + n_new + 16)
+    dec = O.KangarooDecoder(m, gamma=6, eta=0.6)
+    out = [dec.prefill(list(prompt[:n_prompt]))]
+    t0 = time.time()
+    while len(out) < n_new + 1:
+        out += dec.round()
+    dt = time.time() - t0
+    n = len(out) - 1
+    return {"value": n / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"same 7B-shaped weights, first {n_prompt} prompt tokens, {n} new tokens of Kangaroo "
+                      f"decoding (eta 0.6, gamma 6), decode loop only, fp64 C + OpenMP"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--shape", default="7b")
+    ap.add_argument("--prompt", type=int, default=256)
+    ap.add_argument("--new", type=int, default=256)
+    ap.add_argument("--alpha", type=float, default=0.05)
+    ap.add_argument("--alpha2", type=float, default=0.2)
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2404_18911_amd import binding as B
+    from paper_2404_18911_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    threads = min(16, os.cpu_count() or 8)
+    shape = I.SHAPES[args.shape]
+    gamma, eta = 6, 0.6
+    t0 = time.time()
+    keep_host = not args.no_cpu
+    W = {}
+    kg = B.Kangaroo(shape, args.prompt + args.new + gamma + 2, gamma_max=gamma, kv_page_tokens=128)
+    for kind, layer, a in I.iter_weights(shape, seed=1, alpha=args.alpha, threads=threads):
+        kg.load_tensor(kind, layer, a)
+        if keep_host:
+            W[(kind, layer)] = a
+    log(f"[bench] weights generated and loaded in {time.time() - t0:.1f}s")
+    prompt = I.gen_prompt(shape.vocab, args.prompt)
+    p, _ = B.make_params(eta=eta, gamma=gamma)
+
+    def sync():
+        torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        kg.generate(p, prompt, args.new)
+    sync()
+    t_start = time.time()
+    toks = dec_s = 0.0
+    stats = None
+    for _ in range(args.steps):
+        out, stats = kg.generate(p, prompt, args.new)
+        toks += len(out) - 1
+        dec_s += stats.t_total_s
+    sync()
+    wall = time.time() - t_start
+    value = toks / dec_s
+    fb = forward_bytes(shape)
+    rounds = stats.rounds
+    acc_rate = stats.accepted / max(1, stats.drafted)
+    res = {
+        "metric": "Kangaroo decode tokens/s (bs=1, 7B shape) + HBM GB/s per forward vs roofline",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * wall / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"configs[1]: Vicuna-7B-shaped decoder, bf16, exit l={shape.exit_layer}, "
+                               f"alpha={args.alpha}, eta={eta}, gamma_max={gamma}, greedy, prompt {args.prompt} "
+                               f"random ids, generate {args.new}" if args.shape == "7b" else args.shape,
+                   "alpha": args.alpha, "eta": eta, "gamma": gamma, "prompt": args.prompt, "new": args.new,
+                   "rounds": rounds, "drafted": stats.drafted, "accepted": stats.accepted,
+                   "acceptance_rate": acc_rate, "compression_rate": (args.new - 1) / rounds,
+                   "mean_draft_len": stats.drafted / rounds},
+    }
+
+    if not args.no_extras:
+        # per-forward device time and the dominant kernel's bandwidth, from a per-launch-timed pass
+        kg.set_profiling(True)
+        kg.generate(p, prompt, args.new)
+        pr = kg.get_profile()
+        kg.set_profiling(False)
+        g_bytes, g_s, g_n = pr.bytes[0], pr.seconds[0], pr.launches[0]
+        ach = g_bytes / g_s / 1e9
+        res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "kernel": "gemv_bf16_kernel", "launches": int(g_n),
+                           "avg_launch_us": 1e6 * g_s / g_n, "avg_launch_bytes": g_bytes / g_n}
+        res["device_time_share"] = {"projections": pr.seconds[0], "attention": pr.seconds[1], "other": pr.seconds[2]}
+        # plain decoding (the baseline speedups are measured against) and eta = 0
+        out_p, st_p = kg.decode_plain(p, prompt, args.new)
+        res["plain_tokens_per_s"] = (len(out_p) - 1) / st_p.t_total_s
+        res["speedup_vs_plain"] = value / res["plain_tokens_per_s"]
+        res["plain_forward_GBs"] = fb["plain"] * st_p.plain_steps / st_p.t_total_s / 1e9
+        res["lossless_on_gpu"] = bool(out_p == out)
+        # whole-forward bandwidth of the Kangaroo loop: bytes of all forwards / decode wall-clock
+        kang_bytes = stats.draft_steps * fb["draft"] + stats.verify_calls * (fb["shallow"] + fb["verify"])
+        res["kangaroo_forward_GBs"] = kang_bytes / stats.t_total_s / 1e9
+        res["kangaroo_forward_frac_of_peak"] = res["kangaroo_forward_GBs"] / HBM_PEAK_GBS
+        p0, _ = B.make_params(eta=0.0, gamma=gamma)
+        out0, st0 = kg.generate(p0, prompt, args.new)
+        res["eta0"] = {"tokens_per_s": (len(out0) - 1) / st0.t_total_s, "rounds": st0.rounds,
+                       "acceptance_rate": st0.accepted / max(1, st0.drafted),
+                       "compression_rate": (args.new - 1) / st0.rounds, "lossless_on_gpu": bool(out0 == out_p)}
+        if args.alpha2 > 0:
+            reload_alpha(kg, shape, args.alpha2, threads)
+            out2, st2 = kg.generate(p, prompt, args.new)
+            res["alpha2"] = {"alpha": args.alpha2, "tokens_per_s": (len(out2) - 1) / st2.t_total_s,
+                             "acceptance_rate": st2.accepted / max(1, st2.drafted),
+                             "compression_rate": (args.new - 1) / st2.rounds}
+    kg.close()
+    if not args.no_cpu:
+        del kg
+        torch.cuda.empty_cache()
+        res["cpu_baseline"] = cpu_baseline(shape, W, prompt, threads)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

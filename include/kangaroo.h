@@ -46,7 +46,8 @@ typedef struct kg_ctx kg_ctx; /* opaque */
 typedef struct kg_config {
     int n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
     int exit_layer;
-    int dtype;          /* storage type of weights and KV cache: 0 = float32, 1 = bfloat16 */
+    int dtype;          /* storage type of the weights: 0 = float32, 1 = bfloat16 */
+    int kv_dtype;       /* storage type of the KV cache (rotated keys, values): 0 = float32, 1 = bfloat16 */
     float rms_eps, rope_theta;
     int max_seq;        /* token capacity of the caches: prompt + generated + gamma_max + 1 */
     int gamma_max;      /* largest draft length gamma that will be used (<= KG_MAX_ROWS - 1) */
@@ -167,6 +168,20 @@ int kg_read_kv(kg_ctx *ctx, int slot, int pos, float *k_host, float *v_host);
 
 /* Sequence state: committed tokens (`base`), tokens in the adapter's cache, lag flag, drafts so far. */
 int kg_get_state(const kg_ctx *ctx, int *base, int *adapter_len, int *lag, int *n_drafts);
+
+/* Per-kernel-class device timing, for bandwidth accounting (Section 1: decoding is bound by
+ * reading the weights).  With profiling on, a pair of HIP events brackets every kernel launch of
+ * the context's stream; elapsed times are summed when a call synchronises.  Classes: 0 = the
+ * weight-streaming projections (all linear layers and the LM head), 1 = attention, 2 = the rest.
+ * bytes[] is the algorithmic traffic of the launches: weight bytes for class 0, KV bytes read for
+ * class 1.  kg_set_profiling resets the sums. */
+typedef struct kg_profile {
+    long long launches[3];
+    double seconds[3];
+    double bytes[3];
+} kg_profile;
+int kg_set_profiling(kg_ctx *ctx, int on);
+int kg_get_profile(kg_ctx *ctx, kg_profile *out);
 
 /* Drop the sequence state, keep bindings and weights. */
 int kg_reset(kg_ctx *ctx);

@@ -57,7 +57,7 @@ def build(force: bool = False) -> str:
 
 class _Cfg(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn",
-                                            "vocab", "exit_layer", "wdtype", "max_seq")] + \
+                                            "vocab", "exit_layer", "wdtype", "max_seq", "kv_bf16")] + \
                [("rms_eps", ctypes.c_double), ("rope_theta", ctypes.c_double)]
 
 
@@ -110,7 +110,8 @@ class OracleModel:
         for a in weights.values():
             assert a.flags["C_CONTIGUOUS"] and a.dtype == (np.float32 if wd == 0 else np.uint16)
         cfg = _Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
-                   shape.exit_layer, wd, max_seq, shape.rms_eps, shape.rope_theta)
+                   shape.exit_layer, wd, max_seq, 1 if getattr(shape, "kv_dtype", shape.dtype) == "bf16" else 0,
+                   shape.rms_eps, shape.rope_theta)
         w = _W()
 
         def ptr(kind, layer=-1):

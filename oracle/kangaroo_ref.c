@@ -14,6 +14,11 @@
  *   - the adapter A of Section 3.1 / Figure 2 / Table 2 row "Kangaroo": input RMSNorm, one
  *     multi-head attention (its own key/value cache), residual, last RMSNorm, shared LM head.
  *
+ * The key/value cache is a storage format of the configuration, like the weights' type: the
+ * bf16 configurations budget 2 bytes per cached element (16 KB per token and layer at d = 4096),
+ * so with kv_bf16 set the cache holds rotated keys and values rounded to bfloat16 and attention
+ * reads those; with it clear the cache is exact.
+ *
  * Readings where the paper is silent: rotate-half RoPE pairing (i, i+hd/2), base theta, no
  * biases, residual connection around the adapter's attention, early feature = residual stream
  * after block l-1.  The decode loops (plain, draft-and-verify, acceptance) live in
@@ -32,6 +37,7 @@ typedef struct {
     int exit_layer;
     int wdtype;            /* 0 = float32, 1 = bfloat16 bit patterns */
     int max_seq;
+    int kv_bf16;           /* 1: the cache stores rotated keys and values rounded to bfloat16 */
     double rms_eps, rope_theta;
 } ko_config;
 
@@ -55,6 +61,18 @@ static inline double wget(const void *p, int wdtype, size_t i)
     if (wdtype == 0) return (double)((const float *)p)[i];
     uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 16;
     float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* value as a bfloat16 cache would hold it: to float (nearest), then to 8 significant bits (nearest even) */
+static inline double round_bf16(double x)
+{
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
     memcpy(&f, &u, 4);
     return (double)f;
 }
@@ -183,6 +201,11 @@ static void attn_sublayer(ko_model *mo, int slot, const void *g, const void *wq,
             ko_rope(q + (size_t)m * d + h * hd, hd, pos, c->rope_theta);
             ko_rope(k + (size_t)m * d + h * hd, hd, pos, c->rope_theta);
         }
+        if (c->kv_bf16)
+            for (int i = 0; i < d; i++) {
+                k[(size_t)m * d + i] = round_bf16(k[(size_t)m * d + i]);
+                v[(size_t)m * d + i] = round_bf16(v[(size_t)m * d + i]);
+            }
         memcpy(Kc + (size_t)pos * d, k + (size_t)m * d, sizeof(double) * d);
         memcpy(Vc + (size_t)pos * d, v + (size_t)m * d, sizeof(double) * d);
     }

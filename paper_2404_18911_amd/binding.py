@@ -19,7 +19,7 @@ KG_OK, KG_EINVAL, KG_ESTATE, KG_ENOSPC, KG_EHIP, KG_ENOMEM = 0, -1, -2, -3, -4, 
 
 class kg_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
-                                            "exit_layer", "dtype")] + \
+                                            "exit_layer", "dtype", "kv_dtype")] + \
                [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float)] + \
                [(n, ctypes.c_int) for n in ("max_seq", "gamma_max", "kv_page_tokens")]
 
@@ -37,10 +37,14 @@ class kg_stats(ctypes.Structure):
                [(n, ctypes.c_double) for n in ("t_draft_s", "t_verify_s", "t_total_s")]
 
 
+class kg_profile(ctypes.Structure):
+    _fields_ = [("launches", ctypes.c_longlong * 3), ("seconds", ctypes.c_double * 3), ("bytes", ctypes.c_double * 3)]
+
+
 # every symbol include/kangaroo.h declares
 SYMBOLS = ["kg_create", "kg_workspace_bytes", "kg_bind", "kg_load_tensor", "kg_set_page_order", "kg_prefill",
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
-           "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_reset", "kg_last_error",
+           "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
            "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear"]
 
 _lib = None
@@ -73,6 +77,8 @@ def lib() -> ctypes.CDLL:
     L.kg_read_feature.argtypes = [vp, ctypes.c_int, fp]
     L.kg_read_kv.argtypes = [vp, ctypes.c_int, ctypes.c_int, fp, fp]
     L.kg_get_state.argtypes = [vp, ip, ip, ip, ip]
+    L.kg_set_profiling.argtypes = [vp, ctypes.c_int]
+    L.kg_get_profile.argtypes = [vp, ctypes.POINTER(kg_profile)]
     L.kg_reset.argtypes = [vp]
     L.kg_last_error.argtypes = [vp]
     L.kg_last_error.restype = ctypes.c_char_p
@@ -96,7 +102,8 @@ class KangarooError(RuntimeError):
 
 def make_config(shape, max_seq: int, gamma_max: int = 6, kv_page_tokens: int = 128) -> kg_config:
     return kg_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
-                     shape.exit_layer, 0 if shape.dtype == "f32" else 1, shape.rms_eps, shape.rope_theta,
+                     shape.exit_layer, 0 if shape.dtype == "f32" else 1, 0 if shape.kv_dtype == "f32" else 1,
+                     shape.rms_eps, shape.rope_theta,
                      max_seq, gamma_max, kv_page_tokens)
 
 
@@ -236,6 +243,14 @@ class Kangaroo:
         v = [ctypes.c_int32() for _ in range(4)]
         self._chk(self.L.kg_get_state(self.h, *[ctypes.byref(i) for i in v]))
         return tuple(i.value for i in v)
+
+    def set_profiling(self, on: bool) -> None:
+        self._chk(self.L.kg_set_profiling(self.h, int(on)))
+
+    def get_profile(self) -> kg_profile:
+        out = kg_profile()
+        self._chk(self.L.kg_get_profile(self.h, ctypes.byref(out)))
+        return out
 
     def reset(self) -> None:
         self._chk(self.L.kg_reset(self.h))

@@ -29,7 +29,8 @@ struct Phase { enum { NONE = 0, READY = 1, DRAFTING = 2, VERIFIED = 3, PLAIN = 4
 struct kg_ctx {
     kg_config c;
     bool bf;
-    int esz;                 // bytes per stored weight / cache element
+    int esz;                 // bytes per stored weight element
+    bool kvbf; int kvesz;    // KV cache element type
     int KSd, KSf;            // k-steps (32 features) of d_model and d_ffn
     int n_pages, logP;
     // arena layout
@@ -57,6 +58,13 @@ struct kg_ctx {
     int targets[KG_MAX_ROWS];
     int n_target_rows = 0;
     int plain_len = 0;
+    // optional per-launch timing
+    bool profiling = false;
+    kg_profile prof;
+    std::vector<hipEvent_t> ev_pool;
+    struct Pending { int cls; double bytes; size_t e0, e1; };
+    std::vector<Pending> ev_pending;
+    size_t ev_used = 0;
     char err[512];
 };
 
@@ -119,7 +127,7 @@ void layout(kg_ctx *x)
     x->gfinal = take((size_t)d * 4);
     x->arena_bytes = o;
 
-    x->kv_bytes = up((size_t)x->n_pages * (L + 1) * c.n_heads * 2 * c.kv_page_tokens * c.head_dim * x->esz);
+    x->kv_bytes = up((size_t)x->n_pages * (L + 1) * c.n_heads * 2 * c.kv_page_tokens * c.head_dim * x->kvesz);
 
     o = 0;
     x->s_x0 = take((size_t)KG_ROWS * d * 4);
@@ -155,11 +163,58 @@ int check_launch(kg_ctx *x, const char *what)
     return KG_OK;
 }
 
+// ---- optional per-launch timing -----------------------------------------------------------------
+
+size_t prof_event(kg_ctx *x)
+{
+    if (x->ev_used == x->ev_pool.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return (size_t)-1;
+        x->ev_pool.push_back(e);
+    }
+    return x->ev_used++;
+}
+
+struct ProfScope {
+    kg_ctx *x; int cls; double bytes; size_t e0 = (size_t)-1;
+    ProfScope(kg_ctx *x_, int cls_, double bytes_) : x(x_), cls(cls_), bytes(bytes_)
+    {
+        if (x->profiling) {
+            e0 = prof_event(x);
+            if (e0 != (size_t)-1) (void)hipEventRecord(x->ev_pool[e0], x->stream);
+        }
+    }
+    ~ProfScope()
+    {
+        if (x->profiling && e0 != (size_t)-1) {
+            size_t e1 = prof_event(x);
+            if (e1 == (size_t)-1) return;
+            (void)hipEventRecord(x->ev_pool[e1], x->stream);
+            x->ev_pending.push_back({cls, bytes, e0, e1});
+        }
+    }
+};
+
+void prof_collect(kg_ctx *x)   // call after the stream has been synchronised
+{
+    for (auto &p : x->ev_pending) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, x->ev_pool[p.e0], x->ev_pool[p.e1]) == hipSuccess) {
+            x->prof.launches[p.cls]++;
+            x->prof.seconds[p.cls] += ms * 1e-3;
+            x->prof.bytes[p.cls] += p.bytes;
+        }
+    }
+    x->ev_pending.clear();
+    x->ev_used = 0;
+}
+
 // ---- kernel launch helpers ---------------------------------------------------------------------
 
 int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Epi &e)
 {
     if (N % 16) return fail(x, KG_EINVAL, "projection rows %d not a multiple of 16", N);
+    ProfScope ps(x, 0, (double)N * K * x->esz);
     if (x->bf)
         hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(256), 0, x->stream,
                            at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
@@ -176,6 +231,7 @@ int launch_pack_rows(kg_ctx *x, const int *tokens, const float *rows, int M, con
     for (int i = 0; i < KG_ROWS; i++) tk.t[i] = (tokens && i < M) ? tokens[i] : 0;
     const void *emb = tokens ? (const void *)(x->arena + x->embed) : nullptr;
     const int d = x->c.d_model;
+    ProfScope ps(x, 2, 0.0);
     if (x->bf)
         hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(d / 16), dim3(128), 0, x->stream, emb, tk, rows, d, M, gain,
                            xout, act, ssq);
@@ -200,9 +256,13 @@ int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
     a.act_out = x->scr + x->s_actA;
     a.append_only = append_only;
     dim3 grid(c.n_heads, a.S);
-    if (x->bf) {
+    ProfScope ps(x, 1, append_only ? 0.0 : (double)(pos0 + M) * 2 * c.d_model * x->kvesz);
+    if (x->bf && x->kvbf) {
         if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<uint16_t, 128, true>), grid, dim3(256), 0, x->stream, a);
         else hipLaunchKernelGGL((attn_kernel<uint16_t, 64, true>), grid, dim3(256), 0, x->stream, a);
+    } else if (x->bf) {
+        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, true>), grid, dim3(256), 0, x->stream, a);
+        else hipLaunchKernelGGL((attn_kernel<float, 64, true>), grid, dim3(256), 0, x->stream, a);
     } else {
         if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, false>), grid, dim3(256), 0, x->stream, a);
         else hipLaunchKernelGGL((attn_kernel<float, 64, false>), grid, dim3(256), 0, x->stream, a);
@@ -281,6 +341,7 @@ int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float in
     Epi e = epi_base(x, EPI_PLAIN, M, x->c.vocab);
     e.ssq_in = at<float>(x->scr, x->s_ssq0); e.out = logits; e.row_shift = row_shift;
     KGCHK(launch_gemv(x, x->head, x->c.vocab, x->c.d_model, x->scr + x->s_actX, e));
+    ProfScope ps(x, 2, 0.0);
     hipLaunchKernelGGL(head_reduce_kernel, dim3(n_out), dim3(1024), 0, x->stream, logits, x->c.vocab, n_out,
                        inv_temp, at<int>(x->scr, x->s_tok), at<float>(x->scr, x->s_conf));
     return check_launch(x, "head_reduce");
@@ -291,6 +352,7 @@ int fetch_results(kg_ctx *x, int n)
     HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, n * 4, hipMemcpyDeviceToHost, x->stream));
     HIPCHK(x, hipMemcpyAsync(x->h_conf, x->scr + x->s_conf, n * 4, hipMemcpyDeviceToHost, x->stream));
     HIPCHK(x, hipStreamSynchronize(x->stream));
+    if (x->profiling) prof_collect(x);
     return KG_OK;
 }
 
@@ -389,6 +451,8 @@ int kg_create(const kg_config *cfg, kg_ctx **out)
     if (c.d_model % 16 || c.d_ffn % 8 || c.vocab % 16) return KG_EINVAL;
     if (c.exit_layer < 1 || c.exit_layer > c.n_layers) return KG_EINVAL;
     if (c.dtype != 0 && c.dtype != 1) return KG_EINVAL;
+    if (c.kv_dtype != 0 && c.kv_dtype != 1) return KG_EINVAL;
+    if (c.dtype == 0 && c.kv_dtype == 1) return KG_EINVAL;   // fp32 weights keep an fp32 cache
     if (c.gamma_max < 1 || c.gamma_max > KG_MAX_ROWS - 1) return KG_EINVAL;
     if (c.kv_page_tokens < 16 || c.kv_page_tokens > 128 || (c.kv_page_tokens & (c.kv_page_tokens - 1))) return KG_EINVAL;
     if (c.max_seq < 2 || !(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return KG_EINVAL;
@@ -397,11 +461,14 @@ int kg_create(const kg_config *cfg, kg_ctx **out)
     x->c = c;
     x->bf = c.dtype == 1;
     x->esz = x->bf ? 2 : 4;
+    x->kvbf = c.kv_dtype == 1;
+    x->kvesz = x->kvbf ? 2 : 4;
     x->KSd = (c.d_model + 31) / 32;
     x->KSf = (c.d_ffn + 31) / 32;
     x->logP = ilog2(c.kv_page_tokens);
     x->n_pages = (c.max_seq + c.kv_page_tokens - 1) / c.kv_page_tokens;
     x->err[0] = 0;
+    memset(&x->prof, 0, sizeof(x->prof));
     layout(x);
     x->loaded.assign(3 + (size_t)c.n_layers * 9 + 6, 0);
     x->page_order.resize(x->n_pages);
@@ -780,7 +847,7 @@ int kg_read_kv(kg_ctx *x, int slot, int pos, float *k_host, float *v_host)
     if (slot < 0 || slot > c.n_layers || pos < 0 || pos >= c.max_seq) return fail(x, KG_EINVAL, "slot/pos out of range");
     float *tmp = at<float>(x->scr, x->s_misc);
     int n = c.d_model;
-    if (x->bf)
+    if (x->kvbf)
         hipLaunchKernelGGL(kv_read_kernel<uint16_t>, dim3((n + 255) / 256), dim3(256), 0, x->stream, x->kv,
                            at<const int>(x->scr, x->s_pt), slot, c.n_layers + 1, c.n_heads, c.head_dim,
                            c.kv_page_tokens, x->logP, pos, tmp, tmp + n);
@@ -805,6 +872,23 @@ int kg_get_state(const kg_ctx *x, int *base, int *adapter_len, int *lag, int *n_
     return KG_OK;
 }
 
+int kg_set_profiling(kg_ctx *x, int on)
+{
+    if (!x) return KG_EINVAL;
+    if (x->bound) HIPCHK(x, hipStreamSynchronize(x->stream));
+    prof_collect(x);
+    memset(&x->prof, 0, sizeof(x->prof));
+    x->profiling = on != 0;
+    return KG_OK;
+}
+
+int kg_get_profile(kg_ctx *x, kg_profile *out)
+{
+    if (!x || !out) return KG_EINVAL;
+    *out = x->prof;
+    return KG_OK;
+}
+
 const char *kg_last_error(const kg_ctx *x) { return x ? x->err : "NULL context"; }
 
 void kg_destroy(kg_ctx *x)
@@ -812,6 +896,7 @@ void kg_destroy(kg_ctx *x)
     if (!x) return;
     if (x->h_tok) (void)hipHostFree(x->h_tok);
     if (x->h_conf) (void)hipHostFree(x->h_conf);
+    for (hipEvent_t e : x->ev_pool) (void)hipEventDestroy(e);
     delete x;
 }
 

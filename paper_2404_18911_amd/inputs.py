@@ -56,9 +56,14 @@ class ModelShape:
     d_ffn: int
     vocab: int
     exit_layer: int
-    dtype: str = "bf16"          # storage type of weights (and of the KV cache on the GPU): "f32" | "bf16"
+    dtype: str = "bf16"          # storage type of the weights: "f32" | "bf16"
     rms_eps: float = 1e-6
     rope_theta: float = 10000.0
+    kv: str = ""                 # storage type of the key/value cache; "" = same as dtype
+
+    @property
+    def kv_dtype(self) -> str:
+        return self.kv or self.dtype
 
     def layer_params(self) -> int:
         d, f = self.d_model, self.d_ffn

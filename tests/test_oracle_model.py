@@ -44,6 +44,9 @@ def torch_forward(shape, W, tokens, lo_hi=None, with_adapter=False):
         q = rope((a @ wq.T).view(T, H, hd)).transpose(0, 1)          # [H, T, hd]
         k = rope((a @ wk.T).view(T, H, hd)).transpose(0, 1)
         v = (a @ wv.T).view(T, H, hd).transpose(0, 1)
+        if shape.kv_dtype == "bf16":        # the cache stores rotated keys and values as bfloat16
+            k = k.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+            v = v.to(torch.float32).to(torch.bfloat16).to(torch.float64)
         s = q @ k.transpose(1, 2) / np.sqrt(hd)
         s = s.masked_fill(torch.triu(torch.ones(T, T, dtype=torch.bool), 1), float("-inf"))
         o = (torch.softmax(s, -1) @ v).transpose(0, 1).reshape(T, d)
@@ -68,12 +71,13 @@ def torch_forward(shape, W, tokens, lo_hi=None, with_adapter=False):
     return f.numpy(), x.numpy(), logits.numpy(), dlogits.numpy()
 
 
-@pytest.mark.parametrize("name", ["toy", "toy_bf16"])
-def test_incremental_decode_matches_whole_sequence_library_forward(name):
+@pytest.mark.parametrize("name,kv", [("toy", ""), ("toy_bf16", ""), ("toy_bf16", "f32")])
+def test_incremental_decode_matches_whole_sequence_library_forward(name, kv):
     """Oracle run token by token through its caches == library forward of the whole sequence.
     A dropped residual, a wrong RoPE pairing or sign, a transposed operand, a cache indexing
     slip or a wrong widening of bf16 all break this."""
-    shape = I.SHAPES[name]
+    import dataclasses
+    shape = dataclasses.replace(I.SHAPES[name], kv=kv)
     # non-trivial gains so that a missing or misplaced gain is caught too
     W = I.gen_weights(shape, seed=5, alpha=0.7)
     rng = np.random.default_rng(0)
