@@ -39,7 +39,7 @@ struct kg_ctx {
     size_t kv_bytes, scratch_bytes;
     // scratch layout (byte offsets)
     size_t s_x0, s_x1, s_F, s_qkv, s_actX, s_actA, s_actF, s_ssq0, s_ssq1, s_opart, s_mxs, s_sms, s_cnt,
-        s_dlog, s_tlog, s_tok, s_conf, s_pt, s_rope, s_invf, s_misc;
+        s_dlog, s_tlog, s_tok, s_conf, s_pt, s_rope, s_invf, s_misc, s_hstat;
     // bindings
     char *arena = nullptr, *kv = nullptr, *scr = nullptr;
     hipStream_t stream = nullptr;
@@ -151,6 +151,7 @@ void layout(kg_ctx *x)
     x->s_rope = take((size_t)c.max_seq * (c.head_dim / 2) * 8);
     x->s_invf = take((size_t)(c.head_dim / 2) * 8);
     x->s_misc = take((size_t)2 * d * 4);
+    x->s_hstat = take((size_t)(V / 16) * KG_ROWS * 4 * 4);
     x->scratch_bytes = o;
 }
 
@@ -215,8 +216,12 @@ int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Ep
 {
     if (N % 16) return fail(x, KG_EINVAL, "projection rows %d not a multiple of 16", N);
     ProfScope ps(x, 0, (double)N * K * x->esz);
-    if (x->bf)
-        hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(256), 0, x->stream,
+    static const int gemv_u = getenv("KG_GEMV_U") ? atoi(getenv("KG_GEMV_U")) : 8;
+    if (x->bf && gemv_u >= 16)
+        hipLaunchKernelGGL(gemv_bf16_kernel<16>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
+                           at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
+    else if (x->bf)
+        hipLaunchKernelGGL(gemv_bf16_kernel<8>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
                            at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
     else
         hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, x->stream, at<const float>(x->arena, w_off),
@@ -258,14 +263,14 @@ int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
     dim3 grid(c.n_heads, a.S);
     ProfScope ps(x, 1, append_only ? 0.0 : (double)(pos0 + M) * 2 * c.d_model * x->kvesz);
     if (x->bf && x->kvbf) {
-        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<uint16_t, 128, true>), grid, dim3(256), 0, x->stream, a);
-        else hipLaunchKernelGGL((attn_kernel<uint16_t, 64, true>), grid, dim3(256), 0, x->stream, a);
+        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<uint16_t, 128, true>), grid, dim3(512), 0, x->stream, a);
+        else hipLaunchKernelGGL((attn_kernel<uint16_t, 64, true>), grid, dim3(512), 0, x->stream, a);
     } else if (x->bf) {
-        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, true>), grid, dim3(256), 0, x->stream, a);
-        else hipLaunchKernelGGL((attn_kernel<float, 64, true>), grid, dim3(256), 0, x->stream, a);
+        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, true>), grid, dim3(512), 0, x->stream, a);
+        else hipLaunchKernelGGL((attn_kernel<float, 64, true>), grid, dim3(512), 0, x->stream, a);
     } else {
-        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, false>), grid, dim3(256), 0, x->stream, a);
-        else hipLaunchKernelGGL((attn_kernel<float, 64, false>), grid, dim3(256), 0, x->stream, a);
+        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, false>), grid, dim3(512), 0, x->stream, a);
+        else hipLaunchKernelGGL((attn_kernel<float, 64, false>), grid, dim3(512), 0, x->stream, a);
     }
     return check_launch(x, "attention");
 }
@@ -338,13 +343,14 @@ int run_layers(kg_ctx *x, int lo, int hi, int M, int pos0, const float *x_first,
 // arg-max and top-1 probability of rows 0..n_out-1 into the device tok/conf arrays.
 int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float inv_temp)
 {
-    Epi e = epi_base(x, EPI_PLAIN, M, x->c.vocab);
+    Epi e = epi_base(x, EPI_HEAD, M, x->c.vocab);
     e.ssq_in = at<float>(x->scr, x->s_ssq0); e.out = logits; e.row_shift = row_shift;
+    e.hstat = at<float>(x->scr, x->s_hstat); e.inv_temp = inv_temp;
     KGCHK(launch_gemv(x, x->head, x->c.vocab, x->c.d_model, x->scr + x->s_actX, e));
     ProfScope ps(x, 2, 0.0);
-    hipLaunchKernelGGL(head_reduce_kernel, dim3(n_out), dim3(1024), 0, x->stream, logits, x->c.vocab, n_out,
-                       inv_temp, at<int>(x->scr, x->s_tok), at<float>(x->scr, x->s_conf));
-    return check_launch(x, "head_reduce");
+    hipLaunchKernelGGL(head_final_kernel, dim3(n_out), dim3(256), 0, x->stream, at<const float>(x->scr, x->s_hstat),
+                       x->c.vocab / 16, at<int>(x->scr, x->s_tok), at<float>(x->scr, x->s_conf));
+    return check_launch(x, "head_final");
 }
 
 int fetch_results(kg_ctx *x, int n)
@@ -448,13 +454,14 @@ int kg_create(const kg_config *cfg, kg_ctx **out)
     if (c.n_layers < 1 || c.d_model < 16 || c.n_heads < 1 || c.d_ffn < 8 || c.vocab < 16) return KG_EINVAL;
     if (c.head_dim != 64 && c.head_dim != 128) return KG_EINVAL;
     if (c.n_heads * c.head_dim != c.d_model) return KG_EINVAL;
-    if (c.d_model % 16 || c.d_ffn % 8 || c.vocab % 16) return KG_EINVAL;
+    if (c.d_model % 16 || c.d_ffn % 8 || c.vocab % 16 || c.d_model > 8192) return KG_EINVAL;
     if (c.exit_layer < 1 || c.exit_layer > c.n_layers) return KG_EINVAL;
     if (c.dtype != 0 && c.dtype != 1) return KG_EINVAL;
     if (c.kv_dtype != 0 && c.kv_dtype != 1) return KG_EINVAL;
     if (c.dtype == 0 && c.kv_dtype == 1) return KG_EINVAL;   // fp32 weights keep an fp32 cache
     if (c.gamma_max < 1 || c.gamma_max > KG_MAX_ROWS - 1) return KG_EINVAL;
     if (c.kv_page_tokens < 16 || c.kv_page_tokens > 128 || (c.kv_page_tokens & (c.kv_page_tokens - 1))) return KG_EINVAL;
+    if ((c.max_seq + c.kv_page_tokens - 1) / c.kv_page_tokens > 128) return KG_EINVAL;   // at most 128 KV pages
     if (c.max_seq < 2 || !(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return KG_EINVAL;
     kg_ctx *x = new (std::nothrow) kg_ctx();
     if (!x) return KG_ENOMEM;
@@ -938,7 +945,7 @@ int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, i
         if (hipMemsetAsync(work, 0, act_bytes(K), s) != hipSuccess) return KG_EHIP;
         hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, xd, K, M,
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
-        hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(256), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
+        hipLaunchKernelGGL(gemv_bf16_kernel<16>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
                            (const u32x4_t *)work, e);
     } else {
         hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, xd, K, M,

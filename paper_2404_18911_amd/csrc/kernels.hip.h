@@ -22,7 +22,7 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 #define KG_ROWS 8
 
-enum { EPI_PLAIN = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+enum { EPI_PLAIN = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
 
 // What a projection kernel does with a finished 16-row tile y[16][8].
 struct Epi {
@@ -36,6 +36,10 @@ struct Epi {
     // EPI_PLAIN: out[(m + row_shift)][n] = y * scale, rows with m + row_shift < 0 are dropped
     float *out;
     int row_shift;
+    // EPI_HEAD: as EPI_PLAIN, plus per-tile statistics of z * inv_temp for the rows kept:
+    // hstat[(tile * 8 + row) * 4 + {0,1,2}] = max, sum exp(. - max), arg-max index (as float bits)
+    float *hstat;
+    float inv_temp;
     // EPI_RESID: x = res[m][n] + y; xout[m][n] = x; act_out <- x * gain[n]; ssq_out[tile][m] = sum x^2
     const float *res;
     float *xout;
@@ -53,6 +57,10 @@ __device__ __forceinline__ uint16_t f2bf(float f)
     return (uint16_t)(u >> 16);
 }
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// device-scope relaxed accesses for data exchanged between workgroups inside one kernel
+__device__ __forceinline__ void st_dev(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_dev(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // Store activation value v of row m, feature k, for a consumer projection with K features.
 // BF: bf16 hi/lo parts in B-operand tile layout [k/32][lane = (k%32/8)*16 + col][k%8], col = m (hi), m+8 (lo).
@@ -73,18 +81,52 @@ __device__ __forceinline__ void store_act(void *buf, int K, int m, int k, float 
 }
 
 // scale[m] = rsqrt(mean square of the input row + eps), from per-tile partial sums, fixed order.
-// Called by all 256 threads of a block; result valid after the next __syncthreads().
+// Wave w of an 8-wave block serves batch row w.  The partials (at most 8 per lane: d <= 8192) are
+// fetched by scale_fetch at kernel start so that their latency hides behind the weight stream;
+// scale_finish reduces them.  Result valid after the next __syncthreads().
+struct ScaleRegs { float v[8]; };
+__device__ __forceinline__ void scale_fetch(const Epi &e, ScaleRegs &r)
+{
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        int i = lane + 64 * j;
+        r.v[j] = (e.ssq_in && wave < e.M && i < e.nt_in) ? e.ssq_in[(size_t)i * KG_ROWS + wave] : 0.f;
+    }
+}
+__device__ __forceinline__ void scale_finish(const Epi &e, const ScaleRegs &r, float *sc)
+{
+    int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (wave < e.M) {
+        float s = 1.f;
+        if (e.ssq_in) {
+            s = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; j++) s += r.v[j];
+            for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+            s = rsqrtf(s * e.inv_d + e.eps);
+        }
+        if (lane == 0) sc[wave] = s;
+    }
+}
+// for blocks with fewer than 8 waves
 __device__ __forceinline__ void compute_scale(const Epi &e, float *sc)
 {
     int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int m = wave; m < e.M; m += 4) {
-        float s = 0.f;
+    for (int m = wave; m < e.M; m += (int)(blockDim.x >> 6)) {
+        float s = 1.f;
         if (e.ssq_in) {
-            for (int i = lane; i < e.nt_in; i += 64) s += e.ssq_in[(size_t)i * KG_ROWS + m];
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                int i = lane + 64 * j;
+                v[j] = i < e.nt_in ? e.ssq_in[(size_t)i * KG_ROWS + m] : 0.f;
+            }
+            s = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; j++) s += v[j];
             for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
             s = rsqrtf(s * e.inv_d + e.eps);
-        } else {
-            s = 1.f;
         }
         if (lane == 0) sc[m] = s;
     }
@@ -93,14 +135,33 @@ __device__ __forceinline__ void compute_scale(const Epi &e, float *sc)
 // Epilogue on a finished tile: yt[16][8] in LDS (row in tile, batch row), all 256 threads call it.
 template <bool BF>
 __device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_ROWS], const float *sc,
-                                         float (*sq)[KG_ROWS])
+                                         float (*sq)[KG_ROWS], float resv = 0.f, float gainv = 1.f,
+                                         bool prefetched = false)
 {
     int t = threadIdx.x;
-    if (e.kind == EPI_PLAIN) {
+    if (e.kind == EPI_PLAIN || e.kind == EPI_HEAD) {
         if (t < 128) {
             int row = t >> 3, m = t & 7;
             int mo = m + e.row_shift;
-            if (m < e.M && mo >= 0) e.out[(size_t)mo * e.N + rt * 16 + row] = yt[row][m] * sc[m];
+            float z = yt[row][m] * sc[m];
+            if (m < e.M && mo >= 0) e.out[(size_t)mo * e.N + rt * 16 + row] = z;
+            sq[row][m] = z * e.inv_temp;
+        }
+        if (e.kind == EPI_HEAD) {
+            __syncthreads();
+            int mo = t + e.row_shift;
+            if (t < e.M && mo >= 0) {
+                float best = sq[0][t];
+                int bi = 0;
+                for (int r = 1; r < 16; r++)
+                    if (sq[r][t] > best) { best = sq[r][t]; bi = r; }
+                float sum = 0.f;
+                for (int r = 0; r < 16; r++) sum += __expf(sq[r][t] - best);
+                float *hs = e.hstat + ((size_t)rt * KG_ROWS + mo) * 4;
+                hs[0] = best;
+                hs[1] = sum;
+                hs[2] = __int_as_float(rt * 16 + bi);
+            }
         }
     } else if (e.kind == EPI_RESID) {
         if (t < 128) {
@@ -108,9 +169,13 @@ __device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_RO
             float v = 0.f;
             if (m < e.M) {
                 int n = rt * 16 + row;
-                v = e.res[(size_t)m * e.N + n] + yt[row][m];
+                if (!prefetched) {
+                    resv = e.res[(size_t)m * e.N + n];
+                    gainv = e.gain ? e.gain[n] : 1.f;
+                }
+                v = resv + yt[row][m];
                 e.xout[(size_t)m * e.N + n] = v;
-                if (e.act_out) store_act<BF>(e.act_out, e.act_K, m, n, e.gain ? v * e.gain[n] : v);
+                if (e.act_out) store_act<BF>(e.act_out, e.act_K, m, n, e.gain ? v * gainv : v);
             }
             sq[row][m] = v * v;
         }
@@ -135,50 +200,62 @@ __device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_RO
 }
 
 // ---------------------------------------------------------------------------------------------
-// Projection, bf16 weights: one block (4 waves) per 16-row tile; the waves split K; each wave
+// Projection, bf16 weights: one block (8 waves) per 16-row tile; the waves split K; each wave
 // streams its 1 KB weight tiles with 16-byte non-temporal loads and issues one MFMA per tile.
 // W: tiles [rt][ks][64 lanes][8 bf16]; act: B-operand tiles [ks][64 lanes][8 bf16].
-__global__ __launch_bounds__(256) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS,
-                                                        const u32x4_t *__restrict__ act, Epi e)
+#define GEMV_WAVES 8
+
+template <int U>
+__device__ __forceinline__ void gemv_steps(const u32x4_t *&wp, const u32x4_t *&bp, bool bact, f32x4_t &acc)
 {
-    __shared__ float part[4][16][KG_ROWS];
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+    u32x4_t a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; u++) a[u] = __builtin_nontemporal_load(wp + u * 64);
+#pragma unroll
+    for (int u = 0; u < U; u++) b[u] = bact ? bp[u * 64] : zero;
+#pragma unroll
+    for (int u = 0; u < U; u++)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u]),
+                                                      __builtin_bit_cast(bf16x8_t, b[u]), acc, 0, 0, 0);
+    wp += U * 64;
+    bp += U * 64;
+}
+
+template <int UMAX>
+__global__ __launch_bounds__(64 * GEMV_WAVES, UMAX >= 16 ? 1 : 2) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS,
+                                                                   const u32x4_t *__restrict__ act, Epi e)
+{
+    __shared__ float part[GEMV_WAVES][16][KG_ROWS];
     __shared__ float yt[16][KG_ROWS];
     __shared__ float sq[16][KG_ROWS];
     __shared__ float sc[KG_ROWS];
     const int rt = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int ks0 = (wave * KS) >> 2, ks1 = ((wave + 1) * KS) >> 2;
+    const int ks0 = (wave * KS) / GEMV_WAVES, ks1 = ((wave + 1) * KS) / GEMV_WAVES;
     const u32x4_t *wp = W + ((size_t)rt * KS + ks0) * 64 + lane;
     const u32x4_t *bp = act + (size_t)ks0 * 64 + lane;
     const bool bact = (lane & 7) < e.M;
-    const u32x4_t zero = {0u, 0u, 0u, 0u};
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    ScaleRegs sr;
+    scale_fetch(e, sr);
+    float resv = 0.f, gainv = 1.f;       // epilogue operands of thread (row, m), fetched early
+    if (e.kind == EPI_RESID && threadIdx.x < 128 && (threadIdx.x & 7) < e.M) {
+        int nn = rt * 16 + (threadIdx.x >> 3);
+        resv = e.res[(size_t)(threadIdx.x & 7) * e.N + nn];
+        if (e.gain) gainv = e.gain[nn];
+    }
     int n = ks1 - ks0;
-    constexpr int U = 8;
-    while (n >= U) {
-        u32x4_t a[U], b[U];
-#pragma unroll
-        for (int u = 0; u < U; u++) a[u] = __builtin_nontemporal_load(wp + u * 64);
-#pragma unroll
-        for (int u = 0; u < U; u++) b[u] = bact ? bp[u * 64] : zero;
-#pragma unroll
-        for (int u = 0; u < U; u++)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[u]),
-                                                          __builtin_bit_cast(bf16x8_t, b[u]), acc, 0, 0, 0);
-        wp += U * 64;
-        bp += U * 64;
-        n -= U;
+    if (UMAX >= 16) {
+        while (n >= 16) { gemv_steps<16>(wp, bp, bact, acc); n -= 16; }
+        if (n >= 8) { gemv_steps<8>(wp, bp, bact, acc); n -= 8; }
+    } else {
+        while (n >= 8) { gemv_steps<8>(wp, bp, bact, acc); n -= 8; }
     }
-    while (n > 0) {
-        u32x4_t a = __builtin_nontemporal_load(wp);
-        u32x4_t b = bact ? bp[0] : zero;
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                      __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
-        wp += 64;
-        bp += 64;
-        n--;
-    }
-    compute_scale(e, sc);
+    if (n >= 4) { gemv_steps<4>(wp, bp, bact, acc); n -= 4; }
+    if (n >= 2) { gemv_steps<2>(wp, bp, bact, acc); n -= 2; }
+    if (n >= 1) { gemv_steps<1>(wp, bp, bact, acc); }
+    scale_finish(e, sr, sc);
     // D layout: lane holds column (lane & 15) and tile rows 4*(lane >> 4) + r.  Columns m and m+8
     // are the hi and lo parts of batch row m: fold them.
 #pragma unroll
@@ -189,10 +266,13 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(const u32x4_t *__restric
     __syncthreads();
     if (threadIdx.x < 128) {
         int row = threadIdx.x >> 3, m = threadIdx.x & 7;
-        yt[row][m] = ((part[0][row][m] + part[1][row][m]) + part[2][row][m]) + part[3][row][m];
+        float v = part[0][row][m];
+#pragma unroll
+        for (int w = 1; w < GEMV_WAVES; w++) v += part[w][row][m];
+        yt[row][m] = v;
     }
     __syncthreads();
-    epilogue<true>(e, rt, yt, sc, sq);
+    epilogue<true>(e, rt, yt, sc, sq, resv, gainv, true);
 }
 
 // Projection, fp32 weights (row-major [N][K]) and fp32 activations [8][K]: 16 threads per row.
@@ -352,28 +432,77 @@ template <> __device__ __forceinline__ void kv_ld8<uint16_t>(const uint16_t *p, 
     }
 }
 
+template <typename T, int N8> struct KvVec;           // N8 groups of 8 cache elements, loaded as 16-byte pieces
+template <int N8> struct KvVec<uint16_t, N8> {
+    u32x4_t r[N8];
+    __device__ __forceinline__ void load(const uint16_t *p)
+    {
+#pragma unroll
+        for (int i = 0; i < N8; i++) r[i] = *(const u32x4_t *)(p + 8 * i);
+    }
+    __device__ __forceinline__ float get(int i) const
+    {
+        uint32_t w = r[i >> 3][(i >> 1) & 3];
+        return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+    }
+};
+template <int N8> struct KvVec<float, N8> {
+    float4 r[2 * N8];
+    __device__ __forceinline__ void load(const float *p)
+    {
+#pragma unroll
+        for (int i = 0; i < 2 * N8; i++) r[i] = *(const float4 *)(p + 4 * i);
+    }
+    __device__ __forceinline__ float get(int i) const
+    {
+        const float4 &v = r[i >> 2];
+        return (i & 3) == 0 ? v.x : (i & 3) == 1 ? v.y : (i & 3) == 2 ? v.z : v.w;
+    }
+};
+
+// One (head, page) unit, 512 threads.  Scores: 4 lanes per position (a quarter of the head
+// dimension each), all 128 positions of a page in one pass.  Softmax statistics are kept per
+// wave (16 positions), then merged across the 8 waves, then across pages; every level rescales
+// by exp(max_part - max_all), in a fixed order, so a row's result does not depend on the other
+// rows of the batch or on trailing pages.
 template <typename T, int HD, bool BF>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
+__global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
 {
-    constexpr int LPR = HD / 8;        // lanes per cache row (8 elements each)
-    constexpr int NG = 256 / LPR;      // position groups in the block
-    constexpr int GPW = 64 / LPR;      // position groups per wave
+    constexpr int EL = HD / 4;          // elements of one score lane
+    constexpr int LPR = HD / 8;         // lanes per cache row in the P.V pass (8 elements each)
+    constexpr int RPW = 64 / LPR;       // rows per wave instruction in the P.V pass
+    constexpr int NIT = 16 / RPW;       // P.V iterations to cover a wave's 16 positions
     __shared__ float qs[KG_ROWS][HD];
-    __shared__ float sc[KG_ROWS][128];
-    __shared__ float wpart[4][KG_ROWS][HD];
-    __shared__ float mx_s[KG_ROWS], sm_s[KG_ROWS];
+    __shared__ float pw[8][16][KG_ROWS];
+    __shared__ float ow[8][KG_ROWS][HD];
+    __shared__ float mw[8][KG_ROWS], sw[8][KG_ROWS];
     __shared__ int last_flag;
     const int h = blockIdx.x, s = blockIdx.y, t = threadIdx.x;
     const int wave = t >> 6, lane = t & 63;
     const int P = a.P, M = a.M, d = a.d;
     const int p_begin = s << a.logP;
     const int n_valid = min(P, a.pos0 + M - p_begin);      // positions of this page that hold data
+    const int n_old = min(P, max(0, a.pos0 - p_begin));    // ... of which were cached before this call
     T *Kp = (T *)a.kv + ((((size_t)a.page_table[s] * a.n_slots + a.slot) * a.H + h) * 2) * (size_t)P * HD;
     T *Vp = Kp + (size_t)P * HD;
     const float qscale = rsqrtf((float)HD);
 
+    // roles: score lane (position pl, quarter sub); P.V lane (row r of an instruction, chunk c)
+    const int pl = t >> 2, sub = t & 3;
+    const int r = lane / LPR, c = lane % LPR;
+    KvVec<T, EL / 8> kreg;
+    KvVec<T, 1> vreg[NIT];
+    const bool k_old = pl < n_old;
+    if (!a.append_only) {       // rows cached by earlier calls can be fetched before the new rows are written
+        if (k_old) kreg.load(Kp + (size_t)pl * HD + sub * EL);
+#pragma unroll
+        for (int it = 0; it < NIT; it++) {
+            int pv = wave * 16 + it * RPW + r;
+            if (pv < n_old) vreg[it].load(Vp + (size_t)pv * HD + c * 8);
+        }
+    }
     // rotate q into LDS; rotate and append the new k, v rows that live in this page
-    for (int i = t; i < M * (HD / 2); i += 256) {
+    for (int i = t; i < M * (HD / 2); i += 512) {
         int m = i / (HD / 2), j = i % (HD / 2);
         int pos = a.pos0 + m;
         float2 cs = a.rope[(size_t)pos * (HD / 2) + j];
@@ -384,158 +513,186 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
         if (pos >= p_begin && pos < p_begin + P) {
             const float *k = q + d, *v = q + 2 * d;
             float k0 = k[j], k1 = k[j + HD / 2];
-            int pl = pos - p_begin;
-            kv_st<T>(Kp + (size_t)pl * HD + j, k0 * cs.x - k1 * cs.y);
-            kv_st<T>(Kp + (size_t)pl * HD + j + HD / 2, k1 * cs.x + k0 * cs.y);
-            kv_st<T>(Vp + (size_t)pl * HD + j, v[j]);
-            kv_st<T>(Vp + (size_t)pl * HD + j + HD / 2, v[j + HD / 2]);
+            int pp = pos - p_begin;
+            kv_st<T>(Kp + (size_t)pp * HD + j, k0 * cs.x - k1 * cs.y);
+            kv_st<T>(Kp + (size_t)pp * HD + j + HD / 2, k1 * cs.x + k0 * cs.y);
+            kv_st<T>(Vp + (size_t)pp * HD + j, v[j]);
+            kv_st<T>(Vp + (size_t)pp * HD + j + HD / 2, v[j + HD / 2]);
         }
     }
     if (a.append_only) return;
     __syncthreads();
+    if (!k_old && pl < n_valid) kreg.load(Kp + (size_t)pl * HD + sub * EL);
+#pragma unroll
+    for (int it = 0; it < NIT; it++) {
+        int pv = wave * 16 + it * RPW + r;
+        if (pv >= n_old && pv < n_valid) vreg[it].load(Vp + (size_t)pv * HD + c * 8);
+    }
 
-    const int c = t % LPR;             // 8-element chunk of the head dimension
-    const int grp = t / LPR;           // position group: handles positions grp, grp+NG, ...
-    // scores
-    for (int pl = grp; pl < P; pl += NG) {
-        float part[KG_ROWS];
+    // scores and wave-local softmax
+    float pr[KG_ROWS];
 #pragma unroll
-        for (int m = 0; m < KG_ROWS; m++) part[m] = 0.f;
-        if (pl < n_valid) {
-            float kk[8];
-            kv_ld8<T>(Kp + (size_t)pl * HD + c * 8, kk);
+    for (int m = 0; m < KG_ROWS; m++) {
+        float v = 0.f;
+        if (m < M && pl < n_valid) {
 #pragma unroll
-            for (int m = 0; m < KG_ROWS; m++)
-                if (m < M) {
-#pragma unroll
-                    for (int i = 0; i < 8; i++) part[m] = fmaf(kk[i], qs[m][c * 8 + i], part[m]);
-                }
+            for (int i = 0; i < EL; i++) v = fmaf(kreg.get(i), qs[m][sub * EL + i], v);
         }
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        float sc = (m < M && pl < n_valid && p_begin + pl <= a.pos0 + m) ? v : -INFINITY;
+        float mx = sc;
+        for (int o = 4; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float p = (mx == -INFINITY) ? 0.f : __expf(sc - mx);
+        float sum = p;
+        for (int o = 4; o < 64; o <<= 1) sum += __shfl_xor(sum, o);
+        pr[m] = p;
+        if (lane == 0) { mw[wave][m] = mx; sw[wave][m] = sum; }
+    }
+    if (sub == 0) {
 #pragma unroll
-        for (int m = 0; m < KG_ROWS; m++) {
-            float v = part[m];
-#pragma unroll
-            for (int o = LPR / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-            if (c == 0 && m < M) sc[m][pl] = (pl < n_valid && p_begin + pl <= a.pos0 + m) ? v : -INFINITY;
-        }
+        for (int m = 0; m < KG_ROWS; m++) pw[wave][pl & 15][m] = pr[m];
     }
     __syncthreads();
-    // page-local softmax statistics: wave w handles rows w, w+4
-    for (int m = wave; m < M; m += 4) {
-        float mx = -INFINITY;
-        for (int pl = lane; pl < P; pl += 64) mx = fmaxf(mx, sc[m][pl]);
-        for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-        float sum = 0.f;
-        for (int pl = lane; pl < P; pl += 64) {
-            float pr = (mx == -INFINITY) ? 0.f : __expf(sc[m][pl] - mx);
-            sc[m][pl] = pr;
-            sum += pr;
-        }
-        for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
-        if (lane == 0) { mx_s[m] = mx; sm_s[m] = sum; }
-    }
-    __syncthreads();
-    // P.V: thread accumulates its chunk over its positions, then fixed-order reduction
+    // P.V over the wave's 16 positions
     float acc[KG_ROWS][8];
 #pragma unroll
     for (int m = 0; m < KG_ROWS; m++)
 #pragma unroll
         for (int i = 0; i < 8; i++) acc[m][i] = 0.f;
-    for (int pl = grp; pl < n_valid; pl += NG) {
-        float vv[8];
-        kv_ld8<T>(Vp + (size_t)pl * HD + c * 8, vv);
 #pragma unroll
-        for (int m = 0; m < KG_ROWS; m++)
-            if (m < M) {
-                float pr = sc[m][pl];
+    for (int it = 0; it < NIT; it++) {
+        int pw_i = it * RPW + r;
+        if (wave * 16 + pw_i < n_valid) {
 #pragma unroll
-                for (int i = 0; i < 8; i++) acc[m][i] = fmaf(pr, vv[i], acc[m][i]);
-            }
+            for (int m = 0; m < KG_ROWS; m++)
+                if (m < M) {
+                    float p = pw[wave][pw_i][m];
+#pragma unroll
+                    for (int i = 0; i < 8; i++) acc[m][i] = fmaf(p, vreg[it].get(i), acc[m][i]);
+                }
+        }
     }
 #pragma unroll
     for (int m = 0; m < KG_ROWS; m++)
+        if (m < M) {
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            float v = acc[m][i];
+            for (int i = 0; i < 8; i++) {
+                float v = acc[m][i];
 #pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o);
-            if ((lane / LPR) == 0 && m < M) wpart[wave][m][c * 8 + i] = v;
+                for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o);
+                if (r == 0) ow[wave][m][c * 8 + i] = v;
+            }
         }
     __syncthreads();
+    // merge the 8 waves; a single page is final, otherwise store the page partial
+    const bool single = a.S == 1;
     float *op = a.opart + ((size_t)h * a.S + s) * KG_ROWS * HD;
-    for (int i = t; i < M * HD; i += 256) {
+    for (int i = t; i < M * HD; i += 512) {
         int m = i / HD, e = i % HD;
-        op[m * HD + e] = ((wpart[0][m][e] + wpart[1][m][e]) + wpart[2][m][e]) + wpart[3][m][e];
+        float gm = mw[0][m];
+#pragma unroll
+        for (int w = 1; w < 8; w++) gm = fmaxf(gm, mw[w][m]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; w++) {
+            float mv = mw[w][m];
+            if (mv != -INFINITY) {
+                float wt = __expf(mv - gm);
+                num += wt * ow[w][m][e];
+                den += wt * sw[w][m];
+            }
+        }
+        if (single) {
+            store_act<BF>(a.act_out, d, m, h * HD + e, num / den);
+        } else {
+            st_dev(&op[m * HD + e], num);
+            if (e == 0) {
+                st_dev(&a.mxs[((size_t)h * a.S + s) * KG_ROWS + m], gm);
+                st_dev(&a.sms[((size_t)h * a.S + s) * KG_ROWS + m], den);
+            }
+        }
     }
-    if (t < M) {
-        a.mxs[((size_t)h * a.S + s) * KG_ROWS + t] = mx_s[t];
-        a.sms[((size_t)h * a.S + s) * KG_ROWS + t] = sm_s[t];
-    }
-    // last block of this head merges
-    __threadfence();
+    if (single) return;
+    // last block of this head merges the pages in order.  The partials are exchanged with
+    // device-scope relaxed atomic stores / loads (write-through, cache-bypassing accesses), ordered
+    // by a workgroup-scope release before the counter is bumped: a device-scope fence would write
+    // back and invalidate the whole L2 and costs several microseconds here.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (t == 0) {
-        int old = atomicAdd(&a.cnt[h], 1);
+        int old = __hip_atomic_fetch_add(&a.cnt[h], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         last_flag = (old == a.S - 1);
     }
     __syncthreads();
     if (!last_flag) return;
-    __threadfence();
-    for (int i = t; i < M * HD; i += 256) {
-        int m = i / HD, e = i % HD;
+    // page weights exp(max_page - max_all), through LDS so that the page loop has independent loads
+    float (*wgt)[KG_ROWS] = pw[0];                     // reuse: [page][row], S <= 128
+    for (int m = wave; m < M; m += 8) {
         float gm = -INFINITY;
-        for (int ss = 0; ss < a.S; ss++)
-            gm = fmaxf(gm, __builtin_nontemporal_load(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]));
+        for (int ss = lane; ss < a.S; ss += 64) gm = fmaxf(gm, ld_dev(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]));
+        for (int o = 32; o >= 1; o >>= 1) gm = fmaxf(gm, __shfl_xor(gm, o));
+        for (int ss = lane; ss < a.S; ss += 64) {
+            float mxv = ld_dev(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]);
+            wgt[ss][m] = (mxv == -INFINITY) ? 0.f : __expf(mxv - gm);
+        }
+    }
+    __syncthreads();
+    for (int i = t; i < M * HD; i += 512) {
+        int m = i / HD, e = i % HD;
         float num = 0.f, den = 0.f;
         for (int ss = 0; ss < a.S; ss++) {
-            float mxv = __builtin_nontemporal_load(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]);
-            if (mxv == -INFINITY) continue;
-            float w = __expf(mxv - gm);
-            num += w * __builtin_nontemporal_load(&a.opart[(((size_t)h * a.S + ss) * KG_ROWS + m) * HD + e]);
-            den += w * __builtin_nontemporal_load(&a.sms[((size_t)h * a.S + ss) * KG_ROWS + m]);
+            float w = wgt[ss][m];
+            num += w * ld_dev(&a.opart[(((size_t)h * a.S + ss) * KG_ROWS + m) * HD + e]);
+            den += w * ld_dev(&a.sms[((size_t)h * a.S + ss) * KG_ROWS + m]);
         }
         store_act<BF>(a.act_out, d, m, h * HD + e, num / den);
     }
-    if (t == 0) a.cnt[h] = 0;
+    if (t == 0) __hip_atomic_store(&a.cnt[h], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row statistics of logits: arg-max (lowest index among equal maxima), top-1 probability of
-// softmax(z / T) = 1 / sum exp((z - max) / T).  One block per row.
-__global__ __launch_bounds__(1024) void head_reduce_kernel(const float *logits, int V, int M, float inv_temp,
-                                                           int *tok_out, float *conf_out)
+// Final reduction of the per-tile LM-head statistics: arg-max (lowest index among equal maxima)
+// and top-1 probability of softmax(z / T) = 1 / sum exp((z - max) / T).  One block per row.
+__global__ __launch_bounds__(256) void head_final_kernel(const float *hstat, int n_tiles, int *tok_out,
+                                                         float *conf_out)
 {
-    __shared__ float bv[16];
-    __shared__ int bi[16];
-    __shared__ float bs[16];
-    int m = blockIdx.x, t = threadIdx.x, wave = t >> 6, lane = t & 63;
-    const float *z = logits + (size_t)m * V;
-    float best = -INFINITY;
+    __shared__ float bm[4], bs[4];
+    __shared__ int bi[4];
+    const int m = blockIdx.x, t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    float best = -INFINITY, sum = 0.f;
     int idx = 0x7FFFFFFF;
-    for (int i = t; i < V; i += 1024) {
-        float v = z[i];
-        if (v > best) { best = v; idx = i; }
+    for (int i = t; i < n_tiles; i += 256) {
+        const float *hs = hstat + ((size_t)i * KG_ROWS + m) * 4;
+        float mx = hs[0], sm = hs[1];
+        int id = __float_as_int(hs[2]);
+        if (mx > best) { sum = sum * __expf(best - mx) + sm; best = mx; idx = id; }
+        else { sum += sm * __expf(mx - best); if (mx == best && id < idx) idx = id; }
     }
     for (int o = 32; o >= 1; o >>= 1) {
-        float ov = __shfl_xor(best, o);
+        float om = __shfl_xor(best, o), os = __shfl_xor(sum, o);
         int oi = __shfl_xor(idx, o);
-        if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+        float nm = fmaxf(best, om);
+        float a = (best == -INFINITY) ? 0.f : sum * __expf(best - nm);
+        float b = (om == -INFINITY) ? 0.f : os * __expf(om - nm);
+        if (om > best || (om == best && oi < idx)) idx = oi;
+        best = nm;
+        sum = a + b;
     }
-    if (lane == 0) { bv[wave] = best; bi[wave] = idx; }
-    __syncthreads();
-    best = bv[0]; idx = bi[0];
-    for (int w = 1; w < 16; w++)
-        if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
-    float sum = 0.f;
-    for (int i = t; i < V; i += 1024) sum += __expf((z[i] - best) * inv_temp);
-    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o);
-    if (lane == 0) bs[wave] = sum;
+    if (lane == 0) { bm[wave] = best; bs[wave] = sum; bi[wave] = idx; }
     __syncthreads();
     if (t == 0) {
-        float s = 0.f;
-        for (int w = 0; w < 16; w++) s += bs[w];
+        best = bm[0]; sum = bs[0]; idx = bi[0];
+        for (int w = 1; w < 4; w++) {
+            float nm = fmaxf(best, bm[w]);
+            float a = (best == -INFINITY) ? 0.f : sum * __expf(best - nm);
+            float b = (bm[w] == -INFINITY) ? 0.f : bs[w] * __expf(bm[w] - nm);
+            if (bm[w] > best || (bm[w] == best && bi[w] < idx)) idx = bi[w];
+            best = nm;
+            sum = a + b;
+        }
         tok_out[m] = idx;
-        conf_out[m] = 1.f / s;
+        conf_out[m] = 1.f / sum;
     }
 }
 
