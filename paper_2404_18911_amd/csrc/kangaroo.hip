@@ -39,7 +39,7 @@ struct kg_ctx {
     size_t kv_bytes, scratch_bytes;
     // scratch layout (byte offsets)
     size_t s_x0, s_x1, s_F, s_qkv, s_actX, s_actA, s_actF, s_ssq0, s_ssq1, s_opart, s_mxs, s_sms, s_cnt,
-        s_dlog, s_tlog, s_tok, s_conf, s_pt, s_rope, s_invf, s_misc, s_hstat;
+        s_dlog, s_tlog, s_tok, s_conf, s_pt, s_rope, s_invf, s_misc, s_hstat, s_dstat, s_tstat, s_acc;
     // bindings
     char *arena = nullptr, *kv = nullptr, *scr = nullptr;
     hipStream_t stream = nullptr;
@@ -152,6 +152,9 @@ void layout(kg_ctx *x)
     x->s_invf = take((size_t)(c.head_dim / 2) * 8);
     x->s_misc = take((size_t)2 * d * 4);
     x->s_hstat = take((size_t)(V / 16) * KG_ROWS * 4 * 4);
+    x->s_dstat = take(KG_ROWS * 2 * 4);
+    x->s_tstat = take(KG_ROWS * 2 * 4);
+    x->s_acc = take(2 * 4);
     x->scratch_bytes = o;
 }
 
@@ -217,7 +220,7 @@ int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Ep
     if (N % 16) return fail(x, KG_EINVAL, "projection rows %d not a multiple of 16", N);
     ProfScope ps(x, 0, (double)N * K * x->esz);
     static const int gemv_u = getenv("KG_GEMV_U") ? atoi(getenv("KG_GEMV_U")) : 8;
-    if (x->bf && gemv_u >= 16)
+    if (x->bf && (gemv_u >= 16 || (gemv_u == 12 && N / 16 <= 512)))
         hipLaunchKernelGGL(gemv_bf16_kernel<16>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
                            at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
     else if (x->bf)
@@ -341,16 +344,32 @@ int run_layers(kg_ctx *x, int lo, int hi, int M, int pos0, const float *x_first,
 
 // LM head on the rows packed in actX (+ssq0): logits rows (m + row_shift) of `logits`, then
 // arg-max and top-1 probability of rows 0..n_out-1 into the device tok/conf arrays.
-int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float inv_temp)
+// u: per-row uniform numbers for sampling (mode 1), stat: where the rows' (max, sum exp) go.
+int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float inv_temp, int mode = 0,
+             const float *u = nullptr, float *stat = nullptr)
 {
     Epi e = epi_base(x, EPI_HEAD, M, x->c.vocab);
     e.ssq_in = at<float>(x->scr, x->s_ssq0); e.out = logits; e.row_shift = row_shift;
     e.hstat = at<float>(x->scr, x->s_hstat); e.inv_temp = inv_temp;
     KGCHK(launch_gemv(x, x->head, x->c.vocab, x->c.d_model, x->scr + x->s_actX, e));
     ProfScope ps(x, 2, 0.0);
-    hipLaunchKernelGGL(head_final_kernel, dim3(n_out), dim3(256), 0, x->stream, at<const float>(x->scr, x->s_hstat),
-                       x->c.vocab / 16, at<int>(x->scr, x->s_tok), at<float>(x->scr, x->s_conf));
+    F8 uu;
+    for (int i = 0; i < KG_ROWS; i++) uu.v[i] = (u && i < n_out) ? u[i] : 0.f;
+    hipLaunchKernelGGL(head_final_kernel, dim3(n_out), dim3(1024), 0, x->stream, at<const float>(x->scr, x->s_hstat),
+                       x->c.vocab / 16, (const float *)logits, x->c.vocab, inv_temp, mode, uu, at<int>(x->scr, x->s_tok),
+                       at<float>(x->scr, x->s_conf), stat ? stat : at<float>(x->scr, x->s_tstat));
     return check_launch(x, "head_final");
+}
+
+// uniform number of (absolute position, purpose) for sampling mode
+int uniform_at(kg_ctx *x, const kg_params *p, int pos, int purpose, float *out)
+{
+    if (p->mode != 1) { *out = 0.f; return KG_OK; }
+    if (pos < 0 || pos >= p->n_uniform_positions) return fail(x, KG_EINVAL, "uniforms cover %d positions, position %d needed", p->n_uniform_positions, pos);
+    float u = p->uniforms[(size_t)pos * 3 + purpose];
+    if (!(u >= 0.f && u < 1.f)) return fail(x, KG_EINVAL, "uniform number outside [0,1)");
+    *out = u;
+    return KG_OK;
 }
 
 int fetch_results(kg_ctx *x, int n)
@@ -625,6 +644,8 @@ int kg_prefill(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n, int3
     if (n + 1 + p->gamma + 1 > c.max_seq) return fail(x, KG_ENOSPC, "prompt of %d tokens does not fit max_seq %d", n, c.max_seq);
     for (int i = 0; i < n; i++)
         if (prompt[i] < 0 || prompt[i] >= c.vocab) return fail(x, KG_EINVAL, "prompt token %d out of range", prompt[i]);
+    float u_first = 0.f;
+    KGCHK(uniform_at(x, p, n, 2, &u_first));
     KGCHK(kg_reset(x));
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     for (int pos0 = 0; pos0 < n; pos0 += KG_ROWS) {
@@ -632,7 +653,7 @@ int kg_prefill(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n, int3
         KGCHK(run_shallow(x, prompt + pos0, M, pos0, 0));
         KGCHK(run_adapter(x, 1, M, pos0, false));
         KGCHK(run_deep(x, M, pos0));
-        if (pos0 + M == n) KGCHK(run_head(x, M, -(M - 1), at<float>(x->scr, x->s_tlog), 1, inv_t));
+        if (pos0 + M == n) KGCHK(run_head(x, M, -(M - 1), at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first));
     }
     KGCHK(fetch_results(x, 1));
     x->base = n; x->adapter_len = n; x->lag = 0;
@@ -656,6 +677,8 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     if (x->base + j + 2 >= x->c.max_seq) return fail(x, KG_ENOSPC, "sequence would exceed max_seq");
     const int tok = j == 0 ? x->pending : x->drafts[j - 1];
     const int pos = x->base + j;
+    float u_draft = 0.f;
+    KGCHK(uniform_at(x, p, pos + 1, 0, &u_draft));
     KGCHK(run_shallow(x, &tok, 1, pos, j));
     int M = 1;
     if (j == 0 && x->lag) {                       // adapter catches up on [lagged f, f_0] (Figure 2)
@@ -666,7 +689,7 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     }
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     float *dl = at<float>(x->scr, x->s_dlog) + (size_t)j * x->c.vocab;
-    KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t));
+    KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t, p->mode, &u_draft, at<float>(x->scr, x->s_dstat) + 2 * j));
     KGCHK(fetch_results(x, 1));
     x->lag = 0;
     x->adapter_len = pos + 1;
@@ -708,12 +731,36 @@ int kg_accept(kg_ctx *x, const kg_params *p, int32_t *emitted, int *n_emitted)
     KGCHK(check_params(x, p));
     if (!emitted || !n_emitted) return fail(x, KG_EINVAL, "NULL output");
     if (x->phase != Phase::VERIFIED) return fail(x, KG_ESTATE, "accept needs a verified round");
-    if (p->mode != 0) return fail(x, KG_EINVAL, "sampling-mode acceptance is not built yet");
     const int k = x->n_drafts;
     int n = 0;
-    while (n < k && x->drafts[n] == x->targets[n]) n++;
-    for (int i = 0; i < n; i++) emitted[i] = x->drafts[i];
-    emitted[n] = x->targets[n];
+    if (p->mode == 0) {
+        while (n < k && x->drafts[n] == x->targets[n]) n++;
+        for (int i = 0; i < n; i++) emitted[i] = x->drafts[i];
+        emitted[n] = x->targets[n];
+    } else {
+        I8 dr;
+        F8 ua, ur;
+        for (int i = 0; i < KG_ROWS; i++) { dr.v[i] = i < k ? x->drafts[i] : 0; ua.v[i] = 0.f; ur.v[i] = 0.f; }
+        for (int i = 0; i <= k; i++) {             // row i decides the token at position base + i + 1
+            if (i < k) KGCHK(uniform_at(x, p, x->base + i + 1, 1, &ua.v[i]));
+            KGCHK(uniform_at(x, p, x->base + i + 1, 2, &ur.v[i]));
+        }
+        {
+            ProfScope ps(x, 2, 0.0);
+            hipLaunchKernelGGL(accept_sample_kernel, dim3(1), dim3(1024), 0, x->stream, at<const float>(x->scr, x->s_tlog),
+                               at<const float>(x->scr, x->s_dlog), at<const float>(x->scr, x->s_tstat),
+                               at<const float>(x->scr, x->s_dstat), x->c.vocab, k, 1.f / p->temperature, dr, ua, ur,
+                               at<int>(x->scr, x->s_acc));
+            KGCHK(check_launch(x, "accept_sample"));
+        }
+        HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_acc, 8, hipMemcpyDeviceToHost, x->stream));
+        HIPCHK(x, hipStreamSynchronize(x->stream));
+        if (x->profiling) prof_collect(x);
+        n = x->h_tok[0];
+        if (n < 0 || n > k) return fail(x, KG_EHIP, "acceptance kernel returned %d accepted drafts of %d", n, k);
+        for (int i = 0; i < n; i++) emitted[i] = x->drafts[i];
+        emitted[n] = x->h_tok[1];
+    }
     *n_emitted = n + 1;
     // rollback: caches are cut by length; the adapter saw f_0..f_{k-1} only
     const int old = x->base;
@@ -783,7 +830,9 @@ int kg_plain_step(kg_ctx *x, const kg_params *p, int32_t token, int32_t *next_to
                            at<float>(x->scr, x->s_ssq0)));
     KGCHK(run_layers(x, 0, c.n_layers, 1, x->plain_len, x0, x0, at<const float>(x->arena, x->gfinal)));
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
-    KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t));
+    float u_next = 0.f;
+    KGCHK(uniform_at(x, p, x->plain_len + 1, 2, &u_next));
+    KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_next));
     KGCHK(fetch_results(x, 1));
     x->plain_len++;
     x->n_target_rows = 1;

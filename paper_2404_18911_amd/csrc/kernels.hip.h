@@ -652,17 +652,71 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Final reduction of the per-tile LM-head statistics: arg-max (lowest index among equal maxima)
-// and top-1 probability of softmax(z / T) = 1 / sum exp((z - max) / T).  One block per row.
-__global__ __launch_bounds__(256) void head_final_kernel(const float *hstat, int n_tiles, int *tok_out,
-                                                         float *conf_out)
+// Block-wide inverse-CDF draw (1024 threads): smallest index n with w(0) + .. + w(n) > u * total,
+// walking ascending indices; weights are accumulated in double.  Returns -1 when total == 0.
+// All threads must call it; all get the result.
+struct F8 { float v[KG_ROWS]; };
+struct I8 { int v[KG_ROWS]; };
+
+template <class F>
+__device__ int block_inverse_cdf(F w, int V, float u)
 {
-    __shared__ float bm[4], bs[4];
-    __shared__ int bi[4];
+    __shared__ double wsum[16];
+    __shared__ int found, lastpos;
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const int chunk = (V + 1023) >> 10;
+    const int i0 = min(V, t * chunk), i1 = min(V, i0 + chunk);
+    double local = 0.0;
+    for (int i = i0; i < i1; i++) local += (double)w(i);
+    double incl = local;                                   // inclusive scan inside the wave
+    for (int o = 1; o < 64; o <<= 1) {
+        double v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    if (t == 0) { found = -1; lastpos = -1; }
+    __syncthreads();
+    double base = 0.0, total = 0.0;
+    for (int k = 0; k < 16; k++) {
+        if (k < wave) base += wsum[k];
+        total += wsum[k];
+    }
+    if (total <= 0.0) return -1;
+    const double thr = (double)u * total;
+    const double excl = base + incl - local;
+    if (excl <= thr && excl + local > thr) {
+        double acc = excl;
+        for (int i = i0; i < i1; i++) {
+            acc += (double)w(i);
+            if (acc > thr) { found = i; break; }
+        }
+    }
+    __syncthreads();
+    if (found >= 0) return found;
+    // u * total landed beyond the accumulated mass by rounding: last index with weight
+    int lp = -1;
+    for (int i = i0; i < i1; i++) if (w(i) > 0.f) lp = i;
+    if (lp >= 0) atomicMax(&lastpos, lp);
+    __syncthreads();
+    return lastpos;
+}
+
+// Final reduction of the per-tile LM-head statistics for one row per block: arg-max (lowest index
+// among equal maxima) and top-1 probability of softmax(z / T) = 1 / sum exp((z - max) / T).
+// mode 1 additionally draws the token from softmax(z / T) with the row's uniform number.
+// stat_out[row] = (max of z/T, sum exp(z/T - max)).
+__global__ __launch_bounds__(1024) void head_final_kernel(const float *hstat, int n_tiles, const float *logits,
+                                                          int V, float inv_temp, int mode, F8 u, int *tok_out,
+                                                          float *conf_out, float *stat_out)
+{
+    __shared__ float bm[16], bs[16];
+    __shared__ int bi[16];
+    __shared__ float fin[2];
+    __shared__ int fin_i;
     const int m = blockIdx.x, t = threadIdx.x, wave = t >> 6, lane = t & 63;
     float best = -INFINITY, sum = 0.f;
     int idx = 0x7FFFFFFF;
-    for (int i = t; i < n_tiles; i += 256) {
+    for (int i = t; i < n_tiles; i += 1024) {
         const float *hs = hstat + ((size_t)i * KG_ROWS + m) * 4;
         float mx = hs[0], sm = hs[1];
         int id = __float_as_int(hs[2]);
@@ -683,7 +737,7 @@ __global__ __launch_bounds__(256) void head_final_kernel(const float *hstat, int
     __syncthreads();
     if (t == 0) {
         best = bm[0]; sum = bs[0]; idx = bi[0];
-        for (int w = 1; w < 4; w++) {
+        for (int w = 1; w < 16; w++) {
             float nm = fmaxf(best, bm[w]);
             float a = (best == -INFINITY) ? 0.f : sum * __expf(best - nm);
             float b = (bm[w] == -INFINITY) ? 0.f : bs[w] * __expf(bm[w] - nm);
@@ -691,9 +745,59 @@ __global__ __launch_bounds__(256) void head_final_kernel(const float *hstat, int
             best = nm;
             sum = a + b;
         }
-        tok_out[m] = idx;
+        fin[0] = best; fin[1] = sum; fin_i = idx;
         conf_out[m] = 1.f / sum;
+        stat_out[2 * m] = best;
+        stat_out[2 * m + 1] = sum;
+        if (mode == 0) tok_out[m] = idx;
     }
+    if (mode == 0) return;
+    __syncthreads();
+    const float mx = fin[0];
+    const float *z = logits + (size_t)m * V;
+    int tok = block_inverse_cdf([&](int i) { return __expf(z[i] * inv_temp - mx); }, V, u.v[m]);
+    if (t == 0) tok_out[m] = tok < 0 ? fin_i : tok;
+}
+
+// Speculative-sampling acceptance of one round (Section 3: the first rejected draft discards the
+// rest; the sampling distribution of the target is preserved).  Draft d_i ~ q_i is kept while
+// u_acc[i] < min(1, p_i(d_i) / q_i(d_i)); the first rejected position is redrawn from
+// normalize(max(0, p_i - q_i)); if all k are kept a bonus token is drawn from p_k.
+// zt: target logits [k+1][V], zd: draft logits [k][V]; tstat/dstat: (max, sum exp) per row of z/T.
+// out[0] = number of accepted drafts, out[1] = the redrawn / bonus token.
+__global__ __launch_bounds__(1024) void accept_sample_kernel(const float *zt, const float *zd, const float *tstat,
+                                                             const float *dstat, int V, int k, float inv_temp,
+                                                             I8 drafts, F8 u_acc, F8 u_res, int *out)
+{
+    __shared__ int n_acc;
+    const int t = threadIdx.x;
+    if (t == 0) {
+        int n = 0;
+        while (n < k) {
+            int dd = drafts.v[n];
+            float pp = __expf(zt[(size_t)n * V + dd] * inv_temp - tstat[2 * n]) / tstat[2 * n + 1];
+            float qq = __expf(zd[(size_t)n * V + dd] * inv_temp - dstat[2 * n]) / dstat[2 * n + 1];
+            float a = fminf(1.f, pp / qq);
+            if (u_acc.v[n] < a) n++;
+            else break;
+        }
+        n_acc = n;
+    }
+    __syncthreads();
+    const int n = n_acc;
+    const float *zp = zt + (size_t)n * V;
+    const float pm = tstat[2 * n], ps = 1.f / tstat[2 * n + 1];
+    int tok = -1;
+    if (n < k) {
+        const float *zq = zd + (size_t)n * V;
+        const float qm = dstat[2 * n], qs = 1.f / dstat[2 * n + 1];
+        tok = block_inverse_cdf(
+            [&](int i) { return fmaxf(0.f, __expf(zp[i] * inv_temp - pm) * ps - __expf(zq[i] * inv_temp - qm) * qs); }, V,
+            u_res.v[n]);
+        __syncthreads();
+    }
+    if (tok < 0) tok = block_inverse_cdf([&](int i) { return __expf(zp[i] * inv_temp - pm) * ps; }, V, u_res.v[n]);
+    if (t == 0) { out[0] = n; out[1] = tok; }
 }
 
 // Copy cached k and v rows of one position, widened to float (test / debug access).

@@ -149,3 +149,51 @@ def test_rollback_equals_fresh_prefill_and_page_order_is_irrelevant():
     assert seq[len(prompt):] == ref[: len(seq) - len(prompt)]
     kg.close()
     fresh.close()
+
+
+@pytest.mark.parametrize("name,temp,hs,eta", [("toy", 1.0, 25.0, 0.6), ("toy", 0.7, 25.0, 0.3), ("toy", 1.0, 1.0, 0.6),
+                                              ("small_bf16", 1.0, 16.0, 0.5)])
+def test_sampling_mode_follows_oracle(name, temp, hs, eta):
+    """Speculative rejection sampling on the GPU against the oracle, same uniform numbers: every
+    draw, accept and reject is the oracle's decision up to a tolerance on the cumulative sums."""
+    from tests import parity as P
+    shape = I.SHAPES[name]
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=hs)
+    prompt = I.gen_prompt(shape.vocab, 16)
+    U = I.gen_uniforms(128, seed=3)
+    kg = P.load_model(shape, W, 120, gamma_max=6, kv_page_tokens=32)
+    tol = tol_for(shape, hs)
+    fol = P.Follow(tol)
+    # a logit error e moves probabilities by a factor (1 +- 2e), cumulative sums by at most 2e
+    out, rounds = P.follow_kangaroo_sampling(kg, _oracle(shape, W, 120), prompt, 48, 6, eta, temp, U, fol, 2 * tol / temp)
+    assert any(n == k for k, n in rounds) and any(n < k for k, n in rounds)
+    print(f"{name} sampling: max logit err {fol.max_logit_err:.3e}, decisions the oracle takes otherwise "
+          f"{fol.exceptions}/{fol.decisions}, rounds {rounds[:12]}")
+    if shape.dtype == "f32":
+        assert fol.exceptions <= 2
+    kg.close()
+
+
+def test_sampling_plain_decoding_follows_oracle():
+    from oracle import kangaroo_oracle as O
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["toy"]
+    W = I.gen_weights(shape, seed=1, alpha=0.1, head_scale=25.0)
+    prompt = I.gen_prompt(shape.vocab, 16)
+    U = I.gen_uniforms(96, seed=5)
+    kg = P.load_model(shape, W, 96, kv_page_tokens=16)
+    p, keep = B.make_params(mode=1, temperature=0.9, uniforms=U)
+    dec = O.PlainDecoder(_oracle(shape, W, 96), mode="sample", temperature=0.9, uniforms=U)
+    t, ot = kg.prefill(p, prompt), dec.prefill(prompt)
+    diff = int(t != ot)
+    seq = [t]
+    for _ in range(40):
+        nt = kg.plain_step(p, seq[-1])
+        ot = dec.step(seq[-1])
+        np.testing.assert_allclose(kg.read_logits(1, 0), dec.last_logits, rtol=0, atol=1e-4 * 25 * 0.32 / 1.63 * 2)
+        assert P._cdf_valid(O.softmax(dec.last_logits, 0.9), nt, float(U[dec.n, 2]), 1e-4)
+        diff += int(nt != ot)
+        seq.append(nt)
+    assert diff <= 1
+    kg.close()
