@@ -1,0 +1,90 @@
+"""GPU parity at the remaining BASELINE shapes: Vicuna-13B-shaped (config 3), Vicuna-33B-shaped
+(config 4) and the 7B-shaped long-context sampling run (config 5).
+
+As at 7B, element-by-element parity with the oracle is taken on a short request of the full model
+(the oracle needs 1-4 s of host time per forward at these sizes), and the full-size request is
+checked through the properties that hold at any size.  Long-context attention (many KV pages,
+cross-page merge) is compared with the oracle on a 7B-wide, two-layer model, where the oracle can
+afford a prompt of more than a thousand tokens.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2404_18911_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_shape(name, alpha, n_prompt, n_new, short_prompt, short_new):
+    from oracle import kangaroo_oracle as O
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES[name]
+    W = I.gen_weights(shape, seed=1, alpha=alpha, threads=16)
+    kg = P.load_model(shape, W, n_prompt + n_new + 8, gamma_max=6, kv_page_tokens=128)
+    prompt = I.gen_prompt(shape.vocab, n_prompt)
+    fol = P.Follow(2e-2)
+    P.follow_kangaroo(kg, O.OracleModel(shape, W, short_prompt + short_new + 16), prompt[:short_prompt], short_new, 6, 0.6, fol)
+    print(f"{name}: max logit err {fol.max_logit_err:.3e}, near-tie exceptions {fol.exceptions}/{fol.decisions}")
+    p, _ = B.make_params(eta=0.6, gamma=6)
+    plain, stp = kg.decode_plain(p, prompt, n_new)
+    out, st = kg.generate(p, prompt, n_new)
+    assert out == plain and len(out) == n_new
+    assert sum(s * c for s, c in enumerate(st.s_hist)) == n_new - 1 and st.s_hist[0] == 0
+    print(f"{name}: plain {(n_new - 1) / stp.t_total_s:.1f} tok/s, kangaroo {(n_new - 1) / st.t_total_s:.1f} tok/s, "
+          f"acceptance {st.accepted}/{st.drafted}")
+    kg.close()
+
+
+def test_13b_shape():
+    _run_shape("13b", 0.1, 512, 256, 12, 3)
+
+
+def test_33b_shape():
+    _run_shape("33b", 0.1, 512, 128, 8, 2)
+
+
+def test_long_context_attention_follows_oracle():
+    """1100-token prompt on a 7B-wide, two-layer model: nine KV pages, cross-page merge, prefill in
+    8-row chunks, then greedy rounds and sampled rounds, against the oracle."""
+    from oracle import kangaroo_oracle as O
+    from tests import parity as P
+    shape = dataclasses.replace(I.with_layers(I.SHAPES["7b"], 2), exit_layer=1)
+    W = I.gen_weights(shape, seed=1, alpha=0.1, threads=16)
+    prompt = I.gen_prompt(shape.vocab, 1100)
+    kg = P.load_model(shape, W, 1150, gamma_max=6, kv_page_tokens=128)
+    fol = P.Follow(2e-2)
+    P.follow_kangaroo(kg, O.OracleModel(shape, W, 1150), prompt, 6, 6, 0.0, fol)
+    print(f"long context: max logit err {fol.max_logit_err:.3e}, near-tie exceptions {fol.exceptions}/{fol.decisions}")
+    kg.close()
+
+
+def test_config5_long_context_sampling_run():
+    """BASELINE config 5 at full size: 7B shape, 4096-token prompt, temperature-1 rejection sampling,
+    256 new tokens.  Checked: the stepwise calls reproduce kg_generate exactly (same uniforms), every
+    round emits 1..gamma+1 tokens, the stream is a function of the uniforms only (a second run is
+    identical), and on a short prompt every sampled decision is the oracle's up to tolerance."""
+    from oracle import kangaroo_oracle as O
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["7b"]
+    W = I.gen_weights(shape, seed=1, alpha=0.1, threads=16)
+    n_prompt, n_new = 4096, 256
+    kg = P.load_model(shape, W, n_prompt + n_new + 8, gamma_max=6, kv_page_tokens=128)
+    U = I.gen_uniforms(n_prompt + n_new + 16, seed=3)
+    prompt = I.gen_prompt(shape.vocab, n_prompt)
+    p, keep = B.make_params(mode=1, temperature=1.0, eta=0.6, gamma=6, uniforms=U)
+    out, st = kg.generate(p, prompt, n_new)
+    assert len(out) == n_new and sum(s * c for s, c in enumerate(st.s_hist)) == n_new - 1
+    assert st.s_hist[0] == 0 and all(st.s_hist[s] == 0 for s in range(3, 9))     # k = 1 with random-init weights
+    out2, _ = kg.generate(p, prompt, n_new)
+    assert out2 == out
+    print(f"config 5: {(n_new - 1) / st.t_total_s:.1f} tok/s, acceptance {st.accepted}/{st.drafted}")
+    # short-prompt follow in sampling mode
+    fol = P.Follow(2e-2)
+    P.follow_kangaroo_sampling(kg, O.OracleModel(shape, W, 64), prompt[:20], 6, 6, 0.6, 1.0, U, fol, 4e-2)
+    print(f"config 5 short follow: max logit err {fol.max_logit_err:.3e}, decisions the oracle takes otherwise "
+          f"{fol.exceptions}/{fol.decisions}")
+    kg.close()
