@@ -27,6 +27,19 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def profiled_traffic():
+    """HBM bytes per projection launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs of this very command, scaled by a copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "gemv_bf16_attn_7b_kangaroo_decode.txt")
+    try:
+        for line in open(path):
+            if line.strip().startswith("TRAFFIC_BYTES_PER_PROJECTION_LAUNCH"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -112,6 +125,15 @@ def main():
     def sync():
         torch.cuda.synchronize()
 
+    # a plain device-to-device copy of known size (1 GiB read + 1 GiB written): the reference that
+    # the HBM traffic counters of a profiler run are scaled by
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_src.zero_()
+    cal_dst.copy_(cal_src)
+    sync()
+    del cal_src, cal_dst
+
     for _ in range(args.warmup):
         kg.generate(p, prompt, args.new)
     sync()
@@ -151,7 +173,8 @@ def main():
         g_bytes, g_s, g_n = pr.bytes[0], pr.seconds[0], pr.launches[0]
         ach = g_bytes / g_s / 1e9
         res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "frac": ach / HBM_PEAK_GBS,
+                           "traffic": profiled_traffic() if args.shape == "7b" else None,
                            "kernel": "gemv_bf16_kernel", "launches": int(g_n),
                            "avg_launch_us": 1e6 * g_s / g_n, "avg_launch_bytes": g_bytes / g_n}
         res["device_time_share"] = {"projections": pr.seconds[0], "attention": pr.seconds[1], "other": pr.seconds[2]}

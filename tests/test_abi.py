@@ -1,0 +1,102 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, and its host logic (configuration checks, call order, sizes) behaves as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2404_18911_amd import binding as B
+from paper_2404_18911_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "kangaroo.h")).read()
+    declared = set(re.findall(r"\b(kg_[a-z_0-9]+)\s*\(", hdr))
+    declared -= {"kg_ctx"}
+    assert declared == set(B.SYMBOLS), declared ^ set(B.SYMBOLS)
+    L = B.lib()
+    for s in declared:
+        assert hasattr(L, s), s
+
+
+def _create(shape, **over):
+    cfg = B.make_config(shape, over.pop("max_seq", 64), over.pop("gamma_max", 6), over.pop("kv_page_tokens", 16))
+    for k, v in over.items():
+        setattr(cfg, k, v)
+    h = ctypes.c_void_p()
+    rc = B.lib().kg_create(ctypes.byref(cfg), ctypes.byref(h))
+    return rc, h
+
+
+def test_create_validates_the_configuration():
+    shape = I.SHAPES["toy"]
+    rc, h = _create(shape)
+    assert rc == B.KG_OK and h.value
+    B.lib().kg_destroy(h)
+    for bad in (dict(exit_layer=0), dict(exit_layer=5), dict(head_dim=48), dict(n_heads=3), dict(gamma_max=8),
+                dict(kv_page_tokens=24), dict(kv_page_tokens=256), dict(dtype=2), dict(dtype=0, kv_dtype=1),
+                dict(vocab=1000), dict(max_seq=1), dict(max_seq=16 * 129)):
+        rc, h = _create(shape, **bad)
+        assert rc == B.KG_EINVAL and not h.value, bad
+
+
+def test_workspace_sizes_match_the_shape():
+    L = B.lib()
+    for name in ("toy", "7b", "33b"):
+        shape = I.SHAPES[name]
+        rc, h = _create(shape, max_seq=520, kv_page_tokens=128)
+        assert rc == B.KG_OK
+        wb, kb, sb = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+        assert L.kg_workspace_bytes(h, ctypes.byref(wb), ctypes.byref(kb), ctypes.byref(sb)) == B.KG_OK
+        params = shape.n_layers * shape.layer_params() + shape.adapter_params() + 2 * shape.head_params() + shape.d_model
+        esz = shape.bytes_per_weight()
+        # the tiled arena holds every matrix once (gains as fp32): within 1% of the raw parameter bytes
+        assert params * esz <= wb.value <= params * esz * 1.01 + (1 << 20)
+        pages = (520 + 127) // 128
+        kvb = pages * 128 * (shape.n_layers + 1) * 2 * shape.d_model * (4 if shape.kv_dtype == "f32" else 2)
+        assert kb.value == kvb
+        assert sb.value > 0
+        L.kg_destroy(h)
+
+
+def test_calls_before_bind_are_call_order_errors():
+    L = B.lib()
+    rc, h = _create(I.SHAPES["toy"])
+    p, _ = B.make_params()
+    tok, conf, stop = ctypes.c_int32(), ctypes.c_float(), ctypes.c_int32()
+    prompt = (ctypes.c_int32 * 4)(1, 2, 3, 4)
+    assert L.kg_prefill(h, ctypes.byref(p), prompt, 4, ctypes.byref(tok)) == B.KG_ESTATE
+    assert b"kg_bind" in L.kg_last_error(h)
+    assert L.kg_draft_step(h, ctypes.byref(p), ctypes.byref(tok), ctypes.byref(conf), ctypes.byref(stop)) == B.KG_ESTATE
+    buf = (ctypes.c_int32 * 8)()
+    n = ctypes.c_int32()
+    assert L.kg_verify(h, ctypes.byref(p), buf, ctypes.byref(n)) == B.KG_ESTATE
+    assert L.kg_accept(h, ctypes.byref(p), buf, ctypes.byref(n)) == B.KG_ESTATE
+    assert L.kg_load_tensor(h, 0, -1, None, 0) == B.KG_ESTATE
+    assert L.kg_bind(h, None, 0, None, 0, None, 0, None) == B.KG_EINVAL
+    assert L.kg_bind(h, 256, 1, 256, 1, 512, 1, None) == B.KG_ENOSPC          # sizes are checked before any device use
+    assert L.kg_bind(h, 257, 1 << 40, 256, 1 << 40, 512, 1 << 40, None) == B.KG_EINVAL   # alignment
+    assert L.kg_set_page_order(h, (ctypes.c_int32 * 4)(0, 1, 2, 2), 4) == B.KG_EINVAL
+    assert L.kg_set_page_order(h, (ctypes.c_int32 * 4)(3, 1, 2, 0), 4) == B.KG_OK
+    assert L.kg_create(None, None) == B.KG_EINVAL
+    L.kg_destroy(h)
+
+
+def test_op_helpers_report_sizes_and_reject_bad_shapes():
+    L = B.lib()
+    assert L.kg_op_packed_bytes(1, 4096, 4096) == 4096 * 4096 * 2
+    assert L.kg_op_packed_bytes(1, 1024, 688) == 1024 * 704 * 2      # K padded to a multiple of 32
+    assert L.kg_op_packed_bytes(0, 64, 48) == 64 * 48 * 4
+    assert L.kg_op_work_bytes(4096) == 4096 * 32
+    assert L.kg_op_pack(1, 256, 17, 64, 256, None) == B.KG_EINVAL
+    assert L.kg_op_linear(1, 256, 64, 64, 256, 9, 256, 256, None) == B.KG_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
