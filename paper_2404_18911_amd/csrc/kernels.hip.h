@@ -63,7 +63,9 @@ __device__ __forceinline__ void st_dev(float *p, float v) { __hip_atomic_store(p
 __device__ __forceinline__ float ld_dev(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // Store activation value v of row m, feature k, for a consumer projection with K features.
-// BF: bf16 hi/lo parts in B-operand tile layout [k/32][lane = (k%32/8)*16 + col][k%8], col = m (hi), m+8 (lo).
+// BF: bf16 hi/lo parts in 1 KB tiles per 32 features, [k/32][row m][part hi|lo][k%32/8][k%8]: the
+// 128 bytes of one batch row and k-step are contiguous, so a wave that needs M rows touches M cache
+// lines per tile.  MFMA lane (g = lane/16, column j) reads slot ((j%8)*2 + j/8)*4 + g, see b_slot().
 // else: plain float [m][K].
 template <bool BF>
 __device__ __forceinline__ void store_act(void *buf, int K, int m, int k, float v)
@@ -72,13 +74,15 @@ __device__ __forceinline__ void store_act(void *buf, int K, int m, int k, float 
         uint16_t hi = f2bf(v);
         uint16_t lo = f2bf(v - bf2f(hi));
         uint16_t *p = (uint16_t *)buf;
-        size_t base = ((size_t)(k >> 5) * 64 + ((k >> 3) & 3) * 16 + m) * 8 + (k & 7);
+        size_t base = (size_t)(k >> 5) * 512 + (size_t)(m * 8 + ((k >> 3) & 3)) * 8 + (k & 7);
         p[base] = hi;
-        p[base + 64] = lo;
+        p[base + 32] = lo;
     } else {
         ((float *)buf)[(size_t)m * K + k] = v;
     }
 }
+// 16-byte slot of MFMA lane `lane` inside a B-operand tile (column j < 8: hi part of row j; j >= 8: lo part of row j-8)
+__device__ __forceinline__ int b_slot(int lane) { return (((lane & 7) * 2 + ((lane >> 3) & 1)) << 2) + (lane >> 4); }
 
 // scale[m] = rsqrt(mean square of the input row + eps), from per-tile partial sums, fixed order.
 // Wave w of an 8-wave block serves batch row w.  The partials (at most 8 per lane: d <= 8192) are
@@ -234,7 +238,7 @@ __global__ __launch_bounds__(64 * GEMV_WAVES, UMAX >= 16 ? 1 : 2) void gemv_bf16
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ks0 = (wave * KS) / GEMV_WAVES, ks1 = ((wave + 1) * KS) / GEMV_WAVES;
     const u32x4_t *wp = W + ((size_t)rt * KS + ks0) * 64 + lane;
-    const u32x4_t *bp = act + (size_t)ks0 * 64 + lane;
+    const u32x4_t *bp = act + (size_t)ks0 * 64 + b_slot(lane);
     const bool bact = (lane & 7) < e.M;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     ScaleRegs sr;
