@@ -254,7 +254,32 @@ __global__ __launch_bounds__(64 * GEMV_WAVES, UMAX >= 16 ? 1 : 2) void gemv_bf16
         while (n >= 16) { gemv_steps<16>(wp, bp, bact, acc); n -= 16; }
         if (n >= 8) { gemv_steps<8>(wp, bp, bact, acc); n -= 8; }
     } else {
-        while (n >= 8) { gemv_steps<8>(wp, bp, bact, acc); n -= 8; }
+        // chunks of 4 tiles, double-buffered: the loads of chunk i+1 are in flight while chunk i is
+        // multiplied, so a wave never drains its memory pipe between chunks
+        const u32x4_t zero = {0u, 0u, 0u, 0u};
+        u32x4_t a0[4], b0[4], a1[4], b1[4];
+        int rem = n >> 2;
+        n &= 3;
+#define LD4(A, B)                                                                  \
+    {                                                                              \
+        _Pragma("unroll") for (int u = 0; u < 4; u++) A[u] = __builtin_nontemporal_load(wp + u * 64); \
+        _Pragma("unroll") for (int u = 0; u < 4; u++) B[u] = bact ? bp[u * 64] : zero;                \
+        wp += 256; bp += 256;                                                      \
+    }
+#define MMA4(A, B)                                                                 \
+    _Pragma("unroll") for (int u = 0; u < 4; u++)                                  \
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, A[u]), __builtin_bit_cast(bf16x8_t, B[u]), acc, 0, 0, 0);
+        if (rem) LD4(a0, b0)
+        while (rem >= 2) {
+            LD4(a1, b1)
+            MMA4(a0, b0)
+            if (rem > 2) LD4(a0, b0)
+            MMA4(a1, b1)
+            rem -= 2;
+        }
+        if (rem == 1) { MMA4(a0, b0) }
+#undef LD4
+#undef MMA4
     }
     if (n >= 4) { gemv_steps<4>(wp, bp, bact, acc); n -= 4; }
     if (n >= 2) { gemv_steps<2>(wp, bp, bact, acc); n -= 2; }
