@@ -97,6 +97,13 @@ typedef struct kg_stats {
     double t_draft_s, t_verify_s, t_total_s; /* host wall-clock spent in each phase */
 } kg_stats;
 
+/* Metrics of Section 3 from the counters of a run: compression rate CR = mean tokens emitted per
+ * forward of the large model (Eq. 1), and the consistent token acceptance rate CTAR(w) = share of
+ * rounds in which the first w drafts were all accepted, i.e. that emitted more than w tokens
+ * (Eq. 2).  Both return KG_EINVAL for a run without rounds. */
+int kg_stats_cr(const kg_stats *st, double *cr);
+int kg_stats_ctar(const kg_stats *st, int w, double *ctar);
+
 /* Create a context for a shape.  Host-only: no device is touched.  *out is NULL on failure. */
 int kg_create(const kg_config *cfg, kg_ctx **out);
 

@@ -42,7 +42,7 @@ class kg_profile(ctypes.Structure):
 
 
 # every symbol include/kangaroo.h declares
-SYMBOLS = ["kg_create", "kg_workspace_bytes", "kg_bind", "kg_load_tensor", "kg_set_page_order", "kg_prefill",
+SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "kg_bind", "kg_load_tensor", "kg_set_page_order", "kg_prefill",
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
            "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear"]
@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
     L = ctypes.CDLL(path)
     vp, ip, fp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)
     szp, pp = ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(kg_params)
+    L.kg_stats_cr.argtypes = [ctypes.POINTER(kg_stats), ctypes.POINTER(ctypes.c_double)]
+    L.kg_stats_ctar.argtypes = [ctypes.POINTER(kg_stats), ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     L.kg_create.argtypes = [ctypes.POINTER(kg_config), ctypes.POINTER(vp)]
     L.kg_workspace_bytes.argtypes = [vp, szp, szp, szp]
     L.kg_bind.argtypes = [vp, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
@@ -92,6 +94,20 @@ def lib() -> ctypes.CDLL:
     L.kg_op_linear.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_int, vp, vp, vp]
     _lib = L
     return L
+
+
+def stats_cr(st: kg_stats) -> float:
+    out = ctypes.c_double()
+    if lib().kg_stats_cr(ctypes.byref(st), ctypes.byref(out)) != KG_OK:
+        raise ValueError("no rounds")
+    return out.value
+
+
+def stats_ctar(st: kg_stats, w: int) -> float:
+    out = ctypes.c_double()
+    if lib().kg_stats_ctar(ctypes.byref(st), w, ctypes.byref(out)) != KG_OK:
+        raise ValueError("no rounds or bad window")
+    return out.value
 
 
 class KangarooError(RuntimeError):

@@ -465,6 +465,26 @@ double now_s()
 // ================================================================================================
 extern "C" {
 
+int kg_stats_cr(const kg_stats *st, double *cr)
+{
+    if (!st || !cr || st->rounds < 1) return KG_EINVAL;
+    long tokens = 0, rounds = 0;
+    for (int s = 0; s <= KG_MAX_ROWS; s++) { tokens += (long)s * st->s_hist[s]; rounds += st->s_hist[s]; }
+    if (rounds < 1) return KG_EINVAL;
+    *cr = (double)tokens / (double)rounds;
+    return KG_OK;
+}
+
+int kg_stats_ctar(const kg_stats *st, int w, double *ctar)
+{
+    if (!st || !ctar || w < 1) return KG_EINVAL;
+    long over = 0, rounds = 0;
+    for (int s = 0; s <= KG_MAX_ROWS; s++) { rounds += st->s_hist[s]; if (s - w > 0) over += st->s_hist[s]; }
+    if (rounds < 1) return KG_EINVAL;
+    *ctar = (double)over / (double)rounds;
+    return KG_OK;
+}
+
 int kg_create(const kg_config *cfg, kg_ctx **out)
 {
     if (out) *out = nullptr;

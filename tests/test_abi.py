@@ -100,3 +100,27 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_stats_metrics_match_eq1_eq2_golden_values():
+    """kg_stats_cr / kg_stats_ctar on the hand-worked list of tests/golden/metrics_eq1_eq2.txt."""
+    S, cr, ct = None, None, {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "metrics_eq1_eq2.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        p = line.split()
+        if p[0] == "S":
+            S = [int(v) for v in p[1:]]
+        elif p[0] == "CR":
+            cr = float(p[1])
+        else:
+            ct[int(p[1])] = float(p[2])
+    st = B.kg_stats()
+    st.rounds = len(S)
+    for s in S:
+        st.s_hist[s] += 1
+    assert B.stats_cr(st) == cr
+    for w, v in ct.items():
+        assert B.stats_ctar(st, w) == v
+    with pytest.raises(ValueError):
+        B.stats_cr(B.kg_stats())
