@@ -256,6 +256,7 @@ int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
     a.qkv = at<const float>(x->scr, x->s_qkv);
     a.d = c.d_model; a.H = c.n_heads; a.M = M; a.pos0 = pos0; a.P = c.kv_page_tokens; a.logP = x->logP;
     a.page_table = at<const int>(x->scr, x->s_pt);
+    for (int i = 0; i < 16; i++) a.pages[i] = i < x->n_pages ? x->page_order[i] : 0;
     a.kv = x->kv; a.slot = slot; a.n_slots = c.n_layers + 1;
     a.rope = at<const float2>(x->scr, x->s_rope);
     a.opart = at<float>(x->scr, x->s_opart); a.mxs = at<float>(x->scr, x->s_mxs); a.sms = at<float>(x->scr, x->s_sms);

@@ -427,6 +427,7 @@ struct AttnArgs {
     const float *qkv;   // [M][3d]: q | k | v, already RMS-scaled projections
     int d, H, M, pos0, P, logP;
     const int *page_table;
+    int pages[16];      // copy of the first 16 page-table entries (saves a dependent load)
     void *kv;           // pool: [phys page][slot][head][K|V][P][hd]
     int slot, n_slots;
     const float2 *rope; // [max_seq][hd/2]
@@ -441,6 +442,9 @@ struct AttnArgs {
 template <typename T> __device__ __forceinline__ float kv_ld(const T *p);
 template <> __device__ __forceinline__ float kv_ld<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float kv_ld<uint16_t>(const uint16_t *p) { return bf2f(*p); }
+template <typename T> __device__ __forceinline__ float kv_round(float v);     // value as the cache type holds it
+template <> __device__ __forceinline__ float kv_round<float>(float v) { return v; }
+template <> __device__ __forceinline__ float kv_round<uint16_t>(float v) { return bf2f(f2bf(v)); }
 template <typename T> __device__ __forceinline__ void kv_st(T *p, float v);
 template <> __device__ __forceinline__ void kv_st<float>(float *p, float v) { *p = v; }
 template <> __device__ __forceinline__ void kv_st<uint16_t>(uint16_t *p, float v) { *p = f2bf(v); }
@@ -505,6 +509,7 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
     __shared__ float pw[8][16][KG_ROWS];
     __shared__ float ow[8][KG_ROWS][HD];
     __shared__ float mw[8][KG_ROWS], sw[8][KG_ROWS];
+    __shared__ float knew[KG_ROWS][HD], vnew[KG_ROWS][HD];   // this call's k, v rows as the cache holds them
     __shared__ int last_flag;
     const int h = blockIdx.x, s = blockIdx.y, t = threadIdx.x;
     const int wave = t >> 6, lane = t & 63;
@@ -512,7 +517,8 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
     const int p_begin = s << a.logP;
     const int n_valid = min(P, a.pos0 + M - p_begin);      // positions of this page that hold data
     const int n_old = min(P, max(0, a.pos0 - p_begin));    // ... of which were cached before this call
-    T *Kp = (T *)a.kv + ((((size_t)a.page_table[s] * a.n_slots + a.slot) * a.H + h) * 2) * (size_t)P * HD;
+    const int phys = s < 16 ? a.pages[s] : a.page_table[s];
+    T *Kp = (T *)a.kv + ((((size_t)phys * a.n_slots + a.slot) * a.H + h) * 2) * (size_t)P * HD;
     T *Vp = Kp + (size_t)P * HD;
     const float qscale = rsqrtf((float)HD);
 
@@ -543,20 +549,21 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
             const float *k = q + d, *v = q + 2 * d;
             float k0 = k[j], k1 = k[j + HD / 2];
             int pp = pos - p_begin;
-            kv_st<T>(Kp + (size_t)pp * HD + j, k0 * cs.x - k1 * cs.y);
-            kv_st<T>(Kp + (size_t)pp * HD + j + HD / 2, k1 * cs.x + k0 * cs.y);
-            kv_st<T>(Vp + (size_t)pp * HD + j, v[j]);
-            kv_st<T>(Vp + (size_t)pp * HD + j + HD / 2, v[j + HD / 2]);
+            float ka = kv_round<T>(k0 * cs.x - k1 * cs.y), kb = kv_round<T>(k1 * cs.x + k0 * cs.y);
+            float va = kv_round<T>(v[j]), vb = kv_round<T>(v[j + HD / 2]);
+            kv_st<T>(Kp + (size_t)pp * HD + j, ka);
+            kv_st<T>(Kp + (size_t)pp * HD + j + HD / 2, kb);
+            kv_st<T>(Vp + (size_t)pp * HD + j, va);
+            kv_st<T>(Vp + (size_t)pp * HD + j + HD / 2, vb);
+            knew[m][j] = ka; knew[m][j + HD / 2] = kb;
+            vnew[m][j] = va; vnew[m][j + HD / 2] = vb;
         }
     }
     if (a.append_only) return;
     __syncthreads();
-    if (!k_old && pl < n_valid) kreg.load(Kp + (size_t)pl * HD + sub * EL);
-#pragma unroll
-    for (int it = 0; it < NIT; it++) {
-        int pv = wave * 16 + it * RPW + r;
-        if (pv >= n_old && pv < n_valid) vreg[it].load(Vp + (size_t)pv * HD + c * 8);
-    }
+    // positions written by this call are taken from LDS (the very values the cache now holds)
+    const bool k_new = !k_old && pl < n_valid;
+    const int mk = p_begin + pl - a.pos0;
 
     // scores and wave-local softmax
     float pr[KG_ROWS];
@@ -564,8 +571,13 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
     for (int m = 0; m < KG_ROWS; m++) {
         float v = 0.f;
         if (m < M && pl < n_valid) {
+            if (k_new) {
 #pragma unroll
-            for (int i = 0; i < EL; i++) v = fmaf(kreg.get(i), qs[m][sub * EL + i], v);
+                for (int i = 0; i < EL; i++) v = fmaf(knew[mk][sub * EL + i], qs[m][sub * EL + i], v);
+            } else {
+#pragma unroll
+                for (int i = 0; i < EL; i++) v = fmaf(kreg.get(i), qs[m][sub * EL + i], v);
+            }
         }
         v += __shfl_xor(v, 1);
         v += __shfl_xor(v, 2);
@@ -592,13 +604,22 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
         int pw_i = it * RPW + r;
-        if (wave * 16 + pw_i < n_valid) {
+        int pv = wave * 16 + pw_i;
+        if (pv < n_valid) {
+            float vv[8];
+            if (pv >= n_old) {
+#pragma unroll
+                for (int i = 0; i < 8; i++) vv[i] = vnew[p_begin + pv - a.pos0][c * 8 + i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; i++) vv[i] = vreg[it].get(i);
+            }
 #pragma unroll
             for (int m = 0; m < KG_ROWS; m++)
                 if (m < M) {
                     float p = pw[wave][pw_i][m];
 #pragma unroll
-                    for (int i = 0; i < 8; i++) acc[m][i] = fmaf(p, vreg[it].get(i), acc[m][i]);
+                    for (int i = 0; i < 8; i++) acc[m][i] = fmaf(p, vv[i], acc[m][i]);
                 }
         }
     }
@@ -655,6 +676,34 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
     }
     __syncthreads();
     if (!last_flag) return;
+    if (a.S <= 8) {     // few pages: every load of the merge is issued before any is used
+        for (int i = t; i < M * HD; i += 512) {
+            int m = i / HD, e = i % HD;
+            float mv[8], ov[8], sv[8];
+#pragma unroll
+            for (int ss = 0; ss < 8; ss++) {
+                bool in = ss < a.S;
+                mv[ss] = in ? ld_dev(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]) : -INFINITY;
+                ov[ss] = in ? ld_dev(&a.opart[(((size_t)h * a.S + ss) * KG_ROWS + m) * HD + e]) : 0.f;
+                sv[ss] = in ? ld_dev(&a.sms[((size_t)h * a.S + ss) * KG_ROWS + m]) : 0.f;
+            }
+            float gm = -INFINITY;
+#pragma unroll
+            for (int ss = 0; ss < 8; ss++) gm = fmaxf(gm, mv[ss]);
+            float num = 0.f, den = 0.f;
+#pragma unroll
+            for (int ss = 0; ss < 8; ss++) {
+                if (ss < a.S) {
+                    float w = (mv[ss] == -INFINITY) ? 0.f : __expf(mv[ss] - gm);
+                    num += w * ov[ss];
+                    den += w * sv[ss];
+                }
+            }
+            store_act<BF>(a.act_out, d, m, h * HD + e, num / den);
+        }
+        if (t == 0) __hip_atomic_store(&a.cnt[h], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
     // page weights exp(max_page - max_all), through LDS so that the page loop has independent loads
     float (*wgt)[KG_ROWS] = pw[0];                     // reuse: [page][row], S <= 128
     for (int m = wave; m < M; m += 8) {
