@@ -43,6 +43,7 @@ struct kg_ctx {
     // bindings
     char *arena = nullptr, *kv = nullptr, *scr = nullptr;
     hipStream_t stream = nullptr;
+    hipEvent_t ev_fetch = nullptr;
     bool bound = false;
     std::vector<char> loaded; // per (kind, layer) flag
     std::vector<int> page_order;
@@ -58,6 +59,7 @@ struct kg_ctx {
     int targets[KG_MAX_ROWS];
     int n_target_rows = 0;
     int plain_len = 0;
+    int spec_shallow = -1;   // index j of an early feature f_j already computed ahead of the host's decision
     // optional per-launch timing
     bool profiling = false;
     kg_profile prof;
@@ -145,8 +147,8 @@ void layout(kg_ctx *x)
     x->s_cnt = take((size_t)c.n_heads * 4);
     x->s_dlog = take((size_t)KG_ROWS * V * 4);
     x->s_tlog = take((size_t)KG_ROWS * V * 4);
-    x->s_tok = take(KG_ROWS * 4);
-    x->s_conf = take(KG_ROWS * 4);
+    x->s_tok = take(KG_ROWS * 8);            // tokens, then confidences: one 64-byte block, one copy to the host
+    x->s_conf = x->s_tok + KG_ROWS * 4;
     x->s_pt = take((size_t)x->n_pages * 4);
     x->s_rope = take((size_t)c.max_seq * (c.head_dim / 2) * 8);
     x->s_invf = take((size_t)(c.head_dim / 2) * 8);
@@ -233,18 +235,18 @@ int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Ep
 }
 
 int launch_pack_rows(kg_ctx *x, const int *tokens, const float *rows, int M, const float *gain, float *xout,
-                     void *act, float *ssq)
+                     void *act, float *ssq, const int *tok_dev = nullptr)
 {
     Tok8 tk;
     for (int i = 0; i < KG_ROWS; i++) tk.t[i] = (tokens && i < M) ? tokens[i] : 0;
-    const void *emb = tokens ? (const void *)(x->arena + x->embed) : nullptr;
+    const void *emb = (tokens || tok_dev) ? (const void *)(x->arena + x->embed) : nullptr;
     const int d = x->c.d_model;
     ProfScope ps(x, 2, 0.0);
     if (x->bf)
-        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(d / 16), dim3(128), 0, x->stream, emb, tk, rows, d, M, gain,
-                           xout, act, ssq);
+        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(d / 16), dim3(128), 0, x->stream, emb, tk, tok_dev, rows, d, M,
+                           gain, xout, act, ssq);
     else
-        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(d / 16), dim3(128), 0, x->stream, emb, tk, rows, d, M,
+        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(d / 16), dim3(128), 0, x->stream, emb, tk, tok_dev, rows, d, M,
                            gain, xout, act, ssq);
     return check_launch(x, "pack_rows");
 }
@@ -375,8 +377,8 @@ int uniform_at(kg_ctx *x, const kg_params *p, int pos, int purpose, float *out)
 
 int fetch_results(kg_ctx *x, int n)
 {
-    HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, n * 4, hipMemcpyDeviceToHost, x->stream));
-    HIPCHK(x, hipMemcpyAsync(x->h_conf, x->scr + x->s_conf, n * 4, hipMemcpyDeviceToHost, x->stream));
+    (void)n;
+    HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, KG_ROWS * 8, hipMemcpyDeviceToHost, x->stream));
     HIPCHK(x, hipStreamSynchronize(x->stream));
     if (x->profiling) prof_collect(x);
     return KG_OK;
@@ -386,12 +388,12 @@ float *Frow(kg_ctx *x, int j) { return at<float>(x->scr, x->s_F) + (size_t)(j + 
 float *Flag(kg_ctx *x) { return at<float>(x->scr, x->s_F); }
 
 // shallow sub-network M^b[:l] on M tokens at pos0; early features go to rows f_j0..f_{j0+M-1}
-int run_shallow(kg_ctx *x, const int *tokens, int M, int pos0, int j0)
+int run_shallow(kg_ctx *x, const int *tokens, int M, int pos0, int j0, const int *tok_dev = nullptr)
 {
     const kg_config &c = x->c;
     float *x0 = at<float>(x->scr, x->s_x0);
     KGCHK(launch_pack_rows(x, tokens, nullptr, M, at<const float>(x->arena, x->lw[0].g1), x0, x->scr + x->s_actX,
-                           at<float>(x->scr, x->s_ssq0)));
+                           at<float>(x->scr, x->s_ssq0), tok_dev));
     return run_layers(x, 0, c.exit_layer, M, pos0, x0, Frow(x, j0), nullptr);
 }
 
@@ -562,8 +564,9 @@ int kg_bind(kg_ctx *x, void *weights_dev, size_t weight_bytes, void *kv_dev, siz
     x->arena = (char *)weights_dev; x->kv = (char *)kv_dev; x->scr = (char *)scratch_dev;
     x->stream = (hipStream_t)hip_stream;
     if (!x->h_tok) {
-        HIPCHK(x, hipHostMalloc((void **)&x->h_tok, KG_ROWS * 4, hipHostMallocDefault));
-        HIPCHK(x, hipHostMalloc((void **)&x->h_conf, KG_ROWS * 4, hipHostMallocDefault));
+        HIPCHK(x, hipHostMalloc((void **)&x->h_tok, KG_ROWS * 8, hipHostMallocDefault));
+        x->h_conf = reinterpret_cast<float *>(x->h_tok + KG_ROWS);
+        HIPCHK(x, hipEventCreateWithFlags(&x->ev_fetch, hipEventDisableTiming));
     }
     x->bound = true;
     std::fill(x->loaded.begin(), x->loaded.end(), 0);
@@ -649,6 +652,7 @@ int kg_reset(kg_ctx *x)
     x->base = x->adapter_len = x->lag = 0;
     x->n_drafts = x->stopped = 0;
     x->pending = -1;
+    x->spec_shallow = -1;
     if (x->bound) {
         HIPCHK(x, hipMemsetAsync(x->scr + x->s_cnt, 0, (size_t)x->c.n_heads * 4, x->stream));
         HIPCHK(x, hipStreamSynchronize(x->stream));
@@ -700,7 +704,8 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     const int pos = x->base + j;
     float u_draft = 0.f;
     KGCHK(uniform_at(x, p, pos + 1, 0, &u_draft));
-    KGCHK(run_shallow(x, &tok, 1, pos, j));
+    if (x->spec_shallow != j) KGCHK(run_shallow(x, &tok, 1, pos, j));
+    x->spec_shallow = -1;
     int M = 1;
     if (j == 0 && x->lag) {                       // adapter catches up on [lagged f, f_0] (Figure 2)
         M = 2;
@@ -711,7 +716,16 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     float *dl = at<float>(x->scr, x->s_dlog) + (size_t)j * x->c.vocab;
     KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t, p->mode, &u_draft, at<float>(x->scr, x->s_dstat) + 2 * j));
-    KGCHK(fetch_results(x, 1));
+    // The draft token's early feature is needed whatever the host decides next (one more draft
+    // step, or verification): compute it now, reading the token from device memory, so that the
+    // GPU keeps working while the host waits for the token and its confidence.  The results are
+    // copied out first: the copy is ordered before these kernels on the stream.
+    HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, KG_ROWS * 8, hipMemcpyDeviceToHost, x->stream));
+    hipEvent_t ev = x->ev_fetch;
+    HIPCHK(x, hipEventRecord(ev, x->stream));
+    KGCHK(run_shallow(x, nullptr, 1, pos + 1, j + 1, at<const int>(x->scr, x->s_tok)));
+    x->spec_shallow = j + 1;
+    HIPCHK(x, hipEventSynchronize(ev));
     x->lag = 0;
     x->adapter_len = pos + 1;
     x->drafts[j] = x->h_tok[0];
@@ -734,7 +748,8 @@ int kg_verify(kg_ctx *x, const kg_params *p, int32_t *target_tokens, int *k_plus
     const int k = x->n_drafts;
     if (x->base + k + 1 >= x->c.max_seq) return fail(x, KG_ENOSPC, "sequence would exceed max_seq");
     const int tok = x->drafts[k - 1];
-    KGCHK(run_shallow(x, &tok, 1, x->base + k, k));            // next early feature f_k; adapter not run
+    if (x->spec_shallow != k) KGCHK(run_shallow(x, &tok, 1, x->base + k, k));   // next early feature f_k; adapter not run
+    x->spec_shallow = -1;
     KGCHK(run_deep(x, k + 1, x->base));
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     KGCHK(run_head(x, k + 1, 0, at<float>(x->scr, x->s_tlog), k + 1, inv_t));
@@ -972,8 +987,8 @@ void kg_destroy(kg_ctx *x)
 {
     if (!x) return;
     if (x->h_tok) (void)hipHostFree(x->h_tok);
-    if (x->h_conf) (void)hipHostFree(x->h_conf);
     for (hipEvent_t e : x->ev_pool) (void)hipEventDestroy(e);
+    if (x->ev_fetch) (void)hipEventDestroy(x->ev_fetch);
     delete x;
 }
 
@@ -1013,12 +1028,12 @@ int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, i
     e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = yd;
     if (dtype == 1) {
         if (hipMemsetAsync(work, 0, act_bytes(K), s) != hipSuccess) return KG_EHIP;
-        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, xd, K, M,
+        hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, (const int *)nullptr, xd, K, M,
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
         hipLaunchKernelGGL(gemv_bf16_kernel<16>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
                            (const u32x4_t *)work, e);
     } else {
-        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, xd, K, M,
+        hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, (const int *)nullptr, xd, K, M,
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
         hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, s, (const float *)packed, K, (const float *)work, e);
     }

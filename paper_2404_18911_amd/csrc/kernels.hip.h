@@ -342,9 +342,9 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__
 struct Tok8 { int t[KG_ROWS]; };
 
 template <bool BF>
-__global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 tok, const float *rows, int d,
-                                                        int M, const float *gain, float *xout, void *act,
-                                                        float *ssq)
+__global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 tok, const int *tok_dev,
+                                                        const float *rows, int d, int M, const float *gain,
+                                                        float *xout, void *act, float *ssq)
 {
     __shared__ float sq[16][KG_ROWS];
     int rt = blockIdx.x, row = threadIdx.x >> 3, m = threadIdx.x & 7;
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 to
     float v = 0.f;
     if (m < M) {
         if (emb) {
-            size_t idx = (size_t)tok.t[m] * d + n;
+            size_t idx = (size_t)(tok_dev ? tok_dev[m] : tok.t[m]) * d + n;   // token ids from the host or from device memory
             v = BF ? bf2f(((const uint16_t *)emb)[idx]) : ((const float *)emb)[idx];
         } else {
             v = rows[(size_t)m * d + n];
