@@ -251,10 +251,37 @@ int launch_pack_rows(kg_ctx *x, const int *tokens, const float *rows, int M, con
     return check_launch(x, "pack_rows");
 }
 
-int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
+template <typename T, int HD, bool BF>
+void launch_attn_rows(const AttnArgs &a, dim3 grid, int rows, hipStream_t stream)
+{
+    // rows = row capacity of the instantiation (1, 2, 4 or 8 >= rows of a block)
+    if (rows <= 1) hipLaunchKernelGGL((attn_kernel<T, HD, BF, 1>), grid, dim3(512), 0, stream, a);
+    else if (rows <= 2) hipLaunchKernelGGL((attn_kernel<T, HD, BF, 2>), grid, dim3(512), 0, stream, a);
+    else if (rows <= 4) hipLaunchKernelGGL((attn_kernel<T, HD, BF, 4>), grid, dim3(512), 0, stream, a);
+    else hipLaunchKernelGGL((attn_kernel<T, HD, BF, 8>), grid, dim3(512), 0, stream, a);
+}
+
+int launch_attn_args(kg_ctx *x, const AttnArgs &a, dim3 grid, int rows)
+{
+    const int hd = x->c.head_dim;
+    if (x->bf && x->kvbf) {
+        if (hd == 128) launch_attn_rows<uint16_t, 128, true>(a, grid, rows, x->stream);
+        else launch_attn_rows<uint16_t, 64, true>(a, grid, rows, x->stream);
+    } else if (x->bf) {
+        if (hd == 128) launch_attn_rows<float, 128, true>(a, grid, rows, x->stream);
+        else launch_attn_rows<float, 64, true>(a, grid, rows, x->stream);
+    } else {
+        if (hd == 128) launch_attn_rows<float, 128, false>(a, grid, rows, x->stream);
+        else launch_attn_rows<float, 64, false>(a, grid, rows, x->stream);
+    }
+    return check_launch(x, "attention");
+}
+
+AttnArgs attn_args(kg_ctx *x, int slot, int pos0, int M)
 {
     const kg_config &c = x->c;
     AttnArgs a;
+    memset(&a, 0, sizeof(a));
     a.qkv = at<const float>(x->scr, x->s_qkv);
     a.d = c.d_model; a.H = c.n_heads; a.M = M; a.pos0 = pos0; a.P = c.kv_page_tokens; a.logP = x->logP;
     a.page_table = at<const int>(x->scr, x->s_pt);
@@ -265,20 +292,16 @@ int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
     a.cnt = at<int>(x->scr, x->s_cnt);
     a.S = (pos0 + M + c.kv_page_tokens - 1) >> x->logP;
     a.act_out = x->scr + x->s_actA;
+    return a;
+}
+
+int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
+{
+    const kg_config &c = x->c;
+    AttnArgs a = attn_args(x, slot, pos0, M);
     a.append_only = append_only;
-    dim3 grid(c.n_heads, a.S);
     ProfScope ps(x, 1, append_only ? 0.0 : (double)(pos0 + M) * 2 * c.d_model * x->kvesz);
-    if (x->bf && x->kvbf) {
-        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<uint16_t, 128, true>), grid, dim3(512), 0, x->stream, a);
-        else hipLaunchKernelGGL((attn_kernel<uint16_t, 64, true>), grid, dim3(512), 0, x->stream, a);
-    } else if (x->bf) {
-        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, true>), grid, dim3(512), 0, x->stream, a);
-        else hipLaunchKernelGGL((attn_kernel<float, 64, true>), grid, dim3(512), 0, x->stream, a);
-    } else {
-        if (c.head_dim == 128) hipLaunchKernelGGL((attn_kernel<float, 128, false>), grid, dim3(512), 0, x->stream, a);
-        else hipLaunchKernelGGL((attn_kernel<float, 64, false>), grid, dim3(512), 0, x->stream, a);
-    }
-    return check_launch(x, "attention");
+    return launch_attn_args(x, a, dim3(c.n_heads, a.S), M);
 }
 
 Epi epi_base(kg_ctx *x, int kind, int M, int N)

@@ -336,6 +336,196 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
+// Projection for the prompt (prefill): Y[T][N] = X[T][K] . W^T for T up to a few hundred rows, a
+// dense contraction on the MFMA units.  Rows are handled in blocks of 8 (hi/lo columns of one
+// MFMA, exactly as in decoding), so every output is computed by the same instruction sequence as
+// in gemv_bf16_kernel: per output tile the k-steps are split into the same 8 ranges, each range is
+// accumulated in order by MFMA, hi and lo are folded, and the 8 range sums are added in order.
+// A prefilled cache is therefore bit-identical to one written token by token.
+//   grid.x = groups of PF_CBW row blocks, grid.y = groups of 8 weight tiles; wave w of a block owns
+//   weight tile 8*blockIdx.y + w and PF_CBW accumulators; the B tiles (activations) of a stage of
+//   PF_KC k-steps are staged once per block in LDS (double-buffered) and shared by the 8 waves, the
+//   weight tiles of the next stage are prefetched into registers while the current one is multiplied.
+#define PF_KC 8
+#define PF_CBW 2
+
+struct PfArgs {
+    const u32x4_t *W;       // weight tiles [NT][KS][64]
+    int KS, NT;
+    const u32x4_t *act;     // activation tiles, block b at act + b * act_blk
+    size_t act_blk;         // 16-byte units per 8-row block
+    int T;                  // rows in this pass
+    int ssq_in_blk, ssq_out_blk;   // floats per 8-row block of the sum-of-squares arrays
+    size_t act_out_blk;     // bytes per 8-row block of the output activation
+};
+
+__device__ __forceinline__ Epi pf_block_epi(const Epi &e, const PfArgs &a, int b)
+{
+    Epi eb = e;
+    eb.M = min(KG_ROWS, a.T - 8 * b);
+    if (eb.ssq_in) eb.ssq_in += (size_t)b * a.ssq_in_blk;
+    if (eb.out) eb.out += (size_t)8 * b * e.N;
+    if (eb.res) eb.res += (size_t)8 * b * e.N;
+    if (eb.xout) eb.xout += (size_t)8 * b * e.N;
+    if (eb.act_out) eb.act_out = (char *)eb.act_out + (size_t)b * a.act_out_blk;
+    if (eb.ssq_out) eb.ssq_out += (size_t)b * a.ssq_out_blk;
+    return eb;
+}
+
+struct PfStage { int r, k, n; };   // k-range index (0..7, 8 = end), first k-step, k-steps in the stage
+
+__device__ __forceinline__ PfStage pf_stage_at(int r, int k, int KS)
+{
+    while (r < 8) {
+        int k1 = ((r + 1) * KS) >> 3;
+        if (k < k1) return PfStage{r, k, min(PF_KC, k1 - k)};
+        r++;
+        k = (r * KS) >> 3;
+    }
+    return PfStage{8, 0, 0};
+}
+
+__global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
+{
+    __shared__ u32x4_t Bs[2][PF_KC][PF_CBW][64];
+    __shared__ float ytw[8][16][KG_ROWS];
+    __shared__ float sqw[8][16][KG_ROWS];
+    __shared__ float scs[PF_CBW][KG_ROWS];
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const int nb = (a.T + 7) >> 3;
+    const int b0 = blockIdx.x * PF_CBW;
+    const int nbw = min(PF_CBW, nb - b0);
+    const int rt = blockIdx.y * 8 + wave;
+    const bool valid = rt < a.NT;
+    const int KS = a.KS;
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+
+    // RMS scales of this block group's rows (same routine and order as in decoding)
+    for (int cb = 0; cb < PF_CBW; cb++) {
+        if (cb < nbw) {
+            Epi eb = pf_block_epi(e, a, b0 + cb);
+            ScaleRegs sr;
+            scale_fetch(eb, sr);
+            scale_finish(eb, sr, scs[cb]);
+        }
+    }
+
+    f32x4_t acc[PF_CBW], tot[PF_CBW];
+#pragma unroll
+    for (int cb = 0; cb < PF_CBW; cb++) { acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; tot[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+
+    u32x4_t an[PF_KC], ac[PF_KC];      // weight tiles: next stage (in flight), current stage
+    u32x4_t bn[(PF_KC * PF_CBW * 64 + 511) / 512];
+    constexpr int NBL = (PF_KC * PF_CBW * 64 + 511) / 512;
+    const u32x4_t *wrow = a.W + (size_t)(valid ? rt : 0) * KS * 64 + lane;
+
+    auto prefetch = [&](const PfStage &st) {
+#pragma unroll
+        for (int kk = 0; kk < PF_KC; kk++)
+            if (kk < st.n && valid) an[kk] = __builtin_nontemporal_load(wrow + (size_t)(st.k + kk) * 64);
+#pragma unroll
+        for (int i = 0; i < NBL; i++) {
+            int idx = t + 512 * i;                    // (kk, cb, slot)
+            int slot = idx & 63, cb = (idx >> 6) % PF_CBW, kk = idx / (64 * PF_CBW);
+            u32x4_t v = zero;
+            if (kk < st.n && cb < nbw && (slot >> 3) < min(KG_ROWS, a.T - 8 * (b0 + cb)))
+                v = a.act[(size_t)(b0 + cb) * a.act_blk + (size_t)(st.k + kk) * 64 + slot];
+            bn[i] = v;
+        }
+    };
+
+    PfStage cur = pf_stage_at(0, 0, KS);
+    prefetch(cur);
+    int buf = 0;
+    const int bs = b_slot(lane);
+    while (cur.r < 8) {
+#pragma unroll
+        for (int i = 0; i < NBL; i++) {
+            int idx = t + 512 * i;
+            (&Bs[buf][0][0][0])[idx] = bn[i];
+        }
+#pragma unroll
+        for (int kk = 0; kk < PF_KC; kk++) ac[kk] = an[kk];
+        __syncthreads();
+        PfStage nxt = pf_stage_at(cur.r, cur.k + cur.n, KS);
+        if (nxt.r < 8) prefetch(nxt);
+#pragma unroll
+        for (int kk = 0; kk < PF_KC; kk++)
+            if (kk < cur.n) {
+#pragma unroll
+                for (int cb = 0; cb < PF_CBW; cb++)
+                    acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ac[kk]),
+                                                                      __builtin_bit_cast(bf16x8_t, Bs[buf][kk][cb][bs]),
+                                                                      acc[cb], 0, 0, 0);
+            }
+        if (nxt.r != cur.r) {          // end of a k-range: fold hi/lo, add the range sum in range order
+#pragma unroll
+            for (int cb = 0; cb < PF_CBW; cb++) {
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    float v = acc[cb][r] + __shfl_xor(acc[cb][r], 8);
+                    tot[cb][r] = (cur.r == 0) ? v : tot[cb][r] + v;
+                }
+                acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            }
+            // empty ranges between cur.r and nxt.r contribute exact zeros
+        }
+        cur = nxt;
+        buf ^= 1;
+    }
+
+    // epilogue, one 8-row block at a time; every wave finishes its own 16 x 8 tile
+    for (int cb = 0; cb < PF_CBW; cb++) {
+        if (cb >= nbw) break;                 // uniform across the block
+        const Epi eb = pf_block_epi(e, a, b0 + cb);
+        __syncthreads();
+        if ((lane & 15) < 8) {
+#pragma unroll
+            for (int r = 0; r < 4; r++) ytw[wave][4 * (lane >> 4) + r][lane & 7] = tot[cb][r];
+        }
+        __syncthreads();
+        const float *sc = scs[cb];
+        if (valid) {
+            if (eb.kind == EPI_PLAIN) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; h2++) {
+                    int tt = lane + 64 * h2, row = tt >> 3, m = tt & 7;
+                    if (m < eb.M) eb.out[(size_t)m * eb.N + rt * 16 + row] = ytw[wave][row][m] * sc[m];
+                }
+            } else if (eb.kind == EPI_RESID) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; h2++) {
+                    int tt = lane + 64 * h2, row = tt >> 3, m = tt & 7;
+                    float v = 0.f;
+                    if (m < eb.M) {
+                        int n = rt * 16 + row;
+                        v = eb.res[(size_t)m * eb.N + n] + ytw[wave][row][m];
+                        eb.xout[(size_t)m * eb.N + n] = v;
+                        if (eb.act_out) store_act<true>(eb.act_out, eb.act_K, m, n, eb.gain ? v * eb.gain[n] : v);
+                    }
+                    sqw[wave][row][m] = v * v;
+                }
+            } else {                          // EPI_SWIGLU
+                int i = lane >> 3, m = lane & 7;
+                if (m < eb.M) {
+                    float g = ytw[wave][2 * i][m] * sc[m], u = ytw[wave][2 * i + 1][m] * sc[m];
+                    float av = g / (1.f + __expf(-g)) * u;
+                    store_act<true>(eb.act_out, eb.act_K, m, rt * 8 + i, av);
+                }
+            }
+        }
+        if (eb.kind == EPI_RESID && eb.ssq_out) {
+            __syncthreads();
+            if (valid && lane < KG_ROWS) {
+                float s2 = 0.f;
+                for (int r = 0; r < 16; r++) s2 += sqw[wave][r][lane];
+                eb.ssq_out[(size_t)rt * KG_ROWS + lane] = s2;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Rows -> activation for the first projection of a stack: x[m] = E[tok[m]] (emb != null) or the
 // given fp32 rows; writes xout (optional), act = x * gain (hi/lo), ssq[tile][m].  One block per
 // 16 features.
@@ -344,9 +534,22 @@ struct Tok8 { int t[KG_ROWS]; };
 template <bool BF>
 __global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 tok, const int *tok_dev,
                                                         const float *rows, int d, int M, const float *gain,
-                                                        float *xout, void *act, float *ssq)
+                                                        float *xout, void *act, float *ssq,
+                                                        size_t act_blk_bytes = 0, int ssq_blk = 0)
 {
     __shared__ float sq[16][KG_ROWS];
+    // blockIdx.y selects a block of 8 rows (prefill passes many blocks in one launch; M is then the
+    // total row count and every per-row pointer advances by 8 rows per block)
+    const int blk = blockIdx.y;
+    if (blk) {
+        M -= 8 * blk;
+        if (tok_dev) tok_dev += 8 * blk;
+        if (rows) rows += (size_t)8 * blk * d;
+        if (xout) xout += (size_t)8 * blk * d;
+        act = (char *)act + (size_t)blk * act_blk_bytes;
+        if (ssq) ssq += (size_t)blk * ssq_blk;
+    }
+    if (M > KG_ROWS) M = KG_ROWS;
     int rt = blockIdx.x, row = threadIdx.x >> 3, m = threadIdx.x & 7;
     int n = rt * 16 + row;
     float v = 0.f;
@@ -418,11 +621,13 @@ __global__ void rope_table_kernel(float2 *tab, int max_seq, int half, const doub
 
 // ---------------------------------------------------------------------------------------------
 // Decode attention over a paged KV cache for up to 8 query rows at positions pos0..pos0+M-1.
-// grid = (heads, pages in use); block = 256.  A block handles one head and one page of P
-// positions: it rotates q (and k), appends the new k/v rows that fall in its page, computes
-// scores, a page-local softmax and P.V, and stores an unnormalised partial.  The last block to
-// finish for a head merges the partials in page order (so results do not depend on arrival
-// order, nor on how many rows or trailing pages the launch had).
+// grid = (heads, pages in use, blocks of 8 rows); block = 512.  A block handles one head and one
+// page of P positions: it rotates q (and k), appends the new k/v rows that fall in its page,
+// computes scores, a page-local softmax and P.V, and stores an unnormalised partial.  The last
+// block to finish for a head merges the partials in page order (so results do not depend on
+// arrival order, nor on how many rows or trailing pages the launch had).
+// The argument block is only read (never indexed dynamically, never modified): it then stays in
+// scalar registers instead of being copied to private memory.
 struct AttnArgs {
     const float *qkv;   // [M][3d]: q | k | v, already RMS-scaled projections
     int d, H, M, pos0, P, logP;
@@ -431,12 +636,16 @@ struct AttnArgs {
     void *kv;           // pool: [phys page][slot][head][K|V][P][hd]
     int slot, n_slots;
     const float2 *rope; // [max_seq][hd/2]
-    float *opart;       // [H][S][8][hd]
-    float *mxs, *sms;   // [H][S][8]
-    int *cnt;           // [H], zero between launches
+    float *opart;       // [row block][H][S][8][hd]
+    float *mxs, *sms;   // [row block][H][S][8]
+    int *cnt;           // [row block][H], zero between launches
     int S;              // pages covered by this launch = ceil((pos0+M)/P)
     void *act_out;      // attention output as activation for the output projection (K = d)
-    int append_only;    // 1: only append k/v (prefill of the adapter cache)
+    int append_only;    // 1: only append k/v
+    // prefill: blockIdx.z selects a block of 8 rows; M is then the total row count
+    size_t act_blk_bytes;   // bytes per 8-row block of act_out
+    int preappended;    // 1: this call's k/v rows are already in the cache (appended by an earlier launch)
+    int append_all;     // with append_only: write every row of the block to its own page (grid.y = 1)
 };
 
 template <typename T> __device__ __forceinline__ float kv_ld(const T *p);
@@ -448,22 +657,6 @@ template <> __device__ __forceinline__ float kv_round<uint16_t>(float v) { retur
 template <typename T> __device__ __forceinline__ void kv_st(T *p, float v);
 template <> __device__ __forceinline__ void kv_st<float>(float *p, float v) { *p = v; }
 template <> __device__ __forceinline__ void kv_st<uint16_t>(uint16_t *p, float v) { *p = f2bf(v); }
-
-template <typename T> __device__ __forceinline__ void kv_ld8(const T *p, float *o);
-template <> __device__ __forceinline__ void kv_ld8<float>(const float *p, float *o)
-{
-    float4 a = *(const float4 *)p, b = *(const float4 *)(p + 4);
-    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-}
-template <> __device__ __forceinline__ void kv_ld8<uint16_t>(const uint16_t *p, float *o)
-{
-    u32x4_t a = *(const u32x4_t *)p;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        o[2 * i] = __uint_as_float(a[i] << 16);
-        o[2 * i + 1] = __uint_as_float(a[i] & 0xFFFF0000u);
-    }
-}
 
 template <typename T, int N8> struct KvVec;           // N8 groups of 8 cache elements, loaded as 16-byte pieces
 template <int N8> struct KvVec<uint16_t, N8> {
@@ -493,199 +686,246 @@ template <int N8> struct KvVec<float, N8> {
     }
 };
 
-// One (head, page) unit, 512 threads.  Scores: 4 lanes per position (a quarter of the head
-// dimension each), all 128 positions of a page in one pass.  Softmax statistics are kept per
-// wave (16 positions), then merged across the 8 waves, then across pages; every level rescales
-// by exp(max_part - max_all), in a fixed order, so a row's result does not depend on the other
-// rows of the batch or on trailing pages.
-template <typename T, int HD, bool BF>
-__global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
+// E consecutive cache elements owned by one lane in the P.V pass (E = head_dim / 64)
+template <typename T, int E> struct KvLane;
+template <> struct KvLane<uint16_t, 2> {
+    uint32_t r;
+    __device__ __forceinline__ void load(const uint16_t *p) { r = *(const uint32_t *)p; }
+    __device__ __forceinline__ float get(int e) const { return __uint_as_float(e ? (r & 0xFFFF0000u) : (r << 16)); }
+};
+template <> struct KvLane<uint16_t, 1> {
+    uint16_t r;
+    __device__ __forceinline__ void load(const uint16_t *p) { r = *p; }
+    __device__ __forceinline__ float get(int) const { return bf2f(r); }
+};
+template <> struct KvLane<float, 2> {
+    float2 r;
+    __device__ __forceinline__ void load(const float *p) { r = *(const float2 *)p; }
+    __device__ __forceinline__ float get(int e) const { return e ? r.y : r.x; }
+};
+template <> struct KvLane<float, 1> {
+    float r;
+    __device__ __forceinline__ void load(const float *p) { r = *p; }
+    __device__ __forceinline__ float get(int) const { return r; }
+};
+
+// physical page of logical page s: the first 16 come from the argument block through a chain of
+// selects on constant indices
+__device__ __forceinline__ int attn_page(const AttnArgs &a, int s)
+{
+    if (s >= 16) return a.page_table[s];
+    int p = a.pages[0];
+#pragma unroll
+    for (int i = 1; i < 16; i++) p = (s == i) ? a.pages[i] : p;
+    return p;
+}
+
+// rotation of the pair (x0, x1) by the angle whose (cos, sin) is cs; written with explicit fused
+// operations so that every instantiation rounds alike
+__device__ __forceinline__ float rot_lo(float x0, float x1, float2 cs) { return fmaf(x0, cs.x, -__fmul_rn(x1, cs.y)); }
+__device__ __forceinline__ float rot_hi(float x0, float x1, float2 cs) { return fmaf(x1, cs.x, __fmul_rn(x0, cs.y)); }
+
+// One (head, page) unit, 512 threads, MR >= number of rows (1, 2, 4 or 8: less code and fewer
+// registers for the common one- and two-row calls; a row's arithmetic is the same in all of them).
+// Scores: 4 lanes per position (a quarter of the head dimension each), all 128 positions of a
+// page in one pass.  P.V: a wave walks its 16 positions, every lane owning head_dim/64 output
+// elements (no cross-lane reduction).  Softmax statistics are kept per wave, then merged across
+// the 8 waves, then across pages; every level rescales by exp(max_part - max_all), in a fixed
+// order, so a row's result does not depend on the other rows of the batch or on trailing pages.
+template <typename T, int HD, bool BF, int MR>
+__global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a)
 {
     constexpr int EL = HD / 4;          // elements of one score lane
-    constexpr int LPR = HD / 8;         // lanes per cache row in the P.V pass (8 elements each)
-    constexpr int RPW = 64 / LPR;       // rows per wave instruction in the P.V pass
-    constexpr int NIT = 16 / RPW;       // P.V iterations to cover a wave's 16 positions
-    __shared__ float qs[KG_ROWS][HD];
-    __shared__ float pw[8][16][KG_ROWS];
-    __shared__ float ow[8][KG_ROWS][HD];
-    __shared__ float mw[8][KG_ROWS], sw[8][KG_ROWS];
-    __shared__ float knew[KG_ROWS][HD], vnew[KG_ROWS][HD];   // this call's k, v rows as the cache holds them
+    constexpr int EPL = HD / 64;        // output elements of one P.V lane
+    constexpr int HH = HD / 2;
+    __shared__ float qs[MR][HD];
+    __shared__ float kn[MR][HD], vn[MR][HD];     // this call's k, v rows as the cache holds them
+    __shared__ float ow[8][MR][HD];
+    __shared__ float mw[8][MR], sw[8][MR];
     __shared__ int last_flag;
-    const int h = blockIdx.x, s = blockIdx.y, t = threadIdx.x;
+    const int h = blockIdx.x, s = blockIdx.y, zb = blockIdx.z, t = threadIdx.x;
     const int wave = t >> 6, lane = t & 63;
-    const int P = a.P, M = a.M, d = a.d;
-    const int p_begin = s << a.logP;
-    const int n_valid = min(P, a.pos0 + M - p_begin);      // positions of this page that hold data
-    const int n_old = min(P, max(0, a.pos0 - p_begin));    // ... of which were cached before this call
-    const int phys = s < 16 ? a.pages[s] : a.page_table[s];
-    T *Kp = (T *)a.kv + ((((size_t)phys * a.n_slots + a.slot) * a.H + h) * 2) * (size_t)P * HD;
-    T *Vp = Kp + (size_t)P * HD;
-    const float qscale = rsqrtf((float)HD);
+    const int P = a.P, d = a.d, logP = a.logP;
+    const int pos0 = a.pos0 + 8 * zb;
+    const int M = min(MR, a.M - 8 * zb);
+    const int S = (pos0 + M + P - 1) >> logP;               // pages this block of rows attends to
+    if (!a.append_all && s >= S) return;
+    const int hz = zb * a.H + h;                            // index of (row block, head) in the partial buffers
+    const float *qkv = a.qkv + (size_t)8 * zb * 3 * d + h * HD;
+    const int p_begin = s << logP;
+    const int n_valid = min(P, pos0 + M - p_begin);         // positions of this page that hold data
+    const int n_old = a.preappended ? n_valid : min(P, max(0, pos0 - p_begin));   // ... cached before this call
+    const size_t unit = (size_t)2 * P * HD;                 // K then V of one (page, slot, head)
+    T *const Kp = (T *)a.kv + (((size_t)attn_page(a, s) * a.n_slots + a.slot) * a.H + h) * unit;
+    T *const Vp = Kp + (size_t)P * HD;
+    void *const act_out = (char *)a.act_out + (size_t)zb * a.act_blk_bytes;
 
-    // roles: score lane (position pl, quarter sub); P.V lane (row r of an instruction, chunk c)
+    // this call's rows (thread = row rm, rotation pair rj): issued first, they come from the L2
+    const bool has_row = t < M * HH;
+    const int rm = t / HH, rj = t % HH, rpos = pos0 + rm;
+    const bool row_here = has_row && !a.preappended && (a.append_all || (rpos >= p_begin && rpos < p_begin + P));
+    float2 cs = make_float2(1.f, 0.f);
+    float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+    if (has_row) {
+        const float *q = qkv + (size_t)rm * 3 * d;
+        cs = a.rope[(size_t)rpos * HH + rj];
+        q0 = q[rj]; q1 = q[rj + HH];
+        if (row_here) { k0 = q[d + rj]; k1 = q[d + rj + HH]; v0 = q[2 * d + rj]; v1 = q[2 * d + rj + HH]; }
+    }
+    // rows cached by earlier calls: score lane (position pl, quarter sub); P.V lane owns EPL elements
     const int pl = t >> 2, sub = t & 3;
-    const int r = lane / LPR, c = lane % LPR;
-    KvVec<T, EL / 8> kreg;
-    KvVec<T, 1> vreg[NIT];
     const bool k_old = pl < n_old;
-    if (!a.append_only) {       // rows cached by earlier calls can be fetched before the new rows are written
+    KvVec<T, EL / 8> kreg;
+    KvLane<T, EPL> vreg[16];
+    if (!a.append_only) {
         if (k_old) kreg.load(Kp + (size_t)pl * HD + sub * EL);
 #pragma unroll
-        for (int it = 0; it < NIT; it++) {
-            int pv = wave * 16 + it * RPW + r;
-            if (pv < n_old) vreg[it].load(Vp + (size_t)pv * HD + c * 8);
-        }
+        for (int i = 0; i < 16; i++)
+            if (wave * 16 + i < n_old) vreg[i].load(Vp + (size_t)(wave * 16 + i) * HD + EPL * lane);
     }
-    // rotate q into LDS; rotate and append the new k, v rows that live in this page
-    for (int i = t; i < M * (HD / 2); i += 512) {
-        int m = i / (HD / 2), j = i % (HD / 2);
-        int pos = a.pos0 + m;
-        float2 cs = a.rope[(size_t)pos * (HD / 2) + j];
-        const float *q = a.qkv + (size_t)m * 3 * d + h * HD;
-        float x0 = q[j], x1 = q[j + HD / 2];
-        qs[m][j] = (x0 * cs.x - x1 * cs.y) * qscale;
-        qs[m][j + HD / 2] = (x1 * cs.x + x0 * cs.y) * qscale;
-        if (pos >= p_begin && pos < p_begin + P) {
-            const float *k = q + d, *v = q + 2 * d;
-            float k0 = k[j], k1 = k[j + HD / 2];
-            int pp = pos - p_begin;
-            float ka = kv_round<T>(k0 * cs.x - k1 * cs.y), kb = kv_round<T>(k1 * cs.x + k0 * cs.y);
-            float va = kv_round<T>(v[j]), vb = kv_round<T>(v[j + HD / 2]);
-            kv_st<T>(Kp + (size_t)pp * HD + j, ka);
-            kv_st<T>(Kp + (size_t)pp * HD + j + HD / 2, kb);
-            kv_st<T>(Vp + (size_t)pp * HD + j, va);
-            kv_st<T>(Vp + (size_t)pp * HD + j + HD / 2, vb);
-            knew[m][j] = ka; knew[m][j + HD / 2] = kb;
-            vnew[m][j] = va; vnew[m][j + HD / 2] = vb;
+    if (has_row) {
+        const float qscale = rsqrtf((float)HD);
+        qs[rm][rj] = rot_lo(q0, q1, cs) * qscale;
+        qs[rm][rj + HH] = rot_hi(q0, q1, cs) * qscale;
+        if (row_here) {
+            const float ka = kv_round<T>(rot_lo(k0, k1, cs)), kb = kv_round<T>(rot_hi(k0, k1, cs));
+            const float va = kv_round<T>(v0), vb = kv_round<T>(v1);
+            T *Kq = Kp, *Vq = Vp;
+            int pp = rpos - p_begin;
+            if (a.append_all) {
+                pp = rpos & (P - 1);
+                Kq = (T *)a.kv + (((size_t)a.page_table[rpos >> logP] * a.n_slots + a.slot) * a.H + h) * unit;
+                Vq = Kq + (size_t)P * HD;
+            }
+            kv_st<T>(Kq + (size_t)pp * HD + rj, ka);
+            kv_st<T>(Kq + (size_t)pp * HD + rj + HH, kb);
+            kv_st<T>(Vq + (size_t)pp * HD + rj, va);
+            kv_st<T>(Vq + (size_t)pp * HD + rj + HH, vb);
+            kn[rm][rj] = ka; kn[rm][rj + HH] = kb;
+            vn[rm][rj] = va; vn[rm][rj + HH] = vb;
         }
     }
     if (a.append_only) return;
     __syncthreads();
     // positions written by this call are taken from LDS (the very values the cache now holds)
     const bool k_new = !k_old && pl < n_valid;
-    const int mk = p_begin + pl - a.pos0;
+    const int mk = p_begin + pl - pos0;
 
     // scores and wave-local softmax
-    float pr[KG_ROWS];
+    float pr[MR];
 #pragma unroll
-    for (int m = 0; m < KG_ROWS; m++) {
-        float v = 0.f;
-        if (m < M && pl < n_valid) {
+    for (int m = 0; m < MR; m++) {
+        pr[m] = 0.f;
+        if (m < M) {
+            float v = 0.f;
             if (k_new) {
 #pragma unroll
-                for (int i = 0; i < EL; i++) v = fmaf(knew[mk][sub * EL + i], qs[m][sub * EL + i], v);
-            } else {
+                for (int i = 0; i < EL; i++) v = fmaf(kn[mk][sub * EL + i], qs[m][sub * EL + i], v);
+            } else if (k_old) {
 #pragma unroll
                 for (int i = 0; i < EL; i++) v = fmaf(kreg.get(i), qs[m][sub * EL + i], v);
             }
+            v += __shfl_xor(v, 1);
+            v += __shfl_xor(v, 2);
+            const float sc = (pl < n_valid && p_begin + pl <= pos0 + m) ? v : -INFINITY;
+            float mx = sc;
+#pragma unroll
+            for (int o = 4; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            const float p = (mx == -INFINITY) ? 0.f : __expf(sc - mx);
+            float sum = p;
+#pragma unroll
+            for (int o = 4; o < 64; o <<= 1) sum += __shfl_xor(sum, o);
+            pr[m] = p;
+            if (lane == 0) { mw[wave][m] = mx; sw[wave][m] = sum; }
         }
-        v += __shfl_xor(v, 1);
-        v += __shfl_xor(v, 2);
-        float sc = (m < M && pl < n_valid && p_begin + pl <= a.pos0 + m) ? v : -INFINITY;
-        float mx = sc;
-        for (int o = 4; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-        float p = (mx == -INFINITY) ? 0.f : __expf(sc - mx);
-        float sum = p;
-        for (int o = 4; o < 64; o <<= 1) sum += __shfl_xor(sum, o);
-        pr[m] = p;
-        if (lane == 0) { mw[wave][m] = mx; sw[wave][m] = sum; }
     }
-    if (sub == 0) {
+    // P.V over the wave's 16 positions; the probability of position i sits in lane 4 i
+    float acc[MR][EPL];
 #pragma unroll
-        for (int m = 0; m < KG_ROWS; m++) pw[wave][pl & 15][m] = pr[m];
-    }
-    __syncthreads();
-    // P.V over the wave's 16 positions
-    float acc[KG_ROWS][8];
+    for (int m = 0; m < MR; m++)
 #pragma unroll
-    for (int m = 0; m < KG_ROWS; m++)
+        for (int e = 0; e < EPL; e++) acc[m][e] = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; i++) acc[m][i] = 0.f;
-#pragma unroll
-    for (int it = 0; it < NIT; it++) {
-        int pw_i = it * RPW + r;
-        int pv = wave * 16 + pw_i;
-        if (pv < n_valid) {
-            float vv[8];
+    for (int i = 0; i < 16; i++) {
+        const int pv = wave * 16 + i;
+        if (pv < n_valid) {                                  // uniform in the wave
+            float vv[EPL];
             if (pv >= n_old) {
 #pragma unroll
-                for (int i = 0; i < 8; i++) vv[i] = vnew[p_begin + pv - a.pos0][c * 8 + i];
+                for (int e = 0; e < EPL; e++) vv[e] = vn[p_begin + pv - pos0][EPL * lane + e];
             } else {
 #pragma unroll
-                for (int i = 0; i < 8; i++) vv[i] = vreg[it].get(i);
+                for (int e = 0; e < EPL; e++) vv[e] = vreg[i].get(e);
             }
 #pragma unroll
-            for (int m = 0; m < KG_ROWS; m++)
+            for (int m = 0; m < MR; m++)
                 if (m < M) {
-                    float p = pw[wave][pw_i][m];
+                    const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr[m]), 4 * i));
 #pragma unroll
-                    for (int i = 0; i < 8; i++) acc[m][i] = fmaf(p, vv[i], acc[m][i]);
+                    for (int e = 0; e < EPL; e++) acc[m][e] = fmaf(p, vv[e], acc[m][e]);
                 }
         }
     }
 #pragma unroll
-    for (int m = 0; m < KG_ROWS; m++)
+    for (int m = 0; m < MR; m++)
         if (m < M) {
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                float v = acc[m][i];
-#pragma unroll
-                for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o);
-                if (r == 0) ow[wave][m][c * 8 + i] = v;
-            }
+            for (int e = 0; e < EPL; e++) ow[wave][m][EPL * lane + e] = acc[m][e];
         }
     __syncthreads();
     // merge the 8 waves; a single page is final, otherwise store the page partial
-    const bool single = a.S == 1;
-    float *op = a.opart + ((size_t)h * a.S + s) * KG_ROWS * HD;
+    const bool single = S == 1;
+    const size_t pidx = (size_t)hz * a.S + s;
     for (int i = t; i < M * HD; i += 512) {
-        int m = i / HD, e = i % HD;
+        const int m = i / HD, e = i % HD;
         float gm = mw[0][m];
 #pragma unroll
         for (int w = 1; w < 8; w++) gm = fmaxf(gm, mw[w][m]);
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int w = 0; w < 8; w++) {
-            float mv = mw[w][m];
+            const float mv = mw[w][m];
             if (mv != -INFINITY) {
-                float wt = __expf(mv - gm);
-                num += wt * ow[w][m][e];
-                den += wt * sw[w][m];
+                const float wt = __expf(mv - gm);
+                num = fmaf(wt, ow[w][m][e], num);
+                den = fmaf(wt, sw[w][m], den);
             }
         }
         if (single) {
-            store_act<BF>(a.act_out, d, m, h * HD + e, num / den);
+            store_act<BF>(act_out, d, m, h * HD + e, num / den);
         } else {
-            st_dev(&op[m * HD + e], num);
+            st_dev(&a.opart[(pidx * KG_ROWS + m) * HD + e], num);
             if (e == 0) {
-                st_dev(&a.mxs[((size_t)h * a.S + s) * KG_ROWS + m], gm);
-                st_dev(&a.sms[((size_t)h * a.S + s) * KG_ROWS + m], den);
+                st_dev(&a.mxs[pidx * KG_ROWS + m], gm);
+                st_dev(&a.sms[pidx * KG_ROWS + m], den);
             }
         }
     }
     if (single) return;
-    // last block of this head merges the pages in order.  The partials are exchanged with
-    // device-scope relaxed atomic stores / loads (write-through, cache-bypassing accesses), ordered
-    // by a workgroup-scope release before the counter is bumped: a device-scope fence would write
-    // back and invalidate the whole L2 and costs several microseconds here.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    // The last block of this head merges the pages in order.  The partials are exchanged with
+    // device-scope relaxed atomic stores / loads (write-through, cache-bypassing accesses); every
+    // wave waits for its stores to be acknowledged before the block bumps the head's counter.  A
+    // device-scope fence would write back and invalidate the whole L2 and costs several
+    // microseconds here.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (t == 0) {
-        int old = __hip_atomic_fetch_add(&a.cnt[h], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last_flag = (old == a.S - 1);
+        const int old = __hip_atomic_fetch_add(&a.cnt[hz], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last_flag = (old == S - 1);
     }
     __syncthreads();
     if (!last_flag) return;
-    if (a.S <= 8) {     // few pages: every load of the merge is issued before any is used
+    const size_t hb = (size_t)hz * a.S;
+    if (S <= 8) {     // few pages: every load of the merge is issued before any is used
         for (int i = t; i < M * HD; i += 512) {
-            int m = i / HD, e = i % HD;
+            const int m = i / HD, e = i % HD;
             float mv[8], ov[8], sv[8];
 #pragma unroll
             for (int ss = 0; ss < 8; ss++) {
-                bool in = ss < a.S;
-                mv[ss] = in ? ld_dev(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]) : -INFINITY;
-                ov[ss] = in ? ld_dev(&a.opart[(((size_t)h * a.S + ss) * KG_ROWS + m) * HD + e]) : 0.f;
-                sv[ss] = in ? ld_dev(&a.sms[((size_t)h * a.S + ss) * KG_ROWS + m]) : 0.f;
+                const bool in = ss < S;
+                mv[ss] = in ? ld_dev(&a.mxs[(hb + ss) * KG_ROWS + m]) : -INFINITY;
+                ov[ss] = in ? ld_dev(&a.opart[((hb + ss) * KG_ROWS + m) * HD + e]) : 0.f;
+                sv[ss] = in ? ld_dev(&a.sms[(hb + ss) * KG_ROWS + m]) : 0.f;
             }
             float gm = -INFINITY;
 #pragma unroll
@@ -693,40 +933,40 @@ __global__ __launch_bounds__(512) void attn_kernel(AttnArgs a)
             float num = 0.f, den = 0.f;
 #pragma unroll
             for (int ss = 0; ss < 8; ss++) {
-                if (ss < a.S) {
-                    float w = (mv[ss] == -INFINITY) ? 0.f : __expf(mv[ss] - gm);
-                    num += w * ov[ss];
-                    den += w * sv[ss];
+                if (ss < S) {
+                    const float w = (mv[ss] == -INFINITY) ? 0.f : __expf(mv[ss] - gm);
+                    num = fmaf(w, ov[ss], num);
+                    den = fmaf(w, sv[ss], den);
                 }
             }
-            store_act<BF>(a.act_out, d, m, h * HD + e, num / den);
+            store_act<BF>(act_out, d, m, h * HD + e, num / den);
         }
-        if (t == 0) __hip_atomic_store(&a.cnt[h], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (t == 0) __hip_atomic_store(&a.cnt[hz], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     // page weights exp(max_page - max_all), through LDS so that the page loop has independent loads
-    float (*wgt)[KG_ROWS] = pw[0];                     // reuse: [page][row], S <= 128
+    float (*wgt)[MR] = (float (*)[MR]) & ow[0][0][0];    // [page][row], S <= 128 <= 8 * HD
     for (int m = wave; m < M; m += 8) {
         float gm = -INFINITY;
-        for (int ss = lane; ss < a.S; ss += 64) gm = fmaxf(gm, ld_dev(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]));
+        for (int ss = lane; ss < S; ss += 64) gm = fmaxf(gm, ld_dev(&a.mxs[(hb + ss) * KG_ROWS + m]));
         for (int o = 32; o >= 1; o >>= 1) gm = fmaxf(gm, __shfl_xor(gm, o));
-        for (int ss = lane; ss < a.S; ss += 64) {
-            float mxv = ld_dev(&a.mxs[((size_t)h * a.S + ss) * KG_ROWS + m]);
+        for (int ss = lane; ss < S; ss += 64) {
+            const float mxv = ld_dev(&a.mxs[(hb + ss) * KG_ROWS + m]);
             wgt[ss][m] = (mxv == -INFINITY) ? 0.f : __expf(mxv - gm);
         }
     }
     __syncthreads();
     for (int i = t; i < M * HD; i += 512) {
-        int m = i / HD, e = i % HD;
+        const int m = i / HD, e = i % HD;
         float num = 0.f, den = 0.f;
-        for (int ss = 0; ss < a.S; ss++) {
-            float w = wgt[ss][m];
-            num += w * ld_dev(&a.opart[(((size_t)h * a.S + ss) * KG_ROWS + m) * HD + e]);
-            den += w * ld_dev(&a.sms[((size_t)h * a.S + ss) * KG_ROWS + m]);
+        for (int ss = 0; ss < S; ss++) {
+            const float w = wgt[ss][m];
+            num = fmaf(w, ld_dev(&a.opart[((hb + ss) * KG_ROWS + m) * HD + e]), num);
+            den = fmaf(w, ld_dev(&a.sms[(hb + ss) * KG_ROWS + m]), den);
         }
-        store_act<BF>(a.act_out, d, m, h * HD + e, num / den);
+        store_act<BF>(act_out, d, m, h * HD + e, num / den);
     }
-    if (t == 0) __hip_atomic_store(&a.cnt[h], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == 0) __hip_atomic_store(&a.cnt[hz], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---------------------------------------------------------------------------------------------
