@@ -38,7 +38,7 @@ class kg_stats(ctypes.Structure):
 
 
 class kg_profile(ctypes.Structure):
-    _fields_ = [("launches", ctypes.c_longlong * 3), ("seconds", ctypes.c_double * 3), ("bytes", ctypes.c_double * 3)]
+    _fields_ = [("launches", ctypes.c_longlong * 4), ("seconds", ctypes.c_double * 4), ("bytes", ctypes.c_double * 4)]
 
 
 # every symbol include/kangaroo.h declares

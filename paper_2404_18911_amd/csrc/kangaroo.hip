@@ -16,6 +16,7 @@
 namespace {
 
 constexpr size_t ALIGN = 256;
+constexpr int PF_ROWS_MAX = 256;     // prompt rows handled per pass of the prompt kernels
 inline size_t up(size_t x, size_t a = ALIGN) { return (x + a - 1) / a * a; }
 
 struct LayerW {
@@ -40,6 +41,10 @@ struct kg_ctx {
     // scratch layout (byte offsets)
     size_t s_x0, s_x1, s_F, s_qkv, s_actX, s_actA, s_actF, s_ssq0, s_ssq1, s_opart, s_mxs, s_sms, s_cnt,
         s_dlog, s_tlog, s_tok, s_conf, s_pt, s_rope, s_invf, s_misc, s_hstat, s_dstat, s_tstat, s_acc;
+    // prompt pass: device copy of the prompt and buffers for pf_rows rows at a time (bf16 weights)
+    int pf_rows = 0;
+    size_t s_ptok, s_px0, s_px1, s_pF, s_pqkv, s_pactX, s_pactA, s_pactF, s_pssq0, s_pssq1, s_popart, s_pmxs, s_psms,
+        s_pcnt;
     // bindings
     char *arena = nullptr, *kv = nullptr, *scr = nullptr;
     hipStream_t stream = nullptr;
@@ -157,6 +162,25 @@ void layout(kg_ctx *x)
     x->s_dstat = take(KG_ROWS * 2 * 4);
     x->s_tstat = take(KG_ROWS * 2 * 4);
     x->s_acc = take(2 * 4);
+    x->s_ptok = take((size_t)c.max_seq * 4);
+    x->pf_rows = 0;
+    if (x->bf) {
+        x->pf_rows = std::min(PF_ROWS_MAX, (c.max_seq + KG_ROWS - 1) / KG_ROWS * KG_ROWS);
+        const size_t R = x->pf_rows, nb = R / KG_ROWS;
+        x->s_px0 = take(R * d * 4);
+        x->s_px1 = take(R * d * 4);
+        x->s_pF = take(R * d * 4);
+        x->s_pqkv = take(R * 3 * d * 4);
+        x->s_pactX = take(nb * act_bytes(d));
+        x->s_pactA = take(nb * act_bytes(d));
+        x->s_pactF = take(nb * act_bytes(f));
+        x->s_pssq0 = take(nb * (d / 16) * KG_ROWS * 4);
+        x->s_pssq1 = take(nb * (d / 16) * KG_ROWS * 4);
+        x->s_popart = take(nb * c.n_heads * x->n_pages * KG_ROWS * c.head_dim * 4);
+        x->s_pmxs = take(nb * c.n_heads * x->n_pages * KG_ROWS * 4);
+        x->s_psms = take(nb * c.n_heads * x->n_pages * KG_ROWS * 4);
+        x->s_pcnt = take(nb * c.n_heads * 4);
+    }
     x->scratch_bytes = o;
 }
 
@@ -302,6 +326,116 @@ int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
     a.append_only = append_only;
     ProfScope ps(x, 1, append_only ? 0.0 : (double)(pos0 + M) * 2 * c.d_model * x->kvesz);
     return launch_attn_args(x, a, dim3(c.n_heads, a.S), M);
+}
+
+Epi epi_base(kg_ctx *x, int kind, int M, int N);
+
+// ---- prompt pass (dense MFMA projections over many 8-row blocks) ---------------------------------
+
+int launch_pf_pack(kg_ctx *x, const int *tok_dev, const float *rows, int T, const float *gain, float *xout)
+{
+    const int d = x->c.d_model, nb = (T + KG_ROWS - 1) / KG_ROWS;
+    Tok8 tk;
+    memset(&tk, 0, sizeof(tk));
+    const void *emb = tok_dev ? (const void *)(x->arena + x->embed) : nullptr;
+    ProfScope ps(x, 2, 0.0);
+    hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(d / 16, nb), dim3(128), 0, x->stream, emb, tk, tok_dev, rows, d, T, gain,
+                       xout, (void *)(x->scr + x->s_pactX), at<float>(x->scr, x->s_pssq0), act_bytes(d),
+                       (d / 16) * KG_ROWS);
+    return check_launch(x, "prompt pack_rows");
+}
+
+// Y[T][N] = X[T][K] . W^T with the epilogue e applied per 8-row block; in/out block strides follow
+// the prompt buffers (activation tiles of K features per block, d/16 tile sums per block)
+int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T, const Epi &e, bool ssq_in, bool ssq_out,
+                   int act_out_K)
+{
+    if (N % 16) return fail(x, KG_EINVAL, "projection rows %d not a multiple of 16", N);
+    PfArgs a;
+    memset(&a, 0, sizeof(a));
+    a.W = at<const u32x4_t>(x->arena, w_off);
+    a.KS = (K + 31) / 32; a.NT = N / 16;
+    a.act = (const u32x4_t *)act; a.act_blk = act_bytes(K) / 16; a.T = T;
+    const int sq = (x->c.d_model / 16) * KG_ROWS;
+    a.ssq_in_blk = ssq_in ? sq : 0; a.ssq_out_blk = ssq_out ? sq : 0;
+    a.act_out_blk = act_out_K ? act_bytes(act_out_K) : 0;
+    const int nb = (T + KG_ROWS - 1) / KG_ROWS;
+    a.gx = (nb + PF_CBW - 1) / PF_CBW; a.gy = (a.NT + 7) / 8;
+    const int groups = a.gx * 8 * ((a.gy + 7) / 8);
+    ProfScope ps(x, 3, 2.0 * T * (double)N * K);
+    hipLaunchKernelGGL(gemm_prefill_kernel, dim3(groups), dim3(512), 0, x->stream, a, e);
+    return check_launch(x, "prompt projection");
+}
+
+// One decoder block (or the adapter's key/value projection when kv_only) on T prompt rows at pos0.
+// In: pactX = x_in * g_attn, pssq0 = tile sums of x_in.  Out: x rows in x_out, pactX = x_out *
+// next_gain, pssq0 = tile sums of x_out.  Every row's arithmetic is that of the one-token kernels.
+int pf_block(kg_ctx *x, int slot, size_t qkv_off, size_t wo_off, size_t gu_off, size_t wd_off, const float *g2, int T,
+             int pos0, const float *x_in, float *x_out, const float *next_gain, bool kv_only)
+{
+    const kg_config &c = x->c;
+    const int d = c.d_model, f = c.d_ffn, nb = (T + KG_ROWS - 1) / KG_ROWS;
+    float *ssq0 = at<float>(x->scr, x->s_pssq0), *ssq1 = at<float>(x->scr, x->s_pssq1);
+    void *actX = x->scr + x->s_pactX, *actA = x->scr + x->s_pactA, *actF = x->scr + x->s_pactF;
+    float *x_mid = at<float>(x->scr, x->s_px1);
+
+    Epi e = epi_base(x, EPI_PLAIN, KG_ROWS, 3 * d);
+    e.ssq_in = ssq0; e.out = at<float>(x->scr, x->s_pqkv);
+    KGCHK(launch_pf_gemm(x, qkv_off, 3 * d, d, actX, T, e, true, false, 0));
+
+    // all rows' keys and values go to the cache first; then every 8-row block attends to the cache
+    AttnArgs a = attn_args(x, slot, pos0, T);
+    a.qkv = at<const float>(x->scr, x->s_pqkv);
+    a.opart = at<float>(x->scr, x->s_popart); a.mxs = at<float>(x->scr, x->s_pmxs); a.sms = at<float>(x->scr, x->s_psms);
+    a.cnt = at<int>(x->scr, x->s_pcnt);
+    a.act_out = actA; a.act_blk_bytes = act_bytes(d);
+    a.append_only = 1; a.append_all = 1;
+    {
+        ProfScope ps(x, 1, 0.0);
+        KGCHK(launch_attn_args(x, a, dim3(c.n_heads, 1, nb), KG_ROWS));
+    }
+    if (kv_only) return KG_OK;
+    a.append_only = 0; a.append_all = 0; a.preappended = 1;
+    {
+        ProfScope ps(x, 1, 0.0);
+        KGCHK(launch_attn_args(x, a, dim3(c.n_heads, a.S, nb), KG_ROWS));
+    }
+
+    e = epi_base(x, EPI_RESID, KG_ROWS, d);
+    e.res = x_in; e.xout = x_mid; e.act_out = actX; e.act_K = d; e.gain = g2; e.ssq_out = ssq1;
+    KGCHK(launch_pf_gemm(x, wo_off, d, d, actA, T, e, false, true, d));
+
+    e = epi_base(x, EPI_SWIGLU, KG_ROWS, 2 * f);
+    e.ssq_in = ssq1; e.act_out = actF; e.act_K = f;
+    KGCHK(launch_pf_gemm(x, gu_off, 2 * f, d, actX, T, e, true, false, f));
+
+    e = epi_base(x, EPI_RESID, KG_ROWS, d);
+    e.res = x_mid; e.xout = x_out; e.act_out = next_gain ? actX : nullptr; e.act_K = d; e.gain = next_gain;
+    e.ssq_out = ssq0;
+    KGCHK(launch_pf_gemm(x, wd_off, d, f, actF, T, e, false, true, next_gain ? d : 0));
+    return KG_OK;
+}
+
+// Full model M^b and the adapter's cache on prompt rows pos0..pos0+T-1 (token ids in the device
+// copy of the prompt).  Returns the device rows holding the last layer's output.
+int pf_rows_pass(kg_ctx *x, int pos0, int T, const float **x_last)
+{
+    const kg_config &c = x->c;
+    const int L = c.n_layers, l = c.exit_layer;
+    float *x0 = at<float>(x->scr, x->s_px0), *F = at<float>(x->scr, x->s_pF);
+    KGCHK(launch_pf_pack(x, at<const int>(x->scr, x->s_ptok) + pos0, nullptr, T, at<const float>(x->arena, x->lw[0].g1), x0));
+    const float *xin = x0;
+    for (int i = 0; i < L; i++) {
+        const LayerW &w = x->lw[i];
+        float *xout = (i == l - 1) ? F : x0;           // early features of all rows (Section 3.1)
+        const float *ng = (i == L - 1) ? nullptr : at<const float>(x->arena, x->lw[i + 1].g1);
+        KGCHK(pf_block(x, i, w.qkv, w.wo, w.gu, w.wd, at<const float>(x->arena, w.g2), T, pos0, xin, xout, ng, false));
+        xin = xout;
+    }
+    *x_last = xin;
+    // adapter: keys and values of every prompt position (its attention output is not needed here)
+    KGCHK(launch_pf_pack(x, nullptr, F, T, at<const float>(x->arena, x->a_gin), nullptr));
+    return pf_block(x, L, x->a_qkv, 0, 0, 0, nullptr, T, pos0, nullptr, nullptr, nullptr, true);
 }
 
 Epi epi_base(kg_ctx *x, int kind, int M, int N)
@@ -678,6 +812,8 @@ int kg_reset(kg_ctx *x)
     x->spec_shallow = -1;
     if (x->bound) {
         HIPCHK(x, hipMemsetAsync(x->scr + x->s_cnt, 0, (size_t)x->c.n_heads * 4, x->stream));
+        if (x->pf_rows > 0)
+            HIPCHK(x, hipMemsetAsync(x->scr + x->s_pcnt, 0, (size_t)(x->pf_rows / KG_ROWS) * x->c.n_heads * 4, x->stream));
         HIPCHK(x, hipStreamSynchronize(x->stream));
     }
     return KG_OK;
@@ -696,12 +832,28 @@ int kg_prefill(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n, int3
     KGCHK(uniform_at(x, p, n, 2, &u_first));
     KGCHK(kg_reset(x));
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
-    for (int pos0 = 0; pos0 < n; pos0 += KG_ROWS) {
-        int M = std::min(KG_ROWS, n - pos0);
-        KGCHK(run_shallow(x, prompt + pos0, M, pos0, 0));
-        KGCHK(run_adapter(x, 1, M, pos0, false));
-        KGCHK(run_deep(x, M, pos0));
-        if (pos0 + M == n) KGCHK(run_head(x, M, -(M - 1), at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first));
+    if (x->pf_rows > 0) {
+        // bf16 weights: the prompt goes through the MFMA projections, pf_rows rows per pass
+        HIPCHK(x, hipMemcpyAsync(x->scr + x->s_ptok, prompt, (size_t)n * 4, hipMemcpyHostToDevice, x->stream));
+        for (int pos0 = 0; pos0 < n; pos0 += x->pf_rows) {
+            const int T = std::min(x->pf_rows, n - pos0);
+            const float *x_last = nullptr;
+            KGCHK(pf_rows_pass(x, pos0, T, &x_last));
+            if (pos0 + T == n) {
+                // target distribution of the first new token: final norm + LM head on the last row
+                KGCHK(launch_pack_rows(x, nullptr, x_last + (size_t)(T - 1) * c.d_model, 1, at<const float>(x->arena, x->gfinal),
+                                       nullptr, x->scr + x->s_actX, at<float>(x->scr, x->s_ssq0)));
+                KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first));
+            }
+        }
+    } else {
+        for (int pos0 = 0; pos0 < n; pos0 += KG_ROWS) {
+            int M = std::min(KG_ROWS, n - pos0);
+            KGCHK(run_shallow(x, prompt + pos0, M, pos0, 0));
+            KGCHK(run_adapter(x, 1, M, pos0, false));
+            KGCHK(run_deep(x, M, pos0));
+            if (pos0 + M == n) KGCHK(run_head(x, M, -(M - 1), at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first));
+        }
     }
     KGCHK(fetch_results(x, 1));
     x->base = n; x->adapter_len = n; x->lag = 0;

@@ -342,12 +342,15 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__
 // in gemv_bf16_kernel: per output tile the k-steps are split into the same 8 ranges, each range is
 // accumulated in order by MFMA, hi and lo are folded, and the 8 range sums are added in order.
 // A prefilled cache is therefore bit-identical to one written token by token.
-//   grid.x = groups of PF_CBW row blocks, grid.y = groups of 8 weight tiles; wave w of a block owns
-//   weight tile 8*blockIdx.y + w and PF_CBW accumulators; the B tiles (activations) of a stage of
-//   PF_KC k-steps are staged once per block in LDS (double-buffered) and shared by the 8 waves, the
+//   A workgroup handles a group of PF_CBW row blocks (64 rows) and a group of 8 weight tiles; wave w
+//   owns weight tile 8*gy + w and PF_CBW accumulators; the B tiles (activations) of a stage of PF_KC
+//   k-steps are staged once per workgroup in LDS (double-buffered) and shared by the 8 waves, the
 //   weight tiles of the next stage are prefetched into registers while the current one is multiplied.
+//   The grid is one-dimensional: workgroup id -> (XCD = id % 8, j = id / 8), row group = j % gx,
+//   tile group = (j / gx) * 8 + XCD, so the workgroups that stream the same weight tiles for
+//   different row groups run next to each other on one XCD and share its L2.
 #define PF_KC 8
-#define PF_CBW 2
+#define PF_CBW 8
 
 struct PfArgs {
     const u32x4_t *W;       // weight tiles [NT][KS][64]
@@ -357,6 +360,7 @@ struct PfArgs {
     int T;                  // rows in this pass
     int ssq_in_blk, ssq_out_blk;   // floats per 8-row block of the sum-of-squares arrays
     size_t act_out_blk;     // bytes per 8-row block of the output activation
+    int gx, gy;             // row groups, tile groups (the grid holds gx * 8 * ceil(gy / 8) workgroups)
 };
 
 __device__ __forceinline__ Epi pf_block_epi(const Epi &e, const PfArgs &a, int b)
@@ -393,9 +397,12 @@ __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
     __shared__ float scs[PF_CBW][KG_ROWS];
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int nb = (a.T + 7) >> 3;
-    const int b0 = blockIdx.x * PF_CBW;
+    const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+    const int gyi = (jj / a.gx) * 8 + xcd;
+    if (gyi >= a.gy) return;
+    const int b0 = (jj % a.gx) * PF_CBW;
     const int nbw = min(PF_CBW, nb - b0);
-    const int rt = blockIdx.y * 8 + wave;
+    const int rt = gyi * 8 + wave;
     const bool valid = rt < a.NT;
     const int KS = a.KS;
     const u32x4_t zero = {0u, 0u, 0u, 0u};
@@ -422,7 +429,7 @@ __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
     auto prefetch = [&](const PfStage &st) {
 #pragma unroll
         for (int kk = 0; kk < PF_KC; kk++)
-            if (kk < st.n && valid) an[kk] = __builtin_nontemporal_load(wrow + (size_t)(st.k + kk) * 64);
+            if (kk < st.n && valid) an[kk] = wrow[(size_t)(st.k + kk) * 64];
 #pragma unroll
         for (int i = 0; i < NBL; i++) {
             int idx = t + 512 * i;                    // (kk, cb, slot)

@@ -197,3 +197,33 @@ def test_sampling_plain_decoding_follows_oracle():
         seq.append(nt)
     assert diff <= 1
     kg.close()
+
+
+@pytest.mark.parametrize("name,n_prompt,page", [("toy_bf16", 300, 32), ("small_bf16", 77, 64), ("small_bf16", 264, 128)])
+def test_prompt_pass_is_bit_identical_to_one_token_decoding(name, n_prompt, page):
+    """The prompt goes through the dense MFMA projections in passes of 256 rows (groups of 64 rows,
+    blocks of 8, ragged tails here); every row must come out exactly as the one-token kernels
+    compute it: same caches in every layer, same logits for the first new token."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES[name]
+    W = I.gen_weights(shape, seed=5, alpha=0.1)
+    prompt = [int(t) for t in I.gen_prompt(shape.vocab, n_prompt, seed=6)]
+    p, _ = B.make_params()
+    a = P.load_model(shape, W, n_prompt + 16, kv_page_tokens=page)
+    b = P.load_model(shape, W, n_prompt + 16, kv_page_tokens=page)
+    ta = a.prefill(p, prompt)
+    b.prefill(p, prompt[:1])
+    tb = None
+    for t in prompt[1:]:
+        tb = b.plain_step(p, t)
+    assert ta == tb
+    np.testing.assert_array_equal(a.read_logits(1, 0), b.read_logits(1, 0))
+    for slot in range(shape.n_layers):
+        for pos in range(n_prompt):
+            ka, va = a.read_kv(slot, pos)
+            kb, vb = b.read_kv(slot, pos)
+            np.testing.assert_array_equal(ka, kb)
+            np.testing.assert_array_equal(va, vb)
+    a.close()
+    b.close()
