@@ -177,7 +177,17 @@ def main():
                            "traffic": profiled_traffic() if args.shape == "7b" else None,
                            "kernel": "gemv_bf16_kernel", "launches": int(g_n),
                            "avg_launch_us": 1e6 * g_s / g_n, "avg_launch_bytes": g_bytes / g_n}
-        res["device_time_share"] = {"projections": pr.seconds[0], "attention": pr.seconds[1], "other": pr.seconds[2]}
+        res["device_time_share"] = {"projections": pr.seconds[0], "attention": pr.seconds[1], "other": pr.seconds[2],
+                                    "prompt_projections": pr.seconds[3]}
+        # prompt pass (dense MFMA projections, outside the decode metric): wall-clock of kg_prefill and
+        # useful floating-point rate (2 T N K per projection; the bf16 hi+lo split doubles the MFMA work)
+        t0 = time.time()
+        kg.prefill(p, prompt)
+        sync()
+        t_pf = time.time() - t0
+        res["prefill"] = {"tokens": args.prompt, "ms": 1e3 * t_pf, "tokens_per_s": args.prompt / t_pf,
+                          "projection_TFLOPs": pr.bytes[3] / max(pr.seconds[3], 1e-9) / 1e12,
+                          "projection_ms": 1e3 * pr.seconds[3]}
         # plain decoding (the baseline speedups are measured against) and eta = 0
         out_p, st_p = kg.decode_plain(p, prompt, args.new)
         res["plain_tokens_per_s"] = (len(out_p) - 1) / st_p.t_total_s

@@ -24,6 +24,9 @@ def build(force: bool = True, verbose: bool = False) -> str:
         return LIB
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # leading scalar kernel arguments arrive in SGPRs at wave start (no scalar load before the
+           # first weight address can be formed)
+           "-mllvm", "-amdgpu-kernarg-preload-count=16",
            "-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_HERE, "csrc"),
            "-o", LIB] + SOURCES
     if verbose:

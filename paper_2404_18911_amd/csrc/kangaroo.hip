@@ -69,7 +69,7 @@ struct kg_ctx {
     bool profiling = false;
     kg_profile prof;
     std::vector<hipEvent_t> ev_pool;
-    struct Pending { int cls; double bytes; size_t e0, e1; };
+    struct Pending { int cls; double bytes; long long launches; size_t e0, e1; };
     std::vector<Pending> ev_pending;
     size_t ev_used = 0;
     char err[512];
@@ -205,32 +205,43 @@ size_t prof_event(kg_ctx *x)
     return x->ev_used++;
 }
 
+// A run of consecutive launches of one class shares one pair of events: the pair costs about as
+// much device time as a small kernel, so bracketing every launch would inflate what it measures.
+// The run is closed by the first launch of another class, or by prof_flush before the host waits.
+void prof_flush(kg_ctx *x)
+{
+    if (!x->profiling || x->ev_pending.empty()) return;
+    auto &p = x->ev_pending.back();
+    if (p.e1 != (size_t)-1) return;
+    size_t e1 = prof_event(x);
+    if (e1 == (size_t)-1) { x->ev_pending.pop_back(); return; }
+    (void)hipEventRecord(x->ev_pool[e1], x->stream);
+    x->ev_pending.back().e1 = e1;
+}
+
 struct ProfScope {
-    kg_ctx *x; int cls; double bytes; size_t e0 = (size_t)-1;
-    ProfScope(kg_ctx *x_, int cls_, double bytes_) : x(x_), cls(cls_), bytes(bytes_)
+    ProfScope(kg_ctx *x, int cls, double bytes)
     {
-        if (x->profiling) {
-            e0 = prof_event(x);
-            if (e0 != (size_t)-1) (void)hipEventRecord(x->ev_pool[e0], x->stream);
+        if (!x->profiling) return;
+        if (!x->ev_pending.empty() && x->ev_pending.back().e1 == (size_t)-1 && x->ev_pending.back().cls == cls) {
+            x->ev_pending.back().bytes += bytes;
+            x->ev_pending.back().launches++;
+            return;
         }
-    }
-    ~ProfScope()
-    {
-        if (x->profiling && e0 != (size_t)-1) {
-            size_t e1 = prof_event(x);
-            if (e1 == (size_t)-1) return;
-            (void)hipEventRecord(x->ev_pool[e1], x->stream);
-            x->ev_pending.push_back({cls, bytes, e0, e1});
-        }
+        prof_flush(x);
+        size_t e0 = prof_event(x);
+        if (e0 == (size_t)-1) return;
+        (void)hipEventRecord(x->ev_pool[e0], x->stream);
+        x->ev_pending.push_back({cls, bytes, 1, e0, (size_t)-1});
     }
 };
 
-void prof_collect(kg_ctx *x)   // call after the stream has been synchronised
+void prof_collect(kg_ctx *x)   // call after prof_flush and a synchronisation of the stream
 {
     for (auto &p : x->ev_pending) {
         float ms = 0.f;
-        if (hipEventElapsedTime(&ms, x->ev_pool[p.e0], x->ev_pool[p.e1]) == hipSuccess) {
-            x->prof.launches[p.cls]++;
+        if (p.e1 != (size_t)-1 && hipEventElapsedTime(&ms, x->ev_pool[p.e0], x->ev_pool[p.e1]) == hipSuccess) {
+            x->prof.launches[p.cls] += p.launches;
             x->prof.seconds[p.cls] += ms * 1e-3;
             x->prof.bytes[p.cls] += p.bytes;
         }
@@ -245,12 +256,8 @@ int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Ep
 {
     if (N % 16) return fail(x, KG_EINVAL, "projection rows %d not a multiple of 16", N);
     ProfScope ps(x, 0, (double)N * K * x->esz);
-    static const int gemv_u = getenv("KG_GEMV_U") ? atoi(getenv("KG_GEMV_U")) : 8;
-    if (x->bf && (gemv_u >= 16 || (gemv_u == 12 && N / 16 <= 512)))
-        hipLaunchKernelGGL(gemv_bf16_kernel<16>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
-                           at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
-    else if (x->bf)
-        hipLaunchKernelGGL(gemv_bf16_kernel<8>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
+    if (x->bf)
+        hipLaunchKernelGGL((gemv_bf16_kernel<8>), dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
                            at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
     else
         hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, x->stream, at<const float>(x->arena, w_off),
@@ -535,6 +542,7 @@ int uniform_at(kg_ctx *x, const kg_params *p, int pos, int purpose, float *out)
 int fetch_results(kg_ctx *x, int n)
 {
     (void)n;
+    prof_flush(x);
     HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, KG_ROWS * 8, hipMemcpyDeviceToHost, x->stream));
     HIPCHK(x, hipStreamSynchronize(x->stream));
     if (x->profiling) prof_collect(x);
@@ -964,6 +972,7 @@ int kg_accept(kg_ctx *x, const kg_params *p, int32_t *emitted, int *n_emitted)
                                at<int>(x->scr, x->s_acc));
             KGCHK(check_launch(x, "accept_sample"));
         }
+        prof_flush(x);
         HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_acc, 8, hipMemcpyDeviceToHost, x->stream));
         HIPCHK(x, hipStreamSynchronize(x->stream));
         if (x->profiling) prof_collect(x);
@@ -1142,6 +1151,7 @@ int kg_get_state(const kg_ctx *x, int *base, int *adapter_len, int *lag, int *n_
 int kg_set_profiling(kg_ctx *x, int on)
 {
     if (!x) return KG_EINVAL;
+    prof_flush(x);
     if (x->bound) HIPCHK(x, hipStreamSynchronize(x->stream));
     prof_collect(x);
     memset(&x->prof, 0, sizeof(x->prof));
@@ -1205,7 +1215,7 @@ int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, i
         if (hipMemsetAsync(work, 0, act_bytes(K), s) != hipSuccess) return KG_EHIP;
         hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, (const int *)nullptr, xd, K, M,
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
-        hipLaunchKernelGGL(gemv_bf16_kernel<16>, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
+        hipLaunchKernelGGL((gemv_bf16_kernel<8>), dim3(N / 16), dim3(64 * GEMV_WAVES), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
                            (const u32x4_t *)work, e);
     } else {
         hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, (const int *)nullptr, xd, K, M,

@@ -207,7 +207,6 @@ __device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_RO
 // Projection, bf16 weights: one block (8 waves) per 16-row tile; the waves split K; each wave
 // streams its 1 KB weight tiles with 16-byte non-temporal loads and issues one MFMA per tile.
 // W: tiles [rt][ks][64 lanes][8 bf16]; act: B-operand tiles [ks][64 lanes][8 bf16].
-#define GEMV_WAVES 8
 
 template <int U>
 __device__ __forceinline__ void gemv_steps(const u32x4_t *&wp, const u32x4_t *&bp, bool bact, f32x4_t &acc)
@@ -225,6 +224,8 @@ __device__ __forceinline__ void gemv_steps(const u32x4_t *&wp, const u32x4_t *&b
     wp += U * 64;
     bp += U * 64;
 }
+
+#define GEMV_WAVES 8
 
 template <int UMAX>
 __global__ __launch_bounds__(64 * GEMV_WAVES, UMAX >= 16 ? 1 : 2) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS,
