@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--alpha2", type=float, default=0.2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--prefill-only", type=int, default=0,
+                    help="run only this many prompt passes (for profiling the MFMA prompt kernels) and print their timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -133,6 +135,18 @@ def main():
     cal_dst.copy_(cal_src)
     sync()
     del cal_src, cal_dst
+
+    if args.prefill_only:
+        kg.prefill(p, prompt)
+        sync()
+        t0 = time.time()
+        for _ in range(args.prefill_only):
+            kg.prefill(p, prompt)
+        sync()
+        dt = (time.time() - t0) / args.prefill_only
+        print(json.dumps({"prefill_only": True, "tokens": args.prompt, "ms": 1e3 * dt, "tokens_per_s": args.prompt / dt}), flush=True)
+        kg.close()
+        return
 
     for _ in range(args.warmup):
         kg.generate(p, prompt, args.new)
@@ -188,11 +202,23 @@ def main():
         res["prefill"] = {"tokens": args.prompt, "ms": 1e3 * t_pf, "tokens_per_s": args.prompt / t_pf,
                           "projection_TFLOPs": pr.bytes[3] / max(pr.seconds[3], 1e-9) / 1e12,
                           "projection_ms": 1e3 * pr.seconds[3]}
+        # per forward type: algorithmic bytes / host wall-clock of the phase (the draft phase ends when the
+        # draft token is known; the verify phase holds the trailing shallow pass, the deep layers and the head)
+        ceiling = B.op_stream_read_GBs()
+        res["stream_read_ceiling_GBs"] = ceiling
+
+        def fwd(nbytes, seconds):
+            g = nbytes / seconds / 1e9
+            return {"ms": 1e3 * seconds, "GBs": g, "frac_of_peak": g / HBM_PEAK_GBS, "frac_of_ceiling": g / ceiling}
+        res["per_forward"] = {
+            "draft_step": fwd(fb["draft"], stats.t_draft_s / stats.draft_steps),
+            "shallow_plus_verify": fwd(fb["shallow"] + fb["verify"], stats.t_verify_s / stats.verify_calls)}
         # plain decoding (the baseline speedups are measured against) and eta = 0
         out_p, st_p = kg.decode_plain(p, prompt, args.new)
         res["plain_tokens_per_s"] = (len(out_p) - 1) / st_p.t_total_s
         res["speedup_vs_plain"] = value / res["plain_tokens_per_s"]
         res["plain_forward_GBs"] = fb["plain"] * st_p.plain_steps / st_p.t_total_s / 1e9
+        res["per_forward"]["plain"] = fwd(fb["plain"], st_p.t_total_s / st_p.plain_steps)
         res["lossless_on_gpu"] = bool(out_p == out)
         # whole-forward bandwidth of the Kangaroo loop: bytes of all forwards / decode wall-clock
         kang_bytes = stats.draft_steps * fb["draft"] + stats.verify_calls * (fb["shallow"] + fb["verify"])

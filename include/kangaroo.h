@@ -213,6 +213,15 @@ int kg_op_pack(int dtype, const void *src_dev, int N, int K, void *packed_dev, v
 int kg_op_linear(int dtype, const void *packed_dev, int N, int K, const float *x_dev, int M, float *y_dev,
                  void *work_dev, void *hip_stream);
 
+/*
+ * Measured ceiling for a weight stream (Section 1: decoding is bound by reading the weights): one
+ * launch that reads `bytes` bytes (16-byte aligned dev pointer) with no dependencies between the
+ * loads and keeps nothing.  work_dev: 4096 bytes of device scratch (XOR of what was read, so the
+ * loads cannot be dropped).  Launches on `hip_stream`, does not synchronise; the caller times it.
+ * KG_EINVAL for a NULL / misaligned pointer or fewer than 16 bytes.
+ */
+int kg_op_stream_read(const void *src_dev, size_t bytes, void *work_dev, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,7 +45,7 @@ class kg_profile(ctypes.Structure):
 SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "kg_bind", "kg_load_tensor", "kg_set_page_order", "kg_prefill",
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
-           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear"]
+           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_stream_read"]
 
 _lib = None
 
@@ -92,6 +92,7 @@ def lib() -> ctypes.CDLL:
     L.kg_op_work_bytes.restype = ctypes.c_size_t
     L.kg_op_pack.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, vp]
     L.kg_op_linear.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_int, vp, vp, vp]
+    L.kg_op_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     _lib = L
     return L
 
@@ -294,3 +295,26 @@ def op_linear(W_host: np.ndarray, x_host: np.ndarray, device: str = "cuda:0") ->
         raise KangarooError(rc, "kg_op_linear")
     torch.cuda.synchronize(dev)
     return y.cpu().numpy()
+
+
+def op_stream_read_GBs(n_bytes: int = 2 << 30, launches: int = 5, device: str = "cuda:0") -> float:
+    """Bandwidth of kg_op_stream_read over a buffer of n_bytes (dependency-free loads): the measured
+    ceiling that the weight-streaming projections are compared with.  Timed with events on the
+    stream the launches go to."""
+    import torch
+    L = lib()
+    dev = torch.device(device)
+    buf = torch.empty(n_bytes, dtype=torch.uint8, device=dev)
+    buf.zero_()
+    work = torch.zeros(4096, dtype=torch.uint8, device=dev)
+    st = torch.cuda.current_stream(dev)
+    rc = L.kg_op_stream_read(buf.data_ptr(), n_bytes, work.data_ptr(), st.cuda_stream)
+    if rc != KG_OK:
+        raise KangarooError(rc, "kg_op_stream_read")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for _ in range(launches):
+        L.kg_op_stream_read(buf.data_ptr(), n_bytes, work.data_ptr(), st.cuda_stream)
+    e1.record(st)
+    e1.synchronize()
+    return n_bytes * launches / (e0.elapsed_time(e1) * 1e-3) / 1e9

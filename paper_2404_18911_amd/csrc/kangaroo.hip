@@ -367,7 +367,7 @@ int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T
     a.ssq_in_blk = ssq_in ? sq : 0; a.ssq_out_blk = ssq_out ? sq : 0;
     a.act_out_blk = act_out_K ? act_bytes(act_out_K) : 0;
     const int nb = (T + KG_ROWS - 1) / KG_ROWS;
-    a.gx = (nb + PF_CBW - 1) / PF_CBW; a.gy = (a.NT + 7) / 8;
+    a.gx = (nb + PF_CBW - 1) / PF_CBW; a.gy = (a.NT + 8 * PF_TW - 1) / (8 * PF_TW);
     const int groups = a.gx * 8 * ((a.gy + 7) / 8);
     ProfScope ps(x, 3, 2.0 * T * (double)N * K);
     hipLaunchKernelGGL(gemm_prefill_kernel, dim3(groups), dim3(512), 0, x->stream, a, e);
@@ -1222,6 +1222,18 @@ int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, i
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
         hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, s, (const float *)packed, K, (const float *)work, e);
     }
+    return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
+}
+
+int kg_op_stream_read(const void *src, size_t bytes, void *work, void *hip_stream)
+{
+    if (!src || !work || bytes < 16 || ((uintptr_t)src & 15)) return KG_EINVAL;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return KG_EHIP;
+    const int grid = std::max(1, std::min(2 * cus, 1024));       // work holds 1024 words
+    hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(512), 0, (hipStream_t)hip_stream, (const u32x4_t *)src, bytes / 16,
+                       (unsigned *)work);
     return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
 }
 

@@ -15,6 +15,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -58,6 +59,15 @@ __device__ __forceinline__ uint16_t f2bf(float f)
 }
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// A value the compiler must materialise in a register: what is computed from it cannot be fused
+// with what computed it (a * b + c stays a rounded product followed by a sum), so that the same
+// source expression rounds alike in every kernel it is written in.
+__device__ __forceinline__ float rounded(float v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 // device-scope relaxed accesses for data exchanged between workgroups inside one kernel
 __device__ __forceinline__ void st_dev(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float ld_dev(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -71,6 +81,9 @@ template <bool BF>
 __device__ __forceinline__ void store_act(void *buf, int K, int m, int k, float v)
 {
     if (BF) {
+        // the low part is taken from the rounded fp32 value v (fused with a product that made v it
+        // would use the unrounded product, and then depend on the caller's expression)
+        v = rounded(v);
         uint16_t hi = f2bf(v);
         uint16_t lo = f2bf(v - bf2f(hi));
         uint16_t *p = (uint16_t *)buf;
@@ -108,7 +121,7 @@ __device__ __forceinline__ void scale_finish(const Epi &e, const ScaleRegs &r, f
 #pragma unroll
             for (int j = 0; j < 8; j++) s += r.v[j];
             for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
-            s = rsqrtf(s * e.inv_d + e.eps);
+            s = rsqrtf(fmaf(s, e.inv_d, e.eps));
         }
         if (lane == 0) sc[wave] = s;
     }
@@ -130,7 +143,7 @@ __device__ __forceinline__ void compute_scale(const Epi &e, float *sc)
 #pragma unroll
             for (int j = 0; j < 8; j++) s += v[j];
             for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
-            s = rsqrtf(s * e.inv_d + e.eps);
+            s = rsqrtf(fmaf(s, e.inv_d, e.eps));
         }
         if (lane == 0) sc[m] = s;
     }
@@ -343,15 +356,19 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__
 // in gemv_bf16_kernel: per output tile the k-steps are split into the same 8 ranges, each range is
 // accumulated in order by MFMA, hi and lo are folded, and the 8 range sums are added in order.
 // A prefilled cache is therefore bit-identical to one written token by token.
-//   A workgroup handles a group of PF_CBW row blocks (64 rows) and a group of 8 weight tiles; wave w
-//   owns weight tile 8*gy + w and PF_CBW accumulators; the B tiles (activations) of a stage of PF_KC
-//   k-steps are staged once per workgroup in LDS (double-buffered) and shared by the 8 waves, the
-//   weight tiles of the next stage are prefetched into registers while the current one is multiplied.
+//   A workgroup handles a group of PF_CBW row blocks (64 rows) and a group of 8 * PF_TW weight tiles;
+//   wave w owns PF_TW weight tiles and PF_TW * PF_CBW accumulators, so every activation tile read
+//   from LDS feeds PF_TW MFMAs and every weight tile read from memory feeds PF_CBW of them.  The B
+//   tiles (activations) of a stage of PF_KC k-steps are staged once per workgroup in LDS
+//   (double-buffered) and shared by the 8 waves; the weight tiles of the next stage are prefetched
+//   into registers while the current one is multiplied.
 //   The grid is one-dimensional: workgroup id -> (XCD = id % 8, j = id / 8), row group = j % gx,
 //   tile group = (j / gx) * 8 + XCD, so the workgroups that stream the same weight tiles for
 //   different row groups run next to each other on one XCD and share its L2.
-#define PF_KC 8
+#define PF_KC 4
 #define PF_CBW 8
+#define PF_TW 1
+#define PF_RING 4
 
 struct PfArgs {
     const u32x4_t *W;       // weight tiles [NT][KS][64]
@@ -379,6 +396,7 @@ __device__ __forceinline__ Epi pf_block_epi(const Epi &e, const PfArgs &a, int b
 
 struct PfStage { int r, k, n; };   // k-range index (0..7, 8 = end), first k-step, k-steps in the stage
 
+// the stage that starts at k-step k of range r (or the first stage of the next non-empty range)
 __device__ __forceinline__ PfStage pf_stage_at(int r, int k, int KS)
 {
     while (r < 8) {
@@ -393,8 +411,6 @@ __device__ __forceinline__ PfStage pf_stage_at(int r, int k, int KS)
 __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
 {
     __shared__ u32x4_t Bs[2][PF_KC][PF_CBW][64];
-    __shared__ float ytw[8][16][KG_ROWS];
-    __shared__ float sqw[8][16][KG_ROWS];
     __shared__ float scs[PF_CBW][KG_ROWS];
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int nb = (a.T + 7) >> 3;
@@ -403,131 +419,230 @@ __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
     if (gyi >= a.gy) return;
     const int b0 = (jj % a.gx) * PF_CBW;
     const int nbw = min(PF_CBW, nb - b0);
-    const int rt = gyi * 8 + wave;
-    const bool valid = rt < a.NT;
+    const int rt0 = (gyi * 8 + wave) * PF_TW;
     const int KS = a.KS;
     const u32x4_t zero = {0u, 0u, 0u, 0u};
 
-    // RMS scales of this block group's rows (same routine and order as in decoding)
-    for (int cb = 0; cb < PF_CBW; cb++) {
-        if (cb < nbw) {
-            Epi eb = pf_block_epi(e, a, b0 + cb);
-            ScaleRegs sr;
-            scale_fetch(eb, sr);
-            scale_finish(eb, sr, scs[cb]);
+    // RMS scales of this block group's rows: wave w serves row block w; all partial sums of its 8
+    // rows are fetched at once, then every row is reduced exactly as in decoding (lane sums in index
+    // order, then the same butterfly)
+    static_assert(PF_CBW <= 8, "one wave per row block");
+    if (wave < nbw) {
+        const Epi eb = pf_block_epi(e, a, b0 + wave);
+        float pv[KG_ROWS][8];
+#pragma unroll
+        for (int m = 0; m < KG_ROWS; m++)
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const int i = lane + 64 * j;
+                pv[m][j] = (eb.ssq_in && m < eb.M && i < eb.nt_in) ? eb.ssq_in[(size_t)i * KG_ROWS + m] : 0.f;
+            }
+#pragma unroll
+        for (int m = 0; m < KG_ROWS; m++) {
+            float sv = 1.f;
+            if (eb.ssq_in) {
+                sv = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; j++) sv += pv[m][j];
+                for (int o = 32; o >= 1; o >>= 1) sv += __shfl_xor(sv, o);
+                sv = rsqrtf(fmaf(sv, eb.inv_d, eb.eps));
+            }
+            if (lane == 0) scs[wave][m] = sv;
         }
     }
 
-    f32x4_t acc[PF_CBW], tot[PF_CBW];
+    f32x4_t acc[PF_TW][PF_CBW], tot[PF_TW][PF_CBW];
 #pragma unroll
-    for (int cb = 0; cb < PF_CBW; cb++) { acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; tot[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+    for (int tw = 0; tw < PF_TW; tw++)
+#pragma unroll
+        for (int cb = 0; cb < PF_CBW; cb++) {
+            acc[tw][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            tot[tw][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
 
-    u32x4_t an[PF_KC], ac[PF_KC];      // weight tiles: next stage (in flight), current stage
-    u32x4_t bn[(PF_KC * PF_CBW * 64 + 511) / 512];
+    // A stage is up to PF_KC k-steps of one k-range (a range ends a stage early, so the accumulators
+    // are folded between stages only).  Operands travel through a ring of PF_RING stage buffers in
+    // registers: the loads of a stage are issued PF_RING - 1 stages before it is multiplied.  Every
+    // stage issues the same number of loads, unconditionally (pieces beyond its end read a valid
+    // address again and are masked when used).
+    static_assert(PF_RING == 4, "the turns below are written out for a ring of 4");
     constexpr int NBL = (PF_KC * PF_CBW * 64 + 511) / 512;
-    const u32x4_t *wrow = a.W + (size_t)(valid ? rt : 0) * KS * 64 + lane;
-
-    auto prefetch = [&](const PfStage &st) {
+    u32x4_t ra[PF_RING][PF_TW][PF_KC];       // weight tiles
+    u32x4_t rb[PF_RING][NBL];                // this thread's share of the activation tiles
+    bool bmask[PF_RING][NBL];
+    PfStage st[PF_RING];
+    bool valid[PF_TW];
+    const u32x4_t *wrow[PF_TW];
 #pragma unroll
-        for (int kk = 0; kk < PF_KC; kk++)
-            if (kk < st.n && valid) an[kk] = wrow[(size_t)(st.k + kk) * 64];
+    for (int tw = 0; tw < PF_TW; tw++) {
+        valid[tw] = rt0 + tw < a.NT;
+        wrow[tw] = a.W + (size_t)(valid[tw] ? rt0 + tw : 0) * KS * 64 + lane;
+    }
+
+    auto prefetch = [&](auto Q, const PfStage &sg) {
+        constexpr int q = decltype(Q)::value;
+        const bool live = sg.r < 8;
+        const int k0 = live ? sg.k : 0, n = live ? sg.n : 0;
+#pragma unroll
+        for (int tw = 0; tw < PF_TW; tw++)
+#pragma unroll
+            for (int kk = 0; kk < PF_KC; kk++) ra[q][tw][kk] = wrow[tw][(size_t)(k0 + (kk < n ? kk : 0)) * 64];
 #pragma unroll
         for (int i = 0; i < NBL; i++) {
-            int idx = t + 512 * i;                    // (kk, cb, slot)
-            int slot = idx & 63, cb = (idx >> 6) % PF_CBW, kk = idx / (64 * PF_CBW);
-            u32x4_t v = zero;
-            if (kk < st.n && cb < nbw && (slot >> 3) < min(KG_ROWS, a.T - 8 * (b0 + cb)))
-                v = a.act[(size_t)(b0 + cb) * a.act_blk + (size_t)(st.k + kk) * 64 + slot];
-            bn[i] = v;
+            const int idx = t + 512 * i;                    // (kk, cb, slot)
+            const int slot = idx & 63, cb = (idx >> 6) % PF_CBW, kk = idx / (64 * PF_CBW);
+            const int cbx = min(cb, nbw - 1);
+            bmask[q][i] = kk < n && cb < nbw && (slot >> 3) < min(KG_ROWS, a.T - 8 * (b0 + cb));
+            rb[q][i] = a.act[(size_t)(b0 + cbx) * a.act_blk + (size_t)(k0 + (kk < n ? kk : 0)) * 64 + slot];
         }
     };
+    auto next_of = [&](const PfStage &sg) { return sg.r < 8 ? pf_stage_at(sg.r, sg.k + sg.n, KS) : sg; };
 
-    PfStage cur = pf_stage_at(0, 0, KS);
-    prefetch(cur);
     int buf = 0;
-    const int bs = b_slot(lane);
-    while (cur.r < 8) {
+    // multiply stage st[q]; then its buffers take the stage PF_RING further on
+    auto step = [&](auto Q) {
+        constexpr int q = decltype(Q)::value;
+        constexpr int qn = (q + 1) % PF_RING, ql = (q + PF_RING - 1) % PF_RING;
+        const PfStage cur = st[q];
+        if (cur.r >= 8) return;
 #pragma unroll
         for (int i = 0; i < NBL; i++) {
-            int idx = t + 512 * i;
-            (&Bs[buf][0][0][0])[idx] = bn[i];
+            // a tile is kept in LDS in MFMA lane order (piece `slot` of the memory layout goes where the
+            // lane that uses it reads): the 64 lanes of a read then touch consecutive 16-byte pieces,
+            // free of bank conflicts (in memory order a quarter-wave would hit 4 bank groups 4 times)
+            const int idx = t + 512 * i, slot = idx & 63, a4 = slot >> 2;
+            const int pos = ((slot & 3) << 4) | ((a4 & 1) << 3) | (a4 >> 1);
+            (&Bs[buf][0][0][0])[(idx & ~63) | pos] = bmask[q][i] ? rb[q][i] : zero;
         }
-#pragma unroll
-        for (int kk = 0; kk < PF_KC; kk++) ac[kk] = an[kk];
         __syncthreads();
-        PfStage nxt = pf_stage_at(cur.r, cur.k + cur.n, KS);
-        if (nxt.r < 8) prefetch(nxt);
 #pragma unroll
         for (int kk = 0; kk < PF_KC; kk++)
             if (kk < cur.n) {
 #pragma unroll
-                for (int cb = 0; cb < PF_CBW; cb++)
-                    acc[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ac[kk]),
-                                                                      __builtin_bit_cast(bf16x8_t, Bs[buf][kk][cb][bs]),
-                                                                      acc[cb], 0, 0, 0);
-            }
-        if (nxt.r != cur.r) {          // end of a k-range: fold hi/lo, add the range sum in range order
+                for (int cb = 0; cb < PF_CBW; cb++) {
+                    const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, Bs[buf][kk][cb][lane]);
 #pragma unroll
-            for (int cb = 0; cb < PF_CBW; cb++) {
-#pragma unroll
-                for (int r = 0; r < 4; r++) {
-                    float v = acc[cb][r] + __shfl_xor(acc[cb][r], 8);
-                    tot[cb][r] = (cur.r == 0) ? v : tot[cb][r] + v;
+                    for (int tw = 0; tw < PF_TW; tw++)
+                        acc[tw][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ra[q][tw][kk]), bv,
+                                                                              acc[tw][cb], 0, 0, 0);
                 }
-                acc[cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             }
-            // empty ranges between cur.r and nxt.r contribute exact zeros
+        if (st[qn].r != cur.r) {       // end of a k-range: fold hi/lo, add the range sum in range order
+#pragma unroll
+            for (int tw = 0; tw < PF_TW; tw++)
+#pragma unroll
+                for (int cb = 0; cb < PF_CBW; cb++) {
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        float v = acc[tw][cb][r] + __shfl_xor(acc[tw][cb][r], 8);
+                        tot[tw][cb][r] = (cur.r == 0) ? v : tot[tw][cb][r] + v;
+                    }
+                    acc[tw][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                }
+            // empty ranges between cur.r and the next stage's contribute exact zeros
         }
-        cur = nxt;
+        st[q] = next_of(st[ql]);
+        prefetch(Q, st[q]);
         buf ^= 1;
+    };
+
+    st[0] = pf_stage_at(0, 0, KS);
+    prefetch(std::integral_constant<int, 0>{}, st[0]);
+    st[1] = next_of(st[0]);
+    prefetch(std::integral_constant<int, 1>{}, st[1]);
+    st[2] = next_of(st[1]);
+    prefetch(std::integral_constant<int, 2>{}, st[2]);
+    st[3] = next_of(st[2]);
+    prefetch(std::integral_constant<int, 3>{}, st[3]);
+    while (st[0].r < 8) {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
     }
 
-    // epilogue, one 8-row block at a time; every wave finishes its own 16 x 8 tile
-    for (int cb = 0; cb < PF_CBW; cb++) {
-        if (cb >= nbw) break;                 // uniform across the block
-        const Epi eb = pf_block_epi(e, a, b0 + cb);
-        __syncthreads();
-        if ((lane & 15) < 8) {
+    // Epilogue straight from the accumulators: after the fold, lane (column m = lane % 16 < 8, group
+    // g = lane / 16) holds rows 4g..4g+3 of the 16-row tile for batch row m, i.e. four consecutive
+    // output features: vector loads and stores, no staging.  Same arithmetic as the one-token epilogue.
+    const int col = lane & 15, g4 = lane >> 4;
 #pragma unroll
-            for (int r = 0; r < 4; r++) ytw[wave][4 * (lane >> 4) + r][lane & 7] = tot[cb][r];
-        }
-        __syncthreads();
-        const float *sc = scs[cb];
-        if (valid) {
-            if (eb.kind == EPI_PLAIN) {
+    for (int tw = 0; tw < PF_TW; tw++) {
+        const int rt = rt0 + tw;
+        const int n0 = rt * 16 + 4 * g4;
+        const bool okl = valid[tw] && col < KG_ROWS;
+        if (e.kind == EPI_RESID) {
+            float4 rv[PF_CBW];
+            const float4 gv = (okl && e.gain) ? *(const float4 *)(e.gain + n0) : make_float4(1.f, 1.f, 1.f, 1.f);
 #pragma unroll
-                for (int h2 = 0; h2 < 2; h2++) {
-                    int tt = lane + 64 * h2, row = tt >> 3, m = tt & 7;
-                    if (m < eb.M) eb.out[(size_t)m * eb.N + rt * 16 + row] = ytw[wave][row][m] * sc[m];
-                }
-            } else if (eb.kind == EPI_RESID) {
+            for (int cb = 0; cb < PF_CBW; cb++) {
+                const int M = min(KG_ROWS, a.T - 8 * (b0 + cb));
+                rv[cb] = (okl && cb < nbw && col < M) ? *(const float4 *)(e.res + ((size_t)8 * (b0 + cb) + col) * e.N + n0)
+                                                       : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
 #pragma unroll
-                for (int h2 = 0; h2 < 2; h2++) {
-                    int tt = lane + 64 * h2, row = tt >> 3, m = tt & 7;
-                    float v = 0.f;
-                    if (m < eb.M) {
-                        int n = rt * 16 + row;
-                        v = eb.res[(size_t)m * eb.N + n] + ytw[wave][row][m];
-                        eb.xout[(size_t)m * eb.N + n] = v;
-                        if (eb.act_out) store_act<true>(eb.act_out, eb.act_K, m, n, eb.gain ? v * eb.gain[n] : v);
+            for (int cb = 0; cb < PF_CBW; cb++) {
+                if (cb >= nbw) break;
+                const Epi eb = pf_block_epi(e, a, b0 + cb);
+                const bool live = okl && col < eb.M;
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                if (live) {
+                    v[0] = rv[cb].x + tot[tw][cb][0]; v[1] = rv[cb].y + tot[tw][cb][1];
+                    v[2] = rv[cb].z + tot[tw][cb][2]; v[3] = rv[cb].w + tot[tw][cb][3];
+                    *(float4 *)(eb.xout + (size_t)col * eb.N + n0) = make_float4(v[0], v[1], v[2], v[3]);
+                    if (eb.act_out) {
+                        const float gq[4] = {gv.x, gv.y, gv.z, gv.w};
+                        uint16_t hi[4], lo[4];
+#pragma unroll
+                        for (int r = 0; r < 4; r++) {
+                            const float x = rounded(eb.gain ? v[r] * gq[r] : v[r]);
+                            hi[r] = f2bf(x);
+                            lo[r] = f2bf(x - bf2f(hi[r]));
+                        }
+                        uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(n0 >> 5) * 512 + (size_t)(col * 8 + ((n0 >> 3) & 3)) * 8 + (n0 & 7);
+                        *(uint2 *)pa = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                        *(uint2 *)(pa + 32) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
                     }
-                    sqw[wave][row][m] = v * v;
                 }
-            } else {                          // EPI_SWIGLU
-                int i = lane >> 3, m = lane & 7;
-                if (m < eb.M) {
-                    float g = ytw[wave][2 * i][m] * sc[m], u = ytw[wave][2 * i + 1][m] * sc[m];
-                    float av = g / (1.f + __expf(-g)) * u;
-                    store_act<true>(eb.act_out, eb.act_K, m, rt * 8 + i, av);
+                if (eb.ssq_out) {
+                    // sum of squares over the 16 rows of the tile in row order: a chain through the 4 lane groups
+                    float sq = 0.f;
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const float up = __shfl(sq, (lane & 15) + 16 * (g > 0 ? g - 1 : 0));
+                        if (g4 == g) {
+                            float c = g ? up : 0.f;
+#pragma unroll
+                            for (int r = 0; r < 4; r++) c += rounded(v[r] * v[r]);
+                            sq = c;
+                        }
+                    }
+                    if (valid[tw] && g4 == 3 && col < KG_ROWS) eb.ssq_out[(size_t)rt * KG_ROWS + col] = sq;
                 }
             }
-        }
-        if (eb.kind == EPI_RESID && eb.ssq_out) {
-            __syncthreads();
-            if (valid && lane < KG_ROWS) {
-                float s2 = 0.f;
-                for (int r = 0; r < 16; r++) s2 += sqw[wave][r][lane];
-                eb.ssq_out[(size_t)rt * KG_ROWS + lane] = s2;
+        } else {
+#pragma unroll
+            for (int cb = 0; cb < PF_CBW; cb++) {
+                if (cb >= nbw) break;
+                const Epi eb = pf_block_epi(e, a, b0 + cb);
+                if (!(okl && col < eb.M)) continue;
+                const float sc = scs[cb][col];
+                if (eb.kind == EPI_PLAIN) {
+                    *(float4 *)(eb.out + (size_t)col * eb.N + n0) =
+                        make_float4(tot[tw][cb][0] * sc, tot[tw][cb][1] * sc, tot[tw][cb][2] * sc, tot[tw][cb][3] * sc);
+                } else {                          // EPI_SWIGLU: rows (2i, 2i+1) = (gate, up) of feature rt*8 + i
+                    uint16_t hi[2], lo[2];
+#pragma unroll
+                    for (int i = 0; i < 2; i++) {
+                        const float g = tot[tw][cb][2 * i] * sc, u = tot[tw][cb][2 * i + 1] * sc;
+                        const float av = rounded(g / (1.f + __expf(-g)) * u);
+                        hi[i] = f2bf(av);
+                        lo[i] = f2bf(av - bf2f(hi[i]));
+                    }
+                    const int k0 = rt * 8 + 2 * g4;
+                    uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(k0 >> 5) * 512 + (size_t)(col * 8 + ((k0 >> 3) & 3)) * 8 + (k0 & 7);
+                    *(uint32_t *)pa = hi[0] | ((uint32_t)hi[1] << 16);
+                    *(uint32_t *)(pa + 32) = lo[0] | ((uint32_t)lo[1] << 16);
+                }
             }
         }
     }
@@ -1124,6 +1239,31 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *zt, co
     }
     if (tok < 0) tok = block_inverse_cdf([&](int i) { return __expf(zp[i] * inv_temp - pm) * ps; }, V, u_res.v[n]);
     if (t == 0) { out[0] = n; out[1] = tok; }
+}
+
+// Streaming read of a buffer with no dependencies between the loads: the bandwidth that a weight
+// stream could reach at best on this device (the measured ceiling the projections are compared
+// with).  Persistent grid, 8 x 16-byte loads in flight per lane; out[block] keeps the loads alive.
+__global__ __launch_bounds__(512, 2) void stream_read_kernel(const u32x4_t *__restrict__ src, size_t n16, unsigned *out)
+{
+    // a block takes 64 KB pieces; inside a piece every wave reads 8 consecutive KB (as a wave of a
+    // projection reads consecutive 1 KB weight tiles)
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const size_t pieces = (n16 + 4095) >> 12;
+    unsigned x = 0;
+    for (size_t pc = blockIdx.x; pc < pieces; pc += gridDim.x) {
+        const size_t base = (pc << 12) + (size_t)wave * 512 + lane;
+        u32x4_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const size_t i = base + (size_t)u * 64;
+            v[u] = i < n16 ? __builtin_nontemporal_load(src + i) : u32x4_t{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; u++) x ^= v[u][0] ^ v[u][3];
+    }
+    for (int o = 32; o >= 1; o >>= 1) x ^= __shfl_xor(x, o);
+    if (lane == 0) atomicXor(&out[blockIdx.x], x);
 }
 
 // Copy cached k and v rows of one position, widened to float (test / debug access).

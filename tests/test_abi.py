@@ -93,6 +93,9 @@ def test_op_helpers_report_sizes_and_reject_bad_shapes():
     assert L.kg_op_work_bytes(4096) == 4096 * 32
     assert L.kg_op_pack(1, 256, 17, 64, 256, None) == B.KG_EINVAL
     assert L.kg_op_linear(1, 256, 64, 64, 256, 9, 256, 256, None) == B.KG_EINVAL
+    assert L.kg_op_stream_read(None, 1 << 20, 256, None) == B.KG_EINVAL      # NULL source
+    assert L.kg_op_stream_read(264, 1 << 20, 256, None) == B.KG_EINVAL       # misaligned source
+    assert L.kg_op_stream_read(256, 8, 256, None) == B.KG_EINVAL             # fewer than 16 bytes
 
 
 def test_bench_refuses_more_than_one_gpu():
