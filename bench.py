@@ -83,6 +83,60 @@ def cpu_baseline(shape, W, prompt, threads, n_prompt=32, n_new=8):
                       f"decoding (eta 0.6, gamma 6), decode loop only, fp64 C + OpenMP"}
 
 
+def run_sweep(args):
+    """Hyper-parameter sweeps of Section 4.2 on synthetic weights (Figure 3's axes): threshold eta x
+    draft length gamma at the configuration's exit layer, then the exit layer l at (gamma 6, eta 0.6).
+    The LM head is sharpened (--head-scale) so that draft confidences spread over (0, 1) and the stop
+    rule really fires at different lengths; with the plain random head every draft has confidence
+    far below any eta > 0.  Prints one JSON object; not part of the benchmark line."""
+    import dataclasses
+    from paper_2404_18911_amd import binding as B
+    from paper_2404_18911_amd import inputs as I
+    threads = min(16, os.cpu_count() or 8)
+    base = I.SHAPES[args.shape]
+    prompt = I.gen_prompt(base.vocab, args.prompt)
+    gmax = 7
+    out = {"sweep": True, "shape": args.shape, "alpha": args.alpha, "head_scale": args.head_scale,
+           "prompt": args.prompt, "new": args.new, "eta_gamma": [], "exit_layer": []}
+
+    def load(shape):
+        kg = B.Kangaroo(shape, args.prompt + args.new + gmax + 2, gamma_max=gmax, kv_page_tokens=128)
+        for kind, layer, a in I.iter_weights(shape, seed=1, alpha=args.alpha, head_scale=args.head_scale, threads=threads):
+            kg.load_tensor(kind, layer, a)
+        return kg
+
+    def run(kg, gamma, eta):
+        p, _ = B.make_params(eta=eta, gamma=gamma)
+        kg.generate(p, prompt, args.new)
+        toks, st = kg.generate(p, prompt, args.new)
+        return {"gamma": gamma, "eta": eta, "tokens_per_s": (len(toks) - 1) / st.t_total_s,
+                "compression_rate": (args.new - 1) / st.rounds, "mean_draft_len": st.drafted / st.rounds,
+                "acceptance_rate": st.accepted / max(1, st.drafted),
+                "ctar": [sum(c for s_, c in enumerate(st.s_hist) if s_ - w > 0) / st.rounds for w in range(1, gamma + 1)]}
+
+    kg = load(base)
+    p0, _ = B.make_params()
+    toks, stp = kg.decode_plain(p0, prompt, args.new)
+    out["plain_tokens_per_s"] = (len(toks) - 1) / stp.t_total_s
+    for gamma in (2, 4, 6, 7):
+        for eta in (0.0, 0.2, 0.4, 0.6, 0.8, 1.01):
+            r = run(kg, gamma, eta)
+            out["eta_gamma"].append(r)
+            log(f"[sweep] gamma {gamma} eta {eta}: {r['tokens_per_s']:.1f} tok/s, CR {r['compression_rate']:.2f}, k {r['mean_draft_len']:.2f}")
+    kg.close()
+    del kg
+    for l in (1, 2, 3, 4):
+        shape = dataclasses.replace(base, exit_layer=l)
+        kg = load(shape)
+        r = run(kg, 6, 0.6)
+        r["exit_layer"] = l
+        out["exit_layer"].append(r)
+        log(f"[sweep] exit layer {l}: {r['tokens_per_s']:.1f} tok/s, CR {r['compression_rate']:.2f}")
+        kg.close()
+        del kg
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +149,8 @@ def main():
     ap.add_argument("--alpha2", type=float, default=0.2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="eta x gamma and exit-layer sweeps on a sharpened head (not the benchmark line)")
+    ap.add_argument("--head-scale", type=float, default=6.0, help="LM-head multiplier of --sweep")
     ap.add_argument("--prefill-only", type=int, default=0,
                     help="run only this many prompt passes (for profiling the MFMA prompt kernels) and print their timing")
     args = ap.parse_args()
@@ -109,6 +165,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.sweep:
+        run_sweep(args)
+        return
     threads = min(16, os.cpu_count() or 8)
     shape = I.SHAPES[args.shape]
     gamma, eta = 6, 0.6

@@ -227,3 +227,36 @@ def test_prompt_pass_is_bit_identical_to_one_token_decoding(name, n_prompt, page
             np.testing.assert_array_equal(va, vb)
     a.close()
     b.close()
+
+
+def test_hyper_parameter_sweep_keeps_the_stream_and_orders_the_compression_rate():
+    """Section 4.2's sweeps (threshold eta, draft length gamma) on a sharpened head: every setting
+    emits the very same greedy stream (losslessness does not depend on the hyper-parameters),
+    eta = 0 drafts gamma tokens in every round and gives the largest compression rate, eta > 1
+    stops after one draft, and CTAR(w) (Eq. 2) from the round-size histogram is non-increasing."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["small_bf16"]
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=16.0)
+    prompt = I.gen_prompt(shape.vocab, 24)
+    kg = P.load_model(shape, W, 160, gamma_max=6, kv_page_tokens=64)
+    p0, _ = B.make_params()
+    ref, _ = kg.decode_plain(p0, prompt, 96)
+    cr = {}
+    for gamma in (2, 4, 6):
+        for eta in (0.0, 0.3, 0.6, 1.01):
+            p, _ = B.make_params(eta=eta, gamma=gamma)
+            out, st = kg.generate(p, prompt, 96)
+            assert out == ref, (gamma, eta)
+            cr[(gamma, eta)] = 95 / st.rounds
+            if eta == 0.0:
+                assert st.drafted == gamma * st.rounds
+            if eta > 1.0:
+                assert st.drafted == st.rounds
+            ctar = [B.stats_ctar(st, w) for w in range(1, gamma + 1)]
+            assert all(a >= b for a, b in zip(ctar, ctar[1:]))
+            assert abs(B.stats_cr(st) - sum(s * c for s, c in enumerate(st.s_hist)) / st.rounds) < 1e-12
+    for gamma in (2, 4, 6):
+        assert cr[(gamma, 0.0)] >= cr[(gamma, 1.01)]
+    assert cr[(6, 0.0)] >= cr[(2, 0.0)]
+    kg.close()
