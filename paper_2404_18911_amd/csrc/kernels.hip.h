@@ -240,8 +240,7 @@ __device__ __forceinline__ void gemv_steps(const u32x4_t *&wp, const u32x4_t *&b
 
 #define GEMV_WAVES 8
 
-template <int UMAX>
-__global__ __launch_bounds__(64 * GEMV_WAVES, UMAX >= 16 ? 1 : 2) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS,
+__global__ __launch_bounds__(64 * GEMV_WAVES, 2) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS,
                                                                    const u32x4_t *__restrict__ act, Epi e)
 {
     __shared__ float part[GEMV_WAVES][16][KG_ROWS];
@@ -264,10 +263,7 @@ __global__ __launch_bounds__(64 * GEMV_WAVES, UMAX >= 16 ? 1 : 2) void gemv_bf16
         if (e.gain) gainv = e.gain[nn];
     }
     int n = ks1 - ks0;
-    if (UMAX >= 16) {
-        while (n >= 16) { gemv_steps<16>(wp, bp, bact, acc); n -= 16; }
-        if (n >= 8) { gemv_steps<8>(wp, bp, bact, acc); n -= 8; }
-    } else {
+    {
         // chunks of 4 tiles, double-buffered: the loads of chunk i+1 are in flight while chunk i is
         // multiplied, so a wave never drains its memory pipe between chunks
         const u32x4_t zero = {0u, 0u, 0u, 0u};
