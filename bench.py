@@ -44,16 +44,18 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def forward_bytes(shape):
-    """Algorithmic HBM bytes (weights once) of each forward type."""
+def forward_bytes(shape, ctx=0):
+    """Algorithmic HBM bytes of each forward type: weights once, plus the cached keys and values of
+    `ctx` positions once per attention layer of the forward."""
     b = shape.bytes_per_weight()
     d, f, V = shape.d_model, shape.d_ffn, shape.vocab
+    kv = 2 * d * (2 if shape.kv_dtype == "bf16" else 4) * ctx          # one layer's cache
     layer = (4 * d * d + 3 * d * f) * b
     head = d * V * b
     adapter = 4 * d * d * b
     l, L = shape.exit_layer, shape.n_layers
-    return dict(layer=layer, head=head, adapter=adapter, plain=L * layer + head, draft=l * layer + adapter + head,
-                shallow=l * layer, verify=(L - l) * layer + head)
+    return dict(layer=layer, head=head, adapter=adapter, plain=L * (layer + kv) + head,
+                draft=l * (layer + kv) + adapter + kv + head, shallow=l * (layer + kv), verify=(L - l) * (layer + kv) + head)
 
 
 def reload_alpha(kg, shape, alpha, threads):
@@ -220,7 +222,7 @@ def main():
     sync()
     wall = time.time() - t_start
     value = toks / dec_s
-    fb = forward_bytes(shape)
+    fb = forward_bytes(shape, args.prompt + args.new // 2)     # context at mid-run
     rounds = stats.rounds
     acc_rate = stats.accepted / max(1, stats.drafted)
     res = {
