@@ -367,10 +367,13 @@ int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T
     a.ssq_in_blk = ssq_in ? sq : 0; a.ssq_out_blk = ssq_out ? sq : 0;
     a.act_out_blk = act_out_K ? act_bytes(act_out_K) : 0;
     const int nb = (T + KG_ROWS - 1) / KG_ROWS;
-    a.gx = (nb + PF_CBW - 1) / PF_CBW; a.gy = (a.NT + 8 * PF_TW - 1) / (8 * PF_TW);
+    // two weight tiles per multiplying wave where that still leaves enough workgroups for the device
+    const int tw = a.NT >= 512 ? 2 : 1;
+    a.gx = (nb + PF_CBW - 1) / PF_CBW; a.gy = (a.NT + 8 * tw - 1) / (8 * tw);
     const int groups = a.gx * 8 * ((a.gy + 7) / 8);
     ProfScope ps(x, 3, 2.0 * T * (double)N * K);
-    hipLaunchKernelGGL(gemm_prefill_kernel, dim3(groups), dim3(512), 0, x->stream, a, e);
+    if (tw == 2) hipLaunchKernelGGL(gemm_prefill_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e);
+    else hipLaunchKernelGGL(gemm_prefill_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e);
     return check_launch(x, "prompt projection");
 }
 

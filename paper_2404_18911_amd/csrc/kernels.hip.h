@@ -352,19 +352,23 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__
 // in gemv_bf16_kernel: per output tile the k-steps are split into the same 8 ranges, each range is
 // accumulated in order by MFMA, hi and lo are folded, and the 8 range sums are added in order.
 // A prefilled cache is therefore bit-identical to one written token by token.
-//   A workgroup handles a group of PF_CBW row blocks (64 rows) and a group of 8 * PF_TW weight tiles;
-//   wave w owns PF_TW weight tiles and PF_TW * PF_CBW accumulators, so every activation tile read
-//   from LDS feeds PF_TW MFMAs and every weight tile read from memory feeds PF_CBW of them.  The B
-//   tiles (activations) of a stage of PF_KC k-steps are staged once per workgroup in LDS
-//   (double-buffered) and shared by the 8 waves; the weight tiles of the next stage are prefetched
-//   into registers while the current one is multiplied.
+//   A workgroup handles a group of PF_CBW row blocks (64 rows) and a group of 8 * TW weight tiles.
+//   It has 12 waves: waves 8..11 only move data, waves 0..7 only multiply.  The movers bring the
+//   weight tiles and the activation tiles of a stage (PF_KC k-steps) straight from memory into LDS
+//   (global_load_lds: no registers in between), two stages ahead of the multiplication, into a ring
+//   of PF_NB stage buffers, and wait with explicit counts for the stage that is due; the
+//   multipliers read operands from LDS only, so they never wait on memory.  Wave w of the
+//   multipliers owns TW weight tiles and TW * PF_CBW accumulators: every activation tile read from
+//   LDS feeds TW MFMAs.  Activation tiles sit in LDS in MFMA lane order (lane l fetches the piece it
+//   will use), so a read touches 64 consecutive 16-byte pieces, free of bank conflicts.  Rows
+//   beyond the last one of a block are not masked: an MFMA column only depends on its own column of
+//   B, and the results of those columns are never stored.
 //   The grid is one-dimensional: workgroup id -> (XCD = id % 8, j = id / 8), row group = j % gx,
 //   tile group = (j / gx) * 8 + XCD, so the workgroups that stream the same weight tiles for
 //   different row groups run next to each other on one XCD and share its L2.
-#define PF_KC 4
+#define PF_KC 2
 #define PF_CBW 8
-#define PF_TW 1
-#define PF_RING 4
+#define PF_NB 3
 
 struct PfArgs {
     const u32x4_t *W;       // weight tiles [NT][KS][64]
@@ -404,20 +408,23 @@ __device__ __forceinline__ PfStage pf_stage_at(int r, int k, int KS)
     return PfStage{8, 0, 0};
 }
 
-__global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
+template <int PF_TW>
+__device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
 {
-    __shared__ u32x4_t Bs[2][PF_KC][PF_CBW][64];
+    constexpr int NTW = 8 * PF_TW;                         // weight tiles of the workgroup
+    __shared__ u32x4_t As[PF_NB][PF_KC][NTW][64];
+    __shared__ u32x4_t Bs[PF_NB][PF_KC][PF_CBW][64];
     __shared__ float scs[PF_CBW][KG_ROWS];
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const bool mover = wave >= 8;
     const int nb = (a.T + 7) >> 3;
     const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
     const int gyi = (jj / a.gx) * 8 + xcd;
     if (gyi >= a.gy) return;
     const int b0 = (jj % a.gx) * PF_CBW;
     const int nbw = min(PF_CBW, nb - b0);
-    const int rt0 = (gyi * 8 + wave) * PF_TW;
+    const int rt0 = (gyi * 8 + (wave & 7)) * PF_TW;
     const int KS = a.KS;
-    const u32x4_t zero = {0u, 0u, 0u, 0u};
 
     // RMS scales of this block group's rows: wave w serves row block w; all partial sums of its 8
     // rows are fetched at once, then every row is reduced exactly as in decoding (lane sums in index
@@ -447,6 +454,67 @@ __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
         }
     }
 
+    // A stage is up to PF_KC k-steps of one k-range (a range ends a stage early, so the accumulators
+    // are folded between stages only).  Per stage the movers issue a fixed number of tile loads
+    // (pieces beyond the stage's end, beyond the last weight tile or the last row block read a valid
+    // address again; nobody uses them), so the explicit wait counts below are exact.
+    constexpr int TL = PF_KC * (NTW + PF_CBW);             // tile loads of a stage
+    constexpr int LPW = TL / 4;                            // ... per mover wave
+    static_assert(TL % 4 == 0, "tile loads spread evenly over the 4 mover waves");
+    bool valid[PF_TW];
+#pragma unroll
+    for (int tw = 0; tw < PF_TW; tw++) valid[tw] = rt0 + tw < a.NT;
+    const int bsl = b_slot(lane);
+    auto issue = [&](const PfStage &sg, int buf) {         // movers: loads of stage sg into ring slot buf
+        const int k0 = sg.r < 8 ? sg.k : 0, n = sg.r < 8 ? sg.n : 0;
+#pragma unroll
+        for (int i = 0; i < LPW; i++) {
+            const int j = (wave - 8) + 4 * i;              // uniform in the wave
+            if (j < PF_KC * NTW) {
+                const int kk = j / NTW, tile = j % NTW;
+                const int rt = min(gyi * NTW + tile, a.NT - 1);
+                const u32x4_t *src = a.W + ((size_t)rt * KS + k0 + (kk < n ? kk : 0)) * 64 + lane;
+                __builtin_amdgcn_global_load_lds(src, &As[buf][kk][tile][0], 16, 0, 0);
+            } else {
+                const int jb = j - PF_KC * NTW, kk = jb / PF_CBW, cb = jb % PF_CBW;
+                const u32x4_t *src = a.act + (size_t)(b0 + min(cb, nbw - 1)) * a.act_blk + (size_t)(k0 + (kk < n ? kk : 0)) * 64 + bsl;
+                __builtin_amdgcn_global_load_lds(src, &Bs[buf][kk][cb][0], 16, 0, 0);
+            }
+        }
+    };
+    auto next_of = [&](const PfStage &sg) { return sg.r < 8 ? pf_stage_at(sg.r, sg.k + sg.n, KS) : sg; };
+
+    // The waves meet at bare barriers: the movers wait explicitly for exactly the loads that are due
+    // (a fence would wait for all of them, also those issued two stages ahead), and an LDS-direct
+    // load has written its tile once it is counted as complete.  Movers and multipliers run loops
+    // of their own with the same number of barriers.
+    auto meet = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    PfStage cur = pf_stage_at(0, 0, KS), nx1 = next_of(cur);
+    int buf = 0;
+    if (mover) {
+        PfStage nx2 = next_of(nx1);
+        issue(cur, 0);
+        issue(nx1, 1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");     // the first stage has landed
+        __syncthreads();
+        while (cur.r < 8) {
+            // slot buf + 2 held the stage multiplied before the last barrier; the stage after the
+            // current one must have landed before the next barrier
+            issue(nx2, buf >= 1 ? buf - 1 : 2);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");
+            meet();
+            cur = nx1;
+            nx1 = nx2;
+            nx2 = next_of(nx2);
+            buf = buf == PF_NB - 1 ? 0 : buf + 1;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // no load may still be on its way into LDS at the end
+        return;
+    }
     f32x4_t acc[PF_TW][PF_CBW], tot[PF_TW][PF_CBW];
 #pragma unroll
     for (int tw = 0; tw < PF_TW; tw++)
@@ -456,74 +524,23 @@ __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
             tot[tw][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
 
-    // A stage is up to PF_KC k-steps of one k-range (a range ends a stage early, so the accumulators
-    // are folded between stages only).  Operands travel through a ring of PF_RING stage buffers in
-    // registers: the loads of a stage are issued PF_RING - 1 stages before it is multiplied.  Every
-    // stage issues the same number of loads, unconditionally (pieces beyond its end read a valid
-    // address again and are masked when used).
-    static_assert(PF_RING == 4, "the turns below are written out for a ring of 4");
-    constexpr int NBL = (PF_KC * PF_CBW * 64 + 511) / 512;
-    u32x4_t ra[PF_RING][PF_TW][PF_KC];       // weight tiles
-    u32x4_t rb[PF_RING][NBL];                // this thread's share of the activation tiles
-    bool bmask[PF_RING][NBL];
-    PfStage st[PF_RING];
-    bool valid[PF_TW];
-    const u32x4_t *wrow[PF_TW];
-#pragma unroll
-    for (int tw = 0; tw < PF_TW; tw++) {
-        valid[tw] = rt0 + tw < a.NT;
-        wrow[tw] = a.W + (size_t)(valid[tw] ? rt0 + tw : 0) * KS * 64 + lane;
-    }
-
-    auto prefetch = [&](auto Q, const PfStage &sg) {
-        constexpr int q = decltype(Q)::value;
-        const bool live = sg.r < 8;
-        const int k0 = live ? sg.k : 0, n = live ? sg.n : 0;
-#pragma unroll
-        for (int tw = 0; tw < PF_TW; tw++)
-#pragma unroll
-            for (int kk = 0; kk < PF_KC; kk++) ra[q][tw][kk] = wrow[tw][(size_t)(k0 + (kk < n ? kk : 0)) * 64];
-#pragma unroll
-        for (int i = 0; i < NBL; i++) {
-            const int idx = t + 512 * i;                    // (kk, cb, slot)
-            const int slot = idx & 63, cb = (idx >> 6) % PF_CBW, kk = idx / (64 * PF_CBW);
-            const int cbx = min(cb, nbw - 1);
-            bmask[q][i] = kk < n && cb < nbw && (slot >> 3) < min(KG_ROWS, a.T - 8 * (b0 + cb));
-            rb[q][i] = a.act[(size_t)(b0 + cbx) * a.act_blk + (size_t)(k0 + (kk < n ? kk : 0)) * 64 + slot];
-        }
-    };
-    auto next_of = [&](const PfStage &sg) { return sg.r < 8 ? pf_stage_at(sg.r, sg.k + sg.n, KS) : sg; };
-
-    int buf = 0;
-    // multiply stage st[q]; then its buffers take the stage PF_RING further on
-    auto step = [&](auto Q) {
-        constexpr int q = decltype(Q)::value;
-        constexpr int qn = (q + 1) % PF_RING, ql = (q + PF_RING - 1) % PF_RING;
-        const PfStage cur = st[q];
-        if (cur.r >= 8) return;
-#pragma unroll
-        for (int i = 0; i < NBL; i++) {
-            // a tile is kept in LDS in MFMA lane order (piece `slot` of the memory layout goes where the
-            // lane that uses it reads): the 64 lanes of a read then touch consecutive 16-byte pieces,
-            // free of bank conflicts (in memory order a quarter-wave would hit 4 bank groups 4 times)
-            const int idx = t + 512 * i, slot = idx & 63, a4 = slot >> 2;
-            const int pos = ((slot & 3) << 4) | ((a4 & 1) << 3) | (a4 >> 1);
-            (&Bs[buf][0][0][0])[(idx & ~63) | pos] = bmask[q][i] ? rb[q][i] : zero;
-        }
-        __syncthreads();
+    __syncthreads();         // first stage in LDS, RMS scales published
+    while (cur.r < 8) {
 #pragma unroll
         for (int kk = 0; kk < PF_KC; kk++)
             if (kk < cur.n) {
+                bf16x8_t av[PF_TW];
+#pragma unroll
+                for (int tw = 0; tw < PF_TW; tw++) av[tw] = __builtin_bit_cast(bf16x8_t, As[buf][kk][wave * PF_TW + tw][lane]);
 #pragma unroll
                 for (int cb = 0; cb < PF_CBW; cb++) {
                     const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, Bs[buf][kk][cb][lane]);
 #pragma unroll
                     for (int tw = 0; tw < PF_TW; tw++)
-                        acc[tw][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ra[q][tw][kk]), bv,
-                                                                              acc[tw][cb], 0, 0, 0);
+                        acc[tw][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tw], bv, acc[tw][cb], 0, 0, 0);
                 }
             }
-        if (st[qn].r != cur.r) {       // end of a k-range: fold hi/lo, add the range sum in range order
+        if (nx1.r != cur.r) {      // end of a k-range: fold hi/lo, add the range sum in range order
 #pragma unroll
             for (int tw = 0; tw < PF_TW; tw++)
 #pragma unroll
@@ -537,24 +554,10 @@ __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
                 }
             // empty ranges between cur.r and the next stage's contribute exact zeros
         }
-        st[q] = next_of(st[ql]);
-        prefetch(Q, st[q]);
-        buf ^= 1;
-    };
-
-    st[0] = pf_stage_at(0, 0, KS);
-    prefetch(std::integral_constant<int, 0>{}, st[0]);
-    st[1] = next_of(st[0]);
-    prefetch(std::integral_constant<int, 1>{}, st[1]);
-    st[2] = next_of(st[1]);
-    prefetch(std::integral_constant<int, 2>{}, st[2]);
-    st[3] = next_of(st[2]);
-    prefetch(std::integral_constant<int, 3>{}, st[3]);
-    while (st[0].r < 8) {
-        step(std::integral_constant<int, 0>{});
-        step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 3>{});
+        meet();
+        cur = nx1;
+        nx1 = next_of(nx1);
+        buf = buf == PF_NB - 1 ? 0 : buf + 1;
     }
 
     // Epilogue straight from the accumulators: after the fold, lane (column m = lane % 16 < 8, group
@@ -643,6 +646,10 @@ __global__ __launch_bounds__(512) void gemm_prefill_kernel(PfArgs a, Epi e)
         }
     }
 }
+
+// one or two weight tiles per multiplying wave
+__global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1(PfArgs a, Epi e) { gemm_prefill_body<1>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill_kernel_tw2(PfArgs a, Epi e) { gemm_prefill_body<2>(a, e); }
 
 // ---------------------------------------------------------------------------------------------
 // Rows -> activation for the first projection of a stack: x[m] = E[tok[m]] (emb != null) or the
