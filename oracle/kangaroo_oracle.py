@@ -89,6 +89,8 @@ def lib():
         _lib.ko_rope.argtypes = [dp, ctypes.c_int, ctypes.c_int, ctypes.c_double]
         _lib.ko_softmax.argtypes = [dp, ctypes.c_int]
         _lib.ko_attend.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
+        _lib.ko_round_bf16.restype = ctypes.c_double
+        _lib.ko_round_bf16.argtypes = [ctypes.c_double]
         _lib.ko_matvec.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp,
                                    ctypes.c_int, dp]
     return _lib

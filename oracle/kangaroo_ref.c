@@ -303,6 +303,12 @@ void ko_kv_poison(ko_model *mo, int from)
             }
 }
 
+/* the cache's rounding (exposed so that tests can pin ties and the double -> float step) */
+double ko_round_bf16(double x)
+{
+    return round_bf16(x);
+}
+
 /* y = W x for a bare stored matrix (exposed so that tests can pin the widening and the loop) */
 void ko_matvec(const void *W, int wdtype, int N, int K, const double *x, int M, double *y)
 {

@@ -131,6 +131,23 @@ def test_bf16_rounding_of_the_input_generator_is_nearest_even():
     np.testing.assert_array_equal(I.bf16_bits_to_f32(I.f32_to_bf16_bits(t.numpy())), ref)
 
 
+def test_cache_rounding_is_nearest_with_ties_to_even():
+    """bfloat16 keeps 8 significant bits: neighbours of 1 are 2^-7 apart.  Exact halves go to the
+    even neighbour, anything past the half goes up, representable values stay."""
+    r = O.lib().ko_round_bf16
+    e = 2.0 ** -7
+    assert r(1.0 + e / 2) == 1.0                       # tie, lower neighbour even
+    assert r(1.0 + 3 * e / 2) == 1.0 + 2 * e           # tie, upper neighbour even
+    assert r(-(1.0 + e / 2)) == -1.0 and r(-(1.0 + 3 * e / 2)) == -(1.0 + 2 * e)
+    assert r(1.0 + e / 2 + 2.0 ** -20) == 1.0 + e      # just past the half
+    assert r(1.0 + e / 2 - 2.0 ** -20) == 1.0
+    for v in (0.0, 1.0, -3.5, 1.0 + e, 2.0 ** -30, 448.0):
+        assert r(v) == v
+    # a double just above a float tie: float conversion comes first and lands on the tie (2^-40 is
+    # below float resolution at 1), which then goes to even
+    assert r(1.0 + e / 2 + 2.0 ** -40) == 1.0
+
+
 def test_rmsnorm_unit_gain_gives_unit_rms():
     x = np.random.default_rng(3).standard_normal(256) * 5.0
     g = np.ones(256, dtype=np.float32)

@@ -70,7 +70,20 @@ def test_inverse_cdf_cells():
     assert [O.inverse_cdf(p, u) for u in (0.0, 0.2499, 0.25, 0.7499, 0.75, 0.999999)] == [1, 1, 3, 3, 4, 4]
 
 
-def enumerate_law(W, dists, gamma, eta, n_rounds_until, start=None):
+def test_inverse_cdf_past_the_accumulated_mass_returns_the_last_token_with_mass():
+    """Rounding can leave the accumulated mass a hair below u: the answer is then the last token
+    that has mass, never a zero-probability one behind it."""
+    assert O.inverse_cdf(np.array([0.25, 0.25, 0.0, 0.0]), 0.9) == 1
+    assert O.inverse_cdf(np.array([0.0, 1.0 - 2.0 ** -50, 0.0]), 1.0 - 2.0 ** -53) == 1
+
+
+def test_argmax_ties_go_to_the_lowest_token_id_and_softmax_survives_large_logits():
+    assert O.argmax_low(np.array([1.0, 3.0, 3.0, 2.0, 3.0])) == 1
+    np.testing.assert_allclose(O.softmax(np.array([1000.0, 1000.0, -1000.0])), [0.5, 0.5, 0.0], atol=1e-300)
+    np.testing.assert_allclose(O.softmax(np.array([-1000.0, -1000.0 + np.log(3.0)])), [0.25, 0.75], rtol=1e-12)
+
+
+def enumerate_law(W, dists, gamma, eta, n_rounds_until, start=None, temperature=1.0):
     """Exact law of the tokens emitted after the prefill token, conditional on the uniforms in
     `start`.  Returns ({tuple(emitted): prob}, {tuple(emitted): one set of uniforms leading there})."""
     law = {}
@@ -86,7 +99,7 @@ def enumerate_law(W, dists, gamma, eta, n_rounds_until, start=None):
         try:
             runs[0] += 1
             dec = O.KangarooDecoder(O.OracleModel(TINY, W, 16), gamma=gamma, eta=eta, mode="sample",
-                                    uniforms=Uniforms(fixed))
+                                    temperature=temperature, uniforms=Uniforms(fixed))
             state["dec"] = dec
             state["out"] = [dec.prefill(PROMPT)]
             while not n_rounds_until(state["out"][1:], len(dec.S)):
@@ -182,3 +195,75 @@ def test_one_round_gamma2_prefix_laws(world, eta):
                 p3 = dists(base + [a, b])[0]
                 got += short2 * p3 + short1 * p2[b] * p3
                 np.testing.assert_allclose(got, p1[a] * p2[b] * p3, rtol=0, atol=1e-12)
+
+
+def _tempered(z, T):
+    e = np.exp((np.asarray(z, dtype=np.float64) - np.max(z)) / T)
+    return e / e.sum()
+
+
+def test_softmax_temperature_closed_form():
+    """Logits (0, ln 3) at temperature 2 give odds 1 : sqrt(3); temperature 1/2 gives 1 : 9."""
+    z = np.array([0.0, np.log(3.0)])
+    np.testing.assert_allclose(O.softmax(z, 2.0), np.array([1.0, np.sqrt(3.0)]) / (1.0 + np.sqrt(3.0)),
+                               rtol=1e-15)
+    np.testing.assert_allclose(O.softmax(z, 0.5), np.array([0.1, 0.9]), rtol=1e-15)
+
+
+@pytest.mark.parametrize("T", [2.0, 0.5])
+def test_one_round_law_at_other_temperatures(T):
+    """gamma = 2, eta = 0 at temperature T: the first emitted token follows softmax(target / T),
+    the first two follow the product of the tempered conditionals."""
+    W = I.gen_weights(TINY, seed=7, alpha=0.8, std=0.45)
+    ref = O.OracleModel(TINY, W, 16)
+    cache = {}
+
+    def dists(prefix):
+        key = tuple(prefix)
+        if key not in cache:
+            f = ref.shallow(list(prefix), 0)
+            cache[key] = (_tempered(ref.head(ref.deep(f, 0)[-1:], 0)[0], T),
+                          _tempered(ref.head(ref.adapter(f, 0)[-1:], 1)[0], T))
+        return cache[key]
+
+    law, _ = enumerate_law(W, dists, 2, 0.0, lambda out, rounds: rounds >= 1, temperature=T)
+    assert abs(sum(law.values()) - 1.0) < 1e-12
+    c0 = O.inverse_cdf(dists(PROMPT)[0], 0.37)
+    base = PROMPT + [c0]
+    p1 = dists(base)[0]
+    first = np.zeros(16)
+    pair = np.zeros((16, 16))
+    for key, pr in law.items():
+        first[key[0]] += pr
+        if len(key) >= 2:
+            pair[key[0], key[1]] += pr
+        else:
+            pair[key[0], :] += pr * dists(base + [key[0]])[0]
+    np.testing.assert_allclose(first, p1, rtol=0, atol=1e-12)
+    want = np.array([p1[a] * dists(base + [a])[0] for a in range(16)])
+    np.testing.assert_allclose(pair, want, rtol=0, atol=1e-12)
+    # the tempered law is not the untempered one: the test would notice a dropped temperature
+    assert np.abs(p1 - _tempered(np.log(p1) * T, 1.0)).max() > 1e-3
+
+
+def test_draft_confidence_is_taken_from_the_tempered_draft_distribution():
+    """Eq. 4's confidence is the top-1 probability of the distribution the draft is sampled from:
+    at a very high temperature it tends to 1/vocab, so with eta = 0.5 every round stops after one
+    draft, while the same weights at temperature 1 with a sharp head draft longer."""
+    W = I.gen_weights(TINY, seed=7, alpha=0.05, std=0.45)
+    W[(O.LM_HEAD, -1)] = (W[(O.LM_HEAD, -1)] * 40.0).astype(np.float32)
+    rng = np.random.default_rng(5)
+    U = rng.random((16, 3))
+    ks = {}
+    for T in (1.0, 1.0e4):
+        dec = O.KangarooDecoder(O.OracleModel(TINY, W, 16), gamma=4, eta=0.5, mode="sample",
+                                temperature=T, uniforms=U)
+        dec.prefill(PROMPT)
+        while dec.base < 10:
+            dec.round()
+        ks[T] = [r["k"] for r in dec.rounds]
+        if T > 1.0:
+            for r in dec.rounds:
+                assert abs(r["conf"][0] - 1.0 / 16) < 0.02
+    assert set(ks[1.0e4]) == {1}
+    assert max(ks[1.0]) > 1
