@@ -42,6 +42,7 @@ _SO = os.path.join(_HERE, "libkangaroo_ref.so")
 # tensor kinds: the key format of the `weights` dict, (kind, layer); layer = -1 outside the stack
 EMBED, LM_HEAD, FINAL_NORM, WQ, WK, WV, WO, WG, WU, WD, NORM1, NORM2 = range(12)
 A_WQ, A_WK, A_WV, A_WO, A_NORM_IN, A_NORM_LAST = range(12, 18)
+A_HEAD, A_NORM_POST, A_WG, A_WU, A_WD, A_W1, A_W2 = range(18, 25)   # the other adapters of Table 2
 
 U_DRAFT, U_ACCEPT, U_RESAMPLE = 0, 1, 2
 
@@ -57,7 +58,8 @@ def build(force: bool = False) -> str:
 
 class _Cfg(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn",
-                                            "vocab", "exit_layer", "wdtype", "max_seq", "kv_bf16")] + \
+                                            "vocab", "exit_layer", "wdtype", "max_seq", "kv_bf16",
+                                            "adapter_kind")] + \
                [("rms_eps", ctypes.c_double), ("rope_theta", ctypes.c_double)]
 
 
@@ -65,7 +67,8 @@ class _W(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("embed", "lm_head", "final_norm")] + \
                [(n, ctypes.POINTER(ctypes.c_void_p)) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd",
                                                                 "norm1", "norm2")] + \
-               [(n, ctypes.c_void_p) for n in ("a_wq", "a_wk", "a_wv", "a_wo", "a_norm_in", "a_norm_last")]
+               [(n, ctypes.c_void_p) for n in ("a_wq", "a_wk", "a_wv", "a_wo", "a_norm_in", "a_norm_last",
+                                               "a_head", "a_norm_post", "a_wg", "a_wu", "a_wd", "a_w1", "a_w2")]
 
 
 _lib = None
@@ -113,11 +116,14 @@ class OracleModel:
             assert a.flags["C_CONTIGUOUS"] and a.dtype == (np.float32 if wd == 0 else np.uint16)
         cfg = _Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
                    shape.exit_layer, wd, max_seq, 1 if getattr(shape, "kv_dtype", shape.dtype) == "bf16" else 0,
-                   shape.rms_eps, shape.rope_theta)
+                   getattr(shape, "adapter", 0), shape.rms_eps, shape.rope_theta)
         w = _W()
 
         def ptr(kind, layer=-1):
             return ctypes.c_void_p(weights[(kind, layer)].ctypes.data)
+
+        def opt(kind):
+            return ptr(kind) if (kind, -1) in weights else None
 
         w.embed, w.lm_head, w.final_norm = ptr(EMBED), ptr(LM_HEAD), ptr(FINAL_NORM)
         self._arrs = []
@@ -126,8 +132,15 @@ class OracleModel:
             arr = (ctypes.c_void_p * self.L)(*[weights[(kind, i)].ctypes.data for i in range(self.L)])
             self._arrs.append(arr)
             setattr(w, name, ctypes.cast(arr, ctypes.POINTER(ctypes.c_void_p)))
-        w.a_wq, w.a_wk, w.a_wv, w.a_wo = ptr(A_WQ), ptr(A_WK), ptr(A_WV), ptr(A_WO)
+        kind = getattr(shape, "adapter", 0)
+        need = {0: (A_WQ, A_WK, A_WV, A_WO), 1: (A_WQ, A_WK, A_WV, A_WO, A_HEAD),
+                2: (A_WQ, A_WK, A_WV, A_WO, A_NORM_POST, A_WG, A_WU, A_WD), 3: (A_W1, A_W2, A_HEAD)}[kind]
+        for k in need:
+            assert (k, -1) in weights, f"adapter architecture {kind} needs tensor kind {k}"
+        w.a_wq, w.a_wk, w.a_wv, w.a_wo = opt(A_WQ), opt(A_WK), opt(A_WV), opt(A_WO)
         w.a_norm_in, w.a_norm_last = ptr(A_NORM_IN), ptr(A_NORM_LAST)
+        w.a_head, w.a_norm_post = opt(A_HEAD), opt(A_NORM_POST)
+        w.a_wg, w.a_wu, w.a_wd, w.a_w1, w.a_w2 = opt(A_WG), opt(A_WU), opt(A_WD), opt(A_W1), opt(A_W2)
         self._h = lib().ko_create(ctypes.byref(cfg), ctypes.byref(w))
         if not self._h:
             raise MemoryError("ko_create failed")
@@ -166,7 +179,8 @@ class OracleModel:
         return h
 
     def head(self, x: np.ndarray, which: int) -> np.ndarray:
-        """Logits; which = 0: target (final norm), 1: draft (adapter's last norm).  Shared LM head."""
+        """Logits; which = 0: target (final norm, LM head), 1: draft (adapter's last norm; the shared
+        LM head, or the adapter's own for the architectures of Table 2 that have one)."""
         x = np.ascontiguousarray(x, dtype=np.float64)
         z = np.empty((x.shape[0], self.V), dtype=np.float64)
         lib().ko_head(self._h, _dp(x), x.shape[0], which, _dp(z))

@@ -12,7 +12,11 @@
  *   - the shallow sub-network M^b[:l] and the remaining layers M^b[l:] of Section 3.1, as the
  *     same blocks run over a layer range, with a key/value cache per layer;
  *   - the adapter A of Section 3.1 / Figure 2 / Table 2 row "Kangaroo": input RMSNorm, one
- *     multi-head attention (its own key/value cache), residual, last RMSNorm, shared LM head.
+ *     multi-head attention (its own key/value cache), residual, last RMSNorm, shared LM head;
+ *   - the other adapter architectures of Table 2's ablation (adapter_kind): 1 "Kangaroo + Head" =
+ *     the same with an LM head of its own; 2 "1-Layer Transformer" = one whole decoder block
+ *     (attention, post norm, feed-forward, both residuals), last norm, shared head; 3 "MLP Only" =
+ *     input norm, two d x d linear maps, last norm, own head.
  *
  * The key/value cache is a storage format of the configuration, like the weights' type: the
  * bf16 configurations budget 2 bytes per cached element (16 KB per token and layer at d = 4096),
@@ -21,7 +25,9 @@
  *
  * Readings where the paper is silent: rotate-half RoPE pairing (i, i+hd/2), base theta, no
  * biases, residual connection around the adapter's attention, early feature = residual stream
- * after block l-1.  The decode loops (plain, draft-and-verify, acceptance) live in
+ * after block l-1; for the "MLP Only" adapter, h = f + W2 silu(W1 RMSNorm(f)) (the table lists two
+ * linear maps and no activation or residual; SiLU is the model's own activation, the residual is
+ * what the other rows have).  The decode loops (plain, draft-and-verify, acceptance) live in
  * kangaroo_oracle.py, which calls the routines below.
  *
  * Loops are written as the definitions read: no blocking, no fusion.  OpenMP only spreads
@@ -38,6 +44,7 @@ typedef struct {
     int wdtype;            /* 0 = float32, 1 = bfloat16 bit patterns */
     int max_seq;
     int kv_bf16;           /* 1: the cache stores rotated keys and values rounded to bfloat16 */
+    int adapter_kind;      /* Table 2: 0 attention, 1 attention + own head, 2 decoder block, 3 two linear maps + own head */
     double rms_eps, rope_theta;
 } ko_config;
 
@@ -46,6 +53,7 @@ typedef struct {
     const void *const *wq, *const *wk, *const *wv, *const *wo, *const *wg, *const *wu, *const *wd;
     const void *const *norm1, *const *norm2;
     const void *a_wq, *a_wk, *a_wv, *a_wo, *a_norm_in, *a_norm_last;
+    const void *a_head, *a_norm_post, *a_wg, *a_wu, *a_wd, *a_w1, *a_w2;   /* NULL unless the kind has them */
 } ko_weights;
 
 typedef struct {
@@ -220,7 +228,8 @@ static void attn_sublayer(ko_model *mo, int slot, const void *g, const void *wq,
 }
 
 /* feed-forward sub-layer with residual: x <- x + Wd( silu(Wg b) * (Wu b) ), b = RMSNorm(x; g) */
-static void ffn_sublayer(ko_model *mo, int layer, double *x, int M)
+static void ffn_sublayer(ko_model *mo, const void *g, const void *wg, const void *wu, const void *wd,
+                         double *x, int M)
 {
     const ko_config *c = &mo->c;
     int d = c->d_model, f = c->d_ffn, wt = c->wdtype;
@@ -229,14 +238,14 @@ static void ffn_sublayer(ko_model *mo, int layer, double *x, int M)
     double *up = (double *)malloc(sizeof(double) * (size_t)M * f);
     double *y = (double *)malloc(sizeof(double) * (size_t)M * d);
     for (int m = 0; m < M; m++)
-        ko_rmsnorm(x + (size_t)m * d, mo->w.norm2[layer], wt, d, c->rms_eps, b + (size_t)m * d);
-    matvec(mo->w.wg[layer], wt, f, d, b, M, gt);
-    matvec(mo->w.wu[layer], wt, f, d, b, M, up);
+        ko_rmsnorm(x + (size_t)m * d, g, wt, d, c->rms_eps, b + (size_t)m * d);
+    matvec(wg, wt, f, d, b, M, gt);
+    matvec(wu, wt, f, d, b, M, up);
     for (size_t i = 0; i < (size_t)M * f; i++) {
         double z = gt[i];
         gt[i] = z / (1.0 + exp(-z)) * up[i];
     }
-    matvec(mo->w.wd[layer], wt, d, f, gt, M, y);
+    matvec(wd, wt, d, f, gt, M, y);
     for (size_t i = 0; i < (size_t)M * d; i++) x[i] += y[i];
     free(b); free(gt); free(up); free(y);
 }
@@ -258,20 +267,40 @@ void ko_layers(ko_model *mo, int lo, int hi, double *x, int pos0, int M)
     for (int i = lo; i < hi; i++) {
         attn_sublayer(mo, i, mo->w.norm1[i], mo->w.wq[i], mo->w.wk[i], mo->w.wv[i], mo->w.wo[i], x,
                       pos0, M);
-        ffn_sublayer(mo, i, x, M);
+        ffn_sublayer(mo, mo->w.norm2[i], mo->w.wg[i], mo->w.wu[i], mo->w.wd[i], x, M);
     }
 }
 
-/* adapter A without its last norm: h = f + Wo^A . MHA(RMSNorm(f; g_in)); f is [M][d], h likewise */
+/* adapter A without its last norm, f is [M][d], h likewise (Table 2):
+ *   kinds 0, 1: h = f + Wo^A . MHA(RMSNorm(f; g_in))
+ *   kind 2:     the same, then h <- h + Wd^A( silu(Wg^A b) * (Wu^A b) ), b = RMSNorm(h; g_post)
+ *   kind 3:     h = f + W2 . silu(W1 . RMSNorm(f; g_in)), row by row (no cache, pos0 unused) */
 void ko_adapter(ko_model *mo, const double *f, int pos0, int M, double *h)
 {
-    int d = mo->c.d_model;
+    const ko_config *c = &mo->c;
+    int d = c->d_model, wt = c->wdtype;
     memcpy(h, f, sizeof(double) * (size_t)M * d);
+    if (c->adapter_kind == 3) {
+        double *a = (double *)malloc(sizeof(double) * (size_t)M * d);
+        double *u = (double *)malloc(sizeof(double) * (size_t)M * d);
+        double *y = (double *)malloc(sizeof(double) * (size_t)M * d);
+        for (int m = 0; m < M; m++)
+            ko_rmsnorm(f + (size_t)m * d, mo->w.a_norm_in, wt, d, c->rms_eps, a + (size_t)m * d);
+        matvec(mo->w.a_w1, wt, d, d, a, M, u);
+        for (size_t i = 0; i < (size_t)M * d; i++) u[i] = u[i] / (1.0 + exp(-u[i]));
+        matvec(mo->w.a_w2, wt, d, d, u, M, y);
+        for (size_t i = 0; i < (size_t)M * d; i++) h[i] += y[i];
+        free(a); free(u); free(y);
+        return;
+    }
     attn_sublayer(mo, mo->c.n_layers, mo->w.a_norm_in, mo->w.a_wq, mo->w.a_wk, mo->w.a_wv,
                   mo->w.a_wo, h, pos0, M);
+    if (c->adapter_kind == 2)
+        ffn_sublayer(mo, mo->w.a_norm_post, mo->w.a_wg, mo->w.a_wu, mo->w.a_wd, h, M);
 }
 
-/* logits[m] = W_head . RMSNorm(x[m]; g), g = final norm (which = 0) or the adapter's last norm (1) */
+/* logits[m] = W_head . RMSNorm(x[m]; g), g = final norm (which = 0) or the adapter's last norm (1);
+ * the draft head (which = 1) is the adapter's own for kinds 1 and 3, else the shared LM head */
 void ko_head(const ko_model *mo, const double *x, int M, int which, double *logits)
 {
     const ko_config *c = &mo->c;
@@ -279,7 +308,8 @@ void ko_head(const ko_model *mo, const double *x, int M, int which, double *logi
     double *a = (double *)malloc(sizeof(double) * (size_t)M * d);
     const void *g = which ? mo->w.a_norm_last : mo->w.final_norm;
     for (int m = 0; m < M; m++) ko_rmsnorm(x + (size_t)m * d, g, c->wdtype, d, c->rms_eps, a + (size_t)m * d);
-    matvec(mo->w.lm_head, c->wdtype, c->vocab, d, a, M, logits);
+    const void *W = (which && (c->adapter_kind == 1 || c->adapter_kind == 3)) ? mo->w.a_head : mo->w.lm_head;
+    matvec(W, c->wdtype, c->vocab, d, a, M, logits);
     free(a);
 }
 

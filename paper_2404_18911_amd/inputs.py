@@ -4,10 +4,15 @@ prompts and uniform random numbers.
 This module holds no model arithmetic.  It only draws numbers and rounds them to the storage
 type, so that the CPU oracle and the HIP library can be handed the very same bytes.
 
+The adapter comes in the four architectures of Table 2 (ModelShape.adapter): 0 = input norm, one
+multi-head attention, last norm, shared LM head (the paper's choice); 1 = the same with an LM head
+of its own; 2 = one whole decoder block (attention, post norm, feed-forward) and the shared head;
+3 = input norm, two d x d linear maps, last norm, own head.
+
 Recipe (stands in for the Vicuna weights, the trained adapter and the Spec-Bench prompts of
 Section 4.1, none of which are available): every matrix and the embedding are N(0, 0.02); norm
 gains are 1; the o_proj / down_proj of the layers at and above the exit layer, and the adapter's
-output projection, are multiplied by alpha, which is the knob that moves the draft acceptance
+output projection (of whichever residual branch it has), are multiplied by alpha, which is the knob that moves the draft acceptance
 rate.  Prompts are uniform token ids.  Element i of a tensor depends only on (seed, tensor id,
 chunk), so tensors can be produced one at a time and in any order.
 """
@@ -40,8 +45,17 @@ KIND_A_WV = 14
 KIND_A_WO = 15
 KIND_A_NORM_IN = 16
 KIND_A_NORM_LAST = 17
+KIND_A_HEAD = 18        # adapters 1 and 3: an LM head of the adapter's own
+KIND_A_NORM_POST = 19   # adapter 2: norm before its feed-forward
+KIND_A_WG = 20
+KIND_A_WU = 21
+KIND_A_WD = 22
+KIND_A_W1 = 23          # adapter 3: the two linear maps
+KIND_A_W2 = 24
 
-_NORM_KINDS = (KIND_FINAL_NORM, KIND_NORM1, KIND_NORM2, KIND_A_NORM_IN, KIND_A_NORM_LAST)
+ADAPTER_ATTN, ADAPTER_ATTN_HEAD, ADAPTER_LAYER, ADAPTER_MLP = range(4)
+
+_NORM_KINDS = (KIND_FINAL_NORM, KIND_NORM1, KIND_NORM2, KIND_A_NORM_IN, KIND_A_NORM_LAST, KIND_A_NORM_POST)
 _LAYER_KINDS = (KIND_WQ, KIND_WK, KIND_WV, KIND_WO, KIND_WG, KIND_WU, KIND_WD, KIND_NORM1, KIND_NORM2)
 
 
@@ -60,6 +74,7 @@ class ModelShape:
     rms_eps: float = 1e-6
     rope_theta: float = 10000.0
     kv: str = ""                 # storage type of the key/value cache; "" = same as dtype
+    adapter: int = 0             # adapter architecture (Table 2): ADAPTER_ATTN .. ADAPTER_MLP
 
     @property
     def kv_dtype(self) -> str:
@@ -70,8 +85,8 @@ class ModelShape:
         return 4 * d * d + 3 * d * f + 2 * d
 
     def adapter_params(self) -> int:
-        d = self.d_model
-        return 4 * d * d + 2 * d
+        """Parameters the adapter adds to the model (Table 2's column)."""
+        return sum(r * c for _, _, r, c in adapter_tensor_list(self))
 
     def head_params(self) -> int:
         return self.d_model * self.vocab
@@ -95,6 +110,23 @@ def with_layers(shape: ModelShape, n_layers: int, name: str | None = None) -> Mo
     return dataclasses.replace(shape, n_layers=n_layers, name=name or f"{shape.name}_L{n_layers}")
 
 
+def adapter_tensor_list(shape: ModelShape) -> List[Tuple[int, int, int, int]]:
+    """(kind, -1, rows, cols) of the adapter's tensors for the shape's adapter architecture."""
+    d, f, v = shape.d_model, shape.d_ffn, shape.vocab
+    attn = [(KIND_A_WQ, -1, d, d), (KIND_A_WK, -1, d, d), (KIND_A_WV, -1, d, d), (KIND_A_WO, -1, d, d)]
+    norms = [(KIND_A_NORM_IN, -1, 1, d), (KIND_A_NORM_LAST, -1, 1, d)]
+    if shape.adapter == ADAPTER_ATTN:
+        return attn + norms
+    if shape.adapter == ADAPTER_ATTN_HEAD:
+        return attn + norms + [(KIND_A_HEAD, -1, v, d)]
+    if shape.adapter == ADAPTER_LAYER:
+        return attn + norms + [(KIND_A_NORM_POST, -1, 1, d), (KIND_A_WG, -1, f, d), (KIND_A_WU, -1, f, d),
+                               (KIND_A_WD, -1, d, f)]
+    if shape.adapter == ADAPTER_MLP:
+        return [(KIND_A_W1, -1, d, d), (KIND_A_W2, -1, d, d)] + norms + [(KIND_A_HEAD, -1, v, d)]
+    raise ValueError(f"unknown adapter architecture {shape.adapter}")
+
+
 def tensor_list(shape: ModelShape) -> List[Tuple[int, int, int, int]]:
     """(kind, layer, rows, cols) of every tensor; layer is -1 for tensors outside the stack."""
     d, f, v = shape.d_model, shape.d_ffn, shape.vocab
@@ -103,9 +135,7 @@ def tensor_list(shape: ModelShape) -> List[Tuple[int, int, int, int]]:
         out += [(KIND_WQ, i, d, d), (KIND_WK, i, d, d), (KIND_WV, i, d, d), (KIND_WO, i, d, d),
                 (KIND_WG, i, f, d), (KIND_WU, i, f, d), (KIND_WD, i, d, f),
                 (KIND_NORM1, i, 1, d), (KIND_NORM2, i, 1, d)]
-    out += [(KIND_A_WQ, -1, d, d), (KIND_A_WK, -1, d, d), (KIND_A_WV, -1, d, d), (KIND_A_WO, -1, d, d),
-            (KIND_A_NORM_IN, -1, 1, d), (KIND_A_NORM_LAST, -1, 1, d)]
-    return out
+    return out + adapter_tensor_list(shape)
 
 
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
@@ -130,22 +160,25 @@ def _tensor_id(kind: int, layer: int) -> int:
 
 def gen_tensor(shape: ModelShape, kind: int, layer: int, rows: int, cols: int, *, seed: int = 1,
                alpha: float = 0.1, std: float = 0.02, head_scale: float = 1.0,
-               pool: ThreadPoolExecutor | None = None) -> np.ndarray:
+               own_head_copy: bool = True, pool: ThreadPoolExecutor | None = None) -> np.ndarray:
     """One weight tensor in its storage type: float32 array, or uint16 bf16 bit patterns.
 
     head_scale multiplies the LM head (a test-only knob that sharpens the softmax so that the
-    confidence threshold of Eq. 4 is crossed at varying draft lengths).
+    confidence threshold of Eq. 4 is crossed at varying draft lengths).  An adapter's own LM head
+    starts as a copy of the model's (separate memory, same numbers: where its training would start),
+    so that the adapters of Table 2 are compared at like acceptance; own_head_copy=False draws it
+    independently instead.
     """
     n = rows * cols
     if kind in _NORM_KINDS:
         a = np.ones(n, dtype=np.float32)
     else:
         scale = std
-        if (kind in (KIND_WO, KIND_WD) and layer >= shape.exit_layer) or kind == KIND_A_WO:
+        if (kind in (KIND_WO, KIND_WD) and layer >= shape.exit_layer) or kind in (KIND_A_WO, KIND_A_WD, KIND_A_W2):
             scale = std * alpha
-        if kind == KIND_LM_HEAD:
+        if kind in (KIND_LM_HEAD, KIND_A_HEAD):
             scale = std * head_scale
-        tid = _tensor_id(kind, layer)
+        tid = _tensor_id(KIND_LM_HEAD if (kind == KIND_A_HEAD and own_head_copy) else kind, layer)
         nchunk = (n + _CHUNK - 1) // _CHUNK
         a = np.empty(n, dtype=np.float32)
 
@@ -177,19 +210,19 @@ def gen_tensor(shape: ModelShape, kind: int, layer: int, rows: int, cols: int, *
 
 
 def iter_weights(shape: ModelShape, *, seed: int = 1, alpha: float = 0.1, head_scale: float = 1.0,
-                 std: float = 0.02, threads: int = 8) -> Iterator[Tuple[int, int, np.ndarray]]:
+                 std: float = 0.02, threads: int = 8, own_head_copy: bool = True) -> Iterator[Tuple[int, int, np.ndarray]]:
     """Yield (kind, layer, array) for every tensor of the model, one at a time."""
     with ThreadPoolExecutor(max_workers=threads) as pool:
         for kind, layer, rows, cols in tensor_list(shape):
             yield kind, layer, gen_tensor(shape, kind, layer, rows, cols, seed=seed, alpha=alpha, std=std,
-                                          head_scale=head_scale, pool=pool)
+                                          head_scale=head_scale, own_head_copy=own_head_copy, pool=pool)
 
 
 def gen_weights(shape: ModelShape, *, seed: int = 1, alpha: float = 0.1, head_scale: float = 1.0,
-                std: float = 0.02, threads: int = 8) -> Dict[Tuple[int, int], np.ndarray]:
+                std: float = 0.02, threads: int = 8, own_head_copy: bool = True) -> Dict[Tuple[int, int], np.ndarray]:
     """All tensors in host memory, keyed by (kind, layer)."""
-    return {(k, l): a for k, l, a in iter_weights(shape, seed=seed, alpha=alpha, std=std,
-                                                  head_scale=head_scale, threads=threads)}
+    return {(k, l): a for k, l, a in iter_weights(shape, seed=seed, alpha=alpha, std=std, head_scale=head_scale,
+                                                  threads=threads, own_head_copy=own_head_copy)}
 
 
 def gen_prompt(vocab: int, n: int, seed: int = 2) -> np.ndarray:

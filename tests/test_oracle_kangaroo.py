@@ -181,3 +181,57 @@ def test_metrics_match_hand_worked_values():
     vals = [O.ctar(S, w) for w in range(1, 8)]
     assert all(a >= b for a, b in zip(vals, vals[1:]))           # decreasing in w (Section 3)
     assert O.ctar(S, 1) == sum(1 for s in S if s >= 2) / len(S)
+
+
+# ----------------------------------------------------------------------------- Table 2's other adapters
+
+@pytest.mark.parametrize("adapter", [I.ADAPTER_ATTN_HEAD, I.ADAPTER_LAYER, I.ADAPTER_MLP])
+@pytest.mark.parametrize("alpha,head_scale,eta", [(0.05, 25.0, 0.6), (10.0, 25.0, 0.3), (0.1, 1.0, 0.0)])
+def test_every_adapter_architecture_is_lossless_and_lag_free_of_effect(adapter, alpha, head_scale, eta):
+    """Whatever drafts, greedy verification emits the target's own tokens (title, abstract); and
+    the adapter that lags one feature behind drafts exactly what an eager one drafts."""
+    import dataclasses
+    shape = dataclasses.replace(I.SHAPES["toy"], adapter=adapter)
+    W, new = make(shape, alpha, head_scale)
+    prompt = I.gen_prompt(shape.vocab, 16)
+    plain = O.PlainDecoder(new()).generate(prompt, N_NEW)
+    a = O.KangarooDecoder(new(), gamma=5, eta=eta)
+    b = O.KangarooDecoder(new(), gamma=5, eta=eta, eager_adapter=True)
+    assert a.generate(prompt, N_NEW) == plain
+    assert b.generate(prompt, N_NEW) == plain
+    for ra, rb in zip(a.rounds, b.rounds):
+        assert ra["drafts"] == rb["drafts"]
+        np.testing.assert_allclose(ra["conf"], rb["conf"], rtol=1e-12)
+    if alpha == 0.05:
+        assert any(r["n"] == r["k"] for r in a.rounds) and any(r["n"] < r["k"] for r in a.rounds)
+
+
+@pytest.mark.parametrize("adapter", [I.ADAPTER_ATTN_HEAD, I.ADAPTER_LAYER, I.ADAPTER_MLP])
+def test_alpha_zero_switches_every_adapter_architecture_off(adapter):
+    """alpha = 0 zeroes the output projection of every residual branch above the exit layer and in
+    the adapter, so h = f = the final hidden state; with an own head that starts as a copy of the
+    model's, draft logits equal target logits bit for bit and every round is accepted in full."""
+    import dataclasses
+    shape = dataclasses.replace(I.SHAPES["toy"], adapter=adapter)
+    W, new = make(shape, 0.0)
+    prompt = I.gen_prompt(shape.vocab, 16)
+    kd = O.KangarooDecoder(new(), gamma=4, eta=0.0)
+    assert kd.generate(prompt, N_NEW) == O.PlainDecoder(new()).generate(prompt, N_NEW)
+    assert all(r["n"] == r["k"] == 4 for r in kd.rounds)
+    m = new()
+    f = m.shallow(prompt, 0)
+    np.testing.assert_array_equal(m.adapter(f, 0), f)
+    np.testing.assert_array_equal(m.head(m.adapter(f, 0), 1), m.head(m.deep(f, 0), 0))
+
+
+def test_the_mlp_adapter_keeps_no_state():
+    """Two linear maps act row by row: the draft for a feature does not depend on what the adapter
+    saw before, nor on the position."""
+    import dataclasses
+    shape = dataclasses.replace(I.SHAPES["toy"], adapter=I.ADAPTER_MLP)
+    W, new = make(shape, 0.5)
+    m = new()
+    f = m.shallow(I.gen_prompt(shape.vocab, 6), 0)
+    whole = m.adapter(f, 0)
+    for i in (4, 0, 2):
+        np.testing.assert_array_equal(new().adapter(f[i:i + 1], 17), whole[i:i + 1])

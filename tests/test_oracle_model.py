@@ -65,24 +65,38 @@ def torch_forward(shape, W, tokens, lo_hi=None, with_adapter=False):
             f = x
     head = _w64(shape, W, I.KIND_LM_HEAD)
     logits = norm(x, _w64(shape, W, I.KIND_FINAL_NORM)) @ head.T
-    h = attn(f, _w64(shape, W, I.KIND_A_NORM_IN), _w64(shape, W, I.KIND_A_WQ), _w64(shape, W, I.KIND_A_WK),
-             _w64(shape, W, I.KIND_A_WV), _w64(shape, W, I.KIND_A_WO))
-    dlogits = norm(h, _w64(shape, W, I.KIND_A_NORM_LAST)) @ head.T
+    # the adapter, in the architecture of Table 2 the shape names
+    if shape.adapter == I.ADAPTER_MLP:
+        u = norm(f, _w64(shape, W, I.KIND_A_NORM_IN)) @ _w64(shape, W, I.KIND_A_W1).T
+        h = f + torch.nn.functional.silu(u) @ _w64(shape, W, I.KIND_A_W2).T
+    else:
+        h = attn(f, _w64(shape, W, I.KIND_A_NORM_IN), _w64(shape, W, I.KIND_A_WQ), _w64(shape, W, I.KIND_A_WK),
+                 _w64(shape, W, I.KIND_A_WV), _w64(shape, W, I.KIND_A_WO))
+        if shape.adapter == I.ADAPTER_LAYER:
+            b = norm(h, _w64(shape, W, I.KIND_A_NORM_POST))
+            h = h + (torch.nn.functional.silu(b @ _w64(shape, W, I.KIND_A_WG).T)
+                     * (b @ _w64(shape, W, I.KIND_A_WU).T)) @ _w64(shape, W, I.KIND_A_WD).T
+    dhead = _w64(shape, W, I.KIND_A_HEAD) if shape.adapter in (I.ADAPTER_ATTN_HEAD, I.ADAPTER_MLP) else head
+    dlogits = norm(h, _w64(shape, W, I.KIND_A_NORM_LAST)) @ dhead.T
     return f.numpy(), x.numpy(), logits.numpy(), dlogits.numpy()
 
 
-@pytest.mark.parametrize("name,kv", [("toy", ""), ("toy_bf16", ""), ("toy_bf16", "f32")])
-def test_incremental_decode_matches_whole_sequence_library_forward(name, kv):
+@pytest.mark.parametrize("name,kv,adapter", [("toy", "", 0), ("toy_bf16", "", 0), ("toy_bf16", "f32", 0),
+                                             ("toy", "", 1), ("toy", "", 2), ("toy", "", 3),
+                                             ("toy_bf16", "", 2), ("toy_bf16", "", 3)])
+def test_incremental_decode_matches_whole_sequence_library_forward(name, kv, adapter):
     """Oracle run token by token through its caches == library forward of the whole sequence.
     A dropped residual, a wrong RoPE pairing or sign, a transposed operand, a cache indexing
     slip or a wrong widening of bf16 all break this."""
     import dataclasses
-    shape = dataclasses.replace(I.SHAPES[name], kv=kv)
-    # non-trivial gains so that a missing or misplaced gain is caught too
-    W = I.gen_weights(shape, seed=5, alpha=0.7)
+    shape = dataclasses.replace(I.SHAPES[name], kv=kv, adapter=adapter)
+    # non-trivial gains so that a missing or misplaced gain is caught too; an own head that is not
+    # the model's, so that a draft head read from the wrong matrix is caught
+    W = I.gen_weights(shape, seed=5, alpha=0.7, own_head_copy=False)
     rng = np.random.default_rng(0)
     for (k, l), a in list(W.items()):
-        if k in (I.KIND_FINAL_NORM, I.KIND_NORM1, I.KIND_NORM2, I.KIND_A_NORM_IN, I.KIND_A_NORM_LAST):
+        if k in (I.KIND_FINAL_NORM, I.KIND_NORM1, I.KIND_NORM2, I.KIND_A_NORM_IN, I.KIND_A_NORM_LAST,
+                 I.KIND_A_NORM_POST):
             g = (1.0 + 0.3 * rng.standard_normal(a.shape)).astype(np.float32)
             W[(k, l)] = g if shape.dtype == "f32" else I.f32_to_bf16_bits(g)
     toks = I.gen_prompt(shape.vocab, 11, seed=9)
@@ -218,6 +232,11 @@ def test_adapter_and_model_sizes_match_table2():
     assert round((s.adapter_params() + d * V) / 1e6) == gold["kangaroo_plus_head"]
     assert round((4 * d * d + 3 * d * f + 3 * d) / 1e6) == gold["one_layer_transformer"]
     assert round((2 * d * d + d * V + 2 * d) / 1e6) == gold["mlp_only"]
+    # the tensors the generator emits (and both implementations load) for each architecture
+    import dataclasses
+    for kind, row in ((I.ADAPTER_ATTN, "kangaroo"), (I.ADAPTER_ATTN_HEAD, "kangaroo_plus_head"),
+                      (I.ADAPTER_LAYER, "one_layer_transformer"), (I.ADAPTER_MLP, "mlp_only")):
+        assert round(dataclasses.replace(s, adapter=kind).adapter_params() / 1e6) == gold[row]
     medusa = 4 * (d * d + d * V)
     assert round(medusa / 1e6) == gold["medusa"]
     assert round(100 * s.adapter_params() / medusa, 1) == gold["share_percent"]
