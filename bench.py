@@ -50,12 +50,19 @@ def forward_bytes(shape, ctx=0):
     b = shape.bytes_per_weight()
     d, f, V = shape.d_model, shape.d_ffn, shape.vocab
     kv = 2 * d * (2 if shape.kv_dtype == "bf16" else 4) * ctx          # one layer's cache
+    from paper_2404_18911_amd import inputs as I
     layer = (4 * d * d + 3 * d * f) * b
     head = d * V * b
-    adapter = 4 * d * d * b
+    # the adapter's matrices in the architecture of Table 2 the shape names (an own LM head included);
+    # the draft step also reads the shared head unless the adapter has its own, and the adapter's
+    # cache unless it has no attention
+    adapter = sum(r * c for _, _, r, c in I.adapter_tensor_list(shape) if r > 1) * b
+    own_head = shape.adapter in (I.ADAPTER_ATTN_HEAD, I.ADAPTER_MLP)
+    akv = 0 if shape.adapter == I.ADAPTER_MLP else kv
     l, L = shape.exit_layer, shape.n_layers
     return dict(layer=layer, head=head, adapter=adapter, plain=L * (layer + kv) + head,
-                draft=l * (layer + kv) + adapter + kv + head, shallow=l * (layer + kv), verify=(L - l) * (layer + kv) + head)
+                draft=l * (layer + kv) + adapter + akv + (0 if own_head else head), shallow=l * (layer + kv),
+                verify=(L - l) * (layer + kv) + head)
 
 
 def reload_alpha(kg, shape, alpha, threads):
@@ -139,6 +146,54 @@ def run_sweep(args):
     print(json.dumps(out), flush=True)
 
 
+def run_adapters(args):
+    """Cost of the adapter architectures of Table 2's ablation on this GPU: for each one, the bytes a
+    draft step streams, the time it takes, and decode tokens/s of the whole loop at the same
+    synthetic weights (an own LM head starts as a copy of the model's, so acceptance is alike and
+    the differences are the cost of the extra parameters).  Prints one JSON object; not part of
+    the benchmark line."""
+    import dataclasses
+    from paper_2404_18911_amd import binding as B
+    from paper_2404_18911_amd import inputs as I
+    threads = min(16, os.cpu_count() or 8)
+    base = I.SHAPES[args.shape]
+    prompt = I.gen_prompt(base.vocab, args.prompt)
+    gamma, eta = 6, 0.6
+    names = {0: "Kangaroo", 1: "Kangaroo + Head", 2: "1-Layer Transformer", 3: "MLP Only"}
+    out = {"adapters": True, "shape": args.shape, "alpha": args.alpha, "prompt": args.prompt, "new": args.new, "rows": []}
+    plain = None
+    for kind in (0, 1, 2, 3):
+        shape = dataclasses.replace(base, adapter=kind)
+        kg = B.Kangaroo(shape, args.prompt + args.new + gamma + 2, gamma_max=gamma, kv_page_tokens=128)
+        for k, layer, a in I.iter_weights(shape, seed=1, alpha=args.alpha, threads=threads):
+            kg.load_tensor(k, layer, a)
+        p, _ = B.make_params(eta=eta, gamma=gamma)
+        if plain is None:
+            kg.decode_plain(p, prompt, args.new)
+            plain, stp = kg.decode_plain(p, prompt, args.new)
+            out["plain_tokens_per_s"] = (len(plain) - 1) / stp.t_total_s
+        kg.generate(p, prompt, args.new)
+        toks, st = kg.generate(p, prompt, args.new)
+        fb = forward_bytes(shape, args.prompt + args.new // 2)
+        t_draft = st.t_draft_s / st.draft_steps
+        row = {"adapter": names[kind], "kind": kind, "adapter_params_M": shape.adapter_params() / 1e6,
+               "draft_step_bytes": fb["draft"], "draft_step_us": 1e6 * t_draft, "draft_step_GBs": fb["draft"] / t_draft / 1e9,
+               "tokens_per_s": (len(toks) - 1) / st.t_total_s, "speedup_vs_plain": (len(toks) - 1) / st.t_total_s / out["plain_tokens_per_s"],
+               "acceptance_rate": st.accepted / max(1, st.drafted), "compression_rate": (args.new - 1) / st.rounds,
+               "mean_draft_len": st.drafted / st.rounds, "lossless_on_gpu": bool(toks == plain)}
+        # fixed-step drafting (eta = 0): gamma draft steps per round, where the cost per step weighs most
+        p0, _ = B.make_params(eta=0.0, gamma=gamma)
+        toks0, st0 = kg.generate(p0, prompt, args.new)
+        row["eta0"] = {"tokens_per_s": (len(toks0) - 1) / st0.t_total_s, "compression_rate": (args.new - 1) / st0.rounds,
+                       "draft_step_us": 1e6 * st0.t_draft_s / st0.draft_steps, "lossless_on_gpu": bool(toks0 == plain)}
+        out["rows"].append(row)
+        log(f"[adapters] {names[kind]}: {row['adapter_params_M']:.0f}M, draft step {row['draft_step_us']:.0f} us "
+            f"({fb['draft'] / 1e9:.3f} GB), {row['tokens_per_s']:.1f} tok/s, acceptance {row['acceptance_rate']:.2f}")
+        kg.close()
+        del kg
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +208,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="eta x gamma and exit-layer sweeps on a sharpened head (not the benchmark line)")
     ap.add_argument("--head-scale", type=float, default=6.0, help="LM-head multiplier of --sweep")
+    ap.add_argument("--adapters", action="store_true", help="cost of the adapter architectures of Table 2 (not the benchmark line)")
     ap.add_argument("--prefill-only", type=int, default=0,
                     help="run only this many prompt passes (for profiling the MFMA prompt kernels) and print their timing")
     args = ap.parse_args()
@@ -169,6 +225,9 @@ def main():
         sys.exit(1)
     if args.sweep:
         run_sweep(args)
+        return
+    if args.adapters:
+        run_adapters(args)
         return
     threads = min(16, os.cpu_count() or 8)
     shape = I.SHAPES[args.shape]

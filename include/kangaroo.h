@@ -52,12 +52,27 @@ typedef struct kg_config {
     int max_seq;        /* token capacity of the caches: prompt + generated + gamma_max + 1 */
     int gamma_max;      /* largest draft length gamma that will be used (<= KG_MAX_ROWS - 1) */
     int kv_page_tokens; /* tokens per KV page: a power of two in 16..128 */
+    int adapter_kind;   /* architecture of the adapter A (Table 2), one of enum kg_adapter_kind; 0 = the paper's */
 } kg_config;
+
+/* The adapter architectures of Table 2's ablation.  Every one maps the early feature f to a hidden
+ * state h that goes through the adapter's last RMSNorm and an LM head:
+ *   KG_ADAPTER_ATTN       "Kangaroo": h = f + Wo.MHA(RMSNorm(f)); the target's LM head (67M at 7B)
+ *   KG_ADAPTER_ATTN_HEAD  "Kangaroo + Head": the same, with an LM head of its own (198M)
+ *   KG_ADAPTER_LAYER      "1-Layer Transformer": attention, then post norm and SwiGLU feed-forward
+ *                         with their residuals, i.e. one more decoder block; the target's head (202M)
+ *   KG_ADAPTER_MLP        "MLP Only": h = f + W2.silu(W1.RMSNorm(f)), two [d_model][d_model] maps,
+ *                         no attention and no cache; own head (165M) */
+typedef enum kg_adapter_kind {
+    KG_ADAPTER_ATTN = 0, KG_ADAPTER_ATTN_HEAD = 1, KG_ADAPTER_LAYER = 2, KG_ADAPTER_MLP = 3
+} kg_adapter_kind;
 
 /* Tensors of the model.  Per-layer kinds take layer = 0..n_layers-1, the others layer = -1.
  * The adapter A of Section 3.1 / Figure 2 / Table 2 (row "Kangaroo") is one bias-free multi-head
  * attention (KG_A_WQ..KG_A_WO, each [d_model][d_model]) between two RMSNorm gain vectors, and
- * re-uses the target's LM head. */
+ * re-uses the target's LM head.  The kinds from KG_A_HEAD on belong to the other adapter
+ * architectures of Table 2: a context takes exactly the adapter tensors its adapter_kind has
+ * (loading another one is KG_EINVAL). */
 typedef enum kg_tensor_kind {
     KG_EMBED = 0,       /* [vocab][d_model] */
     KG_LM_HEAD = 1,     /* [vocab][d_model] */
@@ -68,7 +83,12 @@ typedef enum kg_tensor_kind {
     KG_NORM1 = 10, KG_NORM2 = 11,                /* [d_model] */
     KG_A_WQ = 12, KG_A_WK = 13, KG_A_WV = 14, KG_A_WO = 15,
     KG_A_NORM_IN = 16, KG_A_NORM_LAST = 17,
-    KG_N_TENSOR_KINDS = 18
+    KG_A_HEAD = 18,                              /* [vocab][d_model]: KG_ADAPTER_ATTN_HEAD, KG_ADAPTER_MLP */
+    KG_A_NORM_POST = 19,                         /* [d_model]: KG_ADAPTER_LAYER */
+    KG_A_WG = 20, KG_A_WU = 21,                  /* [d_ffn][d_model]: KG_ADAPTER_LAYER */
+    KG_A_WD = 22,                                /* [d_model][d_ffn]: KG_ADAPTER_LAYER */
+    KG_A_W1 = 23, KG_A_W2 = 24,                  /* [d_model][d_model]: KG_ADAPTER_MLP */
+    KG_N_TENSOR_KINDS = 25
 } kg_tensor_kind;
 
 /* Decoding parameters.  gamma and eta are the maximum draft length and the confidence

@@ -21,7 +21,7 @@ class kg_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
                                             "exit_layer", "dtype", "kv_dtype")] + \
                [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float)] + \
-               [(n, ctypes.c_int) for n in ("max_seq", "gamma_max", "kv_page_tokens")]
+               [(n, ctypes.c_int) for n in ("max_seq", "gamma_max", "kv_page_tokens", "adapter_kind")]
 
 
 class kg_params(ctypes.Structure):
@@ -121,7 +121,7 @@ def make_config(shape, max_seq: int, gamma_max: int = 6, kv_page_tokens: int = 1
     return kg_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
                      shape.exit_layer, 0 if shape.dtype == "f32" else 1, 0 if shape.kv_dtype == "f32" else 1,
                      shape.rms_eps, shape.rope_theta,
-                     max_seq, gamma_max, kv_page_tokens)
+                     max_seq, gamma_max, kv_page_tokens, getattr(shape, "adapter", 0))
 
 
 def make_params(mode: int = 0, temperature: float = 1.0, eta: float = 0.6, gamma: int = 6,

@@ -37,6 +37,9 @@ struct kg_ctx {
     // arena layout
     std::vector<LayerW> lw;
     size_t a_qkv, a_wo, a_gin, a_glast, head, embed, gfinal, arena_bytes;
+    // tensors of the other adapter architectures of Table 2 (allocated when adapter_kind has them)
+    size_t a_head = 0, a_gpost = 0, a_gu = 0, a_wd = 0, a_w1 = 0, a_w2 = 0;
+    int akind = 0;
     size_t kv_bytes, scratch_bytes;
     // scratch layout (byte offsets)
     size_t s_x0, s_x1, s_F, s_qkv, s_actX, s_actA, s_actF, s_ssq0, s_ssq1, s_opart, s_mxs, s_sms, s_cnt,
@@ -125,8 +128,20 @@ void layout(kg_ctx *x)
         x->lw[i].g1 = take((size_t)d * 4);
         x->lw[i].g2 = take((size_t)d * 4);
     }
-    x->a_qkv = take(packed_bytes(x->bf, 3 * d, d));
-    x->a_wo = take(packed_bytes(x->bf, d, d));
+    x->a_qkv = x->a_wo = 0;
+    if (x->akind != KG_ADAPTER_MLP) {
+        x->a_qkv = take(packed_bytes(x->bf, 3 * d, d));
+        x->a_wo = take(packed_bytes(x->bf, d, d));
+    } else {
+        x->a_w1 = take(packed_bytes(x->bf, d, d));
+        x->a_w2 = take(packed_bytes(x->bf, d, d));
+    }
+    if (x->akind == KG_ADAPTER_LAYER) {
+        x->a_gu = take(packed_bytes(x->bf, 2 * f, d));
+        x->a_wd = take(packed_bytes(x->bf, d, f));
+        x->a_gpost = take((size_t)d * 4);
+    }
+    if (x->akind == KG_ADAPTER_ATTN_HEAD || x->akind == KG_ADAPTER_MLP) x->a_head = take(packed_bytes(x->bf, V, d));
     x->a_gin = take((size_t)d * 4);
     x->a_glast = take((size_t)d * 4);
     x->head = take(packed_bytes(x->bf, V, d));
@@ -443,7 +458,9 @@ int pf_rows_pass(kg_ctx *x, int pos0, int T, const float **x_last)
         xin = xout;
     }
     *x_last = xin;
-    // adapter: keys and values of every prompt position (its attention output is not needed here)
+    // adapter: keys and values of every prompt position (its attention output is not needed here);
+    // the adapter made of two linear maps keeps no cache
+    if (x->akind == KG_ADAPTER_MLP) return KG_OK;
     KGCHK(launch_pf_pack(x, nullptr, F, T, at<const float>(x->arena, x->a_gin), nullptr));
     return pf_block(x, L, x->a_qkv, 0, 0, 0, nullptr, T, pos0, nullptr, nullptr, nullptr, true);
 }
@@ -516,12 +533,14 @@ int run_layers(kg_ctx *x, int lo, int hi, int M, int pos0, const float *x_first,
 // arg-max and top-1 probability of rows 0..n_out-1 into the device tok/conf arrays.
 // u: per-row uniform numbers for sampling (mode 1), stat: where the rows' (max, sum exp) go.
 int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float inv_temp, int mode = 0,
-             const float *u = nullptr, float *stat = nullptr)
+             const float *u = nullptr, float *stat = nullptr, bool draft = false)
 {
+    // the draft head is the adapter's own where its architecture has one (Table 2), else the shared LM head
+    const size_t head_off = (draft && x->a_head) ? x->a_head : x->head;
     Epi e = epi_base(x, EPI_HEAD, M, x->c.vocab);
     e.ssq_in = at<float>(x->scr, x->s_ssq0); e.out = logits; e.row_shift = row_shift;
     e.hstat = at<float>(x->scr, x->s_hstat); e.inv_temp = inv_temp;
-    KGCHK(launch_gemv(x, x->head, x->c.vocab, x->c.d_model, x->scr + x->s_actX, e));
+    KGCHK(launch_gemv(x, head_off, x->c.vocab, x->c.d_model, x->scr + x->s_actX, e));
     ProfScope ps(x, 2, 0.0);
     F8 uu;
     for (int i = 0; i < KG_ROWS; i++) uu.v[i] = (u && i < n_out) ? u[i] : 0.f;
@@ -570,17 +589,33 @@ int run_shallow(kg_ctx *x, const int *tokens, int M, int pos0, int j0, const int
 int run_adapter(kg_ctx *x, int frow, int M, int pos0, bool full)
 {
     const kg_config &c = x->c;
+    const int d = c.d_model;
     const float *rows = at<float>(x->scr, x->s_F) + (size_t)frow * c.d_model;
+    const float *glast = at<const float>(x->arena, x->a_glast);
+    if (x->akind == KG_ADAPTER_MLP && !full) return KG_OK;      // no cache to fill
     KGCHK(launch_pack_rows(x, nullptr, rows, M, at<const float>(x->arena, x->a_gin), nullptr, x->scr + x->s_actX,
                            at<float>(x->scr, x->s_ssq0)));
+    if (x->akind == KG_ADAPTER_MLP) {
+        // h = f + W2 . silu(W1 . RMSNorm(f; g_in)), then the last norm is folded into the head's input
+        Epi e = epi_base(x, EPI_SILU, M, d);
+        e.ssq_in = at<float>(x->scr, x->s_ssq0); e.act_out = x->scr + x->s_actA; e.act_K = d;
+        KGCHK(launch_gemv(x, x->a_w1, d, d, x->scr + x->s_actX, e));
+        e = epi_base(x, EPI_RESID, M, d);
+        e.res = rows; e.xout = at<float>(x->scr, x->s_x1); e.act_out = x->scr + x->s_actX; e.act_K = d;
+        e.gain = glast; e.ssq_out = at<float>(x->scr, x->s_ssq0);
+        return launch_gemv(x, x->a_w2, d, d, x->scr + x->s_actA, e);
+    }
     if (!full) {
         Epi e = epi_base(x, EPI_PLAIN, M, 3 * c.d_model);
         e.ssq_in = at<float>(x->scr, x->s_ssq0); e.out = at<float>(x->scr, x->s_qkv);
         KGCHK(launch_gemv(x, x->a_qkv, 3 * c.d_model, c.d_model, x->scr + x->s_actX, e));
         return launch_attn(x, c.n_layers, pos0, M, 1);
     }
-    return run_block(x, c.n_layers, x->a_qkv, x->a_wo, 0, 0, nullptr, M, pos0, rows, at<float>(x->scr, x->s_x1),
-                     at<const float>(x->arena, x->a_glast), false);
+    if (x->akind == KG_ADAPTER_LAYER)     // one whole decoder block with the adapter's weights
+        return run_block(x, c.n_layers, x->a_qkv, x->a_wo, x->a_gu, x->a_wd, at<const float>(x->arena, x->a_gpost), M,
+                         pos0, rows, at<float>(x->scr, x->s_x0), glast, true);
+    return run_block(x, c.n_layers, x->a_qkv, x->a_wo, 0, 0, nullptr, M, pos0, rows, at<float>(x->scr, x->s_x1), glast,
+                     false);
 }
 
 // remaining layers M^b[l:] on early features f_0..f_{M-1} at pos0, then final norm (folded) —
@@ -618,9 +653,22 @@ int check_params(kg_ctx *x, const kg_params *p)
     return KG_OK;
 }
 
+// does the context's adapter architecture (Table 2) have this adapter tensor?
+bool adapter_has(const kg_ctx *x, int kind)
+{
+    switch (kind) {
+    case KG_A_WQ: case KG_A_WK: case KG_A_WV: case KG_A_WO: return x->akind != KG_ADAPTER_MLP;
+    case KG_A_NORM_IN: case KG_A_NORM_LAST: return true;
+    case KG_A_HEAD: return x->akind == KG_ADAPTER_ATTN_HEAD || x->akind == KG_ADAPTER_MLP;
+    case KG_A_NORM_POST: case KG_A_WG: case KG_A_WU: case KG_A_WD: return x->akind == KG_ADAPTER_LAYER;
+    case KG_A_W1: case KG_A_W2: return x->akind == KG_ADAPTER_MLP;
+    }
+    return false;
+}
+
 int tensor_slot(const kg_ctx *x, int kind, int layer)
 {
-    // slot index into `loaded`: 3 globals, 9 per layer, 6 adapter
+    // slot index into `loaded`: 3 globals, 9 per layer, 13 adapter kinds
     if (kind <= KG_FINAL_NORM) return kind;
     if (kind <= KG_NORM2) return 3 + layer * 9 + (kind - KG_WQ);
     return 3 + x->c.n_layers * 9 + (kind - KG_A_WQ);
@@ -673,9 +721,11 @@ int kg_create(const kg_config *cfg, kg_ctx **out)
     if (c.kv_page_tokens < 16 || c.kv_page_tokens > 128 || (c.kv_page_tokens & (c.kv_page_tokens - 1))) return KG_EINVAL;
     if ((c.max_seq + c.kv_page_tokens - 1) / c.kv_page_tokens > 128) return KG_EINVAL;   // at most 128 KV pages
     if (c.max_seq < 2 || !(c.rms_eps >= 0.f) || !(c.rope_theta > 0.f)) return KG_EINVAL;
+    if (c.adapter_kind < KG_ADAPTER_ATTN || c.adapter_kind > KG_ADAPTER_MLP) return KG_EINVAL;
     kg_ctx *x = new (std::nothrow) kg_ctx();
     if (!x) return KG_ENOMEM;
     x->c = c;
+    x->akind = c.adapter_kind;
     x->bf = c.dtype == 1;
     x->esz = x->bf ? 2 : 4;
     x->kvbf = c.kv_dtype == 1;
@@ -687,7 +737,7 @@ int kg_create(const kg_config *cfg, kg_ctx **out)
     x->err[0] = 0;
     memset(&x->prof, 0, sizeof(x->prof));
     layout(x);
-    x->loaded.assign(3 + (size_t)c.n_layers * 9 + 6, 0);
+    x->loaded.assign(3 + (size_t)c.n_layers * 9 + (KG_N_TENSOR_KINDS - KG_A_WQ), 0);
     x->page_order.resize(x->n_pages);
     for (int i = 0; i < x->n_pages; i++) x->page_order[i] = i;
     *out = x;
@@ -738,6 +788,8 @@ int kg_bind(kg_ctx *x, void *weights_dev, size_t weight_bytes, void *kv_dev, siz
     }
     x->bound = true;
     std::fill(x->loaded.begin(), x->loaded.end(), 0);
+    for (int k = KG_A_WQ; k < KG_N_TENSOR_KINDS; k++)       // adapter tensors this architecture does not have
+        if (!adapter_has(x, k)) x->loaded[tensor_slot(x, k, -1)] = 1;
     x->phase = Phase::NONE;
     return upload_tables(x);
 }
@@ -753,6 +805,8 @@ int kg_load_tensor(kg_ctx *x, int kind, int layer, const void *src, size_t n_ele
     bool per_layer = kind >= KG_WQ && kind <= KG_NORM2;
     if (per_layer ? (layer < 0 || layer >= c.n_layers) : (layer != -1))
         return fail(x, KG_EINVAL, "bad layer %d for tensor kind %d", layer, kind);
+    if (kind >= KG_A_WQ && !adapter_has(x, kind))
+        return fail(x, KG_EINVAL, "tensor kind %d is not part of adapter architecture %d", kind, x->akind);
     int rows = 0, K = 0, row_off = 0, mode = 0;
     size_t dst = 0;
     bool is_gain = false;
@@ -770,6 +824,12 @@ int kg_load_tensor(kg_ctx *x, int kind, int layer, const void *src, size_t n_ele
     case KG_A_WO: rows = d; K = d; dst = x->a_wo; break;
     case KG_A_NORM_IN: is_gain = true; dst = x->a_gin; break;
     case KG_A_NORM_LAST: is_gain = true; dst = x->a_glast; break;
+    case KG_A_HEAD: rows = V; K = d; dst = x->a_head; break;
+    case KG_A_NORM_POST: is_gain = true; dst = x->a_gpost; break;
+    case KG_A_WG: case KG_A_WU: rows = f; K = d; dst = x->a_gu; mode = 1 + (kind - KG_A_WG); break;
+    case KG_A_WD: rows = d; K = f; dst = x->a_wd; break;
+    case KG_A_W1: rows = d; K = d; dst = x->a_w1; break;
+    case KG_A_W2: rows = d; K = d; dst = x->a_w2; break;
     }
     size_t want = is_gain ? (size_t)d : (size_t)rows * K;
     if (n_elements != want) return fail(x, KG_EINVAL, "tensor kind %d: %zu elements given, %zu expected", kind, n_elements, want);
@@ -893,7 +953,7 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     if (x->spec_shallow != j) KGCHK(run_shallow(x, &tok, 1, pos, j));
     x->spec_shallow = -1;
     int M = 1;
-    if (j == 0 && x->lag) {                       // adapter catches up on [lagged f, f_0] (Figure 2)
+    if (j == 0 && x->lag && x->akind != KG_ADAPTER_MLP) {   // adapter catches up on [lagged f, f_0] (Figure 2)
         M = 2;
         KGCHK(run_adapter(x, 0, 2, pos - 1, true));
     } else {
@@ -901,7 +961,7 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     }
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     float *dl = at<float>(x->scr, x->s_dlog) + (size_t)j * x->c.vocab;
-    KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t, p->mode, &u_draft, at<float>(x->scr, x->s_dstat) + 2 * j));
+    KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t, p->mode, &u_draft, at<float>(x->scr, x->s_dstat) + 2 * j, true));
     // The draft token's early feature is needed whatever the host decides next (one more draft
     // step, or verification): compute it now, reading the token from device memory, so that the
     // GPU keeps working while the host waits for the token and its confidence.  The results are

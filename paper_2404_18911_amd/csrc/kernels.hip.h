@@ -23,7 +23,7 @@ typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 #define KG_ROWS 8
 
-enum { EPI_PLAIN = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3 };
+enum { EPI_PLAIN = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_HEAD = 3, EPI_SILU = 4 };
 
 // What a projection kernel does with a finished 16-row tile y[16][8].
 struct Epi {
@@ -44,6 +44,7 @@ struct Epi {
     // EPI_RESID: x = res[m][n] + y; xout[m][n] = x; act_out <- x * gain[n]; ssq_out[tile][m] = sum x^2
     const float *res;
     float *xout;
+    // EPI_SILU: act_out <- silu(y * scale) at K index n (the first map of the two-linear-map adapter)
     // EPI_RESID / EPI_SWIGLU: activation for the next projection (K index = n, or tile*8+i for SwiGLU)
     void *act_out;
     int act_K;
@@ -202,6 +203,14 @@ __device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_RO
                 float s = 0.f;
                 for (int r = 0; r < 16; r++) s += sq[r][t];
                 e.ssq_out[(size_t)rt * KG_ROWS + t] = s;
+            }
+        }
+    } else if (e.kind == EPI_SILU) {
+        if (t < 128) {
+            int row = t >> 3, m = t & 7;
+            if (m < e.M) {
+                float g = yt[row][m] * sc[m];
+                store_act<BF>(e.act_out, e.act_K, m, rt * 16 + row, g / (1.f + __expf(-g)));
             }
         }
     } else { // EPI_SWIGLU: tile rows (2i, 2i+1) = (gate, up) of feed-forward feature rt*8 + i

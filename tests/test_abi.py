@@ -38,15 +38,16 @@ def test_create_validates_the_configuration():
     B.lib().kg_destroy(h)
     for bad in (dict(exit_layer=0), dict(exit_layer=5), dict(head_dim=48), dict(n_heads=3), dict(gamma_max=8),
                 dict(kv_page_tokens=24), dict(kv_page_tokens=256), dict(dtype=2), dict(dtype=0, kv_dtype=1),
-                dict(vocab=1000), dict(max_seq=1), dict(max_seq=16 * 129)):
+                dict(vocab=1000), dict(max_seq=1), dict(max_seq=16 * 129), dict(adapter_kind=4), dict(adapter_kind=-1)):
         rc, h = _create(shape, **bad)
         assert rc == B.KG_EINVAL and not h.value, bad
 
 
 def test_workspace_sizes_match_the_shape():
+    import dataclasses
     L = B.lib()
-    for name in ("toy", "7b", "33b"):
-        shape = I.SHAPES[name]
+    cases = [I.SHAPES[n] for n in ("toy", "7b", "33b")] + [dataclasses.replace(I.SHAPES["7b"], adapter=a) for a in (1, 2, 3)]
+    for shape in cases:
         rc, h = _create(shape, max_seq=520, kv_page_tokens=128)
         assert rc == B.KG_OK
         wb, kb, sb = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()

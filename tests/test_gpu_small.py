@@ -260,3 +260,66 @@ def test_hyper_parameter_sweep_keeps_the_stream_and_orders_the_compression_rate(
         assert cr[(gamma, 0.0)] >= cr[(gamma, 1.01)]
     assert cr[(6, 0.0)] >= cr[(2, 0.0)]
     kg.close()
+
+
+# ----------------------------------------------------------------------------- Table 2's other adapters
+
+@pytest.mark.parametrize("name,adapter,hs,page", [
+    ("toy", 1, 25.0, 16), ("toy", 2, 25.0, 16), ("toy", 3, 25.0, 16),
+    ("toy_bf16", 1, 25.0, 32), ("toy_bf16", 2, 25.0, 32), ("toy_bf16", 3, 25.0, 32),
+    ("small_bf16", 2, 16.0, 64), ("small_bf16", 3, 16.0, 64),
+])
+def test_adapter_architectures_of_table2_follow_oracle(name, adapter, hs, page):
+    """The ablation's adapters (own LM head; one decoder block; two linear maps + own head) through
+    the C ABI against the oracle, stepwise: draft logits, confidences, early features, target
+    logits, emitted tokens, cache bookkeeping; then losslessness on the GPU alone (Kangaroo ==
+    plain decoding, generate == stepwise)."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = dataclasses.replace(I.SHAPES[name], adapter=adapter)
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=hs)
+    prompt = I.gen_prompt(shape.vocab, 16)
+    gamma, eta = 5, 0.6
+    kg = P.load_model(shape, W, 128, gamma_max=6, kv_page_tokens=page)
+    fol = P.Follow(tol_for(shape, hs))
+    out, rounds = P.follow_kangaroo(kg, _oracle(shape, W, 128), prompt, 32, gamma, eta, fol)
+    assert all(1 <= k <= gamma and 0 <= n <= k for k, n in rounds)
+    assert any(n == k for k, n in rounds) and any(n < k for k, n in rounds)
+    print(f"{name} adapter {adapter}: max logit err {fol.max_logit_err:.3e}, near-tie exceptions "
+          f"{fol.exceptions}/{fol.decisions}")
+    p, _ = B.make_params(eta=eta, gamma=gamma)
+    plain, _ = kg.decode_plain(p, prompt, 48)
+    gen, st = kg.generate(p, prompt, 48)
+    assert gen == plain and gen[:32] == out[:32]
+    kg.close()
+
+
+@pytest.mark.parametrize("name,adapter", [("toy", 1), ("toy_bf16", 3)])
+def test_an_own_draft_head_is_read_from_its_own_matrix(name, adapter):
+    """With an own head that is not a copy of the model's, draft logits must come from that matrix
+    (and target logits from the model's): checked against the oracle on a short run."""
+    from tests import parity as P
+    shape = dataclasses.replace(I.SHAPES[name], adapter=adapter)
+    W = I.gen_weights(shape, seed=1, alpha=0.05, own_head_copy=False)
+    assert not np.array_equal(W[(I.KIND_A_HEAD, -1)], W[(I.KIND_LM_HEAD, -1)])
+    kg = P.load_model(shape, W, 64, gamma_max=6, kv_page_tokens=16)
+    fol = P.Follow(TOL[shape.dtype])
+    P.follow_kangaroo(kg, _oracle(shape, W, 64), I.gen_prompt(shape.vocab, 9), 12, 3, 0.0, fol)
+    kg.close()
+
+
+def test_adapter_tensors_outside_the_architecture_are_rejected():
+    from paper_2404_18911_amd import binding as B
+    shape = dataclasses.replace(I.SHAPES["toy"], adapter=I.ADAPTER_MLP)
+    kg = B.Kangaroo(shape, 64, kv_page_tokens=16)
+    d = shape.d_model
+    with pytest.raises(B.KangarooError) as ei:
+        kg.load_tensor(I.KIND_A_WQ, -1, np.zeros((d, d), dtype=np.float32))
+    assert ei.value.code == B.KG_EINVAL
+    kg.load_tensor(I.KIND_A_W1, -1, np.zeros((d, d), dtype=np.float32))
+    kg.close()
+    kg = B.Kangaroo(I.SHAPES["toy"], 64, kv_page_tokens=16)
+    with pytest.raises(B.KangarooError) as ei:
+        kg.load_tensor(I.KIND_A_HEAD, -1, np.zeros((shape.vocab, d), dtype=np.float32))
+    assert ei.value.code == B.KG_EINVAL
+    kg.close()
