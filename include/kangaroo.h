@@ -219,6 +219,50 @@ const char *kg_last_error(const kg_ctx *ctx);
 void kg_destroy(kg_ctx *ctx);
 
 /*
+ * Training of the adapter (Section 3.1 "Training Loss", Eq. 3; Section 4.1: AdamW), one step per
+ * call on one token sequence, for adapter architecture KG_ADAPTER_ATTN.  With the target model
+ * frozen, the adapter is run over all n positions at once (causal attention over the earlier early
+ * features) and
+ *     loss = sum_t sum_v  - p_t[v] log q_t[v],   p_t = softmax(target logits at t), q_t = softmax(draft logits at t)
+ * is differentiated with respect to Wq, Wk, Wv, Wo, g_in, g_last; AdamW (decoupled weight decay on
+ * the four matrices, none on the gains, bias-corrected moments) updates fp32 master copies, and the
+ * adapter tensors the decode calls use are refreshed from them (matrices and gains re-rounded to bf16
+ * where the model is bf16: decoding runs what a checkpoint in the model's type would hold).  All training arithmetic is fp32; keys and values inside the training graph are not
+ * rounded to the cache's type.  The LM head and the target model are never updated.
+ *
+ *   kg_train_workspace_bytes / kg_train_bind: device workspace (256-byte aligned, BORROWED until
+ *     kg_destroy) for sequences of up to max_tokens tokens (<= 256 and <= max_seq); bind copies the
+ *     loaded adapter tensors into the master copies and zeroes the AdamW moments and step count.
+ *     All tensors must be loaded first.
+ *   kg_train_step: tokens_host[n], 1 <= n <= max_tokens.  *loss is Eq. 3 for the parameters before
+ *     the update.  Drops the sequence state of the context (a new kg_prefill is needed to decode).
+ *   kg_train_read: copy one buffer of the last step to the host (tests and monitoring):
+ *     early features [n][d_model], target / draft logits [n][vocab], the gradient block and the
+ *     parameter block (Wq, Wk, Wv, Wo row-major [d][d] each, then g_in, g_last: 4 d^2 + 2 d floats),
+ *     per-position losses [n].  n_floats must be the buffer's exact size.
+ */
+typedef struct kg_train_params {
+    float lr, beta1, beta2, eps, weight_decay;
+} kg_train_params;
+typedef enum kg_train_buffer {
+    KG_TRAIN_FEATURES = 0, KG_TRAIN_TARGET_LOGITS = 1, KG_TRAIN_DRAFT_LOGITS = 2, KG_TRAIN_GRADIENTS = 3,
+    KG_TRAIN_PARAMETERS = 4, KG_TRAIN_ROW_LOSSES = 5
+} kg_train_buffer;
+int kg_train_workspace_bytes(const kg_ctx *ctx, int max_tokens, size_t *bytes);
+int kg_train_bind(kg_ctx *ctx, void *work_dev, size_t bytes, int max_tokens);
+int kg_train_step(kg_ctx *ctx, const kg_train_params *hp, const int32_t *tokens_host, int n, double *loss);
+int kg_train_read(kg_ctx *ctx, int what, float *host_out, size_t n_floats);
+
+/*
+ * The dense contraction of the training step (the products with the LM head and the gradient
+ * products of Eq. 3's chain rule), exposed for kernel-level tests: C[M][N] (+)= sum_k A(m,k) B(k,n)
+ * in fp32 on the matrix units, A(m,k) = A_dev[m*sam + k*sak], B(k,n) = B_dev[k*sbk + n*sbn],
+ * C row-major with leading dimension ldc >= N.  Launches on `hip_stream`, does not synchronise.
+ */
+int kg_op_gemm_f32(const float *A_dev, long sam, long sak, const float *B_dev, long sbk, long sbn, float *C_dev, long ldc,
+                   int M, int N, int K, int accumulate, void *hip_stream);
+
+/*
  * Stand-alone weight-streaming product Y[M][N] = X[M][K] . W^T used by every projection of the
  * decode forwards (Section 1: decoding is bound by reading the weights), exposed for kernel-level
  * tests and bandwidth measurements.

@@ -42,10 +42,17 @@ class kg_profile(ctypes.Structure):
 
 
 # every symbol include/kangaroo.h declares
+class kg_train_params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("lr", "beta1", "beta2", "eps", "weight_decay")]
+
+
+TRAIN_FEATURES, TRAIN_TARGET_LOGITS, TRAIN_DRAFT_LOGITS, TRAIN_GRADIENTS, TRAIN_PARAMETERS, TRAIN_ROW_LOSSES = range(6)
+
 SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "kg_bind", "kg_load_tensor", "kg_set_page_order", "kg_prefill",
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
-           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_stream_read"]
+           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_stream_read",
+           "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_read", "kg_op_gemm_f32"]
 
 _lib = None
 
@@ -93,6 +100,12 @@ def lib() -> ctypes.CDLL:
     L.kg_op_pack.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, vp]
     L.kg_op_linear.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_int, vp, vp, vp]
     L.kg_op_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    L.kg_train_workspace_bytes.argtypes = [vp, ctypes.c_int, szp]
+    L.kg_train_bind.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int]
+    L.kg_train_step.argtypes = [vp, ctypes.POINTER(kg_train_params), ip, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    L.kg_train_read.argtypes = [vp, ctypes.c_int, fp, ctypes.c_size_t]
+    L.kg_op_gemm_f32.argtypes = [vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long,
+                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
     _lib = L
     return L
 
@@ -271,6 +284,64 @@ class Kangaroo:
 
     def reset(self) -> None:
         self._chk(self.L.kg_reset(self.h))
+
+    # -- adapter training (Eq. 3)
+    def train_bind(self, max_tokens: int) -> None:
+        nb = ctypes.c_size_t()
+        self._chk(self.L.kg_train_workspace_bytes(self.h, max_tokens, ctypes.byref(nb)))
+        self.train_work = self._torch.empty(nb.value, dtype=self._torch.uint8, device=self.device)
+        self._chk(self.L.kg_train_bind(self.h, self.train_work.data_ptr(), nb.value, max_tokens))
+        self.train_bytes = nb.value
+
+    def train_step(self, tokens: Sequence[int], lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                   weight_decay: float = 0.01) -> float:
+        a = np.ascontiguousarray(tokens, dtype=np.int32)
+        hp = kg_train_params(lr, beta1, beta2, eps, weight_decay)
+        loss = ctypes.c_double()
+        self._chk(self.L.kg_train_step(self.h, ctypes.byref(hp), a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(a),
+                                       ctypes.byref(loss)))
+        return loss.value
+
+    def train_read(self, what: int, n_tokens: int = 0) -> np.ndarray:
+        d, V = self.shape.d_model, self.shape.vocab
+        shape = {TRAIN_FEATURES: (n_tokens, d), TRAIN_TARGET_LOGITS: (n_tokens, V), TRAIN_DRAFT_LOGITS: (n_tokens, V),
+                 TRAIN_GRADIENTS: (4 * d * d + 2 * d,), TRAIN_PARAMETERS: (4 * d * d + 2 * d,), TRAIN_ROW_LOSSES: (n_tokens,)}[what]
+        out = np.empty(shape, dtype=np.float32)
+        self._chk(self.L.kg_train_read(self.h, what, out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), out.size))
+        return out
+
+
+def split_param_block(block: np.ndarray, d: int) -> dict:
+    """Views of a parameter (or gradient) block: Wq, Wk, Wv, Wo [d][d], g_in, g_last [d]."""
+    dd = d * d
+    return {"wq": block[0:dd].reshape(d, d), "wk": block[dd:2 * dd].reshape(d, d), "wv": block[2 * dd:3 * dd].reshape(d, d),
+            "wo": block[3 * dd:4 * dd].reshape(d, d), "g_in": block[4 * dd:4 * dd + d], "g_last": block[4 * dd + d:4 * dd + 2 * d]}
+
+
+def op_gemm_f32(A: np.ndarray, B: np.ndarray, C0: Optional[np.ndarray] = None, device: str = "cuda:0") -> np.ndarray:
+    """C (+)= A . B through kg_op_gemm_f32; A [M][K] and B [K][N] may be any strided float32 views
+    (their strides are passed on, so transposed views exercise the other load orientation)."""
+    import torch
+    dev = torch.device(device)
+    M, K = A.shape
+    K2, N = B.shape
+    assert K == K2
+    # ship the underlying contiguous buffers and address them with the views' strides
+    def ship(v):
+        base = v if v.base is None else v.base
+        base = np.ascontiguousarray(base, dtype=np.float32) if base is v else base
+        t = torch.from_numpy(base).to(dev)
+        off = (v.__array_interface__["data"][0] - base.__array_interface__["data"][0]) // 4
+        return t, off, v.strides[0] // 4, v.strides[1] // 4
+    ta, oa, sam, sak = ship(A)
+    tb, ob, sbk, sbn = ship(B)
+    c = torch.zeros((M, N), dtype=torch.float32, device=dev) if C0 is None else torch.from_numpy(np.ascontiguousarray(C0, dtype=np.float32)).to(dev)
+    rc = lib().kg_op_gemm_f32(ta.data_ptr() + 4 * oa, sam, sak, tb.data_ptr() + 4 * ob, sbk, sbn, c.data_ptr(), N, M, N, K,
+                              0 if C0 is None else 1, torch.cuda.current_stream(dev).cuda_stream)
+    if rc != KG_OK:
+        raise KangarooError(rc, "kg_op_gemm_f32")
+    torch.cuda.synchronize(dev)
+    return c.cpu().numpy()
 
 
 def op_linear(W_host: np.ndarray, x_host: np.ndarray, device: str = "cuda:0") -> np.ndarray:

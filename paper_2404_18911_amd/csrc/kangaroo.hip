@@ -2,6 +2,7 @@
 // it carves the caller's arena / KV pool / scratch, launches the kernels of kernels.hip.h on the
 // caller's stream, and runs the control flow of the draft-and-verify round (Section 3, Figure 2).
 #include "kernels.hip.h"
+#include "train.hip.h"
 
 #include <chrono>
 #include <cmath>
@@ -24,6 +25,17 @@ struct LayerW {
 };
 
 struct Phase { enum { NONE = 0, READY = 1, DRAFTING = 2, VERIFIED = 3, PLAIN = 4 }; };
+
+// Workspace of the adapter's training step (byte offsets).  The parameter block, and likewise the
+// gradient block and the two AdamW moment blocks, holds Wq, Wk, Wv (stacked, [3d][d]), Wo [d][d],
+// g_in [d], g_last [d] as fp32.
+struct TrainLayout {
+    size_t nparam = 0;
+    size_t P = 0, G = 0, M = 0, V = 0;
+    size_t F = 0, X = 0, Xn = 0, N = 0, QKV = 0, O = 0, H = 0, Mm = 0, Z = 0, Zt = 0, dZ = 0, rin = 0, rlast = 0, rfin = 0,
+           Pm = 0, dS = 0, dMm = 0, dH = 0, dO = 0, dQKV = 0, dN = 0, loss = 0;
+    size_t bytes = 0;
+};
 
 } // namespace
 
@@ -68,6 +80,11 @@ struct kg_ctx {
     int n_target_rows = 0;
     int plain_len = 0;
     int spec_shallow = -1;   // index j of an early feature f_j already computed ahead of the host's decision
+    // adapter training (kg_train_*)
+    char *tr = nullptr;
+    TrainLayout tl;
+    int tr_T = 0, tr_n = 0;
+    long long tr_step = 0;
     // optional per-launch timing
     bool profiling = false;
     kg_profile prof;
@@ -1238,6 +1255,242 @@ void kg_destroy(kg_ctx *x)
     for (hipEvent_t e : x->ev_pool) (void)hipEventDestroy(e);
     if (x->ev_fetch) (void)hipEventDestroy(x->ev_fetch);
     delete x;
+}
+
+// ---- adapter training (Eq. 3, AdamW) --------------------------------------------------------------
+
+static void train_layout(const kg_ctx *x, int Tm, TrainLayout &t)
+{
+    const size_t d = x->c.d_model, V = x->c.vocab, H = x->c.n_heads, T = Tm;
+    size_t o = 0;
+    auto take = [&](size_t floats) { size_t r = o; o += up(floats * 4); return r; };
+    t.nparam = 4 * d * d + 2 * d;
+    t.P = take(t.nparam); t.G = take(t.nparam); t.M = take(t.nparam); t.V = take(t.nparam);
+    t.F = take(T * d); t.X = take(T * d); t.Xn = take(T * d); t.N = take(T * d); t.QKV = take(T * 3 * d);
+    t.O = take(T * d); t.H = take(T * d); t.Mm = take(T * d);
+    t.Z = take(T * V); t.Zt = take(T * V); t.dZ = take(T * V);
+    t.rin = take(T); t.rlast = take(T); t.rfin = take(T);
+    t.Pm = take(H * T * T); t.dS = take(H * T * T);
+    t.dMm = take(T * d); t.dH = take(T * d); t.dO = take(T * d); t.dQKV = take(T * 3 * d); t.dN = take(T * d);
+    t.loss = take(T);
+    t.bytes = o;
+}
+
+static int train_tokens_max(const kg_ctx *x)
+{
+    // one pass of the prompt kernels (bf16 weights), one thread per key in the attention kernels
+    int m = std::min(256, x->c.max_seq);
+    if (x->pf_rows > 0) m = std::min(m, x->pf_rows);
+    return m;
+}
+
+int kg_train_workspace_bytes(const kg_ctx *x, int max_tokens, size_t *bytes)
+{
+    if (!x || !bytes) return KG_EINVAL;
+    if (max_tokens < 1 || max_tokens > train_tokens_max(x)) return KG_EINVAL;
+    TrainLayout t;
+    train_layout(x, max_tokens, t);
+    *bytes = t.bytes;
+    return KG_OK;
+}
+
+int kg_train_bind(kg_ctx *x, void *work_dev, size_t bytes, int max_tokens)
+{
+    KGCHK(check_ready(x));
+    if (x->akind != KG_ADAPTER_ATTN) return fail(x, KG_EINVAL, "training is implemented for adapter architecture 0 (Table 2 row Kangaroo)");
+    if (max_tokens < 1 || max_tokens > train_tokens_max(x)) return fail(x, KG_EINVAL, "max_tokens %d outside 1..%d", max_tokens, train_tokens_max(x));
+    if (!work_dev || ((uintptr_t)work_dev & (ALIGN - 1))) return fail(x, KG_EINVAL, "training workspace must be %zu-byte aligned", ALIGN);
+    TrainLayout t;
+    train_layout(x, max_tokens, t);
+    if (bytes < t.bytes) return fail(x, KG_ENOSPC, "training workspace too small: need %zu bytes", t.bytes);
+    x->tr = (char *)work_dev; x->tl = t; x->tr_T = max_tokens; x->tr_n = 0; x->tr_step = 0;
+    const int d = x->c.d_model;
+    float *P = at<float>(x->tr, t.P);
+    const size_t dd = (size_t)d * d;
+    if (x->bf) {
+        hipLaunchKernelGGL(tr_unpack_bf16_kernel, dim3((unsigned)((3 * dd + 255) / 256)), dim3(256), 0, x->stream,
+                           at<const uint16_t>(x->arena, x->a_qkv), 3 * d, d, x->KSd, P);
+        hipLaunchKernelGGL(tr_unpack_bf16_kernel, dim3((unsigned)((dd + 255) / 256)), dim3(256), 0, x->stream,
+                           at<const uint16_t>(x->arena, x->a_wo), d, d, x->KSd, P + 3 * dd);
+        KGCHK(check_launch(x, "train_unpack"));
+    } else {
+        HIPCHK(x, hipMemcpyAsync(P, x->arena + x->a_qkv, 3 * dd * 4, hipMemcpyDeviceToDevice, x->stream));
+        HIPCHK(x, hipMemcpyAsync(P + 3 * dd, x->arena + x->a_wo, dd * 4, hipMemcpyDeviceToDevice, x->stream));
+    }
+    HIPCHK(x, hipMemcpyAsync(P + 4 * dd, x->arena + x->a_gin, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
+    HIPCHK(x, hipMemcpyAsync(P + 4 * dd + d, x->arena + x->a_glast, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
+    HIPCHK(x, hipMemsetAsync(x->tr + t.M, 0, t.nparam * 4, x->stream));
+    HIPCHK(x, hipMemsetAsync(x->tr + t.V, 0, t.nparam * 4, x->stream));
+    HIPCHK(x, hipMemsetAsync(x->tr + t.G, 0, t.nparam * 4, x->stream));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    return KG_OK;
+}
+
+static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, long sbk, long sbn, int b_mode, float *C,
+                   long ldc, int M, int N, int K, int accumulate)
+{
+    TrGemm g;
+    g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = b_mode; g.b_KS = x ? x->KSd : 0;
+    g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
+    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, x->stream, g);
+    return check_launch(x, "train_gemm");
+}
+
+int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, int n, double *loss)
+{
+    KGCHK(check_ready(x));
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    if (!hp || !tokens || !loss) return fail(x, KG_EINVAL, "NULL argument");
+    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
+    if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->eps > 0.f) ||
+        !(hp->weight_decay >= 0.f))
+        return fail(x, KG_EINVAL, "bad AdamW parameters");
+    const kg_config &c = x->c;
+    for (int i = 0; i < n; i++)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(x, KG_EINVAL, "token %d out of range", tokens[i]);
+    const int d = c.d_model, V = c.vocab, H = c.n_heads, hd = c.head_dim;
+    const size_t dd = (size_t)d * d;
+    const TrainLayout &t = x->tl;
+    auto f = [&](size_t off) { return at<float>(x->tr, off); };
+    float *P = f(t.P), *G = f(t.G);
+    float *Wqkv = P, *Wo = P + 3 * dd, *gin = P + 4 * dd, *glast = P + 4 * dd + d;
+    KGCHK(kg_reset(x));
+
+    // frozen target model on the whole sequence: early features F and last hidden states X
+    if (x->pf_rows > 0) {
+        HIPCHK(x, hipMemcpyAsync(x->scr + x->s_ptok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, x->stream));
+        const float *x_last = nullptr;
+        KGCHK(pf_rows_pass(x, 0, n, &x_last));
+        HIPCHK(x, hipMemcpyAsync(f(t.F), x->scr + x->s_pF, (size_t)n * d * 4, hipMemcpyDeviceToDevice, x->stream));
+        HIPCHK(x, hipMemcpyAsync(f(t.X), x_last, (size_t)n * d * 4, hipMemcpyDeviceToDevice, x->stream));
+    } else {
+        for (int pos0 = 0; pos0 < n; pos0 += KG_ROWS) {
+            const int M = std::min(KG_ROWS, n - pos0);
+            KGCHK(run_shallow(x, tokens + pos0, M, pos0, 0));
+            HIPCHK(x, hipMemcpyAsync(f(t.F) + (size_t)pos0 * d, Frow(x, 0), (size_t)M * d * 4, hipMemcpyDeviceToDevice, x->stream));
+            KGCHK(run_deep(x, M, pos0));
+            const float *xl = c.exit_layer == c.n_layers ? Frow(x, 0) : at<const float>(x->scr, x->s_x0);
+            HIPCHK(x, hipMemcpyAsync(f(t.X) + (size_t)pos0 * d, xl, (size_t)M * d * 4, hipMemcpyDeviceToDevice, x->stream));
+        }
+    }
+    const void *head = x->arena + x->head;
+    const int hm_nt = x->bf ? 1 : 0, hm_nn = x->bf ? 2 : 0;
+    auto rms = [&](const float *in, const float *g, float *out, float *r) {
+        hipLaunchKernelGGL(tr_rmsnorm_kernel, dim3(n), dim3(256), 0, x->stream, in, g, d, c.rms_eps, out, r);
+        return check_launch(x, "train_rmsnorm");
+    };
+    // target logits of every position: Zt = RMSNorm(X; g_final) . head^T
+    KGCHK(rms(f(t.X), at<const float>(x->arena, x->gfinal), f(t.Xn), f(t.rfin)));
+    KGCHK(tr_gemm(x, f(t.Xn), d, 1, head, 1, d, hm_nt, f(t.Zt), V, n, V, d, 0));
+    // adapter forward over all positions
+    KGCHK(rms(f(t.F), gin, f(t.N), f(t.rin)));
+    KGCHK(tr_gemm(x, f(t.N), d, 1, Wqkv, 1, d, 0, f(t.QKV), 3 * d, n, 3 * d, d, 0));
+    const size_t nrope = (size_t)n * (d / hd) * (hd / 2) * 2;
+    hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.QKV), n, d, hd,
+                       at<const float2>(x->scr, x->s_rope), 0);
+    KGCHK(check_launch(x, "train_rope"));
+    hipLaunchKernelGGL(tr_attn_fwd_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), n, d, hd, f(t.Pm), f(t.O));
+    KGCHK(check_launch(x, "train_attn_fwd"));
+    HIPCHK(x, hipMemcpyAsync(f(t.H), f(t.F), (size_t)n * d * 4, hipMemcpyDeviceToDevice, x->stream));
+    KGCHK(tr_gemm(x, f(t.O), d, 1, Wo, 1, d, 0, f(t.H), d, n, d, d, 1));
+    KGCHK(rms(f(t.H), glast, f(t.Mm), f(t.rlast)));
+    KGCHK(tr_gemm(x, f(t.Mm), d, 1, head, 1, d, hm_nt, f(t.Z), V, n, V, d, 0));
+    // Eq. 3 and its gradient with respect to the draft logits
+    hipLaunchKernelGGL(tr_loss_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.Z), (const float *)f(t.Zt), V, f(t.dZ),
+                       f(t.loss));
+    KGCHK(check_launch(x, "train_loss"));
+    // backward
+    KGCHK(tr_gemm(x, f(t.dZ), V, 1, head, d, 1, hm_nn, f(t.dMm), d, n, d, V, 0));
+    hipLaunchKernelGGL(tr_rmsnorm_bwd_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.H), (const float *)glast,
+                       (const float *)f(t.rlast), (const float *)f(t.dMm), d, f(t.dH));
+    hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.H),
+                       (const float *)f(t.rlast), (const float *)f(t.dMm), n, d, G + 4 * dd + d);
+    KGCHK(check_launch(x, "train_rmsnorm_bwd"));
+    KGCHK(tr_gemm(x, f(t.dH), 1, d, f(t.O), d, 1, 0, G + 3 * dd, d, d, d, n, 0));                 // dWo = dH^T . O
+    KGCHK(tr_gemm(x, f(t.dH), d, 1, Wo, d, 1, 0, f(t.dO), d, n, d, d, 0));                        // dO = dH . Wo
+    hipLaunchKernelGGL(tr_attn_bwd_q_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
+                       (const float *)f(t.dO), n, d, hd, f(t.dS), f(t.dQKV));
+    hipLaunchKernelGGL(tr_attn_bwd_kv_kernel, dim3(n, H), dim3(128), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
+                       (const float *)f(t.dS), (const float *)f(t.dO), n, d, hd, f(t.dQKV));
+    KGCHK(check_launch(x, "train_attn_bwd"));
+    hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.dQKV), n, d, hd,
+                       at<const float2>(x->scr, x->s_rope), 1);
+    KGCHK(check_launch(x, "train_rope_bwd"));
+    KGCHK(tr_gemm(x, f(t.dQKV), 1, 3 * d, f(t.N), d, 1, 0, G, d, 3 * d, d, n, 0));                // dWqkv = dQKV^T . N
+    KGCHK(tr_gemm(x, f(t.dQKV), 3 * d, 1, Wqkv, d, 1, 0, f(t.dN), d, n, d, 3 * d, 0));            // dN = dQKV . Wqkv
+    hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.F),
+                       (const float *)f(t.rin), (const float *)f(t.dN), n, d, G + 4 * dd);
+    KGCHK(check_launch(x, "train_gain_grad"));
+    // loss of the step (before the update), summed over positions in double on the host
+    std::vector<float> rows(n);
+    HIPCHK(x, hipMemcpyAsync(rows.data(), f(t.loss), (size_t)n * 4, hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    double L = 0.0;
+    for (int i = 0; i < n; i++) L += rows[i];
+    *loss = L;
+    // AdamW on the fp32 master copies, then the inference copies in the arena are refreshed
+    x->tr_step++;
+    const float c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)x->tr_step));
+    const float c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)x->tr_step));
+    hipLaunchKernelGGL(tr_adamw_kernel, dim3((unsigned)((4 * dd + 255) / 256)), dim3(256), 0, x->stream, P, (const float *)G,
+                       f(t.M), f(t.V), 4 * dd, hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, c1, c2);
+    hipLaunchKernelGGL(tr_adamw_kernel, dim3((2 * d + 255) / 256), dim3(256), 0, x->stream, P + 4 * dd, (const float *)(G + 4 * dd),
+                       f(t.M) + 4 * dd, f(t.V) + 4 * dd, (size_t)2 * d, hp->lr, hp->beta1, hp->beta2, hp->eps, 0.f, c1, c2);
+    KGCHK(check_launch(x, "train_adamw"));
+    if (x->bf) {
+        hipLaunchKernelGGL(tr_pack_bf16_kernel, dim3((unsigned)((3 * dd + 255) / 256)), dim3(256), 0, x->stream, (const float *)Wqkv,
+                           3 * d, d, x->KSd, at<uint16_t>(x->arena, x->a_qkv));
+        hipLaunchKernelGGL(tr_pack_bf16_kernel, dim3((unsigned)((dd + 255) / 256)), dim3(256), 0, x->stream, (const float *)Wo, d, d,
+                           x->KSd, at<uint16_t>(x->arena, x->a_wo));
+        hipLaunchKernelGGL(tr_round_bf16_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)gin, d,
+                           at<float>(x->arena, x->a_gin));
+        hipLaunchKernelGGL(tr_round_bf16_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)glast, d,
+                           at<float>(x->arena, x->a_glast));
+        KGCHK(check_launch(x, "train_pack"));
+    } else {
+        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_qkv, Wqkv, 3 * dd * 4, hipMemcpyDeviceToDevice, x->stream));
+        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_wo, Wo, dd * 4, hipMemcpyDeviceToDevice, x->stream));
+        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_gin, gin, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
+        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_glast, glast, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
+    }
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    x->tr_n = n;
+    x->phase = Phase::NONE;
+    return KG_OK;
+}
+
+int kg_train_read(kg_ctx *x, int what, float *host_out, size_t n_floats)
+{
+    if (!x || !host_out) return KG_EINVAL;
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    const TrainLayout &t = x->tl;
+    const size_t n = x->tr_n, d = x->c.d_model, V = x->c.vocab;
+    size_t off = 0, cnt = 0;
+    switch (what) {
+    case KG_TRAIN_FEATURES: off = t.F; cnt = n * d; break;
+    case KG_TRAIN_TARGET_LOGITS: off = t.Zt; cnt = n * V; break;
+    case KG_TRAIN_DRAFT_LOGITS: off = t.Z; cnt = n * V; break;
+    case KG_TRAIN_GRADIENTS: off = t.G; cnt = t.nparam; break;
+    case KG_TRAIN_PARAMETERS: off = t.P; cnt = t.nparam; break;
+    case KG_TRAIN_ROW_LOSSES: off = t.loss; cnt = n; break;
+    default: return fail(x, KG_EINVAL, "unknown training buffer %d", what);
+    }
+    if (what != KG_TRAIN_PARAMETERS && n == 0) return fail(x, KG_ESTATE, "no training step has run");
+    if (n_floats != cnt) return fail(x, KG_EINVAL, "buffer %d holds %zu floats, %zu asked", what, cnt, n_floats);
+    HIPCHK(x, hipMemcpyAsync(host_out, x->tr + off, cnt * 4, hipMemcpyDeviceToHost, x->stream));
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    return KG_OK;
+}
+
+int kg_op_gemm_f32(const float *A, long sam, long sak, const float *B, long sbk, long sbn, float *C, long ldc, int M, int N, int K,
+                   int accumulate, void *hip_stream)
+{
+    if (!A || !B || !C || M < 1 || N < 1 || K < 1 || ldc < N) return KG_EINVAL;
+    TrGemm g;
+    g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = 0; g.b_KS = 0;
+    g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
+    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, (hipStream_t)hip_stream, g);
+    return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
 }
 
 // ---- stand-alone projection ---------------------------------------------------------------------

@@ -1,0 +1,326 @@
+// Device code of the adapter's training step (Section 3.1, "Training Loss", Eq. 3; AdamW per
+// Section 4.1): the adapter runs over all T positions of a sequence at once, the cross entropy of
+// its draft distribution against the frozen target's is differentiated by hand (chain rule written
+// out: RMSNorm, rotary embedding, causal attention, projections), and AdamW updates fp32 master
+// copies of the adapter's tensors.  All arithmetic is fp32; the dense contractions go through the
+// fp32 MFMA (32x32x2), weights of the frozen LM head are read from their bf16 tiles and widened
+// exactly.  Included by kangaroo.hip after kernels.hip.h.
+#pragma once
+
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------------------
+// C[M][N] (+)= sum_k A(m, k) * B(k, n), fp32, any strides.
+//   A(m, k) = A[m * sam + k * sak]
+//   B(k, n) = b_mode 0: B[k * sbk + n * sbn]
+//             b_mode 1: element (row n, col k) of a matrix stored as bf16 MFMA tiles (the layout of
+//                       pack_w_bf16_kernel: tile (row/16, col/32), 16-byte unit (col%32/8)*16 + row%16)
+//             b_mode 2: element (row k, col n) of such a matrix
+// One workgroup (4 waves) per 64 x 64 tile of C, one 32 x 32 quadrant per wave; k advances in steps
+// of 16 through LDS.  Loads pick the orientation in which the operand is contiguous.
+struct TrGemm {
+    const void *A; long sam, sak;
+    const void *B; long sbk, sbn;
+    int b_mode, b_KS;
+    float *C; long ldc;
+    int M, N, K;
+    int accumulate;
+};
+
+#define TRG_LD 96   // LDS row stride in floats: the two half-waves of an MFMA operand read hit different banks
+
+__device__ __forceinline__ size_t packed_u16_index(int row, int col, int KS)
+{
+    return ((((size_t)(row >> 4) * KS + (col >> 5)) * 64 + ((col >> 3) & 3) * 16 + (row & 15)) << 3) + (col & 7);
+}
+
+__global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
+{
+    __shared__ float As[16][TRG_LD];
+    __shared__ float Bs[16][TRG_LD];
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    const int wm = (wave & 1) * 32, wn = (wave >> 1) * 32;
+    const float *Af = (const float *)g.A;
+    const float *Bf = (const float *)g.B;
+    const uint16_t *Bp = (const uint16_t *)g.B;
+    const bool a_kc = g.sak == 1;                      // A contiguous along k
+    const bool b_kc = g.b_mode == 0 ? g.sbk == 1 : g.b_mode == 1;
+    f32x16_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; i++) acc[i] = 0.f;
+    for (int k0 = 0; k0 < g.K; k0 += 16) {
+        float av[4], bv[4];
+        int am, ak, bn, bk;                             // first of the 4 elements this thread fetches
+        if (a_kc) { am = t >> 2; ak = (t & 3) * 4; } else { ak = t >> 4; am = (t & 15) * 4; }
+        if (b_kc) { bn = t >> 2; bk = (t & 3) * 4; } else { bk = t >> 4; bn = (t & 15) * 4; }
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int m = m0 + am + (a_kc ? 0 : i), k = k0 + ak + (a_kc ? i : 0);
+            av[i] = (m < g.M && k < g.K) ? Af[(size_t)m * g.sam + (size_t)k * g.sak] : 0.f;
+        }
+        if (g.b_mode == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const int n = n0 + bn + (b_kc ? 0 : i), k = k0 + bk + (b_kc ? i : 0);
+                bv[i] = (n < g.N && k < g.K) ? Bf[(size_t)k * g.sbk + (size_t)n * g.sbn] : 0.f;
+            }
+        } else {
+            // four consecutive columns of one row of the tiled matrix: 8 bytes, 8-byte aligned
+            const int n = n0 + bn, k = k0 + bk;
+            const int row = g.b_mode == 1 ? n : k, col = g.b_mode == 1 ? k : n;
+            const bool ok = n < g.N && k < g.K;     // the four columns share the verdict: N, K are multiples of 8 for tiled matrices
+            uint2 raw = make_uint2(0u, 0u);
+            if (ok) raw = *(const uint2 *)(Bp + packed_u16_index(row, col, g.b_KS));
+            bv[0] = __uint_as_float(raw.x << 16);
+            bv[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+            bv[2] = __uint_as_float(raw.y << 16);
+            bv[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+        }
+        __syncthreads();                                // the previous step's MFMAs have read LDS
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            if (a_kc) As[ak + i][am] = av[i]; else As[ak][am + i] = av[i];
+            if (b_kc) Bs[bk + i][bn] = bv[i]; else Bs[bk][bn + i] = bv[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 8; kk++) {
+            const float a = As[2 * kk + (lane >> 5)][wm + (lane & 31)];
+            const float b = Bs[2 * kk + (lane >> 5)][wn + (lane & 31)];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        }
+    }
+    // accumulator register i of lane l: row 8 * (i / 4) + 4 * (l / 32) + i % 4, column l % 32
+    const int n = n0 + wn + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const int m = m0 + wm + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+        if (m < g.M && n < g.N) {
+            float *c = g.C + (size_t)m * g.ldc + n;
+            *c = g.accumulate ? *c + acc[i] : acc[i];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float tr_block_sum(float v, float *red)
+{
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    float s = 0.f;
+    for (int w = 0; w < nw; w++) s += red[w];
+    return s;
+}
+__device__ __forceinline__ float tr_block_max(float v, float *red)
+{
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    float s = red[0];
+    for (int w = 1; w < nw; w++) s = fmaxf(s, red[w]);
+    return s;
+}
+
+// y[t] = x[t] * r[t] * g with r[t] = rsqrt(mean(x[t]^2) + eps); one block per row
+__global__ __launch_bounds__(256) void tr_rmsnorm_kernel(const float *x, const float *g, int d, float eps, float *y, float *r)
+{
+    __shared__ float red[4];
+    const int row = blockIdx.x;
+    const float *xr = x + (size_t)row * d;
+    float s = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) s += xr[i] * xr[i];
+    s = tr_block_sum(s, red);
+    const float rr = 1.f / sqrtf(s / (float)d + eps);
+    if (threadIdx.x == 0) r[row] = rr;
+    for (int i = threadIdx.x; i < d; i += 256) y[(size_t)row * d + i] = xr[i] * rr * g[i];
+}
+
+// dx[t] = r (dy g) - x r^3 mean((dy g) x); one block per row
+__global__ __launch_bounds__(256) void tr_rmsnorm_bwd_kernel(const float *x, const float *g, const float *r, const float *dy,
+                                                             int d, float *dx)
+{
+    __shared__ float red[4];
+    const int row = blockIdx.x;
+    const float *xr = x + (size_t)row * d, *dyr = dy + (size_t)row * d;
+    float s = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) s += dyr[i] * g[i] * xr[i];
+    s = tr_block_sum(s, red) / (float)d;
+    const float rr = r[row], r3 = rr * rr * rr;
+    for (int i = threadIdx.x; i < d; i += 256) dx[(size_t)row * d + i] = rr * dyr[i] * g[i] - xr[i] * r3 * s;
+}
+
+// dg[j] = sum_t dy[t][j] * x[t][j] * r[t]; one thread per column
+__global__ void tr_gain_grad_kernel(const float *x, const float *r, const float *dy, int T, int d, float *dg)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= d) return;
+    float s = 0.f;
+    for (int t = 0; t < T; t++) s += dy[(size_t)t * d + j] * x[(size_t)t * d + j] * r[t];
+    dg[j] = s;
+}
+
+// rotary embedding of the q and k parts of QKV [T][3d] at positions 0..T-1, pairs (i, i + hd/2);
+// inverse rotates by minus the angle (the transpose of the rotation, for the backward pass)
+__global__ void tr_rope_kernel(float *qkv, int T, int d, int hd, const float2 *tab, int inverse)
+{
+    const int half = hd >> 1;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t per_row = (size_t)(d / hd) * half;
+    if (i >= (size_t)T * per_row * 2) return;
+    const int which = (int)(i / ((size_t)T * per_row));          // 0 = q, 1 = k
+    const size_t j = i % ((size_t)T * per_row);
+    const int t = (int)(j / per_row), rem = (int)(j % per_row), h = rem / half, p = rem % half;
+    float2 cs = tab[(size_t)t * half + p];
+    if (inverse) cs.y = -cs.y;
+    float *v = qkv + (size_t)t * 3 * d + (size_t)which * d + (size_t)h * hd;
+    const float a = v[p], b = v[p + half];
+    v[p] = a * cs.x - b * cs.y;
+    v[p + half] = b * cs.x + a * cs.y;
+}
+
+// Causal attention of one (query row i, head h) over keys 0..i: P[h][i][j] = softmax_j(q_i.k_j / sqrt(hd)),
+// o[i][h] = sum_j P_ij v_j.  grid (T, H), block 256; T <= 256 so thread j owns key j.
+__global__ __launch_bounds__(256) void tr_attn_fwd_kernel(const float *qkv, int T, int d, int hd, float *P, float *o)
+{
+    __shared__ float red[4];
+    __shared__ float qs[128];
+    __shared__ float ps[256];
+    const int i = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
+    const float *q = qkv + (size_t)i * 3 * d + (size_t)h * hd;
+    if (t < hd) qs[t] = q[t];
+    __syncthreads();
+    float s = -INFINITY;
+    if (t <= i) {
+        const float *k = qkv + (size_t)t * 3 * d + d + (size_t)h * hd;
+        float a = 0.f;
+        for (int c = 0; c < hd; c++) a += qs[c] * k[c];
+        s = a / sqrtf((float)hd);
+    }
+    const float mx = tr_block_max(s, red);
+    const float e = t <= i ? expf(s - mx) : 0.f;
+    const float sum = tr_block_sum(e, red);
+    const float p = e / sum;
+    ps[t] = p;
+    if (t < T) P[((size_t)h * T + i) * T + t] = p;
+    __syncthreads();
+    if (t < hd) {
+        float a = 0.f;
+        for (int j = 0; j <= i; j++) a += ps[j] * qkv[(size_t)j * 3 * d + 2 * d + (size_t)h * hd + t];
+        o[(size_t)i * d + (size_t)h * hd + t] = a;
+    }
+}
+
+// Backward of the attention for one (query row i, head h): dA_j = do_i . v_j, dS_ij = P_ij (dA_j - sum_j dA_j P_ij),
+// dq_i = sum_j dS_ij k_j / sqrt(hd).  dS is stored for the key-side kernel; dq goes to the q part of dqkv.
+__global__ __launch_bounds__(256) void tr_attn_bwd_q_kernel(const float *qkv, const float *P, const float *dout, int T, int d,
+                                                            int hd, float *dS, float *dqkv)
+{
+    __shared__ float red[4];
+    __shared__ float dos[128];
+    __shared__ float dss[256];
+    const int i = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
+    if (t < hd) dos[t] = dout[(size_t)i * d + (size_t)h * hd + t];
+    __syncthreads();
+    float dA = 0.f, p = 0.f;
+    if (t <= i) {
+        const float *v = qkv + (size_t)t * 3 * d + 2 * d + (size_t)h * hd;
+        for (int c = 0; c < hd; c++) dA += dos[c] * v[c];
+        p = P[((size_t)h * T + i) * T + t];
+    }
+    const float D = tr_block_sum(dA * p, red);
+    const float ds = p * (dA - D);
+    dss[t] = ds;
+    if (t < T) dS[((size_t)h * T + i) * T + t] = ds;
+    __syncthreads();
+    if (t < hd) {
+        float a = 0.f;
+        for (int j = 0; j <= i; j++) a += dss[j] * qkv[(size_t)j * 3 * d + d + (size_t)h * hd + t];
+        dqkv[(size_t)i * 3 * d + (size_t)h * hd + t] = a / sqrtf((float)hd);
+    }
+}
+
+// Key side for one (key row j, head h): dv_j = sum_{i >= j} P_ij do_i, dk_j = sum_{i >= j} dS_ij q_i / sqrt(hd)
+__global__ __launch_bounds__(128) void tr_attn_bwd_kv_kernel(const float *qkv, const float *P, const float *dS, const float *dout,
+                                                             int T, int d, int hd, float *dqkv)
+{
+    const int j = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
+    if (c >= hd) return;
+    float dv = 0.f, dk = 0.f;
+    for (int i = j; i < T; i++) {
+        const size_t pi = ((size_t)h * T + i) * T + j;
+        dv += P[pi] * dout[(size_t)i * d + (size_t)h * hd + c];
+        dk += dS[pi] * qkv[(size_t)i * 3 * d + (size_t)h * hd + c];
+    }
+    dqkv[(size_t)j * 3 * d + d + (size_t)h * hd + c] = dk / sqrtf((float)hd);
+    dqkv[(size_t)j * 3 * d + 2 * d + (size_t)h * hd + c] = dv;
+}
+
+// Eq. 3 for one position: loss[t] = - sum_n p_n log q_n with p = softmax(zt[t]), q = softmax(z[t]);
+// dz[t] = q - p (the gradient of the loss with respect to the draft logits).  One block per row.
+__global__ __launch_bounds__(256) void tr_loss_kernel(const float *z, const float *zt, int V, float *dz, float *loss)
+{
+    __shared__ float red[4];
+    const int row = blockIdx.x;
+    const float *zr = z + (size_t)row * V, *tr = zt + (size_t)row * V;
+    float mz = -INFINITY, mt = -INFINITY;
+    for (int n = threadIdx.x; n < V; n += 256) { mz = fmaxf(mz, zr[n]); mt = fmaxf(mt, tr[n]); }
+    mz = tr_block_max(mz, red);
+    mt = tr_block_max(mt, red);
+    float sz = 0.f, st = 0.f;
+    for (int n = threadIdx.x; n < V; n += 256) { sz += expf(zr[n] - mz); st += expf(tr[n] - mt); }
+    sz = tr_block_sum(sz, red);
+    st = tr_block_sum(st, red);
+    const float lz = logf(sz);
+    float l = 0.f;
+    for (int n = threadIdx.x; n < V; n += 256) {
+        const float p = expf(tr[n] - mt) / st;
+        const float lq = zr[n] - mz - lz;
+        l -= p * lq;
+        dz[(size_t)row * V + n] = expf(lq) - p;
+    }
+    l = tr_block_sum(l, red);
+    if (threadIdx.x == 0) loss[row] = l;
+}
+
+// AdamW with bias correction and decoupled weight decay; c1 = 1 - beta1^step, c2 = 1 - beta2^step
+__global__ void tr_adamw_kernel(float *w, const float *g, float *m, float *v, size_t n, float lr, float b1, float b2, float eps,
+                                float wd, float c1, float c2)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float gi = g[i];
+    const float mi = b1 * m[i] + (1.f - b1) * gi;
+    const float vi = b2 * v[i] + (1.f - b2) * gi * gi;
+    m[i] = mi;
+    v[i] = vi;
+    w[i] = w[i] * (1.f - lr * wd) - lr * (mi / c1) / (sqrtf(vi / c2) + eps);
+}
+
+// dst[i] = src[i] rounded to bfloat16 (nearest even), kept as fp32: what a bf16 checkpoint would hold
+__global__ void tr_round_bf16_kernel(const float *src, int n, float *dst)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = bf2f(f2bf(src[i]));
+}
+
+// fp32 row-major [rows][K] <-> bf16 MFMA tiles (the layout of pack_w_bf16_kernel); K % 8 == 0
+__global__ void tr_unpack_bf16_kernel(const uint16_t *tiles, int rows, int K, int KS, float *dst)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)rows * K) return;
+    const int r = (int)(i / K), k = (int)(i % K);
+    dst[i] = bf2f(tiles[packed_u16_index(r, k, KS)]);
+}
+__global__ void tr_pack_bf16_kernel(const float *src, int rows, int K, int KS, uint16_t *tiles)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)rows * K) return;
+    const int r = (int)(i / K), k = (int)(i % K);
+    tiles[packed_u16_index(r, k, KS)] = f2bf(src[i]);
+}
