@@ -194,6 +194,67 @@ def run_adapters(args):
     print(json.dumps(out), flush=True)
 
 
+def run_train(args):
+    """One training step of the adapter (Eq. 3 + AdamW) on a sequence of --prompt tokens of the
+    configuration's shape: wall-clock per step, split into the frozen model's forward and the
+    training graph, and the fp32 rate of the training graph's contractions (3 products with the LM
+    head, 3 with Wqkv, 3 with Wo: 2 T N K each).  The oracle's step is timed beside it on a bounded
+    sample.  Prints one JSON object; not part of the benchmark line."""
+    import numpy as np
+    import torch
+    from paper_2404_18911_amd import binding as B
+    from paper_2404_18911_amd import inputs as I
+    threads = min(16, os.cpu_count() or 8)
+    shape = I.SHAPES[args.shape]
+    T = min(args.prompt, 256)
+    kg = B.Kangaroo(shape, T + 16, gamma_max=6, kv_page_tokens=128)
+    keep = {}
+    for k, layer, a in I.iter_weights(shape, seed=1, alpha=args.alpha, threads=threads):
+        kg.load_tensor(k, layer, a)
+        if k in (I.KIND_LM_HEAD, I.KIND_A_WQ, I.KIND_A_WK, I.KIND_A_WV, I.KIND_A_WO, I.KIND_A_NORM_IN, I.KIND_A_NORM_LAST):
+            keep[k] = a
+    kg.train_bind(T)
+    toks = I.gen_prompt(shape.vocab, T)
+    p, _ = B.make_params()
+    losses = [kg.train_step(toks, 1e-4) for _ in range(max(1, args.warmup))]
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for _ in range(args.steps):
+        losses.append(kg.train_step(toks, 1e-4))
+    torch.cuda.synchronize()
+    dt = (time.time() - t0) / args.steps
+    kg.prefill(p, toks)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for _ in range(3):
+        kg.prefill(p, toks)
+    torch.cuda.synchronize()
+    t_frozen = (time.time() - t0) / 3
+    d, V = shape.d_model, shape.vocab
+    flops = 2.0 * T * (3 * V * d + 3 * 3 * d * d + 3 * d * d)
+    out = {"train": True, "shape": args.shape, "tokens": T, "ms_per_step": 1e3 * dt, "tokens_per_s": T / dt,
+           "frozen_forward_ms": 1e3 * t_frozen, "training_graph_ms": 1e3 * (dt - t_frozen),
+           "training_graph_TFLOPs_fp32": flops / max(dt - t_frozen, 1e-9) / 1e12, "fp32_matrix_peak_TFLOPs": 157.3,
+           "losses": losses, "workspace_GB": kg.train_bytes / 1e9}
+    log(f"[train] {T} tokens: {1e3 * dt:.1f} ms per step ({1e3 * t_frozen:.1f} frozen forward), losses {losses[0]:.2f} -> {losses[-1]:.2f}")
+    if not args.no_cpu:
+        from oracle import adapter_training as TR
+        Ts = 32
+        F = kg.train_read(B.TRAIN_FEATURES, T)[:Ts].astype(np.float64)
+        Zt = kg.train_read(B.TRAIN_TARGET_LOGITS, T)[:Ts].astype(np.float64)
+        w64 = lambda a: (I.bf16_bits_to_f32(a) if a.dtype == np.uint16 else a).astype(np.float64)
+        P = {"wq": w64(keep[I.KIND_A_WQ]), "wk": w64(keep[I.KIND_A_WK]), "wv": w64(keep[I.KIND_A_WV]), "wo": w64(keep[I.KIND_A_WO]),
+             "g_in": w64(keep[I.KIND_A_NORM_IN]), "g_last": w64(keep[I.KIND_A_NORM_LAST])}
+        head = w64(keep[I.KIND_LM_HEAD])
+        t0 = time.time()
+        TR.loss_and_grads(P, F, Zt, head, shape.n_heads, shape.rms_eps, shape.rope_theta)
+        tc = time.time() - t0
+        out["cpu_baseline"] = {"value": Ts / tc, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                               "sample": f"loss and gradients of the first {Ts} positions (fp64 numpy), training graph only"}
+    kg.close()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -209,6 +270,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="eta x gamma and exit-layer sweeps on a sharpened head (not the benchmark line)")
     ap.add_argument("--head-scale", type=float, default=6.0, help="LM-head multiplier of --sweep")
     ap.add_argument("--adapters", action="store_true", help="cost of the adapter architectures of Table 2 (not the benchmark line)")
+    ap.add_argument("--train", action="store_true", help="time the adapter's training step, Eq. 3 + AdamW (not the benchmark line)")
     ap.add_argument("--prefill-only", type=int, default=0,
                     help="run only this many prompt passes (for profiling the MFMA prompt kernels) and print their timing")
     args = ap.parse_args()
@@ -228,6 +290,9 @@ def main():
         return
     if args.adapters:
         run_adapters(args)
+        return
+    if args.train:
+        run_train(args)
         return
     threads = min(16, os.cpu_count() or 8)
     shape = I.SHAPES[args.shape]

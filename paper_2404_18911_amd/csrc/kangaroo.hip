@@ -33,7 +33,8 @@ struct TrainLayout {
     size_t nparam = 0;
     size_t P = 0, G = 0, M = 0, V = 0;
     size_t F = 0, X = 0, Xn = 0, N = 0, QKV = 0, O = 0, H = 0, Mm = 0, Z = 0, Zt = 0, dZ = 0, rin = 0, rlast = 0, rfin = 0,
-           Pm = 0, dS = 0, dMm = 0, dH = 0, dO = 0, dQKV = 0, dN = 0, loss = 0;
+           Pm = 0, dS = 0, dMm = 0, dH = 0, dO = 0, dQKV = 0, dN = 0, loss = 0, part = 0;
+    size_t part_floats = 0;
     size_t bytes = 0;
 };
 
@@ -1259,6 +1260,8 @@ void kg_destroy(kg_ctx *x)
 
 // ---- adapter training (Eq. 3, AdamW) --------------------------------------------------------------
 
+constexpr int TR_SPLIT_MAX = 8;
+
 static void train_layout(const kg_ctx *x, int Tm, TrainLayout &t)
 {
     const size_t d = x->c.d_model, V = x->c.vocab, H = x->c.n_heads, T = Tm;
@@ -1273,6 +1276,8 @@ static void train_layout(const kg_ctx *x, int Tm, TrainLayout &t)
     t.Pm = take(H * T * T); t.dS = take(H * T * T);
     t.dMm = take(T * d); t.dH = take(T * d); t.dO = take(T * d); t.dQKV = take(T * 3 * d); t.dN = take(T * d);
     t.loss = take(T);
+    t.part_floats = (size_t)TR_SPLIT_MAX * T * 3 * d;      // partial results of split contractions ([slices][T][<= 3d])
+    t.part = take(t.part_floats);
     t.bytes = o;
 }
 
@@ -1326,14 +1331,37 @@ int kg_train_bind(kg_ctx *x, void *work_dev, size_t bytes, int max_tokens)
     return KG_OK;
 }
 
+// may 4 consecutive elements along an operand's contiguous index be fetched as one 16-byte word?
+static void tr_gemm_vec_flags(TrGemm &g)
+{
+    auto ok = [](const void *p, long s_contig, long s_other) {
+        return s_contig == 1 && s_other % 4 == 0 && ((uintptr_t)p & 15) == 0;
+    };
+    g.a_vec = g.sak == 1 ? ok(g.A, g.sak, g.sam) : ok(g.A, g.sam, g.sak);
+    g.b_vec = g.b_mode == 0 && (g.sbk == 1 ? ok(g.B, g.sbk, g.sbn) : ok(g.B, g.sbn, g.sbk));
+}
+
 static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, long sbk, long sbn, int b_mode, float *C,
                    long ldc, int M, int N, int K, int accumulate)
 {
     TrGemm g;
-    g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = b_mode; g.b_KS = x ? x->KSd : 0;
+    g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = b_mode; g.b_KS = x->KSd;
     g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
-    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, x->stream, g);
-    return check_launch(x, "train_gemm");
+    tr_gemm_vec_flags(g);
+    // few output tiles and a long k: slice k so that the launch has enough workgroups to fill the chip
+    const int tiles = ((N + 127) / 128) * ((M + 63) / 64);
+    int S = 1;
+    while (S < TR_SPLIT_MAX && tiles * S < 1024 && K / (2 * S) >= 256 && (size_t)2 * S * M * N <= x->tl.part_floats) S *= 2;
+    g.k_chunk = ((K + S - 1) / S + 15) / 16 * 16;
+    g.part = at<float>(x->tr, x->tl.part);
+    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 127) / 128, (M + 63) / 64, S), dim3(256), 0, x->stream, g);
+    KGCHK(check_launch(x, "train_gemm"));
+    if (S > 1) {
+        hipLaunchKernelGGL(tr_gemm_reduce_kernel, dim3((unsigned)(((size_t)M * N + 255) / 256)), dim3(256), 0, x->stream,
+                           (const float *)g.part, S, M, N, C, ldc, accumulate);
+        KGCHK(check_launch(x, "train_gemm_reduce"));
+    }
+    return KG_OK;
 }
 
 int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, int n, double *loss)
@@ -1489,7 +1517,9 @@ int kg_op_gemm_f32(const float *A, long sam, long sak, const float *B, long sbk,
     TrGemm g;
     g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = 0; g.b_KS = 0;
     g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
-    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, (hipStream_t)hip_stream, g);
+    g.k_chunk = (K + 15) / 16 * 16; g.part = nullptr;
+    tr_gemm_vec_flags(g);
+    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 127) / 128, (M + 63) / 64, 1), dim3(256), 0, (hipStream_t)hip_stream, g);
     return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
 }
 

@@ -16,8 +16,15 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 //             b_mode 1: element (row n, col k) of a matrix stored as bf16 MFMA tiles (the layout of
 //                       pack_w_bf16_kernel: tile (row/16, col/32), 16-byte unit (col%32/8)*16 + row%16)
 //             b_mode 2: element (row k, col n) of such a matrix
-// One workgroup (4 waves) per 64 x 64 tile of C, one 32 x 32 quadrant per wave; k advances in steps
-// of 16 through LDS.  Loads pick the orientation in which the operand is contiguous.
+// One workgroup (4 waves) per 64 x 128 tile of C; a wave owns 32 x 64 of it (two 32x32x2 MFMA tiles
+// that share the A operand).  k advances in steps of 16 through two LDS buffers: the next step's
+// operands are fetched into registers while the current one is multiplied, and stored to the other
+// buffer afterwards, so a step has one barrier.  A thread fetches 4 consecutive elements of A and
+// 2 x 4 of B along whichever index is contiguous in memory (one 16-byte load when the host found
+// the operand aligned for it: a_vec / b_vec), with element-wise guards at the ragged edges.
+// A contraction with few output tiles and a long k is split over blockIdx.z: slice z handles k in
+// [z * k_chunk, (z + 1) * k_chunk) and writes its own partial [M][N] at part + z * M * N; a second
+// kernel adds the slices in order (no atomics: the result does not depend on scheduling).
 struct TrGemm {
     const void *A; long sam, sak;
     const void *B; long sbk, sbn;
@@ -25,9 +32,13 @@ struct TrGemm {
     float *C; long ldc;
     int M, N, K;
     int accumulate;
+    int k_chunk;        // k handled per blockIdx.z slice (a multiple of 16); >= K when not split
+    float *part;        // partial results of a split contraction
+    int a_vec, b_vec;   // 4 consecutive elements along the contiguous index are one aligned 16-byte word
 };
 
-#define TRG_LD 96   // LDS row stride in floats: the two half-waves of an MFMA operand read hit different banks
+#define TRG_LDA 96    // LDS row strides in floats: the two half-waves of an MFMA operand read hit different banks
+#define TRG_LDB 160
 
 __device__ __forceinline__ size_t packed_u16_index(int row, int col, int KS)
 {
@@ -36,71 +47,166 @@ __device__ __forceinline__ size_t packed_u16_index(int row, int col, int KS)
 
 __global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
 {
-    __shared__ float As[16][TRG_LD];
-    __shared__ float Bs[16][TRG_LD];
+    __shared__ float As[2][16][TRG_LDA];
+    __shared__ float Bs[2][16][TRG_LDB];
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
-    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
-    const int wm = (wave & 1) * 32, wn = (wave >> 1) * 32;
-    const float *Af = (const float *)g.A;
-    const float *Bf = (const float *)g.B;
-    const uint16_t *Bp = (const uint16_t *)g.B;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 128;
+    const int wm = (wave & 1) * 32, wn = (wave >> 1) * 64;
     const bool a_kc = g.sak == 1;                      // A contiguous along k
     const bool b_kc = g.b_mode == 0 ? g.sbk == 1 : g.b_mode == 1;
-    f32x16_t acc;
-#pragma unroll
-    for (int i = 0; i < 16; i++) acc[i] = 0.f;
-    for (int k0 = 0; k0 < g.K; k0 += 16) {
-        float av[4], bv[4];
-        int am, ak, bn, bk;                             // first of the 4 elements this thread fetches
-        if (a_kc) { am = t >> 2; ak = (t & 3) * 4; } else { ak = t >> 4; am = (t & 15) * 4; }
-        if (b_kc) { bn = t >> 2; bk = (t & 3) * 4; } else { bk = t >> 4; bn = (t & 15) * 4; }
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const int m = m0 + am + (a_kc ? 0 : i), k = k0 + ak + (a_kc ? i : 0);
-            av[i] = (m < g.M && k < g.K) ? Af[(size_t)m * g.sam + (size_t)k * g.sak] : 0.f;
-        }
-        if (g.b_mode == 0) {
+    const bool split = gridDim.z > 1;
+    const int k_lo = blockIdx.z * g.k_chunk, k_hi = min(g.K, k_lo + g.k_chunk);
+    // first of the 4 (A) and 2 x 4 (B, second group 64 columns further) elements this thread fetches per step
+    int am, ak, bn, bk;
+    if (a_kc) { am = t >> 2; ak = (t & 3) * 4; } else { ak = t >> 4; am = (t & 15) * 4; }
+    if (b_kc) { bn = t >> 2; bk = (t & 3) * 4; } else { bk = t >> 4; bn = (t & 15) * 4; }
+    const float *pa = (const float *)g.A + (size_t)(m0 + am) * g.sam + (size_t)(k_lo + ak) * g.sak;
+    const long a_step = 16 * g.sak, a_el = a_kc ? g.sak : g.sam;
+    const float *pb0 = nullptr, *pb1 = nullptr;        // b_mode 0
+    long b_step = 0, b_el = 0;
+    const uint16_t *Bp = (const uint16_t *)g.B;        // tiled modes
+    size_t rb0 = 0, rb1 = 0;                           // mode 1: per-row part of the tile index; mode 2: full index at k_lo
+    if (g.b_mode == 0) {
+        pb0 = (const float *)g.B + (size_t)(k_lo + bk) * g.sbk + (size_t)(n0 + bn) * g.sbn;
+        pb1 = pb0 + (size_t)64 * g.sbn;
+        b_step = 16 * g.sbk;
+        b_el = b_kc ? g.sbk : g.sbn;
+    } else if (g.b_mode == 1) {
+        rb0 = (size_t)((n0 + bn) >> 4) * g.b_KS * 64 + ((n0 + bn) & 15);
+        rb1 = (size_t)((n0 + bn + 64) >> 4) * g.b_KS * 64 + ((n0 + bn + 64) & 15);
+    } else {
+        rb0 = packed_u16_index(k_lo + bk, n0 + bn, g.b_KS);
+        rb1 = packed_u16_index(k_lo + bk, n0 + bn + 64, g.b_KS);
+    }
+    const bool am_all = a_kc ? (m0 + am < g.M) : (m0 + am + 3 < g.M);
+    float av[4], bv[2][4];
+    auto widen = [](uint2 raw, float *o) {
+        o[0] = __uint_as_float(raw.x << 16);
+        o[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+        o[2] = __uint_as_float(raw.y << 16);
+        o[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+    };
+    auto fetch = [&](int k0) {
+        // ---- A
+        const bool ak_all = a_kc ? (k0 + ak + 3 < k_hi) : (k0 + ak < k_hi);
+        if (g.a_vec && am_all && ak_all) {
+            const float4 v = *(const float4 *)pa;
+            av[0] = v.x; av[1] = v.y; av[2] = v.z; av[3] = v.w;
+        } else {
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const int n = n0 + bn + (b_kc ? 0 : i), k = k0 + bk + (b_kc ? i : 0);
-                bv[i] = (n < g.N && k < g.K) ? Bf[(size_t)k * g.sbk + (size_t)n * g.sbn] : 0.f;
+                const int m = m0 + am + (a_kc ? 0 : i), k = k0 + ak + (a_kc ? i : 0);
+                av[i] = (m < g.M && k < k_hi) ? pa[i * a_el] : 0.f;
             }
-        } else {
-            // four consecutive columns of one row of the tiled matrix: 8 bytes, 8-byte aligned
-            const int n = n0 + bn, k = k0 + bk;
-            const int row = g.b_mode == 1 ? n : k, col = g.b_mode == 1 ? k : n;
-            const bool ok = n < g.N && k < g.K;     // the four columns share the verdict: N, K are multiples of 8 for tiled matrices
-            uint2 raw = make_uint2(0u, 0u);
-            if (ok) raw = *(const uint2 *)(Bp + packed_u16_index(row, col, g.b_KS));
-            bv[0] = __uint_as_float(raw.x << 16);
-            bv[1] = __uint_as_float(raw.x & 0xFFFF0000u);
-            bv[2] = __uint_as_float(raw.y << 16);
-            bv[3] = __uint_as_float(raw.y & 0xFFFF0000u);
         }
-        __syncthreads();                                // the previous step's MFMAs have read LDS
+        pa += a_step;
+        // ---- B
+        if (g.b_mode == 0) {
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const float *pb = h ? pb1 : pb0;
+                const int nb = n0 + bn + 64 * h;
+                const bool n_all = b_kc ? (nb < g.N) : (nb + 3 < g.N);
+                const bool k_all = b_kc ? (k0 + bk + 3 < k_hi) : (k0 + bk < k_hi);
+                if (g.b_vec && n_all && k_all) {
+                    const float4 v = *(const float4 *)pb;
+                    bv[h][0] = v.x; bv[h][1] = v.y; bv[h][2] = v.z; bv[h][3] = v.w;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; i++) {
+                        const int n = nb + (b_kc ? 0 : i), k = k0 + bk + (b_kc ? i : 0);
+                        bv[h][i] = (n < g.N && k < k_hi) ? pb[i * b_el] : 0.f;
+                    }
+                }
+            }
+            pb0 += b_step;
+            pb1 += b_step;
+        } else if (g.b_mode == 1) {
+            // four consecutive columns (k) of rows n, n + 64 of the tiled matrix: 8 bytes each, 8-byte aligned;
+            // N, K and k_chunk are multiples of 8, so the four share the bounds verdict
+            const int col = k0 + bk;
+            const size_t cpart = (size_t)(col >> 5) * 64 + ((col >> 3) & 3) * 16;
+            const bool k_ok = col < k_hi;
+            uint2 r0 = make_uint2(0u, 0u), r1 = make_uint2(0u, 0u);
+            if (k_ok && n0 + bn < g.N) r0 = *(const uint2 *)(Bp + ((rb0 + cpart) << 3) + (col & 7));
+            if (k_ok && n0 + bn + 64 < g.N) r1 = *(const uint2 *)(Bp + ((rb1 + cpart) << 3) + (col & 7));
+            widen(r0, bv[0]);
+            widen(r1, bv[1]);
+        } else {
+            // four consecutive columns (n) of row k: the row advances by 16 per step, i.e. by one tile row
+            const bool k_ok = k0 + bk < k_hi;
+            uint2 r0 = make_uint2(0u, 0u), r1 = make_uint2(0u, 0u);
+            if (k_ok && n0 + bn < g.N) r0 = *(const uint2 *)(Bp + rb0);
+            if (k_ok && n0 + bn + 64 < g.N) r1 = *(const uint2 *)(Bp + rb1);
+            widen(r0, bv[0]);
+            widen(r1, bv[1]);
+            rb0 += (size_t)g.b_KS * 512;
+            rb1 += (size_t)g.b_KS * 512;
+        }
+    };
+    auto stash = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            if (a_kc) As[ak + i][am] = av[i]; else As[ak][am + i] = av[i];
-            if (b_kc) Bs[bk + i][bn] = bv[i]; else Bs[bk][bn + i] = bv[i];
+            if (a_kc) As[buf][ak + i][am] = av[i]; else As[buf][ak][am + i] = av[i];
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                if (b_kc) Bs[buf][bk + i][bn + 64 * h] = bv[h][i]; else Bs[buf][bk][bn + 64 * h + i] = bv[h][i];
+            }
         }
-        __syncthreads();
+    };
+    f32x16_t acc0, acc1;
+#pragma unroll
+    for (int i = 0; i < 16; i++) { acc0[i] = 0.f; acc1[i] = 0.f; }
+    int buf = 0;
+    if (k_lo < k_hi) {
+        fetch(k_lo);
+        stash(0);
+    }
+    __syncthreads();
+    for (int k0 = k_lo; k0 < k_hi; k0 += 16) {
+        const bool more = k0 + 16 < k_hi;
+        if (more) fetch(k0 + 16);                       // in flight while this step is multiplied
 #pragma unroll
         for (int kk = 0; kk < 8; kk++) {
-            const float a = As[2 * kk + (lane >> 5)][wm + (lane & 31)];
-            const float b = Bs[2 * kk + (lane >> 5)][wn + (lane & 31)];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+            const float a = As[buf][2 * kk + (lane >> 5)][wm + (lane & 31)];
+            const float b0 = Bs[buf][2 * kk + (lane >> 5)][wn + (lane & 31)];
+            const float b1 = Bs[buf][2 * kk + (lane >> 5)][wn + 32 + (lane & 31)];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
         }
+        if (more) stash(buf ^ 1);                       // the other buffer was last read before the previous barrier
+        __syncthreads();
+        buf ^= 1;
     }
     // accumulator register i of lane l: row 8 * (i / 4) + 4 * (l / 32) + i % 4, column l % 32
-    const int n = n0 + wn + (lane & 31);
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-        const int m = m0 + wm + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-        if (m < g.M && n < g.N) {
-            float *c = g.C + (size_t)m * g.ldc + n;
-            *c = g.accumulate ? *c + acc[i] : acc[i];
+    for (int h = 0; h < 2; h++) {
+        const int n = n0 + wn + 32 * h + (lane & 31);
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const int m = m0 + wm + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+            const float v = h ? acc1[i] : acc0[i];
+            if (m < g.M && n < g.N) {
+                if (split) {
+                    g.part[((size_t)blockIdx.z * g.M + m) * g.N + n] = v;
+                } else {
+                    float *c = g.C + (size_t)m * g.ldc + n;
+                    *c = g.accumulate ? *c + v : v;
+                }
+            }
         }
     }
+}
+
+// C[m][n] (+)= part[0][m][n] + part[1][m][n] + ... in slice order
+__global__ void tr_gemm_reduce_kernel(const float *part, int S, int M, int N, float *C, long ldc, int accumulate)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)M * N) return;
+    float s = part[i];
+    for (int z = 1; z < S; z++) s += part[(size_t)z * M * N + i];
+    float *c = C + (i / N) * ldc + (i % N);
+    *c = accumulate ? *c + s : s;
 }
 
 // ---------------------------------------------------------------------------------------------
