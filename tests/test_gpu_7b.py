@@ -89,3 +89,47 @@ def test_7b_full_request_lossless_and_round_bounds(model7b, eta):
     else:
         assert st.draft_steps == st.rounds           # confidence never reaches 0.6 with random-init weights
     assert min(out) >= 0 and max(out) < SHAPE.vocab
+
+
+def test_7b_training_step_follows_oracle_and_full_length_step_runs(model7b):
+    """Eq. 3 + AdamW at the 7B shape.  Element-by-element against the fp64 oracle on a 24-token
+    sequence (all six gradients, loss, draft logits); then the 256-token step that the benchmark
+    times, checked by what holds at any size: a finite loss that falls over three steps, and Eq. 3
+    per position >= the entropy of the target row (cross entropy is never below it).  The adapter
+    is restored afterwards: the module's other tests share the model.  (Runs last in this file.)"""
+    from oracle import adapter_training as TR
+    from paper_2404_18911_amd import binding as B
+    kg, W = model7b
+    d, H, V = SHAPE.d_model, SHAPE.n_heads, SHAPE.vocab
+    try:
+        kg.train_bind(256)
+        n = 24
+        toks = I.gen_prompt(V, 256, seed=11)
+        before = kg.train_read(B.TRAIN_PARAMETERS)
+        loss = kg.train_step(toks[:n], 1e-5)
+        F = kg.train_read(B.TRAIN_FEATURES, n).astype(np.float64)
+        Zt = kg.train_read(B.TRAIN_TARGET_LOGITS, n).astype(np.float64)
+        Z = kg.train_read(B.TRAIN_DRAFT_LOGITS, n)
+        G = B.split_param_block(kg.train_read(B.TRAIN_GRADIENTS), d)
+        Po = {k: v.astype(np.float64) for k, v in B.split_param_block(before, d).items()}
+        head64 = I.bf16_bits_to_f32(W[(I.KIND_LM_HEAD, -1)]).astype(np.float64)
+        want, Go, inter = TR.loss_and_grads(Po, F, Zt, head64, H, SHAPE.rms_eps, SHAPE.rope_theta)
+        assert np.abs(Z - inter["Z"]).max() <= 1e-5 * max(1.0, np.abs(inter["Z"]).max())
+        assert abs(loss - want) <= 1e-5 * abs(want), (loss, want)
+        for k in TR.PARAMS:
+            gmax = np.abs(Go[k]).max()
+            err = np.abs(G[k] - Go[k]).max()
+            print(f"7b training gradient {k}: max |g| {gmax:.3e}, max err {err:.3e}")
+            assert gmax > 0 and err <= 2e-4 * gmax, (k, err, gmax)
+        # full length, the configuration bench.py --train times
+        losses = [kg.train_step(toks, 1e-5) for _ in range(3)]
+        assert all(np.isfinite(losses)) and losses[2] < losses[1] < losses[0], losses
+        rows = kg.train_read(B.TRAIN_ROW_LOSSES, 256).astype(np.float64)
+        Zt = kg.train_read(B.TRAIN_TARGET_LOGITS, 256).astype(np.float64)
+        p = TR.softmax_rows(Zt)
+        entropy = -(p * np.log(np.maximum(p, 1e-300))).sum(axis=1)
+        assert np.all(rows >= entropy - 1e-3), float((entropy - rows).max())
+        assert abs(rows.sum() - losses[2]) <= 1e-6 * losses[2]
+    finally:
+        for kind in (I.KIND_A_WQ, I.KIND_A_WK, I.KIND_A_WV, I.KIND_A_WO, I.KIND_A_NORM_IN, I.KIND_A_NORM_LAST):
+            kg.load_tensor(kind, -1, W[(kind, -1)])
