@@ -209,7 +209,7 @@ def run_train(args):
     T = min(args.prompt, 256)
     kg = B.Kangaroo(shape, T + 16, gamma_max=6, kv_page_tokens=128)
     keep = {}
-    for k, layer, a in I.iter_weights(shape, seed=1, alpha=args.alpha, threads=threads):
+    for k, layer, a in I.iter_weights(shape, seed=1, alpha=args.alpha, threads=threads, head_scale=args.train_head_scale):
         kg.load_tensor(k, layer, a)
         if k in (I.KIND_LM_HEAD, I.KIND_A_WQ, I.KIND_A_WK, I.KIND_A_WV, I.KIND_A_WO, I.KIND_A_NORM_IN, I.KIND_A_NORM_LAST):
             keep[k] = a
@@ -251,8 +251,65 @@ def run_train(args):
         tc = time.time() - t0
         out["cpu_baseline"] = {"value": Ts / tc, "unit": "tokens/s", "cores": threads, "kind": "oracle",
                                "sample": f"loss and gradients of the first {Ts} positions (fp64 numpy), training graph only"}
+    if args.epochs > 0:
+        out["self_distillation"] = train_demo(args, kg, shape, T)
     kg.close()
     print(json.dumps(out), flush=True)
+
+
+def train_demo(args, kg, shape, T):
+    """Self-distillation on synthetic token streams (stands in for the paper's ShareGPT epochs): the
+    model's own greedy continuations of random prompts are the training sequences; the adapter is
+    re-initialised from the generator, fitted by Eq. 3 for --epochs passes, and draft acceptance and
+    decode speed are measured on held-out streams before and after.  Every stream decoded with the
+    trained adapter must still equal plain decoding."""
+    from paper_2404_18911_amd import binding as B
+    from paper_2404_18911_amd import inputs as I
+    p, _ = B.make_params(eta=0.6, gamma=6)
+    p0, _ = B.make_params(eta=0.0, gamma=6)
+    n_prompt, held = 32, 2
+    streams = []
+    for i in range(args.streams + held):
+        pr = I.gen_prompt(shape.vocab, n_prompt, seed=100 + i)
+        cont, _ = kg.decode_plain(p, pr, T - n_prompt)
+        streams.append([int(v) for v in pr] + cont)
+
+    def fitted():
+        """Acceptance on two of the training streams: what the optimisation itself achieves."""
+        acc = drafted = 0
+        for sq in streams[:2]:
+            out, st = kg.generate(p, sq[:n_prompt], T - n_prompt)
+            assert out == sq[n_prompt:]
+            acc += st.accepted; drafted += st.drafted
+        return acc / max(1, drafted)
+
+    def evaluate():
+        acc = drafted = 0
+        toks = secs = 0.0
+        cr0 = []
+        for sq in streams[args.streams:]:
+            out, st = kg.generate(p, sq[:n_prompt], T - n_prompt)
+            assert out == sq[n_prompt:], "Kangaroo with the trained adapter left the plain stream"
+            acc += st.accepted; drafted += st.drafted; toks += len(out) - 1; secs += st.t_total_s
+            out0, st0 = kg.generate(p0, sq[:n_prompt], T - n_prompt)
+            assert out0 == sq[n_prompt:]
+            cr0.append((len(out0) - 1) / st0.rounds)
+        return {"acceptance_rate": acc / max(1, drafted), "tokens_per_s": toks / secs, "compression_rate_eta0": sum(cr0) / len(cr0),
+                "acceptance_rate_on_training_streams": fitted()}
+
+    res = {"streams": args.streams, "held_out": held, "tokens_per_stream": T, "lr": args.lr, "epochs": []}
+    res["before"] = evaluate()
+    log(f"[train] before: {res['before']}")
+    for e in range(args.epochs):
+        t0 = time.time()
+        tot = 0.0
+        for sq in streams[:args.streams]:
+            tot += kg.train_step(sq, args.lr)
+        ev = evaluate()
+        ev.update({"epoch": e + 1, "mean_loss_per_token": tot / (args.streams * T), "train_s": time.time() - t0})
+        res["epochs"].append(ev)
+        log(f"[train] epoch {e + 1}: {ev}")
+    return res
 
 
 def main():
@@ -271,6 +328,10 @@ def main():
     ap.add_argument("--head-scale", type=float, default=6.0, help="LM-head multiplier of --sweep")
     ap.add_argument("--adapters", action="store_true", help="cost of the adapter architectures of Table 2 (not the benchmark line)")
     ap.add_argument("--train", action="store_true", help="time the adapter's training step, Eq. 3 + AdamW (not the benchmark line)")
+    ap.add_argument("--epochs", type=int, default=0, help="with --train: passes of self-distillation over --streams synthetic streams")
+    ap.add_argument("--streams", type=int, default=16)
+    ap.add_argument("--train-head-scale", type=float, default=1.0, help="LM-head multiplier of --train (sharpens the target distribution)")
+    ap.add_argument("--lr", type=float, default=2e-5)
     ap.add_argument("--prefill-only", type=int, default=0,
                     help="run only this many prompt passes (for profiling the MFMA prompt kernels) and print their timing")
     args = ap.parse_args()
