@@ -128,3 +128,34 @@ def test_stats_metrics_match_eq1_eq2_golden_values():
         assert B.stats_ctar(st, w) == v
     with pytest.raises(ValueError):
         B.stats_cr(B.kg_stats())
+
+
+def test_training_workspace_size_is_host_logic():
+    """kg_train_workspace_bytes needs no device: sizes scale with the token capacity, hold the four
+    fp32 parameter-sized blocks (master copy, gradient, two AdamW moments), and the capacity is
+    limited to 256 tokens and to max_seq."""
+    L = B.lib()
+    shape = I.SHAPES["7b"]
+    rc, h = _create(shape, max_seq=520, kv_page_tokens=128)
+    assert rc == B.KG_OK
+    nb = ctypes.c_size_t()
+    sizes = []
+    for T in (1, 64, 256):
+        assert L.kg_train_workspace_bytes(h, T, ctypes.byref(nb)) == B.KG_OK
+        sizes.append(nb.value)
+    nparam = 4 * shape.d_model ** 2 + 2 * shape.d_model
+    assert sizes[0] >= 4 * nparam * 4 and sizes[0] < sizes[1] < sizes[2] < 4 * nparam * 4 + (1 << 29)
+    for bad in (0, -3, 257):
+        assert L.kg_train_workspace_bytes(h, bad, ctypes.byref(nb)) == B.KG_EINVAL
+    assert L.kg_train_workspace_bytes(h, 8, None) == B.KG_EINVAL
+    L.kg_destroy(h)
+    rc, h = _create(I.SHAPES["toy"], max_seq=40)
+    assert L.kg_train_workspace_bytes(h, 40, ctypes.byref(nb)) == B.KG_OK
+    assert L.kg_train_workspace_bytes(h, 41, ctypes.byref(nb)) == B.KG_EINVAL
+    # training calls before kg_bind are call-order errors, not crashes
+    hp = B.kg_train_params(1e-3, 0.9, 0.999, 1e-8, 0.0)
+    toks = (ctypes.c_int32 * 2)(1, 2)
+    loss = ctypes.c_double()
+    assert L.kg_train_step(h, ctypes.byref(hp), toks, 2, ctypes.byref(loss)) == B.KG_ESTATE
+    assert L.kg_train_bind(h, None, 0, 8) == B.KG_ESTATE
+    L.kg_destroy(h)
