@@ -233,7 +233,8 @@ void kg_destroy(kg_ctx *ctx);
  *   kg_train_workspace_bytes / kg_train_bind: device workspace (256-byte aligned, BORROWED until
  *     kg_destroy) for sequences of up to max_tokens tokens (<= 256 and <= max_seq); bind copies the
  *     loaded adapter tensors into the master copies and zeroes the AdamW moments and step count.
- *     All tensors must be loaded first.
+ *     All tensors must be loaded first; kg_bind, or loading an adapter tensor afterwards, drops the
+ *     training binding (kg_train_step then returns KG_ESTATE until kg_train_bind is called again).
  *   kg_train_step: tokens_host[n], 1 <= n <= max_tokens.  *loss is Eq. 3 for the parameters before
  *     the update.  Drops the sequence state of the context (a new kg_prefill is needed to decode).
  *   kg_train_read: copy one buffer of the last step to the host (tests and monitoring):

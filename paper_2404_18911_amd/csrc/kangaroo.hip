@@ -805,6 +805,7 @@ int kg_bind(kg_ctx *x, void *weights_dev, size_t weight_bytes, void *kv_dev, siz
         HIPCHK(x, hipEventCreateWithFlags(&x->ev_fetch, hipEventDisableTiming));
     }
     x->bound = true;
+    x->tr = nullptr;
     std::fill(x->loaded.begin(), x->loaded.end(), 0);
     for (int k = KG_A_WQ; k < KG_N_TENSOR_KINDS; k++)       // adapter tensors this architecture does not have
         if (!adapter_has(x, k)) x->loaded[tensor_slot(x, k, -1)] = 1;
@@ -870,6 +871,7 @@ int kg_load_tensor(kg_ctx *x, int kind, int layer, const void *src, size_t n_ele
     KGCHK(check_launch(x, "load_tensor"));
     HIPCHK(x, hipStreamSynchronize(x->stream));
     x->loaded[tensor_slot(x, kind, layer)] = 1;
+    if (kind >= KG_A_WQ) x->tr = nullptr;   // the training master copies no longer match the adapter: bind again
     return KG_OK;
 }
 

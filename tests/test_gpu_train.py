@@ -145,6 +145,14 @@ def test_training_call_order_and_argument_errors():
     with pytest.raises(B.KangarooError) as ei:
         kg.train_step([1, 2], 1e-3, beta1=1.0)
     assert ei.value.code == B.KG_EINVAL
+    # a freshly loaded adapter tensor makes the master copies stale: the binding is dropped
+    kg.train_step([1, 2, 3], 1e-3)
+    kg.load_tensor(I.KIND_A_WO, -1, W[(I.KIND_A_WO, -1)])
+    with pytest.raises(B.KangarooError) as ei:
+        kg.train_step([1, 2, 3], 1e-3)
+    assert ei.value.code == B.KG_ESTATE
+    kg.train_bind(8)
+    kg.train_step([1, 2, 3], 1e-3)
     kg.close()
     shape3 = dataclasses.replace(shape, adapter=I.ADAPTER_MLP)
     kg = P.load_model(shape3, I.gen_weights(shape3, seed=1), 64, kv_page_tokens=16)
