@@ -223,6 +223,12 @@ def run_train(args):
         losses.append(kg.train_step(toks, 1e-4))
     torch.cuda.synchronize()
     dt = (time.time() - t0) / args.steps
+    # the contraction kernel alone, timed with HIP events on its stream over one more step
+    kg.set_profiling(True)
+    kg.train_step(toks, 1e-4)
+    pr = kg.get_profile()
+    kg.set_profiling(False)
+    gemm_tflops = pr.bytes[4] / max(pr.seconds[4], 1e-12) / 1e12
     kg.prefill(p, toks)
     torch.cuda.synchronize()
     t0 = time.time()
@@ -235,6 +241,9 @@ def run_train(args):
     out = {"train": True, "shape": args.shape, "tokens": T, "ms_per_step": 1e3 * dt, "tokens_per_s": T / dt,
            "frozen_forward_ms": 1e3 * t_frozen, "training_graph_ms": 1e3 * (dt - t_frozen),
            "training_graph_TFLOPs_fp32": flops / max(dt - t_frozen, 1e-9) / 1e12, "fp32_matrix_peak_TFLOPs": 157.3,
+           "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": 157.3, "unit": "TFLOP/s", "frac": gemm_tflops / 157.3,
+                        "traffic": None, "kernel": "tr_gemm_kernel", "launches": int(pr.launches[4]),
+                        "avg_launch_us": 1e6 * pr.seconds[4] / max(1, pr.launches[4])},
            "losses": losses, "workspace_GB": kg.train_bytes / 1e9}
     log(f"[train] {T} tokens: {1e3 * dt:.1f} ms per step ({1e3 * t_frozen:.1f} frozen forward), losses {losses[0]:.2f} -> {losses[-1]:.2f}")
     if not args.no_cpu:

@@ -200,14 +200,15 @@ int kg_get_state(const kg_ctx *ctx, int *base, int *adapter_len, int *lag, int *
  * reading the weights).  With profiling on, a pair of HIP events brackets every kernel launch of
  * the context's stream; elapsed times are summed when a call synchronises.  Classes: 0 = the
  * weight-streaming projections of the decode forwards (all linear layers and the LM head),
- * 1 = attention, 2 = the rest, 3 = the dense (MFMA) projections of the prompt pass.
+ * 1 = attention, 2 = the rest, 3 = the dense (MFMA) projections of the prompt pass, 4 = the fp32
+ * contractions of the adapter's training step.
  * bytes[] is the algorithmic traffic of the launches: weight bytes for class 0, KV bytes read for
- * class 1; for class 3 it holds floating-point operations (2 T N K per launch) instead.
+ * class 1; for classes 3 and 4 it holds floating-point operations (2 M N K per launch) instead.
  * kg_set_profiling resets the sums. */
 typedef struct kg_profile {
-    long long launches[4];
-    double seconds[4];
-    double bytes[4];
+    long long launches[5];
+    double seconds[5];
+    double bytes[5];
 } kg_profile;
 int kg_set_profiling(kg_ctx *ctx, int on);
 int kg_get_profile(kg_ctx *ctx, kg_profile *out);

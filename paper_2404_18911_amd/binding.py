@@ -38,7 +38,7 @@ class kg_stats(ctypes.Structure):
 
 
 class kg_profile(ctypes.Structure):
-    _fields_ = [("launches", ctypes.c_longlong * 4), ("seconds", ctypes.c_double * 4), ("bytes", ctypes.c_double * 4)]
+    _fields_ = [("launches", ctypes.c_longlong * 5), ("seconds", ctypes.c_double * 5), ("bytes", ctypes.c_double * 5)]
 
 
 # every symbol include/kangaroo.h declares

@@ -1356,9 +1356,13 @@ static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, 
     while (S < TR_SPLIT_MAX && tiles * S < 1024 && K / (2 * S) >= 256 && (size_t)2 * S * M * N <= x->tl.part_floats) S *= 2;
     g.k_chunk = ((K + S - 1) / S + 15) / 16 * 16;
     g.part = at<float>(x->tr, x->tl.part);
-    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 127) / 128, (M + 63) / 64, S), dim3(256), 0, x->stream, g);
+    {
+        ProfScope ps(x, 4, 2.0 * M * (double)N * K);
+        hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 127) / 128, (M + 63) / 64, S), dim3(256), 0, x->stream, g);
+    }
     KGCHK(check_launch(x, "train_gemm"));
     if (S > 1) {
+        ProfScope ps(x, 2, 0.0);
         hipLaunchKernelGGL(tr_gemm_reduce_kernel, dim3((unsigned)(((size_t)M * N + 255) / 256)), dim3(256), 0, x->stream,
                            (const float *)g.part, S, M, N, C, ldc, accumulate);
         KGCHK(check_launch(x, "train_gemm_reduce"));
@@ -1405,7 +1409,9 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     }
     const void *head = x->arena + x->head;
     const int hm_nt = x->bf ? 1 : 0, hm_nn = x->bf ? 2 : 0;
+    auto other = [&]() { ProfScope ps(x, 2, 0.0); };      // timing class of everything that is not a contraction
     auto rms = [&](const float *in, const float *g, float *out, float *r) {
+        other();
         hipLaunchKernelGGL(tr_rmsnorm_kernel, dim3(n), dim3(256), 0, x->stream, in, g, d, c.rms_eps, out, r);
         return check_launch(x, "train_rmsnorm");
     };
@@ -1416,9 +1422,11 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     KGCHK(rms(f(t.F), gin, f(t.N), f(t.rin)));
     KGCHK(tr_gemm(x, f(t.N), d, 1, Wqkv, 1, d, 0, f(t.QKV), 3 * d, n, 3 * d, d, 0));
     const size_t nrope = (size_t)n * (d / hd) * (hd / 2) * 2;
+    other();
     hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.QKV), n, d, hd,
                        at<const float2>(x->scr, x->s_rope), 0);
     KGCHK(check_launch(x, "train_rope"));
+    other();
     hipLaunchKernelGGL(tr_attn_fwd_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), n, d, hd, f(t.Pm), f(t.O));
     KGCHK(check_launch(x, "train_attn_fwd"));
     HIPCHK(x, hipMemcpyAsync(f(t.H), f(t.F), (size_t)n * d * 4, hipMemcpyDeviceToDevice, x->stream));
@@ -1426,11 +1434,13 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     KGCHK(rms(f(t.H), glast, f(t.Mm), f(t.rlast)));
     KGCHK(tr_gemm(x, f(t.Mm), d, 1, head, 1, d, hm_nt, f(t.Z), V, n, V, d, 0));
     // Eq. 3 and its gradient with respect to the draft logits
+    other();
     hipLaunchKernelGGL(tr_loss_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.Z), (const float *)f(t.Zt), V, f(t.dZ),
                        f(t.loss));
     KGCHK(check_launch(x, "train_loss"));
     // backward
     KGCHK(tr_gemm(x, f(t.dZ), V, 1, head, d, 1, hm_nn, f(t.dMm), d, n, d, V, 0));
+    other();
     hipLaunchKernelGGL(tr_rmsnorm_bwd_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.H), (const float *)glast,
                        (const float *)f(t.rlast), (const float *)f(t.dMm), d, f(t.dH));
     hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.H),
@@ -1438,23 +1448,28 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     KGCHK(check_launch(x, "train_rmsnorm_bwd"));
     KGCHK(tr_gemm(x, f(t.dH), 1, d, f(t.O), d, 1, 0, G + 3 * dd, d, d, d, n, 0));                 // dWo = dH^T . O
     KGCHK(tr_gemm(x, f(t.dH), d, 1, Wo, d, 1, 0, f(t.dO), d, n, d, d, 0));                        // dO = dH . Wo
+    other();
     hipLaunchKernelGGL(tr_attn_bwd_q_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
                        (const float *)f(t.dO), n, d, hd, f(t.dS), f(t.dQKV));
     hipLaunchKernelGGL(tr_attn_bwd_kv_kernel, dim3(n, H), dim3(128), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
                        (const float *)f(t.dS), (const float *)f(t.dO), n, d, hd, f(t.dQKV));
     KGCHK(check_launch(x, "train_attn_bwd"));
+    other();
     hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.dQKV), n, d, hd,
                        at<const float2>(x->scr, x->s_rope), 1);
     KGCHK(check_launch(x, "train_rope_bwd"));
     KGCHK(tr_gemm(x, f(t.dQKV), 1, 3 * d, f(t.N), d, 1, 0, G, d, 3 * d, d, n, 0));                // dWqkv = dQKV^T . N
     KGCHK(tr_gemm(x, f(t.dQKV), 3 * d, 1, Wqkv, d, 1, 0, f(t.dN), d, n, d, 3 * d, 0));            // dN = dQKV . Wqkv
+    other();
     hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.F),
                        (const float *)f(t.rin), (const float *)f(t.dN), n, d, G + 4 * dd);
     KGCHK(check_launch(x, "train_gain_grad"));
     // loss of the step (before the update), summed over positions in double on the host
     std::vector<float> rows(n);
+    prof_flush(x);
     HIPCHK(x, hipMemcpyAsync(rows.data(), f(t.loss), (size_t)n * 4, hipMemcpyDeviceToHost, x->stream));
     HIPCHK(x, hipStreamSynchronize(x->stream));
+    if (x->profiling) prof_collect(x);
     double L = 0.0;
     for (int i = 0; i < n; i++) L += rows[i];
     *loss = L;
@@ -1462,6 +1477,7 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     x->tr_step++;
     const float c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)x->tr_step));
     const float c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)x->tr_step));
+    other();
     hipLaunchKernelGGL(tr_adamw_kernel, dim3((unsigned)((4 * dd + 255) / 256)), dim3(256), 0, x->stream, P, (const float *)G,
                        f(t.M), f(t.V), 4 * dd, hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, c1, c2);
     hipLaunchKernelGGL(tr_adamw_kernel, dim3((2 * d + 255) / 256), dim3(256), 0, x->stream, P + 4 * dd, (const float *)(G + 4 * dd),
@@ -1483,7 +1499,9 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
         HIPCHK(x, hipMemcpyAsync(x->arena + x->a_gin, gin, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
         HIPCHK(x, hipMemcpyAsync(x->arena + x->a_glast, glast, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
     }
+    prof_flush(x);
     HIPCHK(x, hipStreamSynchronize(x->stream));
+    if (x->profiling) prof_collect(x);
     x->tr_n = n;
     x->phase = Phase::NONE;
     return KG_OK;
