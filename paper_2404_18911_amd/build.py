@@ -8,7 +8,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 LIB = os.path.join(_HERE, "libkangaroo.so")
 SOURCES = [os.path.join(_HERE, "csrc", "kangaroo.hip")]
-HEADERS = [os.path.join(_HERE, "csrc", "kernels.hip.h"), os.path.join(_ROOT, "include", "kangaroo.h")]
+HEADERS = [os.path.join(_HERE, "csrc", "kernels.hip.h"), os.path.join(_HERE, "csrc", "train.hip.h"),
+           os.path.join(_ROOT, "include", "kangaroo.h")]
 
 
 def stale() -> bool:

@@ -47,6 +47,7 @@ struct kg_ctx {
     bool kvbf; int kvesz;    // KV cache element type
     int KSd, KSf;            // k-steps (32 features) of d_model and d_ffn
     int n_pages, logP;
+    int n_cus = 256;         // compute units of the device (read at kg_bind)
     // arena layout
     std::vector<LayerW> lw;
     size_t a_qkv, a_wo, a_gin, a_glast, head, embed, gfinal, arena_bytes;
@@ -402,10 +403,15 @@ int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T
     const int nb = (T + KG_ROWS - 1) / KG_ROWS;
     // two weight tiles per multiplying wave where that still leaves enough workgroups for the device
     const int tw = a.NT >= 512 ? 2 : 1;
-    a.gx = (nb + PF_CBW - 1) / PF_CBW; a.gy = (a.NT + 8 * tw - 1) / (8 * tw);
+    a.gy = (a.NT + 8 * tw - 1) / (8 * tw);
+    // row groups of 8 blocks; of 4 where 8 would give fewer workgroups than the device has compute units
+    int cbw = PF_CBW;
+    if (tw == 1 && ((nb + PF_CBW - 1) / PF_CBW) * a.gy < x->n_cus && nb > 4) cbw = 4;
+    a.gx = (nb + cbw - 1) / cbw;
     const int groups = a.gx * 8 * ((a.gy + 7) / 8);
     ProfScope ps(x, 3, 2.0 * T * (double)N * K);
     if (tw == 2) hipLaunchKernelGGL(gemm_prefill_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e);
+    else if (cbw == 4) hipLaunchKernelGGL(gemm_prefill_kernel_tw1_cb4, dim3(groups), dim3(768), 0, x->stream, a, e);
     else hipLaunchKernelGGL(gemm_prefill_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e);
     return check_launch(x, "prompt projection");
 }
@@ -806,6 +812,11 @@ int kg_bind(kg_ctx *x, void *weights_dev, size_t weight_bytes, void *kv_dev, siz
     }
     x->bound = true;
     x->tr = nullptr;
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            x->n_cus = cus;
+    }
     std::fill(x->loaded.begin(), x->loaded.end(), 0);
     for (int k = KG_A_WQ; k < KG_N_TENSOR_KINDS; k++)       // adapter tensors this architecture does not have
         if (!adapter_has(x, k)) x->loaded[tensor_slot(x, k, -1)] = 1;

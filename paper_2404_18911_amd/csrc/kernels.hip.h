@@ -361,13 +361,13 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__
 // in gemv_bf16_kernel: per output tile the k-steps are split into the same 8 ranges, each range is
 // accumulated in order by MFMA, hi and lo are folded, and the 8 range sums are added in order.
 // A prefilled cache is therefore bit-identical to one written token by token.
-//   A workgroup handles a group of PF_CBW row blocks (64 rows) and a group of 8 * TW weight tiles.
+//   A workgroup handles a group of CBW row blocks (CBW = 8: 64 rows) and a group of 8 * TW weight tiles.
 //   It has 12 waves: waves 8..11 only move data, waves 0..7 only multiply.  The movers bring the
 //   weight tiles and the activation tiles of a stage (PF_KC k-steps) straight from memory into LDS
 //   (global_load_lds: no registers in between), two stages ahead of the multiplication, into a ring
 //   of PF_NB stage buffers, and wait with explicit counts for the stage that is due; the
 //   multipliers read operands from LDS only, so they never wait on memory.  Wave w of the
-//   multipliers owns TW weight tiles and TW * PF_CBW accumulators: every activation tile read from
+//   multipliers owns TW weight tiles and TW * CBW accumulators: every activation tile read from
 //   LDS feeds TW MFMAs.  Activation tiles sit in LDS in MFMA lane order (lane l fetches the piece it
 //   will use), so a read touches 64 consecutive 16-byte pieces, free of bank conflicts.  Rows
 //   beyond the last one of a block are not masked: an MFMA column only depends on its own column of
@@ -417,28 +417,28 @@ __device__ __forceinline__ PfStage pf_stage_at(int r, int k, int KS)
     return PfStage{8, 0, 0};
 }
 
-template <int PF_TW>
+template <int PF_TW, int CBW>
 __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
 {
     constexpr int NTW = 8 * PF_TW;                         // weight tiles of the workgroup
     __shared__ u32x4_t As[PF_NB][PF_KC][NTW][64];
-    __shared__ u32x4_t Bs[PF_NB][PF_KC][PF_CBW][64];
-    __shared__ float scs[PF_CBW][KG_ROWS];
+    __shared__ u32x4_t Bs[PF_NB][PF_KC][CBW][64];
+    __shared__ float scs[CBW][KG_ROWS];
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const bool mover = wave >= 8;
     const int nb = (a.T + 7) >> 3;
     const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
     const int gyi = (jj / a.gx) * 8 + xcd;
     if (gyi >= a.gy) return;
-    const int b0 = (jj % a.gx) * PF_CBW;
-    const int nbw = min(PF_CBW, nb - b0);
+    const int b0 = (jj % a.gx) * CBW;
+    const int nbw = min(CBW, nb - b0);
     const int rt0 = (gyi * 8 + (wave & 7)) * PF_TW;
     const int KS = a.KS;
 
     // RMS scales of this block group's rows: wave w serves row block w; all partial sums of its 8
     // rows are fetched at once, then every row is reduced exactly as in decoding (lane sums in index
     // order, then the same butterfly)
-    static_assert(PF_CBW <= 8, "one wave per row block");
+    static_assert(CBW <= 8, "one wave per row block");
     if (wave < nbw) {
         const Epi eb = pf_block_epi(e, a, b0 + wave);
         float pv[KG_ROWS][8];
@@ -467,7 +467,7 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
     // are folded between stages only).  Per stage the movers issue a fixed number of tile loads
     // (pieces beyond the stage's end, beyond the last weight tile or the last row block read a valid
     // address again; nobody uses them), so the explicit wait counts below are exact.
-    constexpr int TL = PF_KC * (NTW + PF_CBW);             // tile loads of a stage
+    constexpr int TL = PF_KC * (NTW + CBW);             // tile loads of a stage
     constexpr int LPW = TL / 4;                            // ... per mover wave
     static_assert(TL % 4 == 0, "tile loads spread evenly over the 4 mover waves");
     bool valid[PF_TW];
@@ -485,7 +485,7 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
                 const u32x4_t *src = a.W + ((size_t)rt * KS + k0 + (kk < n ? kk : 0)) * 64 + lane;
                 __builtin_amdgcn_global_load_lds(src, &As[buf][kk][tile][0], 16, 0, 0);
             } else {
-                const int jb = j - PF_KC * NTW, kk = jb / PF_CBW, cb = jb % PF_CBW;
+                const int jb = j - PF_KC * NTW, kk = jb / CBW, cb = jb % CBW;
                 const u32x4_t *src = a.act + (size_t)(b0 + min(cb, nbw - 1)) * a.act_blk + (size_t)(k0 + (kk < n ? kk : 0)) * 64 + bsl;
                 __builtin_amdgcn_global_load_lds(src, &Bs[buf][kk][cb][0], 16, 0, 0);
             }
@@ -524,11 +524,11 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // no load may still be on its way into LDS at the end
         return;
     }
-    f32x4_t acc[PF_TW][PF_CBW], tot[PF_TW][PF_CBW];
+    f32x4_t acc[PF_TW][CBW], tot[PF_TW][CBW];
 #pragma unroll
     for (int tw = 0; tw < PF_TW; tw++)
 #pragma unroll
-        for (int cb = 0; cb < PF_CBW; cb++) {
+        for (int cb = 0; cb < CBW; cb++) {
             acc[tw][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             tot[tw][cb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         }
@@ -542,7 +542,7 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
 #pragma unroll
                 for (int tw = 0; tw < PF_TW; tw++) av[tw] = __builtin_bit_cast(bf16x8_t, As[buf][kk][wave * PF_TW + tw][lane]);
 #pragma unroll
-                for (int cb = 0; cb < PF_CBW; cb++) {
+                for (int cb = 0; cb < CBW; cb++) {
                     const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, Bs[buf][kk][cb][lane]);
 #pragma unroll
                     for (int tw = 0; tw < PF_TW; tw++)
@@ -553,7 +553,7 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
 #pragma unroll
             for (int tw = 0; tw < PF_TW; tw++)
 #pragma unroll
-                for (int cb = 0; cb < PF_CBW; cb++) {
+                for (int cb = 0; cb < CBW; cb++) {
 #pragma unroll
                     for (int r = 0; r < 4; r++) {
                         float v = acc[tw][cb][r] + __shfl_xor(acc[tw][cb][r], 8);
@@ -579,16 +579,16 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
         const int n0 = rt * 16 + 4 * g4;
         const bool okl = valid[tw] && col < KG_ROWS;
         if (e.kind == EPI_RESID) {
-            float4 rv[PF_CBW];
+            float4 rv[CBW];
             const float4 gv = (okl && e.gain) ? *(const float4 *)(e.gain + n0) : make_float4(1.f, 1.f, 1.f, 1.f);
 #pragma unroll
-            for (int cb = 0; cb < PF_CBW; cb++) {
+            for (int cb = 0; cb < CBW; cb++) {
                 const int M = min(KG_ROWS, a.T - 8 * (b0 + cb));
                 rv[cb] = (okl && cb < nbw && col < M) ? *(const float4 *)(e.res + ((size_t)8 * (b0 + cb) + col) * e.N + n0)
                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
             }
 #pragma unroll
-            for (int cb = 0; cb < PF_CBW; cb++) {
+            for (int cb = 0; cb < CBW; cb++) {
                 if (cb >= nbw) break;
                 const Epi eb = pf_block_epi(e, a, b0 + cb);
                 const bool live = okl && col < eb.M;
@@ -629,7 +629,7 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
             }
         } else {
 #pragma unroll
-            for (int cb = 0; cb < PF_CBW; cb++) {
+            for (int cb = 0; cb < CBW; cb++) {
                 if (cb >= nbw) break;
                 const Epi eb = pf_block_epi(e, a, b0 + cb);
                 if (!(okl && col < eb.M)) continue;
@@ -656,9 +656,11 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
     }
 }
 
-// one or two weight tiles per multiplying wave
-__global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1(PfArgs a, Epi e) { gemm_prefill_body<1>(a, e); }
-__global__ __launch_bounds__(768) void gemm_prefill_kernel_tw2(PfArgs a, Epi e) { gemm_prefill_body<2>(a, e); }
+// one or two weight tiles per multiplying wave; row groups of PF_CBW blocks, or of 4 for projections
+// with so few weight tiles that groups of 8 would leave compute units without a workgroup
+__global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1(PfArgs a, Epi e) { gemm_prefill_body<1, PF_CBW>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill_kernel_tw2(PfArgs a, Epi e) { gemm_prefill_body<2, PF_CBW>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1_cb4(PfArgs a, Epi e) { gemm_prefill_body<1, 4>(a, e); }
 
 // ---------------------------------------------------------------------------------------------
 // Rows -> activation for the first projection of a stack: x[m] = E[tok[m]] (emb != null) or the
