@@ -323,3 +323,22 @@ def test_adapter_tensors_outside_the_architecture_are_rejected():
         kg.load_tensor(I.KIND_A_HEAD, -1, np.zeros((shape.vocab, d), dtype=np.float32))
     assert ei.value.code == B.KG_EINVAL
     kg.close()
+
+
+@pytest.mark.parametrize("adapter", [1, 2, 3])
+def test_sampling_mode_with_the_other_adapter_architectures(adapter):
+    """Rejection sampling reads the draft distribution q from the draft logits: with an own head, a
+    whole block or two linear maps as the adapter, every draw / accept / reject is still the oracle's."""
+    from tests import parity as P
+    shape = dataclasses.replace(I.SHAPES["toy"], adapter=adapter)
+    hs, temp = 25.0, 0.8
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=hs)
+    U = I.gen_uniforms(128, seed=3)
+    kg = P.load_model(shape, W, 120, gamma_max=6, kv_page_tokens=32)
+    tol = tol_for(shape, hs)
+    fol = P.Follow(tol)
+    out, rounds = P.follow_kangaroo_sampling(kg, _oracle(shape, W, 120), I.gen_prompt(shape.vocab, 16), 40, 5, 0.4, temp, U,
+                                             fol, 2 * tol / temp)
+    assert any(n == k for k, n in rounds) and any(n < k for k, n in rounds)
+    assert fol.exceptions <= 2
+    kg.close()
