@@ -206,7 +206,7 @@ def run_train(args):
     from paper_2404_18911_amd import inputs as I
     threads = min(16, os.cpu_count() or 8)
     shape = I.SHAPES[args.shape]
-    T = min(args.prompt, 256)
+    T = min(args.prompt, 2048)
     kg = B.Kangaroo(shape, T + 16, gamma_max=6, kv_page_tokens=128)
     keep = {}
     for k, layer, a in I.iter_weights(shape, seed=1, alpha=args.alpha, threads=threads, head_scale=args.train_head_scale):

@@ -232,7 +232,7 @@ void kg_destroy(kg_ctx *ctx);
  * rounded to the cache's type.  The LM head and the target model are never updated.
  *
  *   kg_train_workspace_bytes / kg_train_bind: device workspace (256-byte aligned, BORROWED until
- *     kg_destroy) for sequences of up to max_tokens tokens (<= 256 and <= max_seq); bind copies the
+ *     kg_destroy) for sequences of up to max_tokens tokens (<= 2048 and <= max_seq); bind copies the
  *     loaded adapter tensors into the master copies and zeroes the AdamW moments and step count.
  *     All tensors must be loaded first; kg_bind, or loading an adapter tensor afterwards, drops the
  *     training binding (kg_train_step then returns KG_ESTATE until kg_train_bind is called again).

@@ -1289,17 +1289,16 @@ static void train_layout(const kg_ctx *x, int Tm, TrainLayout &t)
     t.Pm = take(H * T * T); t.dS = take(H * T * T);
     t.dMm = take(T * d); t.dH = take(T * d); t.dO = take(T * d); t.dQKV = take(T * 3 * d); t.dN = take(T * d);
     t.loss = take(T);
-    t.part_floats = (size_t)TR_SPLIT_MAX * T * 3 * d;      // partial results of split contractions ([slices][T][<= 3d])
+    // partial results of split contractions ([slices][T][<= 3d]); long sequences have enough output tiles unsplit
+    t.part_floats = (size_t)TR_SPLIT_MAX * std::min<size_t>(T, 256) * 3 * d;
     t.part = take(t.part_floats);
     t.bytes = o;
 }
 
 static int train_tokens_max(const kg_ctx *x)
 {
-    // one pass of the prompt kernels (bf16 weights), one thread per key in the attention kernels
-    int m = std::min(256, x->c.max_seq);
-    if (x->pf_rows > 0) m = std::min(m, x->pf_rows);
-    return m;
+    // a row of attention weights is kept in LDS by the training attention kernels
+    return std::min(TR_T_MAX, x->c.max_seq);
 }
 
 int kg_train_workspace_bytes(const kg_ctx *x, int max_tokens, size_t *bytes)
@@ -1404,10 +1403,13 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     // frozen target model on the whole sequence: early features F and last hidden states X
     if (x->pf_rows > 0) {
         HIPCHK(x, hipMemcpyAsync(x->scr + x->s_ptok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, x->stream));
-        const float *x_last = nullptr;
-        KGCHK(pf_rows_pass(x, 0, n, &x_last));
-        HIPCHK(x, hipMemcpyAsync(f(t.F), x->scr + x->s_pF, (size_t)n * d * 4, hipMemcpyDeviceToDevice, x->stream));
-        HIPCHK(x, hipMemcpyAsync(f(t.X), x_last, (size_t)n * d * 4, hipMemcpyDeviceToDevice, x->stream));
+        for (int pos0 = 0; pos0 < n; pos0 += x->pf_rows) {
+            const int T = std::min(x->pf_rows, n - pos0);
+            const float *x_last = nullptr;
+            KGCHK(pf_rows_pass(x, pos0, T, &x_last));
+            HIPCHK(x, hipMemcpyAsync(f(t.F) + (size_t)pos0 * d, x->scr + x->s_pF, (size_t)T * d * 4, hipMemcpyDeviceToDevice, x->stream));
+            HIPCHK(x, hipMemcpyAsync(f(t.X) + (size_t)pos0 * d, x_last, (size_t)T * d * 4, hipMemcpyDeviceToDevice, x->stream));
+        }
     } else {
         for (int pos0 = 0; pos0 < n; pos0 += KG_ROWS) {
             const int M = std::min(KG_ROWS, n - pos0);

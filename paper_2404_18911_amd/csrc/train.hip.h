@@ -290,30 +290,42 @@ __global__ void tr_rope_kernel(float *qkv, int T, int d, int hd, const float2 *t
     v[p + half] = b * cs.x + a * cs.y;
 }
 
+#define TR_T_MAX 2048   // longest training sequence: the attention kernels keep one row of T weights in LDS
+
 // Causal attention of one (query row i, head h) over keys 0..i: P[h][i][j] = softmax_j(q_i.k_j / sqrt(hd)),
-// o[i][h] = sum_j P_ij v_j.  grid (T, H), block 256; T <= 256 so thread j owns key j.
+// o[i][h] = sum_j P_ij v_j.  grid (T, H), block 256; thread t owns keys t, t + 256, ...
 __global__ __launch_bounds__(256) void tr_attn_fwd_kernel(const float *qkv, int T, int d, int hd, float *P, float *o)
 {
     __shared__ float red[4];
     __shared__ float qs[128];
-    __shared__ float ps[256];
+    __shared__ float ps[TR_T_MAX];
     const int i = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
     const float *q = qkv + (size_t)i * 3 * d + (size_t)h * hd;
     if (t < hd) qs[t] = q[t];
     __syncthreads();
-    float s = -INFINITY;
-    if (t <= i) {
-        const float *k = qkv + (size_t)t * 3 * d + d + (size_t)h * hd;
+    const float inv = 1.f / sqrtf((float)hd);
+    float mx = -INFINITY;
+    for (int j = t; j <= i; j += 256) {
+        const float *k = qkv + (size_t)j * 3 * d + d + (size_t)h * hd;
         float a = 0.f;
         for (int c = 0; c < hd; c++) a += qs[c] * k[c];
-        s = a / sqrtf((float)hd);
+        a *= inv;
+        ps[j] = a;
+        mx = fmaxf(mx, a);
     }
-    const float mx = tr_block_max(s, red);
-    const float e = t <= i ? expf(s - mx) : 0.f;
-    const float sum = tr_block_sum(e, red);
-    const float p = e / sum;
-    ps[t] = p;
-    if (t < T) P[((size_t)h * T + i) * T + t] = p;
+    mx = tr_block_max(mx, red);
+    float sum = 0.f;
+    for (int j = t; j <= i; j += 256) {
+        const float e = expf(ps[j] - mx);
+        ps[j] = e;
+        sum += e;
+    }
+    sum = tr_block_sum(sum, red);
+    for (int j = t; j < T; j += 256) {
+        const float p = j <= i ? ps[j] / sum : 0.f;
+        if (j <= i) ps[j] = p;
+        P[((size_t)h * T + i) * T + j] = p;
+    }
     __syncthreads();
     if (t < hd) {
         float a = 0.f;
@@ -329,20 +341,25 @@ __global__ __launch_bounds__(256) void tr_attn_bwd_q_kernel(const float *qkv, co
 {
     __shared__ float red[4];
     __shared__ float dos[128];
-    __shared__ float dss[256];
+    __shared__ float dss[TR_T_MAX];
     const int i = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
     if (t < hd) dos[t] = dout[(size_t)i * d + (size_t)h * hd + t];
     __syncthreads();
-    float dA = 0.f, p = 0.f;
-    if (t <= i) {
-        const float *v = qkv + (size_t)t * 3 * d + 2 * d + (size_t)h * hd;
+    const float *Pr = P + ((size_t)h * T + i) * T;
+    float D = 0.f;
+    for (int j = t; j <= i; j += 256) {
+        const float *v = qkv + (size_t)j * 3 * d + 2 * d + (size_t)h * hd;
+        float dA = 0.f;
         for (int c = 0; c < hd; c++) dA += dos[c] * v[c];
-        p = P[((size_t)h * T + i) * T + t];
+        dss[j] = dA;
+        D += dA * Pr[j];
     }
-    const float D = tr_block_sum(dA * p, red);
-    const float ds = p * (dA - D);
-    dss[t] = ds;
-    if (t < T) dS[((size_t)h * T + i) * T + t] = ds;
+    D = tr_block_sum(D, red);
+    for (int j = t; j < T; j += 256) {
+        const float ds = j <= i ? Pr[j] * (dss[j] - D) : 0.f;
+        if (j <= i) dss[j] = ds;
+        dS[((size_t)h * T + i) * T + j] = ds;
+    }
     __syncthreads();
     if (t < hd) {
         float a = 0.f;

@@ -133,10 +133,10 @@ def test_stats_metrics_match_eq1_eq2_golden_values():
 def test_training_workspace_size_is_host_logic():
     """kg_train_workspace_bytes needs no device: sizes scale with the token capacity, hold the four
     fp32 parameter-sized blocks (master copy, gradient, two AdamW moments), and the capacity is
-    limited to 256 tokens and to max_seq."""
+    limited to 2048 tokens and to max_seq."""
     L = B.lib()
     shape = I.SHAPES["7b"]
-    rc, h = _create(shape, max_seq=520, kv_page_tokens=128)
+    rc, h = _create(shape, max_seq=4100, kv_page_tokens=128)
     assert rc == B.KG_OK
     nb = ctypes.c_size_t()
     sizes = []
@@ -145,7 +145,8 @@ def test_training_workspace_size_is_host_logic():
         sizes.append(nb.value)
     nparam = 4 * shape.d_model ** 2 + 2 * shape.d_model
     assert sizes[0] >= 4 * nparam * 4 and sizes[0] < sizes[1] < sizes[2] < 4 * nparam * 4 + (1 << 29)
-    for bad in (0, -3, 257):
+    assert L.kg_train_workspace_bytes(h, 2048, ctypes.byref(nb)) == B.KG_OK and nb.value < 6 * (1 << 30)
+    for bad in (0, -3, 2049):
         assert L.kg_train_workspace_bytes(h, bad, ctypes.byref(nb)) == B.KG_EINVAL
     assert L.kg_train_workspace_bytes(h, 8, None) == B.KG_EINVAL
     L.kg_destroy(h)

@@ -39,7 +39,9 @@ def _oracle_params(block, d):
     return {k: v.astype(np.float64).copy() for k, v in B.split_param_block(block, d).items()}
 
 
-@pytest.mark.parametrize("name,n,hs", [("toy", 19, 1.0), ("toy_bf16", 19, 1.0), ("small_bf16", 37, 4.0), ("toy", 1, 1.0)])
+@pytest.mark.parametrize("name,n,hs", [("toy", 19, 1.0), ("toy_bf16", 19, 1.0), ("small_bf16", 37, 4.0), ("toy", 1, 1.0),
+                                       ("toy_bf16", 300, 1.0),      # two passes of the prompt kernels, keys beyond one block of threads
+                                       ("toy", 261, 1.0)])
 def test_training_step_follows_the_oracle(name, n, hs):
     from oracle import adapter_training as TR
     from paper_2404_18911_amd import binding as B
@@ -53,8 +55,9 @@ def test_training_step_follows_the_oracle(name, n, hs):
         W[(k, -1)] = g if shape.dtype == "f32" else I.f32_to_bf16_bits(g)
     head = W[(I.KIND_LM_HEAD, -1)]
     head64 = (I.bf16_bits_to_f32(head) if shape.dtype == "bf16" else head).astype(np.float64)
-    kg = P.load_model(shape, W, 96, kv_page_tokens=32)
-    kg.train_bind(40)
+    max_seq = max(96, n + 24)
+    kg = P.load_model(shape, W, max_seq, kv_page_tokens=32)
+    kg.train_bind(max(40, n + 3))
     toks = I.gen_prompt(shape.vocab, n, seed=5)
     lr, wd = 1e-3, 0.05
     M64 = V64 = None
@@ -104,7 +107,7 @@ def test_training_step_follows_the_oracle(name, n, hs):
         from oracle import kangaroo_oracle as O
         shape2 = shape
         fol = P.Follow(1e-4 * max(1.0, hs) if shape.dtype == "f32" else 2e-2 * max(1.0, hs))
-        P.follow_kangaroo(kg, O.OracleModel(shape2, W2, 96), I.gen_prompt(shape.vocab, 12), 16, 4, 0.0, fol)
+        P.follow_kangaroo(kg, O.OracleModel(shape2, W2, max_seq), I.gen_prompt(shape.vocab, 12), 16, 4, 0.0, fol)
     kg.close()
 
 
