@@ -331,6 +331,8 @@ def main():
     ap.add_argument("--new", type=int, default=256)
     ap.add_argument("--alpha", type=float, default=0.05)
     ap.add_argument("--alpha2", type=float, default=0.2)
+    ap.add_argument("--sample", action="store_true", help="temperature sampling with speculative rejection sampling instead of greedy")
+    ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="eta x gamma and exit-layer sweeps on a sharpened head (not the benchmark line)")
@@ -377,7 +379,10 @@ def main():
             W[(kind, layer)] = a
     log(f"[bench] weights generated and loaded in {time.time() - t0:.1f}s")
     prompt = I.gen_prompt(shape.vocab, args.prompt)
-    p, _ = B.make_params(eta=eta, gamma=gamma)
+    # --sample: speculative rejection sampling (and plain sampling for the baseline) with seeded uniforms
+    U = I.gen_uniforms(args.prompt + args.new + gamma + 8, seed=3) if args.sample else None
+    mode = 1 if args.sample else 0
+    p, _keep_u = B.make_params(mode=mode, temperature=args.temperature, eta=eta, gamma=gamma, uniforms=U)
 
     def sync():
         torch.cuda.synchronize()
@@ -425,7 +430,8 @@ def main():
         "ms_per_step": 1e3 * wall / args.steps, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if shape.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"configs[1]: Vicuna-7B-shaped decoder, bf16, exit l={shape.exit_layer}, "
-                               f"alpha={args.alpha}, eta={eta}, gamma_max={gamma}, greedy, prompt {args.prompt} "
+                               f"alpha={args.alpha}, eta={eta}, gamma_max={gamma}, "
+                               f"{'rejection sampling T=' + str(args.temperature) if args.sample else 'greedy'}, prompt {args.prompt} "
                                f"random ids, generate {args.new}" if args.shape == "7b" else args.shape,
                    "alpha": args.alpha, "eta": eta, "gamma": gamma, "prompt": args.prompt, "new": args.new,
                    "rounds": rounds, "drafted": stats.drafted, "accepted": stats.accepted,
@@ -474,16 +480,17 @@ def main():
         res["speedup_vs_plain"] = value / res["plain_tokens_per_s"]
         res["plain_forward_GBs"] = fb["plain"] * st_p.plain_steps / st_p.t_total_s / 1e9
         res["per_forward"]["plain"] = fwd(fb["plain"], st_p.t_total_s / st_p.plain_steps)
-        res["lossless_on_gpu"] = bool(out_p == out)
+        res["lossless_on_gpu"] = None if args.sample else bool(out_p == out)   # sampled streams differ by construction
         # whole-forward bandwidth of the Kangaroo loop: bytes of all forwards / decode wall-clock
         kang_bytes = stats.draft_steps * fb["draft"] + stats.verify_calls * (fb["shallow"] + fb["verify"])
         res["kangaroo_forward_GBs"] = kang_bytes / stats.t_total_s / 1e9
         res["kangaroo_forward_frac_of_peak"] = res["kangaroo_forward_GBs"] / HBM_PEAK_GBS
-        p0, _ = B.make_params(eta=0.0, gamma=gamma)
+        p0, _keep_u0 = B.make_params(mode=mode, temperature=args.temperature, eta=0.0, gamma=gamma, uniforms=U)
         out0, st0 = kg.generate(p0, prompt, args.new)
         res["eta0"] = {"tokens_per_s": (len(out0) - 1) / st0.t_total_s, "rounds": st0.rounds,
                        "acceptance_rate": st0.accepted / max(1, st0.drafted),
-                       "compression_rate": (args.new - 1) / st0.rounds, "lossless_on_gpu": bool(out0 == out_p)}
+                       "compression_rate": (args.new - 1) / st0.rounds,
+                       "lossless_on_gpu": None if args.sample else bool(out0 == out_p)}
         if args.alpha2 > 0:
             reload_alpha(kg, shape, args.alpha2, threads)
             out2, st2 = kg.generate(p, prompt, args.new)
