@@ -238,6 +238,11 @@ void kg_destroy(kg_ctx *ctx);
  *     training binding (kg_train_step then returns KG_ESTATE until kg_train_bind is called again).
  *   kg_train_step: tokens_host[n], 1 <= n <= max_tokens.  *loss is Eq. 3 for the parameters before
  *     the update.  Drops the sequence state of the context (a new kg_prefill is needed to decode).
+ *     It is kg_train_accumulate on a fresh gradient followed by kg_train_apply.
+ *   kg_train_accumulate / kg_train_apply: a step over several sequences (Eq. 3 sums over all their
+ *     positions): each accumulate call adds one sequence's gradient to the gradient block and returns
+ *     that sequence's loss; apply performs the AdamW update with the accumulated gradient, refreshes
+ *     the decode tensors and clears the count (KG_ESTATE when nothing was accumulated).
  *   kg_train_read: copy one buffer of the last step to the host (tests and monitoring):
  *     early features [n][d_model], target / draft logits [n][vocab], the gradient block and the
  *     parameter block (Wq, Wk, Wv, Wo row-major [d][d] each, then g_in, g_last: 4 d^2 + 2 d floats),
@@ -253,6 +258,8 @@ typedef enum kg_train_buffer {
 int kg_train_workspace_bytes(const kg_ctx *ctx, int max_tokens, size_t *bytes);
 int kg_train_bind(kg_ctx *ctx, void *work_dev, size_t bytes, int max_tokens);
 int kg_train_step(kg_ctx *ctx, const kg_train_params *hp, const int32_t *tokens_host, int n, double *loss);
+int kg_train_accumulate(kg_ctx *ctx, const int32_t *tokens_host, int n, double *loss);
+int kg_train_apply(kg_ctx *ctx, const kg_train_params *hp);
 int kg_train_read(kg_ctx *ctx, int what, float *host_out, size_t n_floats);
 
 /*

@@ -52,7 +52,7 @@ SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "k
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
            "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_stream_read",
-           "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_read", "kg_op_gemm_f32"]
+           "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_accumulate", "kg_train_apply", "kg_train_read", "kg_op_gemm_f32"]
 
 _lib = None
 
@@ -103,6 +103,8 @@ def lib() -> ctypes.CDLL:
     L.kg_train_workspace_bytes.argtypes = [vp, ctypes.c_int, szp]
     L.kg_train_bind.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int]
     L.kg_train_step.argtypes = [vp, ctypes.POINTER(kg_train_params), ip, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    L.kg_train_accumulate.argtypes = [vp, ip, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    L.kg_train_apply.argtypes = [vp, ctypes.POINTER(kg_train_params)]
     L.kg_train_read.argtypes = [vp, ctypes.c_int, fp, ctypes.c_size_t]
     L.kg_op_gemm_f32.argtypes = [vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long,
                                  ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
@@ -301,6 +303,16 @@ class Kangaroo:
         self._chk(self.L.kg_train_step(self.h, ctypes.byref(hp), a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(a),
                                        ctypes.byref(loss)))
         return loss.value
+
+    def train_accumulate(self, tokens: Sequence[int]) -> float:
+        a = np.ascontiguousarray(tokens, dtype=np.int32)
+        loss = ctypes.c_double()
+        self._chk(self.L.kg_train_accumulate(self.h, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(a), ctypes.byref(loss)))
+        return loss.value
+
+    def train_apply(self, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01) -> None:
+        hp = kg_train_params(lr, beta1, beta2, eps, weight_decay)
+        self._chk(self.L.kg_train_apply(self.h, ctypes.byref(hp)))
 
     def train_read(self, what: int, n_tokens: int = 0) -> np.ndarray:
         d, V = self.shape.d_model, self.shape.vocab

@@ -85,7 +85,7 @@ struct kg_ctx {
     // adapter training (kg_train_*)
     char *tr = nullptr;
     TrainLayout tl;
-    int tr_T = 0, tr_n = 0;
+    int tr_T = 0, tr_n = 0, tr_pending = 0;   // capacity, tokens of the last sequence, sequences in the gradient block
     long long tr_step = 0;
     // optional per-launch timing
     bool profiling = false;
@@ -1320,7 +1320,7 @@ int kg_train_bind(kg_ctx *x, void *work_dev, size_t bytes, int max_tokens)
     TrainLayout t;
     train_layout(x, max_tokens, t);
     if (bytes < t.bytes) return fail(x, KG_ENOSPC, "training workspace too small: need %zu bytes", t.bytes);
-    x->tr = (char *)work_dev; x->tl = t; x->tr_T = max_tokens; x->tr_n = 0; x->tr_step = 0;
+    x->tr = (char *)work_dev; x->tl = t; x->tr_T = max_tokens; x->tr_n = 0; x->tr_step = 0; x->tr_pending = 0;
     const int d = x->c.d_model;
     float *P = at<float>(x->tr, t.P);
     const size_t dd = (size_t)d * d;
@@ -1380,16 +1380,23 @@ static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, 
     return KG_OK;
 }
 
-int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, int n, double *loss)
+static int check_train_params(kg_ctx *x, const kg_train_params *hp)
 {
-    KGCHK(check_ready(x));
-    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
-    if (!hp || !tokens || !loss) return fail(x, KG_EINVAL, "NULL argument");
-    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
+    if (!hp) return fail(x, KG_EINVAL, "NULL argument");
     if (!(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->eps > 0.f) ||
         !(hp->weight_decay >= 0.f))
         return fail(x, KG_EINVAL, "bad AdamW parameters");
+    return KG_OK;
+}
+
+int kg_train_accumulate(kg_ctx *x, const int32_t *tokens, int n, double *loss)
+{
+    KGCHK(check_ready(x));
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    if (!tokens || !loss) return fail(x, KG_EINVAL, "NULL argument");
+    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
     const kg_config &c = x->c;
+    const int acc = x->tr_pending > 0 ? 1 : 0;     // add to the gradient block, or start it
     for (int i = 0; i < n; i++)
         if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(x, KG_EINVAL, "token %d out of range", tokens[i]);
     const int d = c.d_model, V = c.vocab, H = c.n_heads, hd = c.head_dim;
@@ -1457,9 +1464,9 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     hipLaunchKernelGGL(tr_rmsnorm_bwd_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.H), (const float *)glast,
                        (const float *)f(t.rlast), (const float *)f(t.dMm), d, f(t.dH));
     hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.H),
-                       (const float *)f(t.rlast), (const float *)f(t.dMm), n, d, G + 4 * dd + d);
+                       (const float *)f(t.rlast), (const float *)f(t.dMm), n, d, G + 4 * dd + d, acc);
     KGCHK(check_launch(x, "train_rmsnorm_bwd"));
-    KGCHK(tr_gemm(x, f(t.dH), 1, d, f(t.O), d, 1, 0, G + 3 * dd, d, d, d, n, 0));                 // dWo = dH^T . O
+    KGCHK(tr_gemm(x, f(t.dH), 1, d, f(t.O), d, 1, 0, G + 3 * dd, d, d, d, n, acc));               // dWo (+)= dH^T . O
     KGCHK(tr_gemm(x, f(t.dH), d, 1, Wo, d, 1, 0, f(t.dO), d, n, d, d, 0));                        // dO = dH . Wo
     other();
     hipLaunchKernelGGL(tr_attn_bwd_q_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
@@ -1471,11 +1478,11 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.dQKV), n, d, hd,
                        at<const float2>(x->scr, x->s_rope), 1);
     KGCHK(check_launch(x, "train_rope_bwd"));
-    KGCHK(tr_gemm(x, f(t.dQKV), 1, 3 * d, f(t.N), d, 1, 0, G, d, 3 * d, d, n, 0));                // dWqkv = dQKV^T . N
+    KGCHK(tr_gemm(x, f(t.dQKV), 1, 3 * d, f(t.N), d, 1, 0, G, d, 3 * d, d, n, acc));              // dWqkv (+)= dQKV^T . N
     KGCHK(tr_gemm(x, f(t.dQKV), 3 * d, 1, Wqkv, d, 1, 0, f(t.dN), d, n, d, 3 * d, 0));            // dN = dQKV . Wqkv
     other();
     hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.F),
-                       (const float *)f(t.rin), (const float *)f(t.dN), n, d, G + 4 * dd);
+                       (const float *)f(t.rin), (const float *)f(t.dN), n, d, G + 4 * dd, acc);
     KGCHK(check_launch(x, "train_gain_grad"));
     // loss of the step (before the update), summed over positions in double on the host
     std::vector<float> rows(n);
@@ -1486,6 +1493,25 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     double L = 0.0;
     for (int i = 0; i < n; i++) L += rows[i];
     *loss = L;
+    x->tr_n = n;
+    x->tr_pending++;
+    x->phase = Phase::NONE;
+    return KG_OK;
+}
+
+int kg_train_apply(kg_ctx *x, const kg_train_params *hp)
+{
+    KGCHK(check_ready(x));
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    KGCHK(check_train_params(x, hp));
+    if (x->tr_pending < 1) return fail(x, KG_ESTATE, "no gradient has been accumulated");
+    const int d = x->c.d_model;
+    const size_t dd = (size_t)d * d;
+    const TrainLayout &t = x->tl;
+    auto f = [&](size_t off) { return at<float>(x->tr, off); };
+    auto other = [&]() { ProfScope ps(x, 2, 0.0); };
+    float *P = f(t.P), *G = f(t.G);
+    float *Wqkv = P, *Wo = P + 3 * dd, *gin = P + 4 * dd, *glast = P + 4 * dd + d;
     // AdamW on the fp32 master copies, then the inference copies in the arena are refreshed
     x->tr_step++;
     const float c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)x->tr_step));
@@ -1515,9 +1541,18 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
     prof_flush(x);
     HIPCHK(x, hipStreamSynchronize(x->stream));
     if (x->profiling) prof_collect(x);
-    x->tr_n = n;
+    x->tr_pending = 0;
     x->phase = Phase::NONE;
     return KG_OK;
+}
+
+int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, int n, double *loss)
+{
+    if (!x) return KG_EINVAL;
+    KGCHK(check_train_params(x, hp));
+    x->tr_pending = 0;                          // a step starts from its own gradient
+    KGCHK(kg_train_accumulate(x, tokens, n, loss));
+    return kg_train_apply(x, hp);
 }
 
 int kg_train_read(kg_ctx *x, int what, float *host_out, size_t n_floats)

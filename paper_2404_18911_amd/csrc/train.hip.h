@@ -261,14 +261,14 @@ __global__ __launch_bounds__(256) void tr_rmsnorm_bwd_kernel(const float *x, con
     for (int i = threadIdx.x; i < d; i += 256) dx[(size_t)row * d + i] = rr * dyr[i] * g[i] - xr[i] * r3 * s;
 }
 
-// dg[j] = sum_t dy[t][j] * x[t][j] * r[t]; one thread per column
-__global__ void tr_gain_grad_kernel(const float *x, const float *r, const float *dy, int T, int d, float *dg)
+// dg[j] (+)= sum_t dy[t][j] * x[t][j] * r[t]; one thread per column
+__global__ void tr_gain_grad_kernel(const float *x, const float *r, const float *dy, int T, int d, float *dg, int accumulate)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= d) return;
     float s = 0.f;
     for (int t = 0; t < T; t++) s += dy[(size_t)t * d + j] * x[(size_t)t * d + j] * r[t];
-    dg[j] = s;
+    dg[j] = accumulate ? dg[j] + s : s;
 }
 
 // rotary embedding of the q and k parts of QKV [T][3d] at positions 0..T-1, pairs (i, i + hd/2);

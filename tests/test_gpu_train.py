@@ -163,3 +163,49 @@ def test_training_call_order_and_argument_errors():
         kg.train_bind(8)
     assert ei.value.code == B.KG_EINVAL
     kg.close()
+
+
+def test_gradient_accumulation_over_two_sequences():
+    """Eq. 3 sums over every position it is given: two sequences accumulated into one gradient block
+    give the sum of their gradients, and one AdamW update with that sum."""
+    from oracle import adapter_training as TR
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["toy_bf16"]
+    d, H = shape.d_model, shape.n_heads
+    W = I.gen_weights(shape, seed=2, alpha=0.5, head_scale=2.0)
+    head64 = I.bf16_bits_to_f32(W[(I.KIND_LM_HEAD, -1)]).astype(np.float64)
+    kg = P.load_model(shape, W, 96, kv_page_tokens=32)
+    kg.train_bind(48)
+    with pytest.raises(B.KangarooError) as ei:
+        kg.train_apply(1e-3)
+    assert ei.value.code == B.KG_ESTATE
+    Po = _oracle_params(kg.train_read(B.TRAIN_PARAMETERS), d)
+    total = None
+    losses = []
+    for seed, n in ((21, 33), (22, 17)):
+        toks = I.gen_prompt(shape.vocab, n, seed=seed)
+        losses.append(kg.train_accumulate(toks))
+        F = kg.train_read(B.TRAIN_FEATURES, n).astype(np.float64)
+        Zt = kg.train_read(B.TRAIN_TARGET_LOGITS, n).astype(np.float64)
+        want, Go, _ = TR.loss_and_grads(Po, F, Zt, head64, H, shape.rms_eps, shape.rope_theta)
+        assert abs(losses[-1] - want) <= 1e-5 * abs(want)
+        total = Go if total is None else {k: total[k] + Go[k] for k in TR.PARAMS}
+    G = B.split_param_block(kg.train_read(B.TRAIN_GRADIENTS), d)
+    for k in TR.PARAMS:
+        assert np.abs(G[k] - total[k]).max() <= 2e-4 * np.abs(total[k]).max(), k
+    lr = 1e-3
+    kg.train_apply(lr, weight_decay=0.0)
+    after = B.split_param_block(kg.train_read(B.TRAIN_PARAMETERS), d)
+    M64, V64 = TR.zeros_like_params(Po), TR.zeros_like_params(Po)
+    TR.adamw_step(Po, total, M64, V64, 1, lr, weight_decay=0.0)
+    for k in TR.PARAMS:
+        dg = np.abs(G[k] - total[k])
+        allowed = lr * (4.0 * dg / (np.abs(total[k]) + 1e-8) + 1e-3) + 2.0 ** -22 * np.abs(Po[k])
+        assert np.all(np.abs(after[k] - Po[k]) <= allowed), k
+    # the next step starts from its own gradient
+    toks = I.gen_prompt(shape.vocab, 9, seed=23)
+    kg.train_step(toks, lr)
+    G2 = B.split_param_block(kg.train_read(B.TRAIN_GRADIENTS), d)
+    assert np.abs(G2["wo"]).max() < 0.9 * np.abs(G["wo"]).max() or not np.allclose(G2["wo"], G["wo"])
+    kg.close()
