@@ -88,3 +88,28 @@ def test_config5_long_context_sampling_run():
     print(f"config 5 short follow: max logit err {fol.max_logit_err:.3e}, decisions the oracle takes otherwise "
           f"{fol.exceptions}/{fol.decisions}")
     kg.close()
+
+
+@pytest.mark.parametrize("adapter", [1, 2, 3])
+def test_adapter_architectures_at_7b_width(adapter):
+    """Table 2's other adapters at the 7B layer shape (d 4096, FFN 11008, vocab 32000) on a
+    four-layer model, so that the oracle can follow: own LM head, a whole decoder block
+    (22016-row gate/up projection), two 4096 x 4096 maps with the SiLU epilogue.  Fixed-step drafting
+    (eta = 0) so that several draft steps and a lagging catch-up occur; then losslessness on the GPU."""
+    from oracle import kangaroo_oracle as O
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = dataclasses.replace(I.with_layers(I.SHAPES["7b"], 4), exit_layer=2, adapter=adapter)
+    W = I.gen_weights(shape, seed=1, alpha=0.05, threads=16, own_head_copy=(adapter != 1))
+    prompt = I.gen_prompt(shape.vocab, 20)
+    kg = P.load_model(shape, W, 128, gamma_max=6, kv_page_tokens=128)
+    fol = P.Follow(2e-2)
+    out, rounds = P.follow_kangaroo(kg, O.OracleModel(shape, W, 64), prompt, 9, 3, 0.0, fol)
+    assert all(k == 3 for k, _ in rounds)
+    print(f"7b-wide adapter {adapter}: max logit err {fol.max_logit_err:.3e}, near-tie exceptions {fol.exceptions}/{fol.decisions}, "
+          f"rounds {rounds}")
+    p, _ = B.make_params(eta=0.0, gamma=3)
+    plain, _ = kg.decode_plain(p, prompt, 48)
+    gen, _ = kg.generate(p, prompt, 48)
+    assert gen == plain
+    kg.close()
