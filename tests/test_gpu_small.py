@@ -342,3 +342,21 @@ def test_sampling_mode_with_the_other_adapter_architectures(adapter):
     assert any(n == k for k, n in rounds) and any(n < k for k, n in rounds)
     assert fol.exceptions <= 2
     kg.close()
+
+
+def test_the_largest_page_count_follows_oracle():
+    """128 KV pages, the most a context may have (16-token pages, 2040 tokens of context): the
+    cross-page merge at its widest, prompt rows in several passes, then draft-and-verify rounds that
+    cross page boundaries, against the oracle."""
+    from tests import parity as P
+    shape = I.SHAPES["toy_bf16"]
+    hs = 25.0
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=hs)
+    n_prompt = 2000
+    kg = P.load_model(shape, W, 2048, gamma_max=6, kv_page_tokens=16)
+    fol = P.Follow(tol_for(shape, hs))
+    out, rounds = P.follow_kangaroo(kg, _oracle(shape, W, 2048), I.gen_prompt(shape.vocab, n_prompt), 24, 6, 0.6, fol)
+    print(f"128 pages: max logit err {fol.max_logit_err:.3e}, near-tie exceptions {fol.exceptions}/{fol.decisions}, rounds {rounds}")
+    base, _, _, _ = kg.state()
+    assert base >= n_prompt + 23
+    kg.close()
