@@ -113,3 +113,30 @@ def test_adapter_architectures_at_7b_width(adapter):
     gen, _ = kg.generate(p, prompt, 48)
     assert gen == plain
     kg.close()
+
+
+def test_7b_at_the_maximum_context():
+    """The largest context the library takes (128 pages of 128 tokens = 16384 positions) at the 7B
+    shape: a 16320-token prompt, then greedy Kangaroo (eta 0.6 and fixed-step) against plain
+    decoding on the GPU, token for token; the round bookkeeping must hold as at any size."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["7b"]
+    W = I.gen_weights(shape, seed=1, alpha=0.1, threads=16)
+    n_prompt, n_new = 16384 - 64, 48
+    kg = P.load_model(shape, W, 16384, gamma_max=6, kv_page_tokens=128)
+    prompt = I.gen_prompt(shape.vocab, n_prompt)
+    p, _ = B.make_params(eta=0.6, gamma=6)
+    plain, stp = kg.decode_plain(p, prompt, n_new)
+    out, st = kg.generate(p, prompt, n_new)
+    assert out == plain and len(out) == n_new
+    assert sum(s * c for s, c in enumerate(st.s_hist)) == n_new - 1
+    p0, _ = B.make_params(eta=0.0, gamma=6)
+    out0, st0 = kg.generate(p0, prompt, n_new)
+    assert out0 == plain and st0.draft_steps == 6 * st0.rounds
+    print(f"16K context: plain {(n_new - 1) / stp.t_total_s:.1f} tok/s, kangaroo {(n_new - 1) / st.t_total_s:.1f} tok/s")
+    # one more token than fits is refused, not written out of bounds
+    with pytest.raises(B.KangarooError) as ei:
+        kg.generate(p, I.gen_prompt(shape.vocab, 16384 - 8), 48)
+    assert ei.value.code == B.KG_ENOSPC
+    kg.close()
