@@ -240,7 +240,7 @@ class Kangaroo:
     # -- whole loops
     def _loop(self, fn, params, prompt, max_new):
         a = np.ascontiguousarray(prompt, dtype=np.int32)
-        out = np.empty(max_new, dtype=np.int32)
+        out = np.empty(max(1, max_new), dtype=np.int32)
         n = ctypes.c_int32()
         st = kg_stats()
         self._chk(fn(self.h, ctypes.byref(params), a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(a), max_new,

@@ -360,3 +360,68 @@ def test_the_largest_page_count_follows_oracle():
     base, _, _, _ = kg.state()
     assert base >= n_prompt + 23
     kg.close()
+
+
+@pytest.mark.parametrize("n_prompt", [1, 15, 16, 17])
+def test_degenerate_prompts_follow_oracle(n_prompt):
+    """A one-token prompt, and prompts that end just before, on and just after a KV page boundary
+    (16-token pages), so that the first rounds append across the boundary."""
+    from tests import parity as P
+    shape = I.SHAPES["toy"]
+    hs = 25.0
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=hs)
+    kg = P.load_model(shape, W, 64, gamma_max=6, kv_page_tokens=16)
+    fol = P.Follow(tol_for(shape, hs))
+    out, rounds = P.follow_kangaroo(kg, _oracle(shape, W, 64), I.gen_prompt(shape.vocab, n_prompt, seed=n_prompt), 20, 6, 0.6, fol)
+    assert len(out) >= 20 and fol.exceptions == 0
+    kg.close()
+
+
+def test_short_requests_and_call_order_on_a_bound_context():
+    """max_new of 1 (the prefill token alone), 2, and a count that cuts the last round short: the
+    stream is the prefix of a longer request and the counters agree.  Then the call-order errors of
+    a live sequence: they change nothing, the sequence continues to the same tokens."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["toy_bf16"]
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=25.0)
+    prompt = I.gen_prompt(shape.vocab, 11)
+    kg = P.load_model(shape, W, 96, gamma_max=6, kv_page_tokens=16)
+    p, _ = B.make_params(eta=0.0, gamma=6)             # seven tokens per fully accepted round
+    ref, _ = kg.generate(p, prompt, 40)
+    for n in (1, 2, 3, 9, 23):
+        out, st = kg.generate(p, prompt, n)
+        assert out == ref[:n] and st.emitted == n
+        assert sum(s * c for s, c in enumerate(st.s_hist)) == n - 1
+        assert st.rounds == (0 if n == 1 else st.verify_calls)
+        plain, stp = kg.decode_plain(p, prompt, n)
+        assert plain == ref[:n] and stp.plain_steps == n - 1
+    for bad in (0, -1):
+        with pytest.raises(B.KangarooError) as ei:
+            kg.generate(p, prompt, bad)
+        assert ei.value.code == B.KG_EINVAL
+    # call order on a live sequence
+    def expect_state(fn):
+        before = kg.state()
+        with pytest.raises(B.KangarooError) as ei:
+            fn()
+        assert ei.value.code == B.KG_ESTATE and kg.state() == before
+    t = [kg.prefill(p, prompt)]
+    expect_state(lambda: kg.verify(p))                  # no draft yet
+    expect_state(lambda: kg.accept(p))
+    while not kg.draft_step(p)[2]:
+        pass
+    expect_state(lambda: kg.draft_step(p))              # drafting has ended for this round
+    expect_state(lambda: kg.accept(p))                  # not verified yet
+    kg.verify(p)
+    expect_state(lambda: kg.verify(p))
+    expect_state(lambda: kg.draft_step(p))
+    t += kg.accept(p)
+    expect_state(lambda: kg.accept(p))
+    while len(t) < 20:
+        while not kg.draft_step(p)[2]:
+            pass
+        kg.verify(p)
+        t += kg.accept(p)
+    assert t[:20] == ref[:20]
+    kg.close()
