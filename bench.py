@@ -186,9 +186,21 @@ def run_adapters(args):
         toks0, st0 = kg.generate(p0, prompt, args.new)
         row["eta0"] = {"tokens_per_s": (len(toks0) - 1) / st0.t_total_s, "compression_rate": (args.new - 1) / st0.rounds,
                        "draft_step_us": 1e6 * st0.t_draft_s / st0.draft_steps, "lossless_on_gpu": bool(toks0 == plain)}
+        # one training step of this adapter (Eq. 3 + AdamW) on the prompt: what its parameters cost to fit
+        import torch
+        kg.train_bind(min(args.prompt, 256))
+        kg.train_step(prompt[:256], 1e-5)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for _ in range(2):
+            kg.train_step(prompt[:256], 1e-5)
+        torch.cuda.synchronize()
+        row["train_step_ms"] = 1e3 * (time.time() - t0) / 2
+        row["train_workspace_GB"] = kg.train_bytes / 1e9
         out["rows"].append(row)
         log(f"[adapters] {names[kind]}: {row['adapter_params_M']:.0f}M, draft step {row['draft_step_us']:.0f} us "
-            f"({fb['draft'] / 1e9:.3f} GB), {row['tokens_per_s']:.1f} tok/s, acceptance {row['acceptance_rate']:.2f}")
+            f"({fb['draft'] / 1e9:.3f} GB), {row['tokens_per_s']:.1f} tok/s, acceptance {row['acceptance_rate']:.2f}, "
+            f"training step {row['train_step_ms']:.1f} ms")
         kg.close()
         del kg
     print(json.dumps(out), flush=True)

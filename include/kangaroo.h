@@ -221,15 +221,16 @@ void kg_destroy(kg_ctx *ctx);
 
 /*
  * Training of the adapter (Section 3.1 "Training Loss", Eq. 3; Section 4.1: AdamW), one step per
- * call on one token sequence, for adapter architecture KG_ADAPTER_ATTN.  With the target model
+ * call on one token sequence, for every adapter architecture of kg_adapter_kind.  With the target model
  * frozen, the adapter is run over all n positions at once (causal attention over the earlier early
  * features) and
  *     loss = sum_t sum_v  - p_t[v] log q_t[v],   p_t = softmax(target logits at t), q_t = softmax(draft logits at t)
- * is differentiated with respect to Wq, Wk, Wv, Wo, g_in, g_last; AdamW (decoupled weight decay on
- * the four matrices, none on the gains, bias-corrected moments) updates fp32 master copies, and the
+ * is differentiated with respect to every tensor of the adapter (Wq, Wk, Wv, Wo, g_in, g_last for
+ * the paper's; an own LM head, the feed-forward tensors or the two linear maps for the others); AdamW
+ * (decoupled weight decay on the matrices, none on the gains, bias-corrected moments) updates fp32 master copies, and the
  * adapter tensors the decode calls use are refreshed from them (matrices and gains re-rounded to bf16
  * where the model is bf16: decoding runs what a checkpoint in the model's type would hold).  All training arithmetic is fp32; keys and values inside the training graph are not
- * rounded to the cache's type.  The LM head and the target model are never updated.
+ * rounded to the cache's type.  The target model and its LM head are never updated.
  *
  *   kg_train_workspace_bytes / kg_train_bind: device workspace (256-byte aligned, BORROWED until
  *     kg_destroy) for sequences of up to max_tokens tokens (<= 2048 and <= max_seq); bind copies the
@@ -245,8 +246,10 @@ void kg_destroy(kg_ctx *ctx);
  *     the decode tensors and clears the count (KG_ESTATE when nothing was accumulated).
  *   kg_train_read: copy one buffer of the last step to the host (tests and monitoring):
  *     early features [n][d_model], target / draft logits [n][vocab], the gradient block and the
- *     parameter block (Wq, Wk, Wv, Wo row-major [d][d] each, then g_in, g_last: 4 d^2 + 2 d floats),
- *     per-position losses [n].  n_floats must be the buffer's exact size.
+ *     parameter block, per-position losses [n].  n_floats must be the buffer's exact size.  A block
+ *     holds the adapter's tensors row-major in this order: KG_ADAPTER_ATTN Wq, Wk, Wv, Wo, g_in, g_last
+ *     (4 d^2 + 2 d floats); KG_ADAPTER_ATTN_HEAD the same, then the head [vocab][d]; KG_ADAPTER_LAYER the
+ *     same, then g_post, Wg, Wu [d_ffn][d], Wd [d][d_ffn]; KG_ADAPTER_MLP W1, W2, g_in, g_last, head.
  */
 typedef struct kg_train_params {
     float lr, beta1, beta2, eps, weight_decay;

@@ -314,20 +314,52 @@ class Kangaroo:
         hp = kg_train_params(lr, beta1, beta2, eps, weight_decay)
         self._chk(self.L.kg_train_apply(self.h, ctypes.byref(hp)))
 
+    def train_param_count(self) -> int:
+        return sum(int(np.prod(shp)) for _, shp in train_param_shapes(self.shape))
+
     def train_read(self, what: int, n_tokens: int = 0) -> np.ndarray:
         d, V = self.shape.d_model, self.shape.vocab
+        npar = self.train_param_count()
         shape = {TRAIN_FEATURES: (n_tokens, d), TRAIN_TARGET_LOGITS: (n_tokens, V), TRAIN_DRAFT_LOGITS: (n_tokens, V),
-                 TRAIN_GRADIENTS: (4 * d * d + 2 * d,), TRAIN_PARAMETERS: (4 * d * d + 2 * d,), TRAIN_ROW_LOSSES: (n_tokens,)}[what]
+                 TRAIN_GRADIENTS: (npar,), TRAIN_PARAMETERS: (npar,), TRAIN_ROW_LOSSES: (n_tokens,)}[what]
         out = np.empty(shape, dtype=np.float32)
         self._chk(self.L.kg_train_read(self.h, what, out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), out.size))
         return out
 
 
-def split_param_block(block: np.ndarray, d: int) -> dict:
-    """Views of a parameter (or gradient) block: Wq, Wk, Wv, Wo [d][d], g_in, g_last [d]."""
-    dd = d * d
-    return {"wq": block[0:dd].reshape(d, d), "wk": block[dd:2 * dd].reshape(d, d), "wv": block[2 * dd:3 * dd].reshape(d, d),
-            "wo": block[3 * dd:4 * dd].reshape(d, d), "g_in": block[4 * dd:4 * dd + d], "g_last": block[4 * dd + d:4 * dd + 2 * d]}
+def train_param_shapes(shape) -> list:
+    """(name, shape) of the tensors of a parameter (or gradient) block, in block order, for the
+    shape's adapter architecture: 0 / 1 attention (wq, wk, wv, wo, g_in, g_last [, head]),
+    2 decoder block (.., g_post, wg, wu, wd), 3 two linear maps (w1, w2, g_in, g_last, head)."""
+    d, f, V = shape.d_model, shape.d_ffn, shape.vocab
+    kind = getattr(shape, "adapter", 0)
+    if kind == 3:
+        out = [("w1", (d, d)), ("w2", (d, d))]
+    else:
+        out = [("wq", (d, d)), ("wk", (d, d)), ("wv", (d, d)), ("wo", (d, d))]
+    out += [("g_in", (d,)), ("g_last", (d,))]
+    if kind in (1, 3):
+        out.append(("head", (V, d)))
+    if kind == 2:
+        out += [("g_post", (d,)), ("wg", (f, d)), ("wu", (f, d)), ("wd", (d, f))]
+    return out
+
+
+def split_param_block(block: np.ndarray, shape_or_d) -> dict:
+    """Views of a parameter (or gradient) block by tensor name.  Takes the model shape (or, for the
+    paper's adapter, just d_model)."""
+    if isinstance(shape_or_d, int):
+        d = shape_or_d
+        spec = [("wq", (d, d)), ("wk", (d, d)), ("wv", (d, d)), ("wo", (d, d)), ("g_in", (d,)), ("g_last", (d,))]
+    else:
+        spec = train_param_shapes(shape_or_d)
+    out, o = {}, 0
+    for name, shp in spec:
+        n = int(np.prod(shp))
+        out[name] = block[o:o + n].reshape(shp)
+        o += n
+    assert o == block.size, (o, block.size)
+    return out
 
 
 def op_gemm_f32(A: np.ndarray, B: np.ndarray, C0: Optional[np.ndarray] = None, device: str = "cuda:0") -> np.ndarray:

@@ -27,13 +27,15 @@ struct LayerW {
 struct Phase { enum { NONE = 0, READY = 1, DRAFTING = 2, VERIFIED = 3, PLAIN = 4 }; };
 
 // Workspace of the adapter's training step (byte offsets).  The parameter block, and likewise the
-// gradient block and the two AdamW moment blocks, holds Wq, Wk, Wv (stacked, [3d][d]), Wo [d][d],
-// g_in [d], g_last [d] as fp32.
+// gradient block and the two AdamW moment blocks, holds the adapter's tensors as fp32 in the order
+// of train_tensors(): for the paper's adapter Wq, Wk, Wv (stacked, [3d][d]), Wo [d][d], g_in [d],
+// g_last [d].
 struct TrainLayout {
     size_t nparam = 0;
     size_t P = 0, G = 0, M = 0, V = 0;
     size_t F = 0, X = 0, Xn = 0, N = 0, QKV = 0, O = 0, H = 0, Mm = 0, Z = 0, Zt = 0, dZ = 0, rin = 0, rlast = 0, rfin = 0,
-           Pm = 0, dS = 0, dMm = 0, dH = 0, dO = 0, dQKV = 0, dN = 0, loss = 0, part = 0;
+           Pm = 0, dS = 0, dMm = 0, dH = 0, dO = 0, dQKV = 0, dN = 0, loss = 0, part = 0,
+           H1 = 0, Bn = 0, dB = 0, rpost = 0, Gt = 0, Ut = 0, Act = 0, dAct = 0, dGt = 0, dUt = 0;
     size_t part_floats = 0;
     size_t bytes = 0;
 };
@@ -1275,12 +1277,54 @@ void kg_destroy(kg_ctx *x)
 
 constexpr int TR_SPLIT_MAX = 8;
 
+// One trainable tensor: where it sits in a parameter-sized block (float offset), its shape, whether
+// AdamW decays it, and where and how the decode calls keep it in the arena.
+struct TrTensor {
+    size_t off;
+    int rows, cols;          // gains: rows = 1
+    bool decay;
+    size_t arena_off;
+    int arena_rows;          // rows of the arena matrix the tensor is part of (tile count of the packed form)
+    int row_off, mode;       // map_row() arguments
+};
+
+// the trainable tensors of the context's adapter architecture, in the order of the parameter block
+static std::vector<TrTensor> train_tensors(const kg_ctx *x)
+{
+    const int d = x->c.d_model, f = x->c.d_ffn, V = x->c.vocab;
+    std::vector<TrTensor> v;
+    size_t o = 0;
+    auto mat = [&](int rows, int cols, size_t aoff, int arows, int row_off, int mode) {
+        v.push_back({o, rows, cols, true, aoff, arows, row_off, mode});
+        o += (size_t)rows * cols;
+    };
+    auto gain = [&](size_t aoff) { v.push_back({o, 1, d, false, aoff, 1, 0, 0}); o += d; };
+    if (x->akind == KG_ADAPTER_MLP) {
+        mat(d, d, x->a_w1, d, 0, 0);
+        mat(d, d, x->a_w2, d, 0, 0);
+    } else {
+        mat(3 * d, d, x->a_qkv, 3 * d, 0, 0);
+        mat(d, d, x->a_wo, d, 0, 0);
+    }
+    gain(x->a_gin);
+    gain(x->a_glast);
+    if (x->akind == KG_ADAPTER_ATTN_HEAD || x->akind == KG_ADAPTER_MLP) mat(V, d, x->a_head, V, 0, 0);
+    if (x->akind == KG_ADAPTER_LAYER) {
+        gain(x->a_gpost);
+        mat(f, d, x->a_gu, 2 * f, 0, 1);
+        mat(f, d, x->a_gu, 2 * f, 0, 2);
+        mat(d, f, x->a_wd, d, 0, 0);
+    }
+    return v;
+}
+
 static void train_layout(const kg_ctx *x, int Tm, TrainLayout &t)
 {
-    const size_t d = x->c.d_model, V = x->c.vocab, H = x->c.n_heads, T = Tm;
+    const size_t d = x->c.d_model, f = x->c.d_ffn, V = x->c.vocab, H = x->c.n_heads, T = Tm;
     size_t o = 0;
     auto take = [&](size_t floats) { size_t r = o; o += up(floats * 4); return r; };
-    t.nparam = 4 * d * d + 2 * d;
+    const std::vector<TrTensor> ts = train_tensors(x);
+    t.nparam = ts.back().off + (size_t)ts.back().rows * ts.back().cols;
     t.P = take(t.nparam); t.G = take(t.nparam); t.M = take(t.nparam); t.V = take(t.nparam);
     t.F = take(T * d); t.X = take(T * d); t.Xn = take(T * d); t.N = take(T * d); t.QKV = take(T * 3 * d);
     t.O = take(T * d); t.H = take(T * d); t.Mm = take(T * d);
@@ -1289,6 +1333,10 @@ static void train_layout(const kg_ctx *x, int Tm, TrainLayout &t)
     t.Pm = take(H * T * T); t.dS = take(H * T * T);
     t.dMm = take(T * d); t.dH = take(T * d); t.dO = take(T * d); t.dQKV = take(T * 3 * d); t.dN = take(T * d);
     t.loss = take(T);
+    if (x->akind == KG_ADAPTER_LAYER) {          // the block's feed-forward half
+        t.H1 = take(T * d); t.Bn = take(T * d); t.dB = take(T * d); t.rpost = take(T);
+        t.Gt = take(T * f); t.Ut = take(T * f); t.Act = take(T * f); t.dAct = take(T * f); t.dGt = take(T * f); t.dUt = take(T * f);
+    }
     // partial results of split contractions ([slices][T][<= 3d]); long sequences have enough output tiles unsplit
     t.part_floats = (size_t)TR_SPLIT_MAX * std::min<size_t>(T, 256) * 3 * d;
     t.part = take(t.part_floats);
@@ -1311,31 +1359,42 @@ int kg_train_workspace_bytes(const kg_ctx *x, int max_tokens, size_t *bytes)
     return KG_OK;
 }
 
+// master copy <-> the arena's form of one tensor (gains: fp32 in both; rounded to the storage type on the way back)
+static int train_sync_tensor(kg_ctx *x, const TrTensor &tt, float *master, bool to_arena)
+{
+    const size_t n = (size_t)tt.rows * tt.cols;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (tt.rows == 1) {
+        float *ar = at<float>(x->arena, tt.arena_off);
+        if (!to_arena) HIPCHK(x, hipMemcpyAsync(master, ar, n * 4, hipMemcpyDeviceToDevice, x->stream));
+        else if (x->bf) hipLaunchKernelGGL(tr_round_bf16_kernel, dim3(blocks), dim3(256), 0, x->stream, (const float *)master, (int)n, ar);
+        else HIPCHK(x, hipMemcpyAsync(ar, master, n * 4, hipMemcpyDeviceToDevice, x->stream));
+    } else if (x->bf) {
+        const int KS = (tt.cols + 31) / 32;
+        if (to_arena)
+            hipLaunchKernelGGL(tr_pack_bf16_kernel, dim3(blocks), dim3(256), 0, x->stream, (const float *)master, tt.rows, tt.cols, KS,
+                               tt.row_off, tt.mode, at<uint16_t>(x->arena, tt.arena_off));
+        else
+            hipLaunchKernelGGL(tr_unpack_bf16_kernel, dim3(blocks), dim3(256), 0, x->stream, at<const uint16_t>(x->arena, tt.arena_off),
+                               tt.rows, tt.cols, KS, tt.row_off, tt.mode, master);
+    } else {
+        hipLaunchKernelGGL(tr_copy_rows_f32_kernel, dim3(blocks), dim3(256), 0, x->stream, master, at<float>(x->arena, tt.arena_off),
+                           tt.rows, tt.cols, tt.row_off, tt.mode, to_arena ? 1 : 0);
+    }
+    return check_launch(x, "train_sync_tensor");
+}
+
 int kg_train_bind(kg_ctx *x, void *work_dev, size_t bytes, int max_tokens)
 {
     KGCHK(check_ready(x));
-    if (x->akind != KG_ADAPTER_ATTN) return fail(x, KG_EINVAL, "training is implemented for adapter architecture 0 (Table 2 row Kangaroo)");
     if (max_tokens < 1 || max_tokens > train_tokens_max(x)) return fail(x, KG_EINVAL, "max_tokens %d outside 1..%d", max_tokens, train_tokens_max(x));
     if (!work_dev || ((uintptr_t)work_dev & (ALIGN - 1))) return fail(x, KG_EINVAL, "training workspace must be %zu-byte aligned", ALIGN);
     TrainLayout t;
     train_layout(x, max_tokens, t);
     if (bytes < t.bytes) return fail(x, KG_ENOSPC, "training workspace too small: need %zu bytes", t.bytes);
     x->tr = (char *)work_dev; x->tl = t; x->tr_T = max_tokens; x->tr_n = 0; x->tr_step = 0; x->tr_pending = 0;
-    const int d = x->c.d_model;
     float *P = at<float>(x->tr, t.P);
-    const size_t dd = (size_t)d * d;
-    if (x->bf) {
-        hipLaunchKernelGGL(tr_unpack_bf16_kernel, dim3((unsigned)((3 * dd + 255) / 256)), dim3(256), 0, x->stream,
-                           at<const uint16_t>(x->arena, x->a_qkv), 3 * d, d, x->KSd, P);
-        hipLaunchKernelGGL(tr_unpack_bf16_kernel, dim3((unsigned)((dd + 255) / 256)), dim3(256), 0, x->stream,
-                           at<const uint16_t>(x->arena, x->a_wo), d, d, x->KSd, P + 3 * dd);
-        KGCHK(check_launch(x, "train_unpack"));
-    } else {
-        HIPCHK(x, hipMemcpyAsync(P, x->arena + x->a_qkv, 3 * dd * 4, hipMemcpyDeviceToDevice, x->stream));
-        HIPCHK(x, hipMemcpyAsync(P + 3 * dd, x->arena + x->a_wo, dd * 4, hipMemcpyDeviceToDevice, x->stream));
-    }
-    HIPCHK(x, hipMemcpyAsync(P + 4 * dd, x->arena + x->a_gin, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
-    HIPCHK(x, hipMemcpyAsync(P + 4 * dd + d, x->arena + x->a_glast, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
+    for (const TrTensor &tt : train_tensors(x)) KGCHK(train_sync_tensor(x, tt, P + tt.off, false));
     HIPCHK(x, hipMemsetAsync(x->tr + t.M, 0, t.nparam * 4, x->stream));
     HIPCHK(x, hipMemsetAsync(x->tr + t.V, 0, t.nparam * 4, x->stream));
     HIPCHK(x, hipMemsetAsync(x->tr + t.G, 0, t.nparam * 4, x->stream));
@@ -1380,6 +1439,23 @@ static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, 
     return KG_OK;
 }
 
+// The three products with one weight matrix W [N][K] (row-major fp32 master copy) that the chain rule needs:
+//   forward   Y[T][N] (+)= X[T][K] . W^T
+//   backward  dX[T][K] (+)= dY[T][N] . W
+//   gradient  dW[N][K] (+)= dY^T . X
+static int tr_fwd(kg_ctx *x, const float *X, const float *W, float *Y, int T, int N, int K, int acc)
+{
+    return tr_gemm(x, X, K, 1, W, 1, K, 0, Y, N, T, N, K, acc);
+}
+static int tr_bwd(kg_ctx *x, const float *dY, const float *W, float *dX, int T, int N, int K, int acc)
+{
+    return tr_gemm(x, dY, N, 1, W, K, 1, 0, dX, K, T, K, N, acc);
+}
+static int tr_wgrad(kg_ctx *x, const float *dY, const float *X, float *dW, int T, int N, int K, int acc)
+{
+    return tr_gemm(x, dY, 1, N, X, K, 1, 0, dW, K, N, K, T, acc);
+}
+
 static int check_train_params(kg_ctx *x, const kg_train_params *hp)
 {
     if (!hp) return fail(x, KG_EINVAL, "NULL argument");
@@ -1399,12 +1475,17 @@ int kg_train_accumulate(kg_ctx *x, const int32_t *tokens, int n, double *loss)
     const int acc = x->tr_pending > 0 ? 1 : 0;     // add to the gradient block, or start it
     for (int i = 0; i < n; i++)
         if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(x, KG_EINVAL, "token %d out of range", tokens[i]);
-    const int d = c.d_model, V = c.vocab, H = c.n_heads, hd = c.head_dim;
-    const size_t dd = (size_t)d * d;
+    const int d = c.d_model, ff = c.d_ffn, V = c.vocab, H = c.n_heads, hd = c.head_dim;
+    const int kind = x->akind;
+    const bool own_head = kind == KG_ADAPTER_ATTN_HEAD || kind == KG_ADAPTER_MLP;
     const TrainLayout &t = x->tl;
     auto f = [&](size_t off) { return at<float>(x->tr, off); };
+    // the tensors of the parameter block and of the gradient block, by role
     float *P = f(t.P), *G = f(t.G);
-    float *Wqkv = P, *Wo = P + 3 * dd, *gin = P + 4 * dd, *glast = P + 4 * dd + d;
+    const std::vector<TrTensor> ts = train_tensors(x);
+    size_t o_a = ts[0].off, o_b = ts[1].off, o_gin = ts[2].off, o_glast = ts[3].off, o_head = 0, o_gpost = 0, o_wg = 0, o_wu = 0, o_wd = 0;
+    if (own_head) o_head = ts[4].off;
+    if (kind == KG_ADAPTER_LAYER) { o_gpost = ts[4].off; o_wg = ts[5].off; o_wu = ts[6].off; o_wd = ts[7].off; }
     KGCHK(kg_reset(x));
 
     // frozen target model on the whole sequence: early features F and last hidden states X
@@ -1435,56 +1516,109 @@ int kg_train_accumulate(kg_ctx *x, const int32_t *tokens, int n, double *loss)
         hipLaunchKernelGGL(tr_rmsnorm_kernel, dim3(n), dim3(256), 0, x->stream, in, g, d, c.rms_eps, out, r);
         return check_launch(x, "train_rmsnorm");
     };
+    auto rms_bwd = [&](const float *in, const float *g, const float *r, const float *dy, float *dx, float *dg) {
+        other();
+        hipLaunchKernelGGL(tr_rmsnorm_bwd_kernel, dim3(n), dim3(256), 0, x->stream, in, g, r, dy, d, dx);
+        hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, in, r, dy, n, d, dg, acc);
+        return check_launch(x, "train_rmsnorm_bwd");
+    };
+    auto ew_blocks = [](size_t cnt) { return dim3((unsigned)((cnt + 255) / 256)); };
+    const size_t nd = (size_t)n * d, nf = (size_t)n * ff;
     // target logits of every position: Zt = RMSNorm(X; g_final) . head^T
     KGCHK(rms(f(t.X), at<const float>(x->arena, x->gfinal), f(t.Xn), f(t.rfin)));
     KGCHK(tr_gemm(x, f(t.Xn), d, 1, head, 1, d, hm_nt, f(t.Zt), V, n, V, d, 0));
-    // adapter forward over all positions
-    KGCHK(rms(f(t.F), gin, f(t.N), f(t.rin)));
-    KGCHK(tr_gemm(x, f(t.N), d, 1, Wqkv, 1, d, 0, f(t.QKV), 3 * d, n, 3 * d, d, 0));
+    // ---- adapter forward over all positions
+    KGCHK(rms(f(t.F), P + o_gin, f(t.N), f(t.rin)));
+    HIPCHK(x, hipMemcpyAsync(f(t.H), f(t.F), nd * 4, hipMemcpyDeviceToDevice, x->stream));
     const size_t nrope = (size_t)n * (d / hd) * (hd / 2) * 2;
-    other();
-    hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.QKV), n, d, hd,
-                       at<const float2>(x->scr, x->s_rope), 0);
-    KGCHK(check_launch(x, "train_rope"));
-    other();
-    hipLaunchKernelGGL(tr_attn_fwd_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), n, d, hd, f(t.Pm), f(t.O));
-    KGCHK(check_launch(x, "train_attn_fwd"));
-    HIPCHK(x, hipMemcpyAsync(f(t.H), f(t.F), (size_t)n * d * 4, hipMemcpyDeviceToDevice, x->stream));
-    KGCHK(tr_gemm(x, f(t.O), d, 1, Wo, 1, d, 0, f(t.H), d, n, d, d, 1));
-    KGCHK(rms(f(t.H), glast, f(t.Mm), f(t.rlast)));
-    KGCHK(tr_gemm(x, f(t.Mm), d, 1, head, 1, d, hm_nt, f(t.Z), V, n, V, d, 0));
+    if (kind == KG_ADAPTER_MLP) {
+        // h = f + W2 . silu(W1 . n): U1 in QKV's first [n][d], S1 in O
+        KGCHK(tr_fwd(x, f(t.N), P + o_a, f(t.QKV), n, d, d, 0));
+        other();
+        hipLaunchKernelGGL(tr_silu_kernel, ew_blocks(nd), dim3(256), 0, x->stream, (const float *)f(t.QKV), nd, f(t.O));
+        KGCHK(check_launch(x, "train_silu"));
+        KGCHK(tr_fwd(x, f(t.O), P + o_b, f(t.H), n, d, d, 1));
+    } else {
+        KGCHK(tr_fwd(x, f(t.N), P + o_a, f(t.QKV), n, 3 * d, d, 0));
+        other();
+        hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.QKV), n, d, hd,
+                           at<const float2>(x->scr, x->s_rope), 0);
+        hipLaunchKernelGGL(tr_attn_fwd_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), n, d, hd, f(t.Pm), f(t.O));
+        KGCHK(check_launch(x, "train_attn_fwd"));
+        KGCHK(tr_fwd(x, f(t.O), P + o_b, f(t.H), n, d, d, 1));
+        if (kind == KG_ADAPTER_LAYER) {
+            // h <- h + Wd (silu(Wg b) * (Wu b)), b = RMSNorm(h; g_post); the attention's output h is kept in H1
+            HIPCHK(x, hipMemcpyAsync(f(t.H1), f(t.H), nd * 4, hipMemcpyDeviceToDevice, x->stream));
+            KGCHK(rms(f(t.H1), P + o_gpost, f(t.Bn), f(t.rpost)));
+            KGCHK(tr_fwd(x, f(t.Bn), P + o_wg, f(t.Gt), n, ff, d, 0));
+            KGCHK(tr_fwd(x, f(t.Bn), P + o_wu, f(t.Ut), n, ff, d, 0));
+            other();
+            hipLaunchKernelGGL(tr_swiglu_kernel, ew_blocks(nf), dim3(256), 0, x->stream, (const float *)f(t.Gt), (const float *)f(t.Ut), nf,
+                               f(t.Act));
+            KGCHK(check_launch(x, "train_swiglu"));
+            KGCHK(tr_fwd(x, f(t.Act), P + o_wd, f(t.H), n, d, ff, 1));
+        }
+    }
+    KGCHK(rms(f(t.H), P + o_glast, f(t.Mm), f(t.rlast)));
+    if (own_head) KGCHK(tr_fwd(x, f(t.Mm), P + o_head, f(t.Z), n, V, d, 0));
+    else KGCHK(tr_gemm(x, f(t.Mm), d, 1, head, 1, d, hm_nt, f(t.Z), V, n, V, d, 0));
     // Eq. 3 and its gradient with respect to the draft logits
     other();
     hipLaunchKernelGGL(tr_loss_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.Z), (const float *)f(t.Zt), V, f(t.dZ),
                        f(t.loss));
     KGCHK(check_launch(x, "train_loss"));
-    // backward
-    KGCHK(tr_gemm(x, f(t.dZ), V, 1, head, d, 1, hm_nn, f(t.dMm), d, n, d, V, 0));
-    other();
-    hipLaunchKernelGGL(tr_rmsnorm_bwd_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.H), (const float *)glast,
-                       (const float *)f(t.rlast), (const float *)f(t.dMm), d, f(t.dH));
-    hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.H),
-                       (const float *)f(t.rlast), (const float *)f(t.dMm), n, d, G + 4 * dd + d, acc);
-    KGCHK(check_launch(x, "train_rmsnorm_bwd"));
-    KGCHK(tr_gemm(x, f(t.dH), 1, d, f(t.O), d, 1, 0, G + 3 * dd, d, d, d, n, acc));               // dWo (+)= dH^T . O
-    KGCHK(tr_gemm(x, f(t.dH), d, 1, Wo, d, 1, 0, f(t.dO), d, n, d, d, 0));                        // dO = dH . Wo
-    other();
-    hipLaunchKernelGGL(tr_attn_bwd_q_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
-                       (const float *)f(t.dO), n, d, hd, f(t.dS), f(t.dQKV));
-    hipLaunchKernelGGL(tr_attn_bwd_kv_kernel, dim3(n, H), dim3(128), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
-                       (const float *)f(t.dS), (const float *)f(t.dO), n, d, hd, f(t.dQKV));
-    KGCHK(check_launch(x, "train_attn_bwd"));
-    other();
-    hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.dQKV), n, d, hd,
-                       at<const float2>(x->scr, x->s_rope), 1);
-    KGCHK(check_launch(x, "train_rope_bwd"));
-    KGCHK(tr_gemm(x, f(t.dQKV), 1, 3 * d, f(t.N), d, 1, 0, G, d, 3 * d, d, n, acc));              // dWqkv (+)= dQKV^T . N
-    KGCHK(tr_gemm(x, f(t.dQKV), 3 * d, 1, Wqkv, d, 1, 0, f(t.dN), d, n, d, 3 * d, 0));            // dN = dQKV . Wqkv
+    // ---- backward
+    if (own_head) {
+        KGCHK(tr_wgrad(x, f(t.dZ), f(t.Mm), G + o_head, n, V, d, acc));
+        KGCHK(tr_bwd(x, f(t.dZ), P + o_head, f(t.dMm), n, V, d, 0));
+    } else {
+        KGCHK(tr_gemm(x, f(t.dZ), V, 1, head, d, 1, hm_nn, f(t.dMm), d, n, d, V, 0));
+    }
+    KGCHK(rms_bwd(f(t.H), P + o_glast, f(t.rlast), f(t.dMm), f(t.dH), G + o_glast));
+    if (kind == KG_ADAPTER_MLP) {
+        KGCHK(tr_wgrad(x, f(t.dH), f(t.O), G + o_b, n, d, d, acc));                 // dW2 = dH^T . S1
+        KGCHK(tr_bwd(x, f(t.dH), P + o_b, f(t.dO), n, d, d, 0));                    // dS1 = dH . W2
+        other();
+        hipLaunchKernelGGL(tr_silu_bwd_kernel, ew_blocks(nd), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.dO), nd,
+                           f(t.dQKV));
+        KGCHK(check_launch(x, "train_silu_bwd"));
+        KGCHK(tr_wgrad(x, f(t.dQKV), f(t.N), G + o_a, n, d, d, acc));               // dW1 = dU1^T . N
+        KGCHK(tr_bwd(x, f(t.dQKV), P + o_a, f(t.dN), n, d, d, 0));                  // dN = dU1 . W1
+    } else {
+        if (kind == KG_ADAPTER_LAYER) {
+            KGCHK(tr_wgrad(x, f(t.dH), f(t.Act), G + o_wd, n, d, ff, acc));         // dWd = dH^T . Act
+            KGCHK(tr_bwd(x, f(t.dH), P + o_wd, f(t.dAct), n, d, ff, 0));            // dAct = dH . Wd
+            other();
+            hipLaunchKernelGGL(tr_swiglu_bwd_kernel, ew_blocks(nf), dim3(256), 0, x->stream, (const float *)f(t.Gt), (const float *)f(t.Ut),
+                               (const float *)f(t.dAct), nf, f(t.dGt), f(t.dUt));
+            KGCHK(check_launch(x, "train_swiglu_bwd"));
+            KGCHK(tr_wgrad(x, f(t.dGt), f(t.Bn), G + o_wg, n, ff, d, acc));
+            KGCHK(tr_wgrad(x, f(t.dUt), f(t.Bn), G + o_wu, n, ff, d, acc));
+            KGCHK(tr_bwd(x, f(t.dGt), P + o_wg, f(t.dB), n, ff, d, 0));
+            KGCHK(tr_bwd(x, f(t.dUt), P + o_wu, f(t.dB), n, ff, d, 1));
+            KGCHK(rms_bwd(f(t.H1), P + o_gpost, f(t.rpost), f(t.dB), f(t.dO), G + o_gpost));   // dO is free here: d(norm input)
+            other();
+            hipLaunchKernelGGL(tr_add_kernel, ew_blocks(nd), dim3(256), 0, x->stream, f(t.dH), (const float *)f(t.dO), nd);   // dH1
+            KGCHK(check_launch(x, "train_add"));
+        }
+        KGCHK(tr_wgrad(x, f(t.dH), f(t.O), G + o_b, n, d, d, acc));                 // dWo = dH^T . O
+        KGCHK(tr_bwd(x, f(t.dH), P + o_b, f(t.dO), n, d, d, 0));                    // dO = dH . Wo
+        other();
+        hipLaunchKernelGGL(tr_attn_bwd_q_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
+                           (const float *)f(t.dO), n, d, hd, f(t.dS), f(t.dQKV));
+        hipLaunchKernelGGL(tr_attn_bwd_kv_kernel, dim3(n, H), dim3(128), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
+                           (const float *)f(t.dS), (const float *)f(t.dO), n, d, hd, f(t.dQKV));
+        hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.dQKV), n, d, hd,
+                           at<const float2>(x->scr, x->s_rope), 1);
+        KGCHK(check_launch(x, "train_attn_bwd"));
+        KGCHK(tr_wgrad(x, f(t.dQKV), f(t.N), G + o_a, n, 3 * d, d, acc));           // dWqkv = dQKV^T . N
+        KGCHK(tr_bwd(x, f(t.dQKV), P + o_a, f(t.dN), n, 3 * d, d, 0));              // dN = dQKV . Wqkv
+    }
     other();
     hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.F),
-                       (const float *)f(t.rin), (const float *)f(t.dN), n, d, G + 4 * dd, acc);
+                       (const float *)f(t.rin), (const float *)f(t.dN), n, d, G + o_gin, acc);
     KGCHK(check_launch(x, "train_gain_grad"));
-    // loss of the step (before the update), summed over positions in double on the host
+    // loss of this sequence (before any update), summed over positions in double on the host
     std::vector<float> rows(n);
     prof_flush(x);
     HIPCHK(x, hipMemcpyAsync(rows.data(), f(t.loss), (size_t)n * 4, hipMemcpyDeviceToHost, x->stream));
@@ -1505,38 +1639,20 @@ int kg_train_apply(kg_ctx *x, const kg_train_params *hp)
     if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
     KGCHK(check_train_params(x, hp));
     if (x->tr_pending < 1) return fail(x, KG_ESTATE, "no gradient has been accumulated");
-    const int d = x->c.d_model;
-    const size_t dd = (size_t)d * d;
     const TrainLayout &t = x->tl;
-    auto f = [&](size_t off) { return at<float>(x->tr, off); };
-    auto other = [&]() { ProfScope ps(x, 2, 0.0); };
-    float *P = f(t.P), *G = f(t.G);
-    float *Wqkv = P, *Wo = P + 3 * dd, *gin = P + 4 * dd, *glast = P + 4 * dd + d;
-    // AdamW on the fp32 master copies, then the inference copies in the arena are refreshed
+    float *P = at<float>(x->tr, t.P), *G = at<float>(x->tr, t.G), *Mo = at<float>(x->tr, t.M), *Vo = at<float>(x->tr, t.V);
+    // AdamW on the fp32 master copies, then the copies the decode calls read are refreshed
     x->tr_step++;
     const float c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)x->tr_step));
     const float c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)x->tr_step));
-    other();
-    hipLaunchKernelGGL(tr_adamw_kernel, dim3((unsigned)((4 * dd + 255) / 256)), dim3(256), 0, x->stream, P, (const float *)G,
-                       f(t.M), f(t.V), 4 * dd, hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, c1, c2);
-    hipLaunchKernelGGL(tr_adamw_kernel, dim3((2 * d + 255) / 256), dim3(256), 0, x->stream, P + 4 * dd, (const float *)(G + 4 * dd),
-                       f(t.M) + 4 * dd, f(t.V) + 4 * dd, (size_t)2 * d, hp->lr, hp->beta1, hp->beta2, hp->eps, 0.f, c1, c2);
-    KGCHK(check_launch(x, "train_adamw"));
-    if (x->bf) {
-        hipLaunchKernelGGL(tr_pack_bf16_kernel, dim3((unsigned)((3 * dd + 255) / 256)), dim3(256), 0, x->stream, (const float *)Wqkv,
-                           3 * d, d, x->KSd, at<uint16_t>(x->arena, x->a_qkv));
-        hipLaunchKernelGGL(tr_pack_bf16_kernel, dim3((unsigned)((dd + 255) / 256)), dim3(256), 0, x->stream, (const float *)Wo, d, d,
-                           x->KSd, at<uint16_t>(x->arena, x->a_wo));
-        hipLaunchKernelGGL(tr_round_bf16_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)gin, d,
-                           at<float>(x->arena, x->a_gin));
-        hipLaunchKernelGGL(tr_round_bf16_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)glast, d,
-                           at<float>(x->arena, x->a_glast));
-        KGCHK(check_launch(x, "train_pack"));
-    } else {
-        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_qkv, Wqkv, 3 * dd * 4, hipMemcpyDeviceToDevice, x->stream));
-        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_wo, Wo, dd * 4, hipMemcpyDeviceToDevice, x->stream));
-        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_gin, gin, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
-        HIPCHK(x, hipMemcpyAsync(x->arena + x->a_glast, glast, (size_t)d * 4, hipMemcpyDeviceToDevice, x->stream));
+    { ProfScope ps(x, 2, 0.0); }
+    for (const TrTensor &tt : train_tensors(x)) {
+        const size_t cnt = (size_t)tt.rows * tt.cols;
+        hipLaunchKernelGGL(tr_adamw_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, x->stream, P + tt.off,
+                           (const float *)(G + tt.off), Mo + tt.off, Vo + tt.off, cnt, hp->lr, hp->beta1, hp->beta2, hp->eps,
+                           tt.decay ? hp->weight_decay : 0.f, c1, c2);
+        KGCHK(check_launch(x, "train_adamw"));
+        KGCHK(train_sync_tensor(x, tt, P + tt.off, true));
     }
     prof_flush(x);
     HIPCHK(x, hipStreamSynchronize(x->stream));

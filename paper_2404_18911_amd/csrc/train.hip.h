@@ -432,18 +432,67 @@ __global__ void tr_round_bf16_kernel(const float *src, int n, float *dst)
     if (i < n) dst[i] = bf2f(f2bf(src[i]));
 }
 
-// fp32 row-major [rows][K] <-> bf16 MFMA tiles (the layout of pack_w_bf16_kernel); K % 8 == 0
-__global__ void tr_unpack_bf16_kernel(const uint16_t *tiles, int rows, int K, int KS, float *dst)
+// fp32 row-major [rows][K] <-> the arena's form of a matrix: bf16 MFMA tiles (the layout of
+// pack_w_bf16_kernel) or fp32 rows, with source row r living at arena row map_row(r, row_off, mode)
+// (mode 1 / 2: the interleaved gate / up rows of a feed-forward pair); K % 8 == 0 for tiles
+__global__ void tr_unpack_bf16_kernel(const uint16_t *tiles, int rows, int K, int KS, int row_off, int mode, float *dst)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)rows * K) return;
     const int r = (int)(i / K), k = (int)(i % K);
-    dst[i] = bf2f(tiles[packed_u16_index(r, k, KS)]);
+    dst[i] = bf2f(tiles[packed_u16_index(map_row(r, row_off, mode), k, KS)]);
 }
-__global__ void tr_pack_bf16_kernel(const float *src, int rows, int K, int KS, uint16_t *tiles)
+__global__ void tr_pack_bf16_kernel(const float *src, int rows, int K, int KS, int row_off, int mode, uint16_t *tiles)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)rows * K) return;
     const int r = (int)(i / K), k = (int)(i % K);
-    tiles[packed_u16_index(r, k, KS)] = f2bf(src[i]);
+    tiles[packed_u16_index(map_row(r, row_off, mode), k, KS)] = f2bf(src[i]);
+}
+// the same for fp32 models; to_arena: master -> arena, else arena -> master
+__global__ void tr_copy_rows_f32_kernel(float *master, float *arena, int rows, int K, int row_off, int mode, int to_arena)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)rows * K) return;
+    const int r = (int)(i / K), k = (int)(i % K);
+    const size_t j = (size_t)map_row(r, row_off, mode) * K + k;
+    if (to_arena) arena[j] = master[i]; else master[i] = arena[j];
+}
+
+// ---- element-wise pieces of the feed-forward and two-linear-map adapters --------------------
+__device__ __forceinline__ float tr_sigmoid(float z) { return 1.f / (1.f + expf(-z)); }
+// s = silu(u)
+__global__ void tr_silu_kernel(const float *u, size_t n, float *s)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) s[i] = u[i] * tr_sigmoid(u[i]);
+}
+// du = ds * silu'(u), silu'(u) = sg (1 + u (1 - sg))
+__global__ void tr_silu_bwd_kernel(const float *u, const float *ds, size_t n, float *du)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float z = u[i], sg = tr_sigmoid(z);
+    du[i] = ds[i] * sg * (1.f + z * (1.f - sg));
+}
+// a = silu(g) * u
+__global__ void tr_swiglu_kernel(const float *g, const float *u, size_t n, float *a)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) a[i] = g[i] * tr_sigmoid(g[i]) * u[i];
+}
+// dg = da * u * silu'(g), du = da * silu(g)
+__global__ void tr_swiglu_bwd_kernel(const float *g, const float *u, const float *da, size_t n, float *dg, float *du)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float z = g[i], sg = tr_sigmoid(z), d = da[i];
+    dg[i] = d * u[i] * sg * (1.f + z * (1.f - sg));
+    du[i] = d * z * sg;
+}
+// a += b
+__global__ void tr_add_kernel(float *a, const float *b, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) a[i] += b[i];
 }
