@@ -244,6 +244,11 @@ void kg_destroy(kg_ctx *ctx);
  *     positions): each accumulate call adds one sequence's gradient to the gradient block and returns
  *     that sequence's loss; apply performs the AdamW update with the accumulated gradient, refreshes
  *     the decode tensors and clears the count (KG_ESTATE when nothing was accumulated).
+ *   kg_train_features / kg_train_accumulate_features: the frozen model's part of a step on its own.
+ *     Several epochs over fixed sequences need the target model only once per sequence: features
+ *     writes the early features F_dev [n][d_model] and the target logits Zt_dev [n][vocab] (fp32,
+ *     caller-owned device memory) of a sequence; accumulate_features does what kg_train_accumulate
+ *     does from such a pair instead of from tokens.
  *   kg_train_read: copy one buffer of the last step to the host (tests and monitoring):
  *     early features [n][d_model], target / draft logits [n][vocab], the gradient block and the
  *     parameter block, per-position losses [n].  n_floats must be the buffer's exact size.  A block
@@ -263,6 +268,8 @@ int kg_train_bind(kg_ctx *ctx, void *work_dev, size_t bytes, int max_tokens);
 int kg_train_step(kg_ctx *ctx, const kg_train_params *hp, const int32_t *tokens_host, int n, double *loss);
 int kg_train_accumulate(kg_ctx *ctx, const int32_t *tokens_host, int n, double *loss);
 int kg_train_apply(kg_ctx *ctx, const kg_train_params *hp);
+int kg_train_features(kg_ctx *ctx, const int32_t *tokens_host, int n, float *F_dev, float *Zt_dev);
+int kg_train_accumulate_features(kg_ctx *ctx, const float *F_dev, const float *Zt_dev, int n, double *loss);
 int kg_train_read(kg_ctx *ctx, int what, float *host_out, size_t n_floats);
 
 /*

@@ -52,7 +52,8 @@ SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "k
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
            "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_stream_read",
-           "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_accumulate", "kg_train_apply", "kg_train_read", "kg_op_gemm_f32"]
+           "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_accumulate", "kg_train_apply", "kg_train_features", "kg_train_accumulate_features",
+           "kg_train_read", "kg_op_gemm_f32"]
 
 _lib = None
 
@@ -105,6 +106,8 @@ def lib() -> ctypes.CDLL:
     L.kg_train_step.argtypes = [vp, ctypes.POINTER(kg_train_params), ip, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     L.kg_train_accumulate.argtypes = [vp, ip, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     L.kg_train_apply.argtypes = [vp, ctypes.POINTER(kg_train_params)]
+    L.kg_train_features.argtypes = [vp, ip, ctypes.c_int, vp, vp]
+    L.kg_train_accumulate_features.argtypes = [vp, vp, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     L.kg_train_read.argtypes = [vp, ctypes.c_int, fp, ctypes.c_size_t]
     L.kg_op_gemm_f32.argtypes = [vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long,
                                  ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
@@ -308,6 +311,20 @@ class Kangaroo:
         a = np.ascontiguousarray(tokens, dtype=np.int32)
         loss = ctypes.c_double()
         self._chk(self.L.kg_train_accumulate(self.h, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(a), ctypes.byref(loss)))
+        return loss.value
+
+    def train_features(self, tokens: Sequence[int]):
+        """(F, Zt) of a sequence as device tensors: what the frozen model contributes to a training step."""
+        torch = self._torch
+        a = np.ascontiguousarray(tokens, dtype=np.int32)
+        F = torch.empty((len(a), self.shape.d_model), dtype=torch.float32, device=self.device)
+        Zt = torch.empty((len(a), self.shape.vocab), dtype=torch.float32, device=self.device)
+        self._chk(self.L.kg_train_features(self.h, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(a), F.data_ptr(), Zt.data_ptr()))
+        return F, Zt
+
+    def train_accumulate_features(self, F, Zt) -> float:
+        loss = ctypes.c_double()
+        self._chk(self.L.kg_train_accumulate_features(self.h, F.data_ptr(), Zt.data_ptr(), F.shape[0], ctypes.byref(loss)))
         return loss.value
 
     def train_apply(self, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01) -> None:

@@ -1465,30 +1465,17 @@ static int check_train_params(kg_ctx *x, const kg_train_params *hp)
     return KG_OK;
 }
 
-int kg_train_accumulate(kg_ctx *x, const int32_t *tokens, int n, double *loss)
+// The frozen target model on a whole sequence: early features F and target logits Zt of every
+// position into the training workspace.
+static int train_frozen_forward(kg_ctx *x, const int32_t *tokens, int n)
 {
-    KGCHK(check_ready(x));
-    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
-    if (!tokens || !loss) return fail(x, KG_EINVAL, "NULL argument");
-    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
     const kg_config &c = x->c;
-    const int acc = x->tr_pending > 0 ? 1 : 0;     // add to the gradient block, or start it
-    for (int i = 0; i < n; i++)
-        if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(x, KG_EINVAL, "token %d out of range", tokens[i]);
-    const int d = c.d_model, ff = c.d_ffn, V = c.vocab, H = c.n_heads, hd = c.head_dim;
-    const int kind = x->akind;
-    const bool own_head = kind == KG_ADAPTER_ATTN_HEAD || kind == KG_ADAPTER_MLP;
+    const int d = c.d_model, V = c.vocab;
     const TrainLayout &t = x->tl;
     auto f = [&](size_t off) { return at<float>(x->tr, off); };
-    // the tensors of the parameter block and of the gradient block, by role
-    float *P = f(t.P), *G = f(t.G);
-    const std::vector<TrTensor> ts = train_tensors(x);
-    size_t o_a = ts[0].off, o_b = ts[1].off, o_gin = ts[2].off, o_glast = ts[3].off, o_head = 0, o_gpost = 0, o_wg = 0, o_wu = 0, o_wd = 0;
-    if (own_head) o_head = ts[4].off;
-    if (kind == KG_ADAPTER_LAYER) { o_gpost = ts[4].off; o_wg = ts[5].off; o_wu = ts[6].off; o_wd = ts[7].off; }
+    for (int i = 0; i < n; i++)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(x, KG_EINVAL, "token %d out of range", tokens[i]);
     KGCHK(kg_reset(x));
-
-    // frozen target model on the whole sequence: early features F and last hidden states X
     if (x->pf_rows > 0) {
         HIPCHK(x, hipMemcpyAsync(x->scr + x->s_ptok, tokens, (size_t)n * 4, hipMemcpyHostToDevice, x->stream));
         for (int pos0 = 0; pos0 < n; pos0 += x->pf_rows) {
@@ -1508,6 +1495,74 @@ int kg_train_accumulate(kg_ctx *x, const int32_t *tokens, int n, double *loss)
             HIPCHK(x, hipMemcpyAsync(f(t.X) + (size_t)pos0 * d, xl, (size_t)M * d * 4, hipMemcpyDeviceToDevice, x->stream));
         }
     }
+    // target logits of every position: Zt = RMSNorm(X; g_final) . head^T
+    {
+        ProfScope ps(x, 2, 0.0);
+        hipLaunchKernelGGL(tr_rmsnorm_kernel, dim3(n), dim3(256), 0, x->stream, (const float *)f(t.X), at<const float>(x->arena, x->gfinal),
+                           d, c.rms_eps, f(t.Xn), f(t.rfin));
+        KGCHK(check_launch(x, "train_rmsnorm"));
+    }
+    return tr_gemm(x, f(t.Xn), d, 1, x->arena + x->head, 1, d, x->bf ? 1 : 0, f(t.Zt), V, n, V, d, 0);
+}
+
+static int train_graph(kg_ctx *x, int n, double *loss);
+
+int kg_train_accumulate(kg_ctx *x, const int32_t *tokens, int n, double *loss)
+{
+    KGCHK(check_ready(x));
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    if (!tokens || !loss) return fail(x, KG_EINVAL, "NULL argument");
+    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
+    KGCHK(train_frozen_forward(x, tokens, n));
+    return train_graph(x, n, loss);
+}
+
+int kg_train_features(kg_ctx *x, const int32_t *tokens, int n, float *F_dev, float *Zt_dev)
+{
+    KGCHK(check_ready(x));
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    if (!tokens || !F_dev || !Zt_dev) return fail(x, KG_EINVAL, "NULL argument");
+    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
+    KGCHK(train_frozen_forward(x, tokens, n));
+    const TrainLayout &t = x->tl;
+    HIPCHK(x, hipMemcpyAsync(F_dev, x->tr + t.F, (size_t)n * x->c.d_model * 4, hipMemcpyDeviceToDevice, x->stream));
+    HIPCHK(x, hipMemcpyAsync(Zt_dev, x->tr + t.Zt, (size_t)n * x->c.vocab * 4, hipMemcpyDeviceToDevice, x->stream));
+    prof_flush(x);
+    HIPCHK(x, hipStreamSynchronize(x->stream));
+    if (x->profiling) prof_collect(x);
+    x->phase = Phase::NONE;
+    return KG_OK;
+}
+
+int kg_train_accumulate_features(kg_ctx *x, const float *F_dev, const float *Zt_dev, int n, double *loss)
+{
+    KGCHK(check_ready(x));
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    if (!F_dev || !Zt_dev || !loss) return fail(x, KG_EINVAL, "NULL argument");
+    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
+    const TrainLayout &t = x->tl;
+    HIPCHK(x, hipMemcpyAsync(x->tr + t.F, F_dev, (size_t)n * x->c.d_model * 4, hipMemcpyDeviceToDevice, x->stream));
+    HIPCHK(x, hipMemcpyAsync(x->tr + t.Zt, Zt_dev, (size_t)n * x->c.vocab * 4, hipMemcpyDeviceToDevice, x->stream));
+    return train_graph(x, n, loss);
+}
+
+// The adapter's forward over all n positions from the workspace's F and Zt, Eq. 3, and the backward
+// pass into the gradient block (added to it when sequences are pending).
+static int train_graph(kg_ctx *x, int n, double *loss)
+{
+    const kg_config &c = x->c;
+    const int acc = x->tr_pending > 0 ? 1 : 0;     // add to the gradient block, or start it
+    const int d = c.d_model, ff = c.d_ffn, V = c.vocab, H = c.n_heads, hd = c.head_dim;
+    const int kind = x->akind;
+    const bool own_head = kind == KG_ADAPTER_ATTN_HEAD || kind == KG_ADAPTER_MLP;
+    const TrainLayout &t = x->tl;
+    auto f = [&](size_t off) { return at<float>(x->tr, off); };
+    // the tensors of the parameter block and of the gradient block, by role
+    float *P = f(t.P), *G = f(t.G);
+    const std::vector<TrTensor> ts = train_tensors(x);
+    size_t o_a = ts[0].off, o_b = ts[1].off, o_gin = ts[2].off, o_glast = ts[3].off, o_head = 0, o_gpost = 0, o_wg = 0, o_wu = 0, o_wd = 0;
+    if (own_head) o_head = ts[4].off;
+    if (kind == KG_ADAPTER_LAYER) { o_gpost = ts[4].off; o_wg = ts[5].off; o_wu = ts[6].off; o_wd = ts[7].off; }
     const void *head = x->arena + x->head;
     const int hm_nt = x->bf ? 1 : 0, hm_nn = x->bf ? 2 : 0;
     auto other = [&]() { ProfScope ps(x, 2, 0.0); };      // timing class of everything that is not a contraction
@@ -1524,9 +1579,6 @@ int kg_train_accumulate(kg_ctx *x, const int32_t *tokens, int n, double *loss)
     };
     auto ew_blocks = [](size_t cnt) { return dim3((unsigned)((cnt + 255) / 256)); };
     const size_t nd = (size_t)n * d, nf = (size_t)n * ff;
-    // target logits of every position: Zt = RMSNorm(X; g_final) . head^T
-    KGCHK(rms(f(t.X), at<const float>(x->arena, x->gfinal), f(t.Xn), f(t.rfin)));
-    KGCHK(tr_gemm(x, f(t.Xn), d, 1, head, 1, d, hm_nt, f(t.Zt), V, n, V, d, 0));
     // ---- adapter forward over all positions
     KGCHK(rms(f(t.F), P + o_gin, f(t.N), f(t.rin)));
     HIPCHK(x, hipMemcpyAsync(f(t.H), f(t.F), nd * 4, hipMemcpyDeviceToDevice, x->stream));

@@ -214,3 +214,38 @@ def test_gradient_accumulation_over_two_sequences():
     G2 = B.split_param_block(kg.train_read(B.TRAIN_GRADIENTS), d)
     assert np.abs(G2["wo"]).max() < 0.9 * np.abs(G["wo"]).max() or not np.allclose(G2["wo"], G["wo"])
     kg.close()
+
+
+def test_cached_features_give_the_same_step_as_tokens():
+    """The frozen model's part of a step (early features, target logits) computed once and handed
+    back in gives bit for bit the gradient, loss and update of a step from tokens; epochs over the
+    cached pair lower the loss without running the target model again."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["toy_bf16"]
+    W = I.gen_weights(shape, seed=3, alpha=0.5, head_scale=4.0)
+    toks = I.gen_prompt(shape.vocab, 41, seed=9)
+    kg = P.load_model(shape, W, 96, kv_page_tokens=32)
+    kg.train_bind(48)
+    F, Zt = kg.train_features(toks)
+    loss_a = kg.train_accumulate(toks)
+    Ga = kg.train_read(B.TRAIN_GRADIENTS).copy()
+    np.testing.assert_array_equal(kg.train_read(B.TRAIN_FEATURES, 41), F.cpu().numpy())
+    np.testing.assert_array_equal(kg.train_read(B.TRAIN_TARGET_LOGITS, 41), Zt.cpu().numpy())
+    kg.train_apply(1e-3)
+    Pa = kg.train_read(B.TRAIN_PARAMETERS).copy()
+    # again from the cached pair, on a fresh copy of the same adapter
+    for kind in (I.KIND_A_WQ, I.KIND_A_WK, I.KIND_A_WV, I.KIND_A_WO, I.KIND_A_NORM_IN, I.KIND_A_NORM_LAST):
+        kg.load_tensor(kind, -1, W[(kind, -1)])
+    kg.train_bind(48)
+    loss_b = kg.train_accumulate_features(F, Zt)
+    assert loss_b == loss_a
+    np.testing.assert_array_equal(kg.train_read(B.TRAIN_GRADIENTS), Ga)
+    kg.train_apply(1e-3)
+    np.testing.assert_array_equal(kg.train_read(B.TRAIN_PARAMETERS), Pa)
+    losses = [loss_b]
+    for _ in range(5):
+        losses.append(kg.train_accumulate_features(F, Zt))
+        kg.train_apply(2e-4)
+    assert all(b < a for a, b in zip(losses[1:-1], losses[2:])), losses
+    kg.close()
