@@ -37,8 +37,14 @@ struct TrGemm {
     int a_vec, b_vec;   // 4 consecutive elements along the contiguous index are one aligned 16-byte word
 };
 
-#define TRG_LDA 96    // LDS row strides in floats: the two half-waves of an MFMA operand read hit different banks
-#define TRG_LDB 160
+// LDS row strides in floats.  A thread stores its 4 fetched elements either down 4 consecutive rows
+// (operand contiguous along k: the lanes of a wave then cover rows 4 apart) or as one 16-byte word
+// (operand contiguous along m / n).  With 4 * stride = 16 (mod 64) the first pattern spreads over all
+// banks; strides are multiples of 4 floats so that the 16-byte stores are aligned.
+#ifndef TRG_LDA
+#define TRG_LDA 100
+#define TRG_LDB 164
+#endif
 
 __device__ __forceinline__ size_t packed_u16_index(int row, int col, int KS)
 {
@@ -47,8 +53,8 @@ __device__ __forceinline__ size_t packed_u16_index(int row, int col, int KS)
 
 __global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
 {
-    __shared__ float As[2][16][TRG_LDA];
-    __shared__ float Bs[2][16][TRG_LDB];
+    __shared__ __attribute__((aligned(16))) float As[2][16][TRG_LDA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][16][TRG_LDB];
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
     const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 128;
     const int wm = (wave & 1) * 32, wn = (wave >> 1) * 64;
@@ -145,12 +151,19 @@ __global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
         }
     };
     auto stash = [&](int buf) {
+        if (a_kc) {
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            if (a_kc) As[buf][ak + i][am] = av[i]; else As[buf][ak][am + i] = av[i];
+            for (int i = 0; i < 4; i++) As[buf][ak + i][am] = av[i];
+        } else {
+            *(float4 *)&As[buf][ak][am] = make_float4(av[0], av[1], av[2], av[3]);
+        }
 #pragma unroll
-            for (int h = 0; h < 2; h++) {
-                if (b_kc) Bs[buf][bk + i][bn + 64 * h] = bv[h][i]; else Bs[buf][bk][bn + 64 * h + i] = bv[h][i];
+        for (int h = 0; h < 2; h++) {
+            if (b_kc) {
+#pragma unroll
+                for (int i = 0; i < 4; i++) Bs[buf][bk + i][bn + 64 * h] = bv[h][i];
+            } else {
+                *(float4 *)&Bs[buf][bk][bn + 64 * h] = make_float4(bv[h][0], bv[h][1], bv[h][2], bv[h][3]);
             }
         }
     };
