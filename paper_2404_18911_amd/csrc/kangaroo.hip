@@ -1574,7 +1574,7 @@ static int train_graph(kg_ctx *x, int n, double *loss)
     auto rms_bwd = [&](const float *in, const float *g, const float *r, const float *dy, float *dx, float *dg) {
         other();
         hipLaunchKernelGGL(tr_rmsnorm_bwd_kernel, dim3(n), dim3(256), 0, x->stream, in, g, r, dy, d, dx);
-        hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, in, r, dy, n, d, dg, acc);
+        hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 63) / 64), dim3(1024), 0, x->stream, in, r, dy, n, d, dg, acc);
         return check_launch(x, "train_rmsnorm_bwd");
     };
     auto ew_blocks = [](size_t cnt) { return dim3((unsigned)((cnt + 255) / 256)); };
@@ -1658,7 +1658,7 @@ static int train_graph(kg_ctx *x, int n, double *loss)
         other();
         hipLaunchKernelGGL(tr_attn_bwd_q_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
                            (const float *)f(t.dO), n, d, hd, f(t.dS), f(t.dQKV));
-        hipLaunchKernelGGL(tr_attn_bwd_kv_kernel, dim3(n, H), dim3(128), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
+        hipLaunchKernelGGL(tr_attn_bwd_kv_kernel, dim3(n, H), dim3(512), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
                            (const float *)f(t.dS), (const float *)f(t.dO), n, d, hd, f(t.dQKV));
         hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.dQKV), n, d, hd,
                            at<const float2>(x->scr, x->s_rope), 1);
@@ -1667,7 +1667,7 @@ static int train_graph(kg_ctx *x, int n, double *loss)
         KGCHK(tr_bwd(x, f(t.dQKV), P + o_a, f(t.dN), n, 3 * d, d, 0));              // dN = dQKV . Wqkv
     }
     other();
-    hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 255) / 256), dim3(256), 0, x->stream, (const float *)f(t.F),
+    hipLaunchKernelGGL(tr_gain_grad_kernel, dim3((d + 63) / 64), dim3(1024), 0, x->stream, (const float *)f(t.F),
                        (const float *)f(t.rin), (const float *)f(t.dN), n, d, G + o_gin, acc);
     KGCHK(check_launch(x, "train_gain_grad"));
     // loss of this sequence (before any update), summed over positions in double on the host

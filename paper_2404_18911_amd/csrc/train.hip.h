@@ -274,14 +274,25 @@ __global__ __launch_bounds__(256) void tr_rmsnorm_bwd_kernel(const float *x, con
     for (int i = threadIdx.x; i < d; i += 256) dx[(size_t)row * d + i] = rr * dyr[i] * g[i] - xr[i] * r3 * s;
 }
 
-// dg[j] (+)= sum_t dy[t][j] * x[t][j] * r[t]; one thread per column
-__global__ void tr_gain_grad_kernel(const float *x, const float *r, const float *dy, int T, int d, float *dg, int accumulate)
+// dg[j] (+)= sum_t dy[t][j] * x[t][j] * r[t]; a block of 1024 threads handles 64 columns, its 16 groups of
+// 64 threads take every 16th row and their partial sums are added in group order
+__global__ __launch_bounds__(1024) void tr_gain_grad_kernel(const float *x, const float *r, const float *dy, int T, int d, float *dg,
+                                                            int accumulate)
 {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= d) return;
+    __shared__ float part[16][64];
+    const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + c;
     float s = 0.f;
-    for (int t = 0; t < T; t++) s += dy[(size_t)t * d + j] * x[(size_t)t * d + j] * r[t];
-    dg[j] = accumulate ? dg[j] + s : s;
+    if (j < d)
+        for (int t = grp; t < T; t += 16) s += dy[(size_t)t * d + j] * x[(size_t)t * d + j] * r[t];
+    part[grp][c] = s;
+    __syncthreads();
+    if (grp == 0 && j < d) {
+        float tot = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; g++) tot += part[g][c];
+        dg[j] = accumulate ? dg[j] + tot : tot;
+    }
 }
 
 // rotary embedding of the q and k parts of QKV [T][3d] at positions 0..T-1, pairs (i, i + hd/2);
@@ -381,20 +392,30 @@ __global__ __launch_bounds__(256) void tr_attn_bwd_q_kernel(const float *qkv, co
     }
 }
 
-// Key side for one (key row j, head h): dv_j = sum_{i >= j} P_ij do_i, dk_j = sum_{i >= j} dS_ij q_i / sqrt(hd)
-__global__ __launch_bounds__(128) void tr_attn_bwd_kv_kernel(const float *qkv, const float *P, const float *dS, const float *dout,
+// Key side for one (key row j, head h): dv_j = sum_{i >= j} P_ij do_i, dk_j = sum_{i >= j} dS_ij q_i / sqrt(hd).
+// Block of 512 threads: thread (c, g) owns element c of the head and the query rows i = j + g, j + g + 4, ...;
+// the four partial sums are added in order.
+__global__ __launch_bounds__(512) void tr_attn_bwd_kv_kernel(const float *qkv, const float *P, const float *dS, const float *dout,
                                                              int T, int d, int hd, float *dqkv)
 {
-    const int j = blockIdx.x, h = blockIdx.y, c = threadIdx.x;
-    if (c >= hd) return;
+    __shared__ float pv[4][128], pk[4][128];
+    const int j = blockIdx.x, h = blockIdx.y, c = threadIdx.x & 127, g = threadIdx.x >> 7;
     float dv = 0.f, dk = 0.f;
-    for (int i = j; i < T; i++) {
-        const size_t pi = ((size_t)h * T + i) * T + j;
-        dv += P[pi] * dout[(size_t)i * d + (size_t)h * hd + c];
-        dk += dS[pi] * qkv[(size_t)i * 3 * d + (size_t)h * hd + c];
+    if (c < hd)
+        for (int i = j + g; i < T; i += 4) {
+            const size_t pi = ((size_t)h * T + i) * T + j;
+            dv += P[pi] * dout[(size_t)i * d + (size_t)h * hd + c];
+            dk += dS[pi] * qkv[(size_t)i * 3 * d + (size_t)h * hd + c];
+        }
+    pv[g][c] = dv;
+    pk[g][c] = dk;
+    __syncthreads();
+    if (g == 0 && c < hd) {
+        const float sv = ((pv[0][c] + pv[1][c]) + pv[2][c]) + pv[3][c];
+        const float sk = ((pk[0][c] + pk[1][c]) + pk[2][c]) + pk[3][c];
+        dqkv[(size_t)j * 3 * d + d + (size_t)h * hd + c] = sk / sqrtf((float)hd);
+        dqkv[(size_t)j * 3 * d + 2 * d + (size_t)h * hd + c] = sv;
     }
-    dqkv[(size_t)j * 3 * d + d + (size_t)h * hd + c] = dk / sqrtf((float)hd);
-    dqkv[(size_t)j * 3 * d + 2 * d + (size_t)h * hd + c] = dv;
 }
 
 // Eq. 3 for one position: loss[t] = - sum_n p_n log q_n with p = softmax(zt[t]), q = softmax(z[t]);
