@@ -1371,8 +1371,8 @@ static int train_sync_tensor(kg_ctx *x, const TrTensor &tt, float *master, bool 
         else HIPCHK(x, hipMemcpyAsync(ar, master, n * 4, hipMemcpyDeviceToDevice, x->stream));
     } else if (x->bf) {
         const int KS = (tt.cols + 31) / 32;
-        if (to_arena)
-            hipLaunchKernelGGL(tr_pack_bf16_kernel, dim3(blocks), dim3(256), 0, x->stream, (const float *)master, tt.rows, tt.cols, KS,
+        if (to_arena)     // columns are a multiple of 8 for every tiled matrix (checked at load), master rows 16-byte aligned
+            hipLaunchKernelGGL(tr_pack_bf16_kernel, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, x->stream, (const float *)master, tt.rows, tt.cols, KS,
                                tt.row_off, tt.mode, at<uint16_t>(x->arena, tt.arena_off));
         else
             hipLaunchKernelGGL(tr_unpack_bf16_kernel, dim3(blocks), dim3(256), 0, x->stream, at<const uint16_t>(x->arena, tt.arena_off),

@@ -476,12 +476,20 @@ __global__ void tr_unpack_bf16_kernel(const uint16_t *tiles, int rows, int K, in
     const int r = (int)(i / K), k = (int)(i % K);
     dst[i] = bf2f(tiles[packed_u16_index(map_row(r, row_off, mode), k, KS)]);
 }
+// one thread per 16-byte unit of a tile: 8 consecutive columns of one row
 __global__ void tr_pack_bf16_kernel(const float *src, int rows, int K, int KS, int row_off, int mode, uint16_t *tiles)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (size_t)rows * K) return;
-    const int r = (int)(i / K), k = (int)(i % K);
-    tiles[packed_u16_index(map_row(r, row_off, mode), k, KS)] = f2bf(src[i]);
+    const int K8 = K >> 3;
+    if (i >= (size_t)rows * K8) return;
+    const int r = (int)(i / K8), k = (int)(i % K8) * 8;
+    const float4 a = *(const float4 *)(src + (size_t)r * K + k), b = *(const float4 *)(src + (size_t)r * K + k + 4);
+    u32x4_t v;
+    v[0] = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+    v[1] = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+    v[2] = (uint32_t)f2bf(b.x) | ((uint32_t)f2bf(b.y) << 16);
+    v[3] = (uint32_t)f2bf(b.z) | ((uint32_t)f2bf(b.w) << 16);
+    *(u32x4_t *)(tiles + packed_u16_index(map_row(r, row_off, mode), k, KS)) = v;
 }
 // the same for fp32 models; to_arena: master -> arena, else arena -> master
 __global__ void tr_copy_rows_f32_kernel(float *master, float *arena, int rows, int K, int row_off, int mode, int to_arena)
