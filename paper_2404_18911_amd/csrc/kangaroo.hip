@@ -1410,6 +1410,10 @@ static void tr_gemm_vec_flags(TrGemm &g)
     };
     g.a_vec = g.sak == 1 ? ok(g.A, g.sak, g.sam) : ok(g.A, g.sam, g.sak);
     g.b_vec = g.b_mode == 0 && (g.sbk == 1 ? ok(g.B, g.sbk, g.sbn) : ok(g.B, g.sbn, g.sbk));
+    if (g.batch > 1) {      // every batch member must keep the alignment
+        g.a_vec = g.a_vec && g.bsa % 4 == 0;
+        g.b_vec = g.b_vec && g.bsb % 4 == 0;
+    }
 }
 
 static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, long sbk, long sbn, int b_mode, float *C,
@@ -1418,6 +1422,7 @@ static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, 
     TrGemm g;
     g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = b_mode; g.b_KS = x->KSd;
     g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
+    g.batch = 1; g.bsa = g.bsb = g.bsc = 0;
     tr_gemm_vec_flags(g);
     // few output tiles and a long k: slice k so that the launch has enough workgroups to fill the chip
     const int tiles = ((N + 127) / 128) * ((M + 63) / 64);
@@ -1437,6 +1442,22 @@ static int tr_gemm(kg_ctx *x, const void *A, long sam, long sak, const void *B, 
         KGCHK(check_launch(x, "train_gemm_reduce"));
     }
     return KG_OK;
+}
+
+// One product per attention head in a single launch: head h reads A + h * bsa, B + h * bsb and writes C + h * bsc.
+static int tr_gemm_heads(kg_ctx *x, const float *A, long sam, long sak, long bsa, const float *B, long sbk, long sbn, long bsb,
+                         float *C, long ldc, long bsc, int M, int N, int K, int heads)
+{
+    TrGemm g;
+    g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = 0; g.b_KS = 0;
+    g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.accumulate = 0;
+    g.batch = heads; g.bsa = bsa; g.bsb = bsb; g.bsc = bsc;
+    g.k_chunk = (K + 15) / 16 * 16; g.part = nullptr;
+    tr_gemm_vec_flags(g);
+    if (heads == 1) { g.batch = 1; }
+    ProfScope ps(x, 4, 2.0 * M * (double)N * K * heads);
+    hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 127) / 128, (M + 63) / 64, heads), dim3(256), 0, x->stream, g);
+    return check_launch(x, "train_gemm_heads");
 }
 
 // The three products with one weight matrix W [N][K] (row-major fp32 master copy) that the chain rule needs:
@@ -1595,8 +1616,17 @@ static int train_graph(kg_ctx *x, int n, double *loss)
         other();
         hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.QKV), n, d, hd,
                            at<const float2>(x->scr, x->s_rope), 0);
-        hipLaunchKernelGGL(tr_attn_fwd_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), n, d, hd, f(t.Pm), f(t.O));
-        KGCHK(check_launch(x, "train_attn_fwd"));
+        KGCHK(check_launch(x, "train_rope"));
+        {
+            // causal attention, one product per head: S = Q.K^T, P = softmax(S / sqrt(hd)), O = P.V
+            const float *Q = f(t.QKV), *K = f(t.QKV) + d, *Vv = f(t.QKV) + 2 * d;
+            const long TT = (long)n * n;
+            KGCHK(tr_gemm_heads(x, Q, 3 * d, 1, hd, K, 1, 3 * d, hd, f(t.Pm), n, TT, n, n, hd, H));
+            other();
+            hipLaunchKernelGGL(tr_softmax_causal_kernel, dim3(n, H), dim3(256), 0, x->stream, f(t.Pm), n, 1.f / sqrtf((float)hd));
+            KGCHK(check_launch(x, "train_softmax"));
+            KGCHK(tr_gemm_heads(x, f(t.Pm), n, 1, TT, Vv, 3 * d, 1, hd, f(t.O), d, hd, n, hd, n, H));
+        }
         KGCHK(tr_fwd(x, f(t.O), P + o_b, f(t.H), n, d, d, 1));
         if (kind == KG_ADAPTER_LAYER) {
             // h <- h + Wd (silu(Wg b) * (Wu b)), b = RMSNorm(h; g_post); the attention's output h is kept in H1
@@ -1655,11 +1685,20 @@ static int train_graph(kg_ctx *x, int n, double *loss)
         }
         KGCHK(tr_wgrad(x, f(t.dH), f(t.O), G + o_b, n, d, d, acc));                 // dWo = dH^T . O
         KGCHK(tr_bwd(x, f(t.dH), P + o_b, f(t.dO), n, d, d, 0));                    // dO = dH . Wo
+        {
+            // dP = dO.V^T, dV = P^T.dO, dS = P (dP - rowsum(dP P)) / sqrt(hd), dQ = dS.K, dK = dS^T.Q, per head
+            const float *Q = f(t.QKV), *K = f(t.QKV) + d, *Vv = f(t.QKV) + 2 * d;
+            const long TT = (long)n * n;
+            KGCHK(tr_gemm_heads(x, f(t.dO), d, 1, hd, Vv, 1, 3 * d, hd, f(t.dS), n, TT, n, n, hd, H));
+            KGCHK(tr_gemm_heads(x, f(t.Pm), 1, n, TT, f(t.dO), d, 1, hd, f(t.dQKV) + 2 * d, 3 * d, hd, n, hd, n, H));
+            other();
+            hipLaunchKernelGGL(tr_dsoftmax_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.Pm), f(t.dS), n,
+                               1.f / sqrtf((float)hd));
+            KGCHK(check_launch(x, "train_dsoftmax"));
+            KGCHK(tr_gemm_heads(x, f(t.dS), n, 1, TT, K, 3 * d, 1, hd, f(t.dQKV), 3 * d, hd, n, hd, n, H));
+            KGCHK(tr_gemm_heads(x, f(t.dS), 1, n, TT, Q, 3 * d, 1, hd, f(t.dQKV) + d, 3 * d, hd, n, hd, n, H));
+        }
         other();
-        hipLaunchKernelGGL(tr_attn_bwd_q_kernel, dim3(n, H), dim3(256), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
-                           (const float *)f(t.dO), n, d, hd, f(t.dS), f(t.dQKV));
-        hipLaunchKernelGGL(tr_attn_bwd_kv_kernel, dim3(n, H), dim3(512), 0, x->stream, (const float *)f(t.QKV), (const float *)f(t.Pm),
-                           (const float *)f(t.dS), (const float *)f(t.dO), n, d, hd, f(t.dQKV));
         hipLaunchKernelGGL(tr_rope_kernel, dim3((unsigned)((nrope + 255) / 256)), dim3(256), 0, x->stream, f(t.dQKV), n, d, hd,
                            at<const float2>(x->scr, x->s_rope), 1);
         KGCHK(check_launch(x, "train_attn_bwd"));
@@ -1754,6 +1793,7 @@ int kg_op_gemm_f32(const float *A, long sam, long sak, const float *B, long sbk,
     g.A = A; g.sam = sam; g.sak = sak; g.B = B; g.sbk = sbk; g.sbn = sbn; g.b_mode = 0; g.b_KS = 0;
     g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
     g.k_chunk = (K + 15) / 16 * 16; g.part = nullptr;
+    g.batch = 1; g.bsa = g.bsb = g.bsc = 0;
     tr_gemm_vec_flags(g);
     hipLaunchKernelGGL(tr_gemm_kernel, dim3((N + 127) / 128, (M + 63) / 64, 1), dim3(256), 0, (hipStream_t)hip_stream, g);
     return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;

@@ -25,6 +25,8 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 // A contraction with few output tiles and a long k is split over blockIdx.z: slice z handles k in
 // [z * k_chunk, (z + 1) * k_chunk) and writes its own partial [M][N] at part + z * M * N; a second
 // kernel adds the slices in order (no atomics: the result does not depend on scheduling).
+// With batch > 1 the launch holds one product per blockIdx.z instead (the per-head products of the
+// attention: operands and result advance by bsa / bsb / bsc elements per head).
 struct TrGemm {
     const void *A; long sam, sak;
     const void *B; long sbk, sbn;
@@ -35,6 +37,8 @@ struct TrGemm {
     int k_chunk;        // k handled per blockIdx.z slice (a multiple of 16); >= K when not split
     float *part;        // partial results of a split contraction
     int a_vec, b_vec;   // 4 consecutive elements along the contiguous index are one aligned 16-byte word
+    int batch;          // > 1: blockIdx.z is a batch index (one product per attention head), k is not split
+    long bsa, bsb, bsc; // element offsets of A, B (b_mode 0) and C per batch index
 };
 
 // LDS row strides in floats.  A thread stores its 4 fetched elements either down 4 consecutive rows
@@ -60,20 +64,23 @@ __global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
     const int wm = (wave & 1) * 32, wn = (wave >> 1) * 64;
     const bool a_kc = g.sak == 1;                      // A contiguous along k
     const bool b_kc = g.b_mode == 0 ? g.sbk == 1 : g.b_mode == 1;
-    const bool split = gridDim.z > 1;
-    const int k_lo = blockIdx.z * g.k_chunk, k_hi = min(g.K, k_lo + g.k_chunk);
+    const bool batched = g.batch > 1;
+    const bool split = !batched && gridDim.z > 1;
+    const int k_lo = batched ? 0 : blockIdx.z * g.k_chunk, k_hi = batched ? g.K : min(g.K, k_lo + g.k_chunk);
+    const size_t boa = batched ? (size_t)blockIdx.z * g.bsa : 0, bob = batched ? (size_t)blockIdx.z * g.bsb : 0,
+                 boc = batched ? (size_t)blockIdx.z * g.bsc : 0;
     // first of the 4 (A) and 2 x 4 (B, second group 64 columns further) elements this thread fetches per step
     int am, ak, bn, bk;
     if (a_kc) { am = t >> 2; ak = (t & 3) * 4; } else { ak = t >> 4; am = (t & 15) * 4; }
     if (b_kc) { bn = t >> 2; bk = (t & 3) * 4; } else { bk = t >> 4; bn = (t & 15) * 4; }
-    const float *pa = (const float *)g.A + (size_t)(m0 + am) * g.sam + (size_t)(k_lo + ak) * g.sak;
+    const float *pa = (const float *)g.A + boa + (size_t)(m0 + am) * g.sam + (size_t)(k_lo + ak) * g.sak;
     const long a_step = 16 * g.sak, a_el = a_kc ? g.sak : g.sam;
     const float *pb0 = nullptr, *pb1 = nullptr;        // b_mode 0
     long b_step = 0, b_el = 0;
     const uint16_t *Bp = (const uint16_t *)g.B;        // tiled modes
     size_t rb0 = 0, rb1 = 0;                           // mode 1: per-row part of the tile index; mode 2: full index at k_lo
     if (g.b_mode == 0) {
-        pb0 = (const float *)g.B + (size_t)(k_lo + bk) * g.sbk + (size_t)(n0 + bn) * g.sbn;
+        pb0 = (const float *)g.B + bob + (size_t)(k_lo + bk) * g.sbk + (size_t)(n0 + bn) * g.sbn;
         pb1 = pb0 + (size_t)64 * g.sbn;
         b_step = 16 * g.sbk;
         b_el = b_kc ? g.sbk : g.sbn;
@@ -203,7 +210,7 @@ __global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
                 if (split) {
                     g.part[((size_t)blockIdx.z * g.M + m) * g.N + n] = v;
                 } else {
-                    float *c = g.C + (size_t)m * g.ldc + n;
+                    float *c = g.C + boc + (size_t)m * g.ldc + n;
                     *c = g.accumulate ? *c + v : v;
                 }
             }
@@ -314,107 +321,62 @@ __global__ void tr_rope_kernel(float *qkv, int T, int d, int hd, const float2 *t
     v[p + half] = b * cs.x + a * cs.y;
 }
 
-#define TR_T_MAX 2048   // longest training sequence: the attention kernels keep one row of T weights in LDS
+#define TR_T_MAX 2048   // longest training sequence: the attention row kernels keep a row of T weights in registers
 
-// Causal attention of one (query row i, head h) over keys 0..i: P[h][i][j] = softmax_j(q_i.k_j / sqrt(hd)),
-// o[i][h] = sum_j P_ij v_j.  grid (T, H), block 256; thread t owns keys t, t + 256, ...
-__global__ __launch_bounds__(256) void tr_attn_fwd_kernel(const float *qkv, int T, int d, int hd, float *P, float *o)
+// Attention over all positions at once goes through the contraction kernel, one product per head:
+// S = Q.K^T, P = causal softmax(S / sqrt(hd)), O = P.V forward; dP = dO.V^T, dV = P^T.dO,
+// dS = P (dP - rowsum(dP P)) / sqrt(hd), dQ = dS.K, dK = dS^T.Q backward.  The two kernels below are
+// the row-wise pieces; both work in place on [H][T][T], one block per (row i, head h), and leave
+// exact zeros above the diagonal.
+__global__ __launch_bounds__(256) void tr_softmax_causal_kernel(float *P, int T, float scale)
 {
     __shared__ float red[4];
-    __shared__ float qs[128];
-    __shared__ float ps[TR_T_MAX];
     const int i = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
-    const float *q = qkv + (size_t)i * 3 * d + (size_t)h * hd;
-    if (t < hd) qs[t] = q[t];
-    __syncthreads();
-    const float inv = 1.f / sqrtf((float)hd);
+    float *row = P + ((size_t)h * T + i) * T;
+    float v[TR_T_MAX / 256];
     float mx = -INFINITY;
-    for (int j = t; j <= i; j += 256) {
-        const float *k = qkv + (size_t)j * 3 * d + d + (size_t)h * hd;
-        float a = 0.f;
-        for (int c = 0; c < hd; c++) a += qs[c] * k[c];
-        a *= inv;
-        ps[j] = a;
-        mx = fmaxf(mx, a);
+#pragma unroll
+    for (int c = 0; c < TR_T_MAX / 256; c++) {
+        const int j = t + 256 * c;
+        v[c] = (j <= i) ? row[j] * scale : -INFINITY;      // j <= i < T
+        mx = fmaxf(mx, v[c]);
     }
     mx = tr_block_max(mx, red);
     float sum = 0.f;
-    for (int j = t; j <= i; j += 256) {
-        const float e = expf(ps[j] - mx);
-        ps[j] = e;
-        sum += e;
+#pragma unroll
+    for (int c = 0; c < TR_T_MAX / 256; c++) {
+        v[c] = (t + 256 * c <= i) ? expf(v[c] - mx) : 0.f;
+        sum += v[c];
     }
     sum = tr_block_sum(sum, red);
-    for (int j = t; j < T; j += 256) {
-        const float p = j <= i ? ps[j] / sum : 0.f;
-        if (j <= i) ps[j] = p;
-        P[((size_t)h * T + i) * T + j] = p;
-    }
-    __syncthreads();
-    if (t < hd) {
-        float a = 0.f;
-        for (int j = 0; j <= i; j++) a += ps[j] * qkv[(size_t)j * 3 * d + 2 * d + (size_t)h * hd + t];
-        o[(size_t)i * d + (size_t)h * hd + t] = a;
+#pragma unroll
+    for (int c = 0; c < TR_T_MAX / 256; c++) {
+        const int j = t + 256 * c;
+        if (j < T) row[j] = v[c] / sum;
     }
 }
 
-// Backward of the attention for one (query row i, head h): dA_j = do_i . v_j, dS_ij = P_ij (dA_j - sum_j dA_j P_ij),
-// dq_i = sum_j dS_ij k_j / sqrt(hd).  dS is stored for the key-side kernel; dq goes to the q part of dqkv.
-__global__ __launch_bounds__(256) void tr_attn_bwd_q_kernel(const float *qkv, const float *P, const float *dout, int T, int d,
-                                                            int hd, float *dS, float *dqkv)
+// dS[i][j] = P[i][j] * (dP[i][j] - sum_j dP[i][j] P[i][j]) * scale, in place on dP
+__global__ __launch_bounds__(256) void tr_dsoftmax_kernel(const float *P, float *dP, int T, float scale)
 {
     __shared__ float red[4];
-    __shared__ float dos[128];
-    __shared__ float dss[TR_T_MAX];
     const int i = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
-    if (t < hd) dos[t] = dout[(size_t)i * d + (size_t)h * hd + t];
-    __syncthreads();
-    const float *Pr = P + ((size_t)h * T + i) * T;
+    const float *prow = P + ((size_t)h * T + i) * T;
+    float *drow = dP + ((size_t)h * T + i) * T;
+    float p[TR_T_MAX / 256], g[TR_T_MAX / 256];
     float D = 0.f;
-    for (int j = t; j <= i; j += 256) {
-        const float *v = qkv + (size_t)j * 3 * d + 2 * d + (size_t)h * hd;
-        float dA = 0.f;
-        for (int c = 0; c < hd; c++) dA += dos[c] * v[c];
-        dss[j] = dA;
-        D += dA * Pr[j];
+#pragma unroll
+    for (int c = 0; c < TR_T_MAX / 256; c++) {
+        const int j = t + 256 * c;
+        p[c] = (j <= i) ? prow[j] : 0.f;
+        g[c] = (j <= i) ? drow[j] : 0.f;
+        D += p[c] * g[c];
     }
     D = tr_block_sum(D, red);
-    for (int j = t; j < T; j += 256) {
-        const float ds = j <= i ? Pr[j] * (dss[j] - D) : 0.f;
-        if (j <= i) dss[j] = ds;
-        dS[((size_t)h * T + i) * T + j] = ds;
-    }
-    __syncthreads();
-    if (t < hd) {
-        float a = 0.f;
-        for (int j = 0; j <= i; j++) a += dss[j] * qkv[(size_t)j * 3 * d + d + (size_t)h * hd + t];
-        dqkv[(size_t)i * 3 * d + (size_t)h * hd + t] = a / sqrtf((float)hd);
-    }
-}
-
-// Key side for one (key row j, head h): dv_j = sum_{i >= j} P_ij do_i, dk_j = sum_{i >= j} dS_ij q_i / sqrt(hd).
-// Block of 512 threads: thread (c, g) owns element c of the head and the query rows i = j + g, j + g + 4, ...;
-// the four partial sums are added in order.
-__global__ __launch_bounds__(512) void tr_attn_bwd_kv_kernel(const float *qkv, const float *P, const float *dS, const float *dout,
-                                                             int T, int d, int hd, float *dqkv)
-{
-    __shared__ float pv[4][128], pk[4][128];
-    const int j = blockIdx.x, h = blockIdx.y, c = threadIdx.x & 127, g = threadIdx.x >> 7;
-    float dv = 0.f, dk = 0.f;
-    if (c < hd)
-        for (int i = j + g; i < T; i += 4) {
-            const size_t pi = ((size_t)h * T + i) * T + j;
-            dv += P[pi] * dout[(size_t)i * d + (size_t)h * hd + c];
-            dk += dS[pi] * qkv[(size_t)i * 3 * d + (size_t)h * hd + c];
-        }
-    pv[g][c] = dv;
-    pk[g][c] = dk;
-    __syncthreads();
-    if (g == 0 && c < hd) {
-        const float sv = ((pv[0][c] + pv[1][c]) + pv[2][c]) + pv[3][c];
-        const float sk = ((pk[0][c] + pk[1][c]) + pk[2][c]) + pk[3][c];
-        dqkv[(size_t)j * 3 * d + d + (size_t)h * hd + c] = sk / sqrtf((float)hd);
-        dqkv[(size_t)j * 3 * d + 2 * d + (size_t)h * hd + c] = sv;
+#pragma unroll
+    for (int c = 0; c < TR_T_MAX / 256; c++) {
+        const int j = t + 256 * c;
+        if (j < T) drow[j] = p[c] * (g[c] - D) * scale;
     }
 }
 
