@@ -160,3 +160,31 @@ def test_training_workspace_size_is_host_logic():
     assert L.kg_train_step(h, ctypes.byref(hp), toks, 2, ctypes.byref(loss)) == B.KG_ESTATE
     assert L.kg_train_bind(h, None, 0, 8) == B.KG_ESTATE
     L.kg_destroy(h)
+
+
+def test_algorithmic_bytes_of_the_benchmark_match_the_shapes():
+    """bench.py prices every forward by its algorithmic bytes: weights once plus the cached keys and
+    values once.  At the 7B shape these are the hand-computed figures (GB, bf16): a layer 404.75 MB,
+    LM head 262.14 MB, adapter 134.22 MB; plain forward 13.215, draft step 1.206, shallow part
+    0.8095, verification 12.405; the other adapter architectures change the draft step only."""
+    import dataclasses
+    import bench
+    s = I.SHAPES["7b"]
+    fb = bench.forward_bytes(s, 0)
+    assert fb["layer"] == (4 * 4096 * 4096 + 3 * 4096 * 11008) * 2 == 404_750_336
+    assert fb["head"] == 262_144_000 and fb["adapter"] == 134_217_728
+    assert round(fb["plain"] / 1e9, 3) == 13.214 or round(fb["plain"] / 1e9, 3) == 13.215
+    assert round(fb["draft"] / 1e9, 3) == 1.206 and round(fb["shallow"] / 1e9, 4) == 0.8095
+    assert round(fb["verify"] / 1e9, 3) == 12.405 or round(fb["verify"] / 1e9, 3) == 12.404
+    assert fb["plain"] == 32 * fb["layer"] + fb["head"] and fb["verify"] == 30 * fb["layer"] + fb["head"]
+    # cached keys and values: 16 KB per token and layer, read once per attention layer of the forward
+    ctx = 384
+    fk = bench.forward_bytes(s, ctx)
+    assert fk["plain"] - fb["plain"] == 32 * 16384 * ctx
+    assert fk["draft"] - fb["draft"] == 3 * 16384 * ctx          # two shallow layers and the adapter
+    assert fk["verify"] - fb["verify"] == 30 * 16384 * ctx
+    d, f, V = s.d_model, s.d_ffn, s.vocab
+    draft = {k: bench.forward_bytes(dataclasses.replace(s, adapter=k), 0)["draft"] for k in range(4)}
+    assert draft[1] == draft[0]                                   # an own head replaces the shared one byte for byte
+    assert draft[2] - draft[0] == 3 * d * f * 2                   # the block's feed-forward
+    assert draft[0] - draft[3] == 2 * d * d * 2                   # two maps instead of four
