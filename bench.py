@@ -466,7 +466,9 @@ def main():
                    "alpha": args.alpha, "eta": eta, "gamma": gamma, "prompt": args.prompt, "new": args.new,
                    "rounds": rounds, "drafted": stats.drafted, "accepted": stats.accepted,
                    "acceptance_rate": acc_rate, "compression_rate": (args.new - 1) / rounds,
-                   "mean_draft_len": stats.drafted / rounds},
+                   "mean_draft_len": stats.drafted / rounds,
+                   # consistent token acceptance rate, Eq. 2: share of rounds whose first w drafts were all accepted
+                   "ctar": [B.stats_ctar(stats, w) for w in range(1, gamma + 1)]},
     }
 
     if not args.no_extras:
@@ -520,6 +522,7 @@ def main():
         res["eta0"] = {"tokens_per_s": (len(out0) - 1) / st0.t_total_s, "rounds": st0.rounds,
                        "acceptance_rate": st0.accepted / max(1, st0.drafted),
                        "compression_rate": (args.new - 1) / st0.rounds,
+                       "ctar": [B.stats_ctar(st0, w) for w in range(1, gamma + 1)],
                        "lossless_on_gpu": None if args.sample else bool(out0 == out_p)}
         if args.alpha2 > 0:
             reload_alpha(kg, shape, args.alpha2, threads)
