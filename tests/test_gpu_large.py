@@ -140,3 +140,36 @@ def test_7b_at_the_maximum_context():
         kg.generate(p, I.gen_prompt(shape.vocab, 16384 - 8), 48)
     assert ei.value.code == B.KG_ENOSPC
     kg.close()
+
+
+@pytest.mark.parametrize("adapter", [1, 2, 3])
+def test_training_step_of_each_adapter_architecture_at_7b_width(adapter):
+    """Eq. 3 + its gradient for the other adapter architectures at the 7B layer shape (own head
+    32000 x 4096 trained, feed-forward 11008 wide, two 4096 x 4096 maps) on a four-layer model:
+    loss, draft logits and every gradient against the fp64 oracle on a 24-token sequence."""
+    from oracle import adapter_training as TR
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = dataclasses.replace(I.with_layers(I.SHAPES["7b"], 4), exit_layer=2, adapter=adapter)
+    W = I.gen_weights(shape, seed=1, alpha=0.3, threads=16, own_head_copy=False)
+    kg = P.load_model(shape, W, 64, gamma_max=6, kv_page_tokens=64)
+    kg.train_bind(32)
+    n = 24
+    toks = I.gen_prompt(shape.vocab, n, seed=13)
+    before = kg.train_read(B.TRAIN_PARAMETERS)
+    loss = kg.train_step(toks, 1e-5)
+    F = kg.train_read(B.TRAIN_FEATURES, n).astype(np.float64)
+    Zt = kg.train_read(B.TRAIN_TARGET_LOGITS, n).astype(np.float64)
+    Z = kg.train_read(B.TRAIN_DRAFT_LOGITS, n)
+    G = B.split_param_block(kg.train_read(B.TRAIN_GRADIENTS), shape)
+    Po = {k: v.astype(np.float64) for k, v in B.split_param_block(before, shape).items()}
+    head64 = I.bf16_bits_to_f32(W[(I.KIND_LM_HEAD, -1)]).astype(np.float64)
+    want, Go, inter = TR.loss_and_grads(Po, F, Zt, head64, shape.n_heads, shape.rms_eps, shape.rope_theta, adapter)
+    assert np.abs(Z - inter["Z"]).max() <= 1e-5 * max(1.0, np.abs(inter["Z"]).max())
+    assert abs(loss - want) <= 1e-5 * abs(want), (loss, want)
+    for k in TR.KIND_PARAMS[adapter]:
+        gmax = np.abs(Go[k]).max()
+        err = np.abs(G[k] - Go[k]).max()
+        print(f"7b-wide adapter {adapter} gradient {k}: max |g| {gmax:.3e}, max err {err:.3e}")
+        assert gmax > 0 and err <= 2e-4 * gmax, (k, err, gmax)
+    kg.close()
