@@ -857,6 +857,40 @@ __device__ __forceinline__ int attn_page(const AttnArgs &a, int s)
     return p;
 }
 
+// Lane exchanges of the softmax reductions as data-parallel-primitive moves (no trip through the
+// LDS crossbar as __shfl_xor takes).  All 64 lanes must be active.  quad_x1 / quad_x2: the value of
+// lane ^ 1 / lane ^ 2.  half_mirror / row_mirror: the value of the mirrored lane inside a group of
+// 8 / 16 lanes; where the value is already uniform over groups of 4 / 8 lanes that is the value
+// lane ^ 4 / lane ^ 8 holds, so a butterfly built from them gives every lane the bits the xor
+// butterfly gives.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float quad_x1(float v) { return dpp_move<0xB1>(v); }       // quad_perm [1,0,3,2]
+__device__ __forceinline__ float quad_x2(float v) { return dpp_move<0x4E>(v); }       // quad_perm [2,3,0,1]
+__device__ __forceinline__ float half_mirror(float v) { return dpp_move<0x141>(v); }
+__device__ __forceinline__ float row_mirror(float v) { return dpp_move<0x140>(v); }
+__device__ __forceinline__ float lane_value(float v, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+// max / sum over the wave of a value that is uniform over groups of 4 lanes, in the order of the
+// xor butterfly over offsets 4, 8, 16, 32 (the last two levels combine the four 16-lane rows as
+// (r0 . r1) . (r2 . r3), which is what every lane of that butterfly ends with)
+__device__ __forceinline__ float wave_max_q4(float v)
+{
+    v = fmaxf(v, half_mirror(v));
+    v = fmaxf(v, row_mirror(v));
+    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
+}
+__device__ __forceinline__ float wave_sum_q4(float v)
+{
+    v += half_mirror(v);
+    v += row_mirror(v);
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+
 // rotation of the pair (x0, x1) by the angle whose (cos, sin) is cs; written with explicit fused
 // operations so that every instantiation rounds alike
 __device__ __forceinline__ float rot_lo(float x0, float x1, float2 cs) { return fmaf(x0, cs.x, -__fmul_rn(x1, cs.y)); }
@@ -870,12 +904,12 @@ __device__ __forceinline__ float rot_hi(float x0, float x1, float2 cs) { return 
 // the 8 waves, then across pages; every level rescales by exp(max_part - max_all), in a fixed
 // order, so a row's result does not depend on the other rows of the batch or on trailing pages.
 template <typename T, int HD, bool BF, int MR>
-__global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a)
+__global__ __launch_bounds__(512, (sizeof(T) == 2 ? 6 : 1)) void attn_kernel(const AttnArgs a)
 {
     constexpr int EL = HD / 4;          // elements of one score lane
     constexpr int EPL = HD / 64;        // output elements of one P.V lane
     constexpr int HH = HD / 2;
-    __shared__ float qs[MR][HD];
+    __shared__ __align__(16) float qs[MR][HD];
     __shared__ float kn[MR][HD], vn[MR][HD];     // this call's k, v rows as the cache holds them
     __shared__ float ow[8][MR][HD];
     __shared__ float mw[8][MR], sw[8][MR];
@@ -920,6 +954,7 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a)
         for (int i = 0; i < 16; i++)
             if (wave * 16 + i < n_old) vreg[i].load(Vp + (size_t)(wave * 16 + i) * HD + EPL * lane);
     }
+    if (!has_row && t < MR * HH) { qs[rm][rj] = 0.f; qs[rm][rj + HH] = 0.f; }   // unused rows of the instantiation
     if (has_row) {
         const float qscale = rsqrtf((float)HD);
         qs[rm][rj] = rot_lo(q0, q1, cs) * qscale;
@@ -949,29 +984,43 @@ __global__ __launch_bounds__(512) void attn_kernel(const AttnArgs a)
     const int mk = p_begin + pl - pos0;
 
     // scores and wave-local softmax
-    float pr[MR];
+    // Every row's dot product runs over the lane's EL elements in ascending order; the cached keys
+    // are widened once per 4 elements and used for all rows (rows beyond M multiply zeros).
+    float pr[MR], dot[MR];
+#pragma unroll
+    for (int m = 0; m < MR; m++) dot[m] = 0.f;
+    if (k_new) {
+#pragma unroll
+        for (int m = 0; m < MR; m++)
+            if (m < M) {
+#pragma unroll
+                for (int i = 0; i < EL; i++) dot[m] = fmaf(kn[mk][sub * EL + i], qs[m][sub * EL + i], dot[m]);
+            }
+    } else if (k_old) {
+#pragma unroll
+        for (int i4 = 0; i4 < EL; i4 += 4) {
+            const float kf0 = kreg.get(i4), kf1 = kreg.get(i4 + 1), kf2 = kreg.get(i4 + 2), kf3 = kreg.get(i4 + 3);
+#pragma unroll
+            for (int m = 0; m < MR; m++) {
+                const float4 qv = *(const float4 *)&qs[m][sub * EL + i4];
+                dot[m] = fmaf(kf0, qv.x, dot[m]);
+                dot[m] = fmaf(kf1, qv.y, dot[m]);
+                dot[m] = fmaf(kf2, qv.z, dot[m]);
+                dot[m] = fmaf(kf3, qv.w, dot[m]);
+            }
+        }
+    }
 #pragma unroll
     for (int m = 0; m < MR; m++) {
         pr[m] = 0.f;
         if (m < M) {
-            float v = 0.f;
-            if (k_new) {
-#pragma unroll
-                for (int i = 0; i < EL; i++) v = fmaf(kn[mk][sub * EL + i], qs[m][sub * EL + i], v);
-            } else if (k_old) {
-#pragma unroll
-                for (int i = 0; i < EL; i++) v = fmaf(kreg.get(i), qs[m][sub * EL + i], v);
-            }
-            v += __shfl_xor(v, 1);
-            v += __shfl_xor(v, 2);
+            float v = dot[m];
+            v += quad_x1(v);
+            v += quad_x2(v);
             const float sc = (pl < n_valid && p_begin + pl <= pos0 + m) ? v : -INFINITY;
-            float mx = sc;
-#pragma unroll
-            for (int o = 4; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            const float mx = wave_max_q4(sc);
             const float p = (mx == -INFINITY) ? 0.f : __expf(sc - mx);
-            float sum = p;
-#pragma unroll
-            for (int o = 4; o < 64; o <<= 1) sum += __shfl_xor(sum, o);
+            const float sum = wave_sum_q4(p);
             pr[m] = p;
             if (lane == 0) { mw[wave][m] = mx; sw[wave][m] = sum; }
         }
