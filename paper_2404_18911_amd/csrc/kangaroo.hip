@@ -17,7 +17,7 @@
 namespace {
 
 constexpr size_t ALIGN = 256;
-constexpr int PF_ROWS_MAX = 256;     // prompt rows handled per pass of the prompt kernels
+constexpr int PF_ROWS_MAX = 1024;     // prompt rows handled per pass of the prompt kernels
 inline size_t up(size_t x, size_t a = ALIGN) { return (x + a - 1) / a * a; }
 
 struct LayerW {
