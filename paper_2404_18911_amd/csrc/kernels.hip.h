@@ -913,9 +913,11 @@ __global__ __launch_bounds__(512, (sizeof(T) == 2 ? 6 : 1)) void attn_kernel(con
     __shared__ float kn[MR][HD], vn[MR][HD];     // this call's k, v rows as the cache holds them
     __shared__ float ow[8][MR][HD];
     __shared__ float mw[8][MR], sw[8][MR];
+    __shared__ __align__(16) float pw[8][MR][16];   // a wave's probabilities [row][position]
     __shared__ int last_flag;
     const int h = blockIdx.x, s = blockIdx.y, zb = blockIdx.z, t = threadIdx.x;
-    const int wave = t >> 6, lane = t & 63;
+    // the wave index as a scalar: conditions on it (which positions a wave owns) become scalar branches
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
     const int P = a.P, d = a.d, logP = a.logP;
     const int pos0 = a.pos0 + 8 * zb;
     const int M = min(MR, a.M - 8 * zb);
@@ -1031,25 +1033,49 @@ __global__ __launch_bounds__(512, (sizeof(T) == 2 ? 6 : 1)) void attn_kernel(con
     for (int m = 0; m < MR; m++)
 #pragma unroll
         for (int e = 0; e < EPL; e++) acc[m][e] = 0.f;
+    // With 4 or 8 rows the wave passes its probabilities through a private LDS row and reads them
+    // back four positions at a time as broadcasts (one lane read per (position, row) otherwise:
+    // a third of this loop's vector instructions); the products and their order are the same.
+    if (MR >= 4) {
+        if ((lane & 3) == 0) {
 #pragma unroll
-    for (int i = 0; i < 16; i++) {
-        const int pv = wave * 16 + i;
-        if (pv < n_valid) {                                  // uniform in the wave
-            float vv[EPL];
-            if (pv >= n_old) {
+            for (int m = 0; m < MR; m++) pw[wave][m][lane >> 2] = pr[m];
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
 #pragma unroll
-                for (int e = 0; e < EPL; e++) vv[e] = vn[p_begin + pv - pos0][EPL * lane + e];
-            } else {
+    for (int i4 = 0; i4 < 16; i4 += 4) {
+        float4 p4[MR];
+        if (MR >= 4) {
 #pragma unroll
-                for (int e = 0; e < EPL; e++) vv[e] = vreg[i].get(e);
-            }
+            for (int m = 0; m < MR; m++) p4[m] = *(const float4 *)&pw[wave][m][i4];
+        }
 #pragma unroll
-            for (int m = 0; m < MR; m++)
-                if (m < M) {
-                    const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr[m]), 4 * i));
+        for (int j = 0; j < 4; j++) {
+            const int i = i4 + j;
+            const int pv = wave * 16 + i;
+            if (pv < n_valid) {                                  // uniform in the wave
+                float vv[EPL];
+                if (pv >= n_old) {
 #pragma unroll
-                    for (int e = 0; e < EPL; e++) acc[m][e] = fmaf(p, vv[e], acc[m][e]);
+                    for (int e = 0; e < EPL; e++) vv[e] = vn[p_begin + pv - pos0][EPL * lane + e];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPL; e++) vv[e] = vreg[i].get(e);
                 }
+#pragma unroll
+                for (int m = 0; m < MR; m++) {
+                    if (MR >= 4) {          // rows beyond M carry probability 0 and are not stored
+                        const float p = j == 0 ? p4[m].x : j == 1 ? p4[m].y : j == 2 ? p4[m].z : p4[m].w;
+#pragma unroll
+                        for (int e = 0; e < EPL; e++) acc[m][e] = fmaf(p, vv[e], acc[m][e]);
+                    } else if (m < M) {
+                        const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr[m]), 4 * i));
+#pragma unroll
+                        for (int e = 0; e < EPL; e++) acc[m][e] = fmaf(p, vv[e], acc[m][e]);
+                    }
+                }
+            }
         }
     }
 #pragma unroll
