@@ -914,6 +914,8 @@ __global__ __launch_bounds__(512, (sizeof(T) == 2 ? 6 : 1)) void attn_kernel(con
     __shared__ float ow[8][MR][HD];
     __shared__ float mw[8][MR], sw[8][MR];
     __shared__ __align__(16) float pw[8][MR][16];   // a wave's probabilities [row][position]
+    __shared__ __align__(16) float wtl[MR][8];      // weights of the wave merge [row][wave]
+    __shared__ float gml[MR];
     __shared__ int last_flag;
     const int h = blockIdx.x, s = blockIdx.y, zb = blockIdx.z, t = threadIdx.x;
     // the wave index as a scalar: conditions on it (which positions a wave owns) become scalar branches
@@ -1088,20 +1090,27 @@ __global__ __launch_bounds__(512, (sizeof(T) == 2 ? 6 : 1)) void attn_kernel(con
     // merge the 8 waves; a single page is final, otherwise store the page partial
     const bool single = S == 1;
     const size_t pidx = (size_t)hz * a.S + s;
+    // weight exp(max_wave - max_all) of every (row, wave), once per block: thread (m, w) = (t / 8, t % 8);
+    // a wave without a valid position gets weight 0 (its sums are 0 too)
+    if (t < 8 * MR) {
+        const float mv = mw[t & 7][t >> 3];
+        float gm = mv;
+        gm = fmaxf(gm, quad_x1(gm));
+        gm = fmaxf(gm, quad_x2(gm));
+        gm = fmaxf(gm, half_mirror(gm));
+        wtl[t >> 3][t & 7] = (mv == -INFINITY) ? 0.f : __expf(mv - gm);
+        if ((t & 7) == 0) gml[t >> 3] = gm;
+    }
+    __syncthreads();
     for (int i = t; i < M * HD; i += 512) {
         const int m = i / HD, e = i % HD;
-        float gm = mw[0][m];
-#pragma unroll
-        for (int w = 1; w < 8; w++) gm = fmaxf(gm, mw[w][m]);
+        const float gm = gml[m];
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int w = 0; w < 8; w++) {
-            const float mv = mw[w][m];
-            if (mv != -INFINITY) {
-                const float wt = __expf(mv - gm);
-                num = fmaf(wt, ow[w][m][e], num);
-                den = fmaf(wt, sw[w][m], den);
-            }
+            const float wt = wtl[m][w];
+            num = fmaf(wt, ow[w][m][e], num);
+            den = fmaf(wt, sw[w][m], den);
         }
         if (single) {
             store_act<BF>(act_out, d, m, h * HD + e, num / den);
