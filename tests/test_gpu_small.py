@@ -199,11 +199,13 @@ def test_sampling_plain_decoding_follows_oracle():
     kg.close()
 
 
-@pytest.mark.parametrize("name,n_prompt,page", [("toy_bf16", 300, 32), ("small_bf16", 77, 64), ("small_bf16", 264, 128)])
+@pytest.mark.parametrize("name,n_prompt,page", [("toy_bf16", 300, 32), ("small_bf16", 77, 64), ("small_bf16", 264, 128),
+                                                ("toy_bf16", 1100, 128)])
 def test_prompt_pass_is_bit_identical_to_one_token_decoding(name, n_prompt, page):
-    """The prompt goes through the dense MFMA projections in passes of 256 rows (groups of 64 rows,
-    blocks of 8, ragged tails here); every row must come out exactly as the one-token kernels
-    compute it: same caches in every layer, same logits for the first new token."""
+    """The prompt goes through the dense MFMA projections in passes of up to 1024 rows (groups of 64
+    rows, blocks of 8, ragged tails here; the 1100-token case takes two passes); every row must come
+    out exactly as the one-token kernels compute it: same caches in every layer, same logits for the
+    first new token."""
     from paper_2404_18911_amd import binding as B
     from tests import parity as P
     shape = I.SHAPES[name]
