@@ -294,7 +294,8 @@ int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Ep
     ProfScope ps(x, 0, (double)N * K * x->esz);
     if (x->bf)
         hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
-                           at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, (const u32x4_t *)act, e);
+                           at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, e.M, (const u32x4_t *)act, e.ssq_in, e.nt_in,
+                           e.N, e.kind == EPI_RESID ? e.res : nullptr, e.gain, e);
     else
         hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, x->stream, at<const float>(x->arena, w_off),
                            K, (const float *)act, e);
@@ -1838,7 +1839,7 @@ int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, i
         hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, (const int *)nullptr, xd, K, M,
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
         hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
-                           (const u32x4_t *)work, e);
+                           e.M, (const u32x4_t *)work, e.ssq_in, e.nt_in, e.N, (const float *)nullptr, e.gain, e);
     } else {
         hipLaunchKernelGGL(pack_rows_kernel<false>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, (const int *)nullptr, xd, K, M,
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);

@@ -103,15 +103,16 @@ __device__ __forceinline__ int b_slot(int lane) { return (((lane & 7) * 2 + ((la
 // fetched by scale_fetch at kernel start so that their latency hides behind the weight stream;
 // scale_finish reduces them.  Result valid after the next __syncthreads().
 struct ScaleRegs { float v[8]; };
-__device__ __forceinline__ void scale_fetch(const Epi &e, ScaleRegs &r)
+__device__ __forceinline__ void scale_fetch(const float *ssq_in, int M, int nt_in, ScaleRegs &r)
 {
     int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         int i = lane + 64 * j;
-        r.v[j] = (e.ssq_in && wave < e.M && i < e.nt_in) ? e.ssq_in[(size_t)i * KG_ROWS + wave] : 0.f;
+        r.v[j] = (ssq_in && wave < M && i < nt_in) ? ssq_in[(size_t)i * KG_ROWS + wave] : 0.f;
     }
 }
+__device__ __forceinline__ void scale_fetch(const Epi &e, ScaleRegs &r) { scale_fetch(e.ssq_in, e.M, e.nt_in, r); }
 __device__ __forceinline__ void scale_finish(const Epi &e, const ScaleRegs &r, float *sc)
 {
     int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -249,8 +250,14 @@ __device__ __forceinline__ void gemv_steps(const u32x4_t *&wp, const u32x4_t *&b
 
 #define GEMV_WAVES 8
 
-__global__ __launch_bounds__(64 * GEMV_WAVES, 2) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS,
-                                                                   const u32x4_t *__restrict__ act, Epi e)
+// Everything a wave needs before its first weight load is a leading scalar argument (a copy of the
+// fields of e named alike): those arrive preloaded in SGPRs, a field of the by-value struct costs a
+// scalar load from the argument block at the start of every launch.
+// 14 dwords fit: W, KS, M, act, ssq_in, nt_in, N, res (null unless the epilogue adds a residual), gain.
+__global__ __launch_bounds__(64 * GEMV_WAVES, 2) void gemv_bf16_kernel(const u32x4_t *__restrict__ W, int KS, int M,
+                                                                   const u32x4_t *__restrict__ act,
+                                                                   const float *ssq_in, int nt_in, int N,
+                                                                   const float *res, const float *gain, Epi e)
 {
     __shared__ float part[GEMV_WAVES][16][KG_ROWS];
     __shared__ float yt[16][KG_ROWS];
@@ -261,15 +268,15 @@ __global__ __launch_bounds__(64 * GEMV_WAVES, 2) void gemv_bf16_kernel(const u32
     const int ks0 = (wave * KS) / GEMV_WAVES, ks1 = ((wave + 1) * KS) / GEMV_WAVES;
     const u32x4_t *wp = W + ((size_t)rt * KS + ks0) * 64 + lane;
     const u32x4_t *bp = act + (size_t)ks0 * 64 + b_slot(lane);
-    const bool bact = (lane & 7) < e.M;
+    const bool bact = (lane & 7) < M;
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     ScaleRegs sr;
-    scale_fetch(e, sr);
+    scale_fetch(ssq_in, M, nt_in, sr);
     float resv = 0.f, gainv = 1.f;       // epilogue operands of thread (row, m), fetched early
-    if (e.kind == EPI_RESID && threadIdx.x < 128 && (threadIdx.x & 7) < e.M) {
+    if (res && threadIdx.x < 128 && (threadIdx.x & 7) < M) {
         int nn = rt * 16 + (threadIdx.x >> 3);
-        resv = e.res[(size_t)(threadIdx.x & 7) * e.N + nn];
-        if (e.gain) gainv = e.gain[nn];
+        resv = res[(size_t)(threadIdx.x & 7) * N + nn];
+        if (gain) gainv = gain[nn];
     }
     int n = ks1 - ks0;
     {
