@@ -307,6 +307,7 @@ int launch_pack_rows(kg_ctx *x, const int *tokens, const float *rows, int M, con
 {
     Tok8 tk;
     for (int i = 0; i < KG_ROWS; i++) tk.t[i] = (tokens && i < M) ? tokens[i] : 0;
+    tk.vocab = x->c.vocab;
     const void *emb = (tokens || tok_dev) ? (const void *)(x->arena + x->embed) : nullptr;
     const int d = x->c.d_model;
     ProfScope ps(x, 2, 0.0);
@@ -381,6 +382,7 @@ int launch_pf_pack(kg_ctx *x, const int *tok_dev, const float *rows, int T, cons
     const int d = x->c.d_model, nb = (T + KG_ROWS - 1) / KG_ROWS;
     Tok8 tk;
     memset(&tk, 0, sizeof(tk));
+    tk.vocab = x->c.vocab;
     const void *emb = tok_dev ? (const void *)(x->arena + x->embed) : nullptr;
     ProfScope ps(x, 2, 0.0);
     hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(d / 16, nb), dim3(128), 0, x->stream, emb, tk, tok_dev, rows, d, T, gain,
@@ -588,14 +590,22 @@ int uniform_at(kg_ctx *x, const kg_params *p, int pos, int purpose, float *out)
     return KG_OK;
 }
 
+// a token outside the vocabulary means the logits were not finite (the arg-max found no maximum)
+int check_tokens(kg_ctx *x, int n)
+{
+    for (int i = 0; i < n; i++)
+        if (x->h_tok[i] < 0 || x->h_tok[i] >= x->c.vocab)
+            return fail(x, KG_EHIP, "row %d: the LM head produced no valid token (non-finite logits)", i);
+    return KG_OK;
+}
+
 int fetch_results(kg_ctx *x, int n)
 {
-    (void)n;
     prof_flush(x);
     HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, KG_ROWS * 8, hipMemcpyDeviceToHost, x->stream));
     HIPCHK(x, hipStreamSynchronize(x->stream));
     if (x->profiling) prof_collect(x);
-    return KG_OK;
+    return check_tokens(x, n);
 }
 
 float *Frow(kg_ctx *x, int j) { return at<float>(x->scr, x->s_F) + (size_t)(j + 1) * x->c.d_model; } // f_j
@@ -1006,6 +1016,7 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     KGCHK(run_shallow(x, nullptr, 1, pos + 1, j + 1, at<const int>(x->scr, x->s_tok)));
     x->spec_shallow = j + 1;
     HIPCHK(x, hipEventSynchronize(ev));
+    KGCHK(check_tokens(x, 1));
     x->lag = 0;
     x->adapter_len = pos + 1;
     x->drafts[j] = x->h_tok[0];
@@ -1075,6 +1086,8 @@ int kg_accept(kg_ctx *x, const kg_params *p, int32_t *emitted, int *n_emitted)
         if (x->profiling) prof_collect(x);
         n = x->h_tok[0];
         if (n < 0 || n > k) return fail(x, KG_EHIP, "acceptance kernel returned %d accepted drafts of %d", n, k);
+        if (x->h_tok[1] < 0 || x->h_tok[1] >= x->c.vocab)
+            return fail(x, KG_EHIP, "acceptance kernel drew no valid token (non-finite logits)");
         for (int i = 0; i < n; i++) emitted[i] = x->drafts[i];
         emitted[n] = x->h_tok[1];
     }

@@ -673,7 +673,7 @@ __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1_cb4(PfArgs a, Epi
 // Rows -> activation for the first projection of a stack: x[m] = E[tok[m]] (emb != null) or the
 // given fp32 rows; writes xout (optional), act = x * gain (hi/lo), ssq[tile][m].  One block per
 // 16 features.
-struct Tok8 { int t[KG_ROWS]; };
+struct Tok8 { int t[KG_ROWS]; int vocab; };   // token ids given by the host; vocab bounds the ids read from device memory too
 
 template <bool BF>
 __global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 tok, const int *tok_dev,
@@ -699,7 +699,11 @@ __global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 to
     float v = 0.f;
     if (m < M) {
         if (emb) {
-            size_t idx = (size_t)(tok_dev ? tok_dev[m] : tok.t[m]) * d + n;   // token ids from the host or from device memory
+            // token ids from the host or from device memory; an id a kernel produced from non-finite
+            // logits may be anything: it is clamped so that the gather stays inside the table (the host
+            // reports the bad token)
+            const int id = min(max(tok_dev ? tok_dev[m] : tok.t[m], 0), tok.vocab - 1);
+            size_t idx = (size_t)id * d + n;
             v = BF ? bf2f(((const uint16_t *)emb)[idx]) : ((const float *)emb)[idx];
         } else {
             v = rows[(size_t)m * d + n];
