@@ -52,7 +52,7 @@ struct TrGemm {
 
 __device__ __forceinline__ size_t packed_u16_index(int row, int col, int KS)
 {
-    return ((((size_t)(row >> 4) * KS + (col >> 5)) * 64 + ((col >> 3) & 3) * 16 + (row & 15)) << 3) + (col & 7);
+    return ((((size_t)(row >> 4) * KS + tile_pos(col >> 5, KS)) * 64 + ((col >> 3) & 3) * 16 + (row & 15)) << 3) + (col & 7);
 }
 
 __global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void tr_gemm_kernel(const TrGemm g)
             // four consecutive columns (k) of rows n, n + 64 of the tiled matrix: 8 bytes each, 8-byte aligned;
             // N, K and k_chunk are multiples of 8, so the four share the bounds verdict
             const int col = k0 + bk;
-            const size_t cpart = (size_t)(col >> 5) * 64 + ((col >> 3) & 3) * 16;
+            const size_t cpart = (size_t)tile_pos(col >> 5, g.b_KS) * 64 + ((col >> 3) & 3) * 16;
             const bool k_ok = col < k_hi;
             uint2 r0 = make_uint2(0u, 0u), r1 = make_uint2(0u, 0u);
             if (k_ok && n0 + bn < g.N) r0 = *(const uint2 *)(Bp + ((rb0 + cpart) << 3) + (col & 7));
