@@ -291,6 +291,11 @@ int kg_op_gemm_f32(const float *A_dev, long sam, long sak, const float *B_dev, l
  *                 device scratch; M <= KG_MAX_ROWS.  Launches on `hip_stream`, does not synchronise.
  */
 size_t kg_op_packed_bytes(int dtype, int N, int K);
+/* Position (0 .. KS-1) of k-step ks among the KS = ceil(K / 32) weight tiles of one 16-row tile in
+ * the packed bf16 form: the tiles are stored in the order the projection workgroup reads them (its
+ * eight waves own contiguous k ranges and walk them in step).  Host arithmetic only, no GPU: the
+ * tests check that it is a permutation for every KS.  Returns -1 unless 0 <= ks < KS. */
+int kg_op_tile_pos(int ks, int KS);
 size_t kg_op_work_bytes(int K);
 int kg_op_pack(int dtype, const void *src_dev, int N, int K, void *packed_dev, void *hip_stream);
 int kg_op_linear(int dtype, const void *packed_dev, int N, int K, const float *x_dev, int M, float *y_dev,

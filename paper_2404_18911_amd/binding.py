@@ -53,7 +53,7 @@ SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "k
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
            "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_stream_read",
            "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_accumulate", "kg_train_apply", "kg_train_features", "kg_train_accumulate_features",
-           "kg_train_read", "kg_op_gemm_f32"]
+           "kg_train_read", "kg_op_gemm_f32", "kg_op_tile_pos"]
 
 _lib = None
 
@@ -109,6 +109,8 @@ def lib() -> ctypes.CDLL:
     L.kg_train_features.argtypes = [vp, ip, ctypes.c_int, vp, vp]
     L.kg_train_accumulate_features.argtypes = [vp, vp, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     L.kg_train_read.argtypes = [vp, ctypes.c_int, fp, ctypes.c_size_t]
+    L.kg_op_tile_pos.argtypes = [ctypes.c_int, ctypes.c_int]
+    L.kg_op_tile_pos.restype = ctypes.c_int
     L.kg_op_gemm_f32.argtypes = [vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long, ctypes.c_long, vp, ctypes.c_long,
                                  ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
     _lib = L

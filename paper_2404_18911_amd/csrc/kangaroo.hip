@@ -1816,6 +1816,12 @@ int kg_op_gemm_f32(const float *A, long sam, long sak, const float *B, long sbk,
 // ---- stand-alone projection ---------------------------------------------------------------------
 
 size_t kg_op_packed_bytes(int dtype, int N, int K) { return packed_bytes(dtype == 1, N, K); }
+int kg_op_tile_pos(int ks, int KS)
+{
+    if (KS < 1 || ks < 0 || ks >= KS) return -1;
+    return tile_pos(ks, KS);
+}
+
 size_t kg_op_work_bytes(int K) { return up(act_bytes(K)) ; }
 
 int kg_op_pack(int dtype, const void *src, int N, int K, void *packed, void *hip_stream)

@@ -188,3 +188,24 @@ def test_algorithmic_bytes_of_the_benchmark_match_the_shapes():
     assert draft[1] == draft[0]                                   # an own head replaces the shared one byte for byte
     assert draft[2] - draft[0] == 3 * d * f * 2                   # the block's feed-forward
     assert draft[0] - draft[3] == 2 * d * d * 2                   # two maps instead of four
+
+
+def test_weight_tile_order_is_a_permutation_that_follows_the_waves():
+    """The packed bf16 form stores a row tile's KS tiles in the order the projection workgroup
+    reads them.  For every KS the map must be a permutation of 0..KS-1 (or tiles would be lost or
+    written twice), and wave w, which sums the contiguous k range [w KS / 8, (w + 1) KS / 8), must
+    find its i-th tile next to the other waves' i-th tiles: 8 tiles apart from its previous one, with
+    the first tile of the one-longer ranges in front."""
+    L = B.lib()
+    for KS in list(range(1, 130)) + [160, 208, 344, 432, 560, 1000]:
+        pos = [L.kg_op_tile_pos(ks, KS) for ks in range(KS)]
+        assert sorted(pos) == list(range(KS)), KS
+        q, n_long = KS // 8, KS % 8
+        for w in range(8):
+            ks0, ks1 = (w * KS) // 8, ((w + 1) * KS) // 8
+            mine = pos[ks0:ks1]
+            regular = mine[1:] if ks1 - ks0 > q else mine
+            assert regular == [n_long + w + 8 * j for j in range(q)], (KS, w)
+            if ks1 - ks0 > q:
+                assert 0 <= mine[0] < n_long, (KS, w)
+    assert L.kg_op_tile_pos(-1, 8) == -1 and L.kg_op_tile_pos(8, 8) == -1 and L.kg_op_tile_pos(0, 0) == -1
