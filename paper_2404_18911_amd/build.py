@@ -19,17 +19,29 @@ def stale() -> bool:
     return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
 
 
+_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17",
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          # leading scalar kernel arguments arrive in SGPRs at wave start (no scalar load before the
+          # first weight address can be formed)
+          "-mllvm", "-amdgpu-kernarg-preload-count=16",
+          "-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_HERE, "csrc")]
+
+
+def device_asm(out_path: str) -> str:
+    """The device code of the library as gfx950 assembly, with the flags of build() (for checks of
+    the generated code; nothing runs it)."""
+    cmd = ["hipcc"] + _FLAGS + ["--cuda-device-only", "-S", "-o", out_path] + SOURCES
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return out_path
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile the library for gfx950.  Packed-FP32 instruction selection is switched off."""
     if not force and not stale():
         return LIB
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           # leading scalar kernel arguments arrive in SGPRs at wave start (no scalar load before the
-           # first weight address can be formed)
-           "-mllvm", "-amdgpu-kernarg-preload-count=16",
-           "-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_HERE, "csrc"),
-           "-o", LIB] + SOURCES
+    cmd = ["hipcc"] + _FLAGS + ["-fPIC", "-shared", "-o", LIB] + SOURCES
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)

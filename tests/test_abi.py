@@ -209,3 +209,35 @@ def test_weight_tile_order_is_a_permutation_that_follows_the_waves():
             if ks1 - ks0 > q:
                 assert 0 <= mine[0] < n_long, (KS, w)
     assert L.kg_op_tile_pos(-1, 8) == -1 and L.kg_op_tile_pos(8, 8) == -1 and L.kg_op_tile_pos(0, 0) == -1
+
+
+def test_no_matrix_instruction_sits_in_an_exec_masked_region_without_a_skip_branch(tmp_path):
+    """An MFMA ignores the EXEC mask, and the compiler drops the skip branch around a short
+    exec-masked region: an `if` on a per-lane copy of a wave-uniform condition that holds nothing
+    but an MFMA then runs it also in the waves where the condition is false, on registers they never
+    loaded (this once put NaNs into a few logits).  Scan the generated gfx950 code of every kernel:
+    walking back from each MFMA, a branch, a label or the end of a masked region must come before
+    any instruction that narrows EXEC."""
+    import re
+    import shutil
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not available")
+    from paper_2404_18911_amd import build as BLD
+    asm = open(BLD.device_asm(str(tmp_path / "kangaroo.s"))).read()
+    kernels = re.findall(r"^(_Z\w+):", asm, flags=re.M)
+    assert any("gemv_bf16_kernel" in k for k in kernels) and any("gemm_prefill" in k for k in kernels)
+    n_mfma = 0
+    for name in kernels:
+        i = asm.index(name + ":")
+        j = asm.find(".Lfunc_end", i)
+        lines = [l.strip() for l in asm[i:j].split("\n") if l.strip() and not l.strip().startswith(";")]
+        for k, line in enumerate(lines):
+            if not line.startswith("v_mfma"):
+                continue
+            n_mfma += 1
+            for kk in range(k - 1, -1, -1):
+                p = lines[kk]
+                assert not p.startswith(("s_and_saveexec", "s_andn2_saveexec", "s_or_saveexec")), (name, k, p)
+                if p.startswith(("s_cbranch", "s_branch", "s_or_b64 exec", "s_endpgm")) or p.endswith(":"):
+                    break
+    assert n_mfma > 20
