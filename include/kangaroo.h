@@ -128,7 +128,14 @@ int kg_stats_ctar(const kg_stats *st, int w, double *ctar);
 int kg_create(const kg_config *cfg, kg_ctx **out);
 
 /* Bytes the caller must provide to kg_bind: the arena that will hold the re-tiled weights, the KV
- * pool (n_layers + 1 caches: one per decoder layer plus the adapter's), and scratch. */
+ * pool (n_layers + 1 caches: one per decoder layer plus the adapter's), and scratch.
+ * Layout of the KV pool, in elements of kv_dtype, row-major:
+ *   [physical page][cache 0..n_layers][head][0 = keys, 1 = values][position in page][head_dim],
+ * with ceil(max_seq / kv_page_tokens) pages; logical page i (positions i * kv_page_tokens ..) lives in
+ * physical page perm[i] of kg_set_page_order (default i); keys are stored after the rotary embedding.
+ * Between rounds (after kg_prefill or kg_accept, before the next kg_draft_step) only positions
+ * below the committed length (kg_get_state: base; adapter_len for the adapter's cache) will ever be
+ * read again: a caller may overwrite everything beyond them at that point. */
 int kg_workspace_bytes(const kg_ctx *ctx, size_t *weight_bytes, size_t *kv_bytes, size_t *scratch_bytes);
 
 /* Bind caller-owned device memory (256-byte aligned, at least the sizes above; all BORROWED until
@@ -177,8 +184,10 @@ int kg_generate(kg_ctx *ctx, const kg_params *p, const int32_t *prompt_host, int
 int kg_decode_plain(kg_ctx *ctx, const kg_params *p, const int32_t *prompt_host, int n_prompt, int max_new,
                     int32_t *out, int *n_out, kg_stats *stats);
 
-/* One plain step after kg_prefill (or after earlier plain steps): feed `token` at the next
- * position through all layers and return the next token.  Lets a caller force the token stream. */
+/* One plain step after kg_prefill, after earlier plain steps, or after a kg_accept: feed `token` at
+ * the next uncommitted position (the pending token's) through all layers and return the next token.
+ * Lets a caller force the token stream.  After a plain step the adapter's cache is no longer in step
+ * with the sequence: draft calls return KG_ESTATE until the next kg_prefill. */
 int kg_plain_step(kg_ctx *ctx, const kg_params *p, int32_t token, int32_t *next_token);
 
 /* Copy one row of the most recent logits to the host (float[vocab]).  which = 0: draft logits of
@@ -186,7 +195,9 @@ int kg_plain_step(kg_ctx *ctx, const kg_params *p, int32_t token, int32_t *next_
  * verify / prefill / plain step. */
 int kg_read_logits(kg_ctx *ctx, int which, int row, float *host_out);
 
-/* Copy the early feature f_row of the current round (float[d_model]) to the host. */
+/* Copy the early feature f_row of the current round (float[d_model]) to the host: row = 0..KG_MAX_ROWS-1,
+ * or row = -1 for the lagged feature (Figure 2: the early feature of the last accepted token that the
+ * adapter has not seen yet; meaningful while kg_get_state reports lag = 1).  Other rows: KG_EINVAL. */
 int kg_read_feature(kg_ctx *ctx, int row, float *host_out);
 
 /* Copy the cached key and value vectors (float[d_model] each, widened from the cache type) of

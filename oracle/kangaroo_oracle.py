@@ -47,13 +47,17 @@ A_HEAD, A_NORM_POST, A_WG, A_WU, A_WD, A_W1, A_W2 = range(18, 25)   # the other 
 U_DRAFT, U_ACCEPT, U_RESAMPLE = 0, 1, 2
 
 
-def build(force: bool = False) -> str:
-    """Compile kangaroo_ref.c with gcc (portable AVX2 target so the library also runs elsewhere)."""
-    src = os.path.join(_HERE, "kangaroo_ref.c")
-    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
-        subprocess.check_call(["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-shared", "-fPIC",
-                               "-o", _SO, src, "-lm"])
-    return _SO
+SOURCES = [os.path.join(_HERE, "kangaroo_ref.c"), os.path.join(_HERE, "philox_ref.c")]
+
+
+def build(force: bool = False, out: Optional[str] = None, extra_flags: Sequence[str] = ()) -> str:
+    """Compile the C sources with gcc (portable AVX2 target so the library also runs elsewhere).
+    `out` / `extra_flags` build a second copy with other flags (the sanitizer build of the tests)."""
+    so = out or _SO
+    if force or not os.path.exists(so) or any(os.path.getmtime(so) < os.path.getmtime(s) for s in SOURCES):
+        subprocess.check_call(["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-shared", "-fPIC", *extra_flags,
+                               "-o", so, *SOURCES, "-lm"])
+    return so
 
 
 class _Cfg(ctypes.Structure):
@@ -96,6 +100,10 @@ def lib():
         _lib.ko_round_bf16.argtypes = [ctypes.c_double]
         _lib.ko_matvec.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp,
                                    ctypes.c_int, dp]
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        _lib.ko_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        _lib.ko_philox_words.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int, u32p]
+        _lib.ko_philox_uniforms.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
     return _lib
 
 
@@ -194,6 +202,31 @@ class OracleModel:
 
     def kv_poison(self, frm: int) -> None:
         lib().ko_kv_poison(self._h, frm)
+
+
+# ----------------------------------------------------------------------------- random numbers
+
+def philox4x32_10(counter: Sequence[int], key: Sequence[int]) -> List[int]:
+    """One block of Philox4x32-10 (philox_ref.c)."""
+    c = (ctypes.c_uint32 * 4)(*counter)
+    k = (ctypes.c_uint32 * 2)(*key)
+    o = (ctypes.c_uint32 * 4)()
+    lib().ko_philox4x32_10(c, k, o)
+    return list(o)
+
+
+def philox_words(seed: int, pos0: int, purpose: int, n: int) -> np.ndarray:
+    out = np.empty(n, dtype=np.uint32)
+    lib().ko_philox_words(seed, pos0, purpose, n, out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)))
+    return out
+
+
+def philox_uniforms(seed: int, n_positions: int) -> np.ndarray:
+    """float32 [n_positions][3] in [0, 1): the uniform number of every (absolute position, purpose)
+    for a seed, u = (first Philox word >> 8) * 2^-24 (philox_ref.c)."""
+    u = np.empty((n_positions, 3), dtype=np.float32)
+    lib().ko_philox_uniforms(seed, n_positions, u.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    return u
 
 
 # ----------------------------------------------------------------------------- distributions
@@ -312,13 +345,22 @@ class KangarooDecoder:
         self.target_logits: Optional[np.ndarray] = None
         self.stopped = False
 
-    # -- prefill: the full model and the adapter see the whole prompt; first token is the target's
-    def prefill(self, prompt: Sequence[int]) -> int:
+    # -- prefill: the full model and the adapter see the whole prompt; first token is the target's.
+    #    `chunk` feeds the prompt rows through in pieces of that many rows: with the caches in place
+    #    a row's arithmetic does not depend on how many rows travel with it (pinned by the
+    #    mixed-row-count test), so this only bounds the size of the temporaries for long prompts;
+    #    `progress(rows_done)` is called after each piece.
+    def prefill(self, prompt: Sequence[int], chunk: Optional[int] = None, progress=None) -> int:
         T = len(prompt)
-        f = self.m.shallow(prompt, 0)
-        self.m.adapter(f, 0)                       # fills the adapter's cache; outputs unused
-        x = self.m.deep(f, 0)
-        z = self.m.head(x[-1:], 0)[0]
+        step = T if not chunk else int(chunk)
+        x_last = None
+        for lo in range(0, T, step):
+            f = self.m.shallow(prompt[lo:lo + step], lo)
+            self.m.adapter(f, lo)                  # fills the adapter's cache; outputs unused
+            x_last = self.m.deep(f, lo)[-1:]
+            if progress is not None:
+                progress(min(T, lo + step))
+        z = self.m.head(x_last, 0)[0]
         self.prefill_logits = z
         self.base, self.adapter_len, self.lag = T, T, None
         if self.mode == "greedy":

@@ -178,6 +178,7 @@ class Kangaroo:
         self.kv = torch.empty(kb.value, dtype=torch.uint8, device=self.device)
         self.scratch = torch.empty(sb.value, dtype=torch.uint8, device=self.device)
         self.stream = torch.cuda.current_stream(self.device)
+        self.page_order = list(range((max_seq + kv_page_tokens - 1) // kv_page_tokens))
         self._chk(self.L.kg_bind(self.h, self.arena.data_ptr(), wb.value, self.kv.data_ptr(), kb.value,
                                  self.scratch.data_ptr(), sb.value, self.stream.cuda_stream))
 
@@ -210,6 +211,7 @@ class Kangaroo:
     def set_page_order(self, perm: Sequence[int]) -> None:
         a = np.ascontiguousarray(perm, dtype=np.int32)
         self._chk(self.L.kg_set_page_order(self.h, a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(a)))
+        self.page_order = a.tolist()
 
     # -- stepwise calls
     def prefill(self, params: kg_params, prompt: Sequence[int]) -> int:

@@ -1101,6 +1101,7 @@ int kg_accept(kg_ctx *x, const kg_params *p, int32_t *emitted, int *n_emitted)
         HIPCHK(x, hipMemcpyAsync(Flag(x), Frow(x, k), (size_t)x->c.d_model * 4, hipMemcpyDeviceToDevice, x->stream));
     }
     x->pending = emitted[n];
+    x->plain_len = x->base;      // a plain step after this round continues the committed sequence
     x->n_drafts = 0; x->stopped = 0;
     x->phase = Phase::READY;
     return KG_OK;
@@ -1219,7 +1220,7 @@ int kg_read_feature(kg_ctx *x, int row, float *host_out)
 {
     if (!x || !host_out) return KG_EINVAL;
     if (!x->bound) return fail(x, KG_ESTATE, "not bound");
-    if (row < -1 || row >= KG_ROWS) return fail(x, KG_EINVAL, "feature row out of range");
+    if (row < -1 || row >= KG_ROWS) return fail(x, KG_EINVAL, "feature row outside -1..%d", KG_ROWS - 1);
     HIPCHK(x, hipMemcpyAsync(host_out, Frow(x, row), (size_t)x->c.d_model * 4, hipMemcpyDeviceToHost, x->stream));
     HIPCHK(x, hipStreamSynchronize(x->stream));
     return KG_OK;
@@ -1771,7 +1772,12 @@ int kg_train_step(kg_ctx *x, const kg_train_params *hp, const int32_t *tokens, i
 {
     if (!x) return KG_EINVAL;
     KGCHK(check_train_params(x, hp));
-    x->tr_pending = 0;                          // a step starts from its own gradient
+    // a step starts from its own gradient; a call that is refused leaves what was accumulated alone
+    KGCHK(check_ready(x));
+    if (!x->tr) return fail(x, KG_ESTATE, "kg_train_bind has not been called");
+    if (!tokens || !loss) return fail(x, KG_EINVAL, "NULL argument");
+    if (n < 1 || n > x->tr_T) return fail(x, KG_EINVAL, "%d tokens outside 1..%d", n, x->tr_T);
+    x->tr_pending = 0;
     KGCHK(kg_train_accumulate(x, tokens, n, loss));
     return kg_train_apply(x, hp);
 }

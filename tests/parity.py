@@ -43,13 +43,17 @@ class Follow:
             self.exceptions += 1
 
 
-def follow_kangaroo(kg, model, prompt, n_new, gamma, eta, fol: Follow):
+def follow_kangaroo(kg, model, prompt, n_new, gamma, eta, fol: Follow, after_commit=None, chunk=None):
     """Run the GPU stepwise for n_new tokens with the oracle following.  Returns the GPU stream and
-    the per-round records [(k, n)]."""
+    the per-round records [(k, n)].  after_commit(kg) is called after the prefill and after every
+    accept (the points where the committed length changes); chunk: the oracle takes the prompt in
+    pieces of that many rows."""
     p, _ = B.make_params(mode=0, eta=eta, gamma=gamma)
     dec = O.KangarooDecoder(model, gamma=gamma, eta=eta)
     t = kg.prefill(p, prompt)
-    dec.prefill(prompt)
+    if after_commit:
+        after_commit(kg)
+    dec.prefill(prompt, chunk=chunk)
     fol.logits(kg.read_logits(1, 0), dec.prefill_logits, "prefill")
     fol.token(t, dec.prefill_logits, "prefill token")
     dec.pending = t
@@ -80,9 +84,28 @@ def follow_kangaroo(kg, model, prompt, n_new, gamma, eta, fol: Follow):
         assert em == oem
         base, alen, lag, nd = kg.state()
         assert (base, alen, bool(lag), nd) == (dec.base, dec.adapter_len, dec.lag is not None, 0)
+        if after_commit:
+            after_commit(kg)
         rounds.append((dec.rounds[-1]["k"], dec.rounds[-1]["n"]))
         out += em
     return out, rounds
+
+
+def poison_kv_tail(kg, frm):
+    """Overwrite every entry of the caller-owned KV pool at positions >= frm, in every cache, with
+    NaN, so that a read of anything that is not committed shows up in the logits.  Pool layout (as
+    include/kangaroo.h documents it): [physical page][cache][head][K|V][position in page][head_dim]."""
+    import torch
+    c = kg.cfg
+    P, hd, H, slots = c.kv_page_tokens, c.head_dim, c.n_heads, c.n_layers + 1
+    n_pages = (c.max_seq + P - 1) // P
+    dt = torch.bfloat16 if c.kv_dtype == 1 else torch.float32
+    n = n_pages * slots * H * 2 * P * hd
+    pool = kg.kv.view(dt)[:n].view(n_pages, slots, H, 2, P, hd)
+    for lp in range(frm // P, n_pages):
+        lo = max(0, frm - lp * P)
+        pool[kg.page_order[lp], :, :, :, lo:, :] = float("nan")
+    torch.cuda.synchronize()
 
 
 def follow_plain(kg, model, prompt, n_new, fol: Follow):
@@ -110,7 +133,7 @@ def _cdf_valid(p, tok, u, ctol):
     return (lo - ctol <= u < c[tok] + ctol) and (p[tok] > 0.0 or ctol > 0.0)
 
 
-def follow_kangaroo_sampling(kg, model, prompt, n_new, gamma, eta, temperature, U, fol: Follow, ctol):
+def follow_kangaroo_sampling(kg, model, prompt, n_new, gamma, eta, temperature, U, fol: Follow, ctol, chunk=None):
     """Sampling mode (speculative rejection sampling) with the oracle following.  Every GPU decision
     is checked against the oracle's quantities for the same uniform numbers: a drawn token must be
     the inverse-CDF result up to ctol on the cumulative sums, an accept / reject must be on the
@@ -119,7 +142,7 @@ def follow_kangaroo_sampling(kg, model, prompt, n_new, gamma, eta, temperature, 
     p, keep = B.make_params(mode=1, temperature=temperature, eta=eta, gamma=gamma, uniforms=U)
     dec = O.KangarooDecoder(model, gamma=gamma, eta=eta, mode="sample", temperature=temperature, uniforms=U)
     t = kg.prefill(p, prompt)
-    own = dec.prefill(prompt)
+    own = dec.prefill(prompt, chunk=chunk)
     fol.logits(kg.read_logits(1, 0), dec.prefill_logits, "prefill")
     assert _cdf_valid(O.softmax(dec.prefill_logits, temperature), t, float(U[len(prompt), O.U_RESAMPLE]), ctol)
     fol.decisions += 1
@@ -177,3 +200,170 @@ def follow_kangaroo_sampling(kg, model, prompt, n_new, gamma, eta, temperature, 
         rounds.append((k, n))
         out += em
     return out, rounds
+
+
+# ------------------------------------------------------------------------------------------------
+# Full-size requests: the oracle's results come from a stored stream (tests/golden/oracle_streams,
+# written by tests/golden/make_oracle_streams.py from the oracle alone), the GPU walks the request.
+
+class StreamRecord:
+    """One stored oracle stream: records by absolute position (see make_oracle_streams.py)."""
+
+    def __init__(self, path):
+        import json
+        with np.load(path, allow_pickle=False) as z:
+            self.a = {k: z[k] for k in z.files}
+        self.meta = json.loads(str(self.a["meta"]))
+        self.stream = self.a["stream"].tolist()
+        self.sample_ids = self.a["sample_ids"]
+        self.T = {int(p): i for i, p in enumerate(self.a["t_pos"])}
+        self.D = {int(p): i for i, p in enumerate(self.a["d_pos"])}
+        self.rounds = list(zip(self.a["round_base"].tolist(), self.a["round_k"].tolist(), self.a["round_n"].tolist()))
+
+    def row(self, kind, pos):
+        """(top ids, top logits, sampled logits, lse) of the target ('t') / draft ('d') row that
+        predicts position pos, or None."""
+        i = (self.T if kind == "t" else self.D).get(pos)
+        if i is None:
+            return None
+        return (self.a[kind + "_top_ids"][i], self.a[kind + "_top"][i], self.a[kind + "_samples"][i].astype(np.float64),
+                float(self.a[kind + "_lse"][i]))
+
+    def conf(self, pos):
+        return float(self.a["d_conf"][self.D[pos]])
+
+
+def check_probe(rec: StreamRecord, model, prompt, tol=1e-9):
+    """The stored file belongs to this oracle and these weights: the live oracle recomputes the
+    probe record (target logits after the first few prompt tokens only)."""
+    pd = O.PlainDecoder(model)
+    pd.prefill(prompt[:rec.meta["probe_len"]])
+    z = pd.last_logits
+    assert np.array_equal(np.lexsort((np.arange(z.size), -z))[:len(rec.a["probe_top_ids"])], rec.a["probe_top_ids"])
+    assert np.max(np.abs(z[rec.a["probe_top_ids"]] - rec.a["probe_top"])) <= tol
+    assert np.max(np.abs(z[rec.sample_ids] - rec.a["probe_samples"])) <= tol
+
+
+class CachedFollow(Follow):
+    def __init__(self, logit_tol, conf_tol=None):
+        super().__init__(logit_tol, conf_tol)
+        self.rows_t = self.rows_d = 0          # rows compared with a stored record
+        self.rows_off = 0                      # rows whose context was not the stored stream (not comparable)
+        self.rows_norec = 0                    # on-stream draft rows the oracle's run never computed
+        self.resyncs = 0
+        self.max_lse_err = 0.0
+
+    def row(self, got, want, what):
+        """GPU logits row against a stored record: its four largest entries, the sampled entries,
+        and the log-sum-exp of the whole row."""
+        ids, top, samples, lse = want
+        g = got.astype(np.float64)
+        err = max(float(np.max(np.abs(g[ids] - top))), float(np.max(np.abs(g[self._sid] - samples))))
+        self.max_logit_err = max(self.max_logit_err, err)
+        assert err <= self.tol, f"{what}: logits differ by {err:.3e} > {self.tol:.1e}"
+        mx = g.max()
+        lerr = abs(mx + np.log(np.exp(g - mx).sum()) - lse)
+        self.max_lse_err = max(self.max_lse_err, lerr)
+        assert lerr <= self.tol, f"{what}: log-sum-exp differs by {lerr:.3e}"
+
+    def token_rec(self, tok, want, what):
+        """GPU token against the stored top entries: the oracle's arg-max, or an entry within the
+        tolerance of it (a near-tie exception).  Returns True when it is the arg-max."""
+        ids, top = want[0], want[1]
+        self.decisions += 1
+        if tok == int(ids[0]):
+            return True
+        where = np.nonzero(ids == tok)[0]
+        assert where.size, f"{what}: GPU token {tok} is not among the oracle's {len(ids)} best {ids.tolist()}"
+        gap = float(top[0] - top[where[0]])
+        assert gap <= self.tol, f"{what}: GPU token {tok} is {gap:.3e} below the oracle's best {int(ids[0])}"
+        self.exceptions += 1
+        return False
+
+
+def follow_stored_stream(kg, rec: StreamRecord, prompt, fol: CachedFollow, max_resyncs=8):
+    """Greedy Kangaroo on the GPU, stepwise, along a stored oracle stream.  Every draft and target
+    row whose context is the stored stream is compared with the record of the position it predicts;
+    the emitted tokens must be the stream's.  Where the GPU legitimately emits another token (a
+    near-tie inside the tolerance), the GPU is started again on prompt + stream up to there and goes
+    on.  Returns the GPU's rounds [(base, k, n)] (without those cut short by such a restart)."""
+    m = rec.meta
+    n_prompt, n_new, gamma, eta = m["n_prompt"], m["n_new"], m["gamma"], m["eta"]
+    stream = rec.stream
+    fol._sid = rec.sample_ids
+    p, _ = B.make_params(mode=0, eta=eta, gamma=gamma)
+    prompt = [int(t) for t in prompt]
+    rounds = []
+
+    def start(e):
+        """(Re)start the GPU on prompt + stream[:e]; its first token predicts stream[e].  Returns
+        the number of stream tokens known to both sides afterwards."""
+        while True:
+            t = kg.prefill(p, prompt + stream[:e])
+            want = rec.row("t", n_prompt + e)
+            fol.row(kg.read_logits(1, 0), want, f"prefill row for position {n_prompt + e}")
+            fol.rows_t += 1
+            if fol.token_rec(t, want, f"prefill token for position {n_prompt + e}") or e + 1 >= n_new:
+                return e + 1
+            fol.resyncs += 1
+            assert fol.resyncs <= max_resyncs, "too many near-tie restarts"
+            e += 1
+
+    e = start(0)
+    while e < n_new:
+        base = n_prompt + e - 1
+        drafts = []
+        on = True                                   # the drafts so far are the stream's tokens
+        while True:
+            tok, conf, stop = kg.draft_step(p)
+            j, pos = len(drafts), base + len(drafts) + 1
+            want = rec.row("d", pos) if on else None
+            if want is not None:
+                fol.row(kg.read_logits(0, j), want, f"draft row for position {pos}")
+                fol.token_rec(tok, want, f"draft token for position {pos}")
+                oconf = rec.conf(pos)
+                slack = 3 * fol.conf_tol * max(oconf, 1e-3) + 1e-6
+                assert abs(conf - oconf) <= slack, (pos, conf, oconf)
+                ostop = oconf < eta or j + 1 == gamma
+                if stop != ostop:                   # legitimate only with the confidence on the threshold
+                    assert abs(oconf - eta) <= slack, (pos, conf, oconf, eta)
+                    fol.exceptions += 1
+                fol.rows_d += 1
+            elif on:
+                fol.rows_norec += 1
+            else:
+                fol.rows_off += 1
+            drafts.append(tok)
+            on = on and e + j < len(stream) and tok == stream[e + j]
+            if stop:
+                break
+        tg = kg.verify(p)
+        assert len(tg) == len(drafts) + 1
+        bad = None                                  # first on-stream row whose token is not the stream's
+        for i, tk in enumerate(tg):
+            ctx = e + i <= len(stream) and all(drafts[q] == stream[e + q] for q in range(i))
+            want = rec.row("t", base + i + 1) if ctx else None
+            if want is None:
+                fol.rows_off += 1
+                continue
+            fol.row(kg.read_logits(1, i), want, f"target row for position {base + i + 1}")
+            fol.rows_t += 1
+            if not fol.token_rec(tk, want, f"target token for position {base + i + 1}") and bad is None:
+                bad = i
+        em = kg.accept(p)
+        n = len(em) - 1
+        assert 0 <= n <= len(drafts) and em[:n] == drafts[:n] and em[n] == tg[n]
+        bs, alen, lag, nd = kg.state()
+        assert (bs, alen, bool(lag), nd) == (base + n + 1, base + min(n + 1, len(drafts)), n == len(drafts), 0)
+        take = min(len(em), len(stream) - e)
+        if em[:take] == stream[e:e + take]:
+            rounds.append((base, len(drafts), n))
+            e += take
+            continue
+        # the GPU left the stream: only ever at a row that was just adjudicated as a near-tie
+        mism = next(q for q in range(take) if em[q] != stream[e + q])
+        assert bad is not None and bad <= mism, (em, stream[e:e + take], bad)
+        fol.resyncs += 1
+        assert fol.resyncs <= max_resyncs, "too many near-tie restarts"
+        e = start(e + mism + 1)
+    return rounds

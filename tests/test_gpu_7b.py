@@ -1,15 +1,19 @@
 """GPU parity at the full Vicuna-7B shape (BASELINE config 2), in the launch configuration the
-benchmark times (same context geometry, page size, gamma, eta).
+benchmark times (same context geometry, page size, gamma, eta), for both values of alpha.
 
-The oracle cannot decode 256 tokens after a 256-token prompt in test time (about half a second of
-host work per forward, more than a minute for the prompt alone), so:
-  * element-by-element parity against the oracle is taken on a shorter request of the same model
-    (24-token prompt, a few rounds), logits of every draft and target row within 2e-2, tokens
-    adjudicated by the oracle's logits;
-  * on the full-size request the checks are the properties that hold at any size: greedy
-    Kangaroo output token-identical to plain decoding on the GPU (exact), every round within
-    1..gamma+1 tokens, eta = 0 drafts exactly gamma tokens, the round sizes sum to N - 1.
+At full size (256-token prompt, 256 new tokens):
+  * the live oracle follows the GPU through the whole request (follow mode): every draft and target
+    row of every round element by element within 2e-2, every token adjudicated by the oracle's
+    logits, confidences, stop decisions, cache bookkeeping;
+  * the GPU walks the oracle's stored stream of the same request (tests/golden/oracle_streams):
+    the emitted tokens are the oracle's, every on-stream row agrees with the stored record;
+  * the properties that hold at any size: greedy Kangaroo output token-identical to plain
+    decoding on the GPU (exact), every round within 1..gamma+1 tokens, eta = 0 drafts exactly
+    gamma tokens, the round sizes sum to N - 1.
+Shorter requests cover what the configuration itself never reaches: seven- and eight-row
+verification (eta = 0, gamma 6 and 7), an exact cache on either side.
 """
+import os
 import numpy as np
 import pytest
 
@@ -22,12 +26,96 @@ MAX_SEQ = 256 + 256 + 8
 ALPHA = 0.05
 
 
+STREAMS = os.path.join(os.path.dirname(__file__), "golden", "oracle_streams")
+
+
 @pytest.fixture(scope="module")
 def model7b():
     from tests import parity as P
     W = I.gen_weights(SHAPE, seed=1, alpha=ALPHA, threads=16)
     kg = P.load_model(SHAPE, W, MAX_SEQ, gamma_max=6, kv_page_tokens=128)
     yield kg, W
+    kg.close()
+
+
+def full_request_against_the_oracle(kg, W, stream_name):
+    """Config 2 at full size, both ways: the live oracle follows the GPU (all logits of all rows),
+    and the GPU walks the oracle's stored stream (tokens are the oracle's own)."""
+    from oracle import kangaroo_oracle as O
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    prompt = I.gen_prompt(SHAPE.vocab, 256)
+    fol = P.Follow(2e-2)
+    out, rounds = P.follow_kangaroo(kg, O.OracleModel(SHAPE, W, MAX_SEQ), prompt, 256, 6, 0.6, fol)
+    print(f"7b {stream_name} live follow, 256 + 256: max logit err {fol.max_logit_err:.3e}, near-tie exceptions "
+          f"{fol.exceptions}/{fol.decisions}, {len(rounds)} rounds, accepted {sum(n for _, n in rounds)}")
+    assert len(out) >= 256 and all(k == 1 for k, _ in rounds)
+    rec = P.StreamRecord(os.path.join(STREAMS, stream_name + ".npz"))
+    assert (rec.meta["n_prompt"], rec.meta["n_new"], rec.meta["shape"]) == (256, 256, "7b")
+    P.check_probe(rec, O.OracleModel(SHAPE, W, 16), prompt)
+    cf = P.CachedFollow(2e-2)
+    grounds = P.follow_stored_stream(kg, rec, prompt, cf)
+    print(f"7b {stream_name} stored stream: max logit err {cf.max_logit_err:.3e}, lse err {cf.max_lse_err:.3e}, target rows "
+          f"{cf.rows_t}, draft rows {cf.rows_d}, off-stream rows {cf.rows_off}, near-tie exceptions {cf.exceptions}/"
+          f"{cf.decisions}, restarts {cf.resyncs}")
+    assert cf.rows_t >= 256
+    if cf.exceptions == 0:
+        assert grounds == rec.rounds                       # same drafts, same acceptances, round by round
+        p, _ = B.make_params(eta=0.6, gamma=6)
+        gen, _ = kg.generate(p, prompt, 256)
+        assert gen == rec.stream                           # the whole-loop call emits the oracle's stream
+    if fol.exceptions == 0:
+        assert out[:256] == rec.stream
+
+
+def test_7b_full_request_follows_oracle(model7b):
+    kg, W = model7b
+    full_request_against_the_oracle(kg, W, "c2_a005")
+
+
+def test_7b_alpha_020_full_request_follows_oracle(model7b):
+    """The other alpha of config 2 (few drafts accepted).  Only the projections that alpha scales
+    are loaded again; the fixture's weights are restored afterwards."""
+    kg, W = model7b
+    scaled = [(k, l, r, c) for k, l, r, c in I.tensor_list(SHAPE)
+              if (k in (I.KIND_WO, I.KIND_WD) and l >= SHAPE.exit_layer) or k == I.KIND_A_WO]
+    W2 = dict(W)
+    try:
+        for k, l, r, c in scaled:
+            W2[(k, l)] = I.gen_tensor(SHAPE, k, l, r, c, seed=1, alpha=0.2)
+            kg.load_tensor(k, l, W2[(k, l)])
+        full_request_against_the_oracle(kg, W2, "c2_a020")
+    finally:
+        for k, l, r, c in scaled:
+            kg.load_tensor(k, l, W[(k, l)])
+
+
+def test_7b_bf16_cache_against_the_exact_cache_oracle(model7b):
+    """The GPU as configured (keys and values cached as bf16) against the oracle with an exact cache:
+    what storing the cache in 2 bytes costs against the plain definition stays inside the 2e-2 bound."""
+    import dataclasses
+    from oracle import kangaroo_oracle as O
+    from tests import parity as P
+    kg, W = model7b
+    exact = dataclasses.replace(SHAPE, kv="f32")
+    prompt = I.gen_prompt(SHAPE.vocab, 256)[:96]
+    fol = P.Follow(2e-2)
+    P.follow_kangaroo(kg, O.OracleModel(exact, W, 128), prompt, 12, 6, 0.6, fol)
+    print(f"7b bf16 cache vs exact-cache oracle: max logit err {fol.max_logit_err:.3e}, near-tie exceptions "
+          f"{fol.exceptions}/{fol.decisions}")
+
+
+def test_7b_gamma_7_eight_row_verification_follows_oracle(model7b):
+    """gamma = 7, eta = 0: seven drafts and an eight-row verification per round (the most rows a
+    forward takes), followed by the oracle; a context of its own, since gamma_max is part of the shape."""
+    from oracle import kangaroo_oracle as O
+    from tests import parity as P
+    _, W = model7b
+    kg = P.load_model(SHAPE, W, 96, gamma_max=7, kv_page_tokens=128)
+    fol = P.Follow(2e-2)
+    out, rounds = P.follow_kangaroo(kg, O.OracleModel(SHAPE, W, 96), I.gen_prompt(SHAPE.vocab, 256)[:20], 12, 7, 0.0, fol)
+    print(f"7b gamma 7: max logit err {fol.max_logit_err:.3e}, rounds {rounds}")
+    assert all(k == 7 for k, _ in rounds) and len(rounds) >= 2
     kg.close()
 
 

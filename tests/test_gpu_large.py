@@ -1,13 +1,16 @@
 """GPU parity at the remaining BASELINE shapes: Vicuna-13B-shaped (config 3), Vicuna-33B-shaped
 (config 4) and the 7B-shaped long-context sampling run (config 5).
 
-As at 7B, element-by-element parity with the oracle is taken on a short request of the full model
-(the oracle needs 1-4 s of host time per forward at these sizes), and the full-size request is
-checked through the properties that hold at any size.  Long-context attention (many KV pages,
-cross-page merge) is compared with the oracle on a 7B-wide, two-layer model, where the oracle can
-afford a prompt of more than a thousand tokens.
+At full size the GPU walks the oracle's stored stream of each request (tests/golden/oracle_streams,
+written by the oracle alone): every emitted token is the oracle's, every draft and target row whose
+context is the stream agrees with the stored record (largest entries, sampled entries, log-sum-exp)
+within 2e-2.  The live oracle follows a shorter request of the same full model element by element
+(128-token prompt, 32 tokens at 13B and 33B; a 1024-token prompt and 16 sampled tokens for the
+long-context sampling configuration), and the full-size requests are also checked through the
+properties that hold at any size.
 """
 import dataclasses
+import os
 
 import numpy as np
 import pytest
@@ -17,7 +20,33 @@ from paper_2404_18911_amd import inputs as I
 pytestmark = pytest.mark.gpu
 
 
-def _run_shape(name, alpha, n_prompt, n_new, short_prompt, short_new):
+STREAMS = os.path.join(os.path.dirname(__file__), "golden", "oracle_streams")
+
+
+def walk_stored_stream(kg, W, shape, stream_name, prompt):
+    """The GPU along the oracle's stored stream of a full-size request; prints what was covered."""
+    from oracle import kangaroo_oracle as O
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    rec = P.StreamRecord(os.path.join(STREAMS, stream_name + ".npz"))
+    m = rec.meta
+    assert (m["n_prompt"], m["shape"]) == (len(prompt), shape.name)
+    P.check_probe(rec, O.OracleModel(shape, W, 16), prompt)
+    cf = P.CachedFollow(2e-2)
+    rounds = P.follow_stored_stream(kg, rec, prompt, cf)
+    print(f"{stream_name} stored stream ({m['n_prompt']} + {m['n_new']}): max logit err {cf.max_logit_err:.3e}, lse err "
+          f"{cf.max_lse_err:.3e}, target rows {cf.rows_t}, draft rows {cf.rows_d}, off-stream rows {cf.rows_off}, "
+          f"near-tie exceptions {cf.exceptions}/{cf.decisions}, restarts {cf.resyncs}")
+    assert cf.rows_t >= m["n_new"]
+    if cf.exceptions == 0:
+        assert rounds == rec.rounds
+        p, _ = B.make_params(eta=m["eta"], gamma=m["gamma"])
+        gen, _ = kg.generate(p, prompt, m["n_new"])
+        assert gen == rec.stream
+    return rec
+
+
+def _run_shape(name, alpha, n_prompt, n_new, short_prompt, short_new, stream_name):
     from oracle import kangaroo_oracle as O
     from paper_2404_18911_amd import binding as B
     from tests import parity as P
@@ -25,9 +54,11 @@ def _run_shape(name, alpha, n_prompt, n_new, short_prompt, short_new):
     W = I.gen_weights(shape, seed=1, alpha=alpha, threads=16)
     kg = P.load_model(shape, W, n_prompt + n_new + 8, gamma_max=6, kv_page_tokens=128)
     prompt = I.gen_prompt(shape.vocab, n_prompt)
+    walk_stored_stream(kg, W, shape, stream_name, prompt)
     fol = P.Follow(2e-2)
     P.follow_kangaroo(kg, O.OracleModel(shape, W, short_prompt + short_new + 16), prompt[:short_prompt], short_new, 6, 0.6, fol)
-    print(f"{name}: max logit err {fol.max_logit_err:.3e}, near-tie exceptions {fol.exceptions}/{fol.decisions}")
+    print(f"{name} live follow ({short_prompt} + {short_new}): max logit err {fol.max_logit_err:.3e}, near-tie exceptions "
+          f"{fol.exceptions}/{fol.decisions}")
     p, _ = B.make_params(eta=0.6, gamma=6)
     plain, stp = kg.decode_plain(p, prompt, n_new)
     out, st = kg.generate(p, prompt, n_new)
@@ -39,11 +70,11 @@ def _run_shape(name, alpha, n_prompt, n_new, short_prompt, short_new):
 
 
 def test_13b_shape():
-    _run_shape("13b", 0.1, 512, 256, 12, 3)
+    _run_shape("13b", 0.1, 512, 256, 128, 32, "c3_13b")
 
 
 def test_33b_shape():
-    _run_shape("33b", 0.1, 512, 128, 8, 2)
+    _run_shape("33b", 0.1, 512, 128, 128, 32, "c4_33b")
 
 
 def test_long_context_attention_follows_oracle():
@@ -62,10 +93,13 @@ def test_long_context_attention_follows_oracle():
 
 
 def test_config5_long_context_sampling_run():
-    """BASELINE config 5 at full size: 7B shape, 4096-token prompt, temperature-1 rejection sampling,
-    256 new tokens.  Checked: the stepwise calls reproduce kg_generate exactly (same uniforms), every
-    round emits 1..gamma+1 tokens, the stream is a function of the uniforms only (a second run is
-    identical), and on a short prompt every sampled decision is the oracle's up to tolerance."""
+    """BASELINE config 5: 7B shape, 4096-token prompt, temperature-1 rejection sampling, 256 new
+    tokens.  At full size: every round emits 1..gamma+1 tokens and the stream is a function of the
+    uniforms only (a second run is identical); the same context geometry decoded greedily walks the
+    oracle's stored stream (every token and on-stream row at 4096..4351 tokens of context, all 32
+    layers).  Sampled decisions cannot be stored (a uniform number within rounding of a cumulative
+    sum moves the token, so the oracle has to follow the GPU's own draws): the live oracle follows
+    a 1024-token prompt through 16 sampled tokens, decision by decision."""
     from oracle import kangaroo_oracle as O
     from paper_2404_18911_amd import binding as B
     from tests import parity as P
@@ -82,11 +116,13 @@ def test_config5_long_context_sampling_run():
     out2, _ = kg.generate(p, prompt, n_new)
     assert out2 == out
     print(f"config 5: {(n_new - 1) / st.t_total_s:.1f} tok/s, acceptance {st.accepted}/{st.drafted}")
-    # short-prompt follow in sampling mode
+    walk_stored_stream(kg, W, shape, "c5_greedy", prompt)
+    # sampling mode, decision by decision, after a prompt of eight KV pages
     fol = P.Follow(2e-2)
-    P.follow_kangaroo_sampling(kg, O.OracleModel(shape, W, 64), prompt[:20], 6, 6, 0.6, 1.0, U, fol, 4e-2)
-    print(f"config 5 short follow: max logit err {fol.max_logit_err:.3e}, decisions the oracle takes otherwise "
-          f"{fol.exceptions}/{fol.decisions}")
+    _, rounds = P.follow_kangaroo_sampling(kg, O.OracleModel(shape, W, 1024 + 48), prompt[:1024], 16, 6, 0.6, 1.0, U, fol, 4e-2,
+                                           chunk=256)
+    print(f"config 5 live follow (1024 + 16, sampling): max logit err {fol.max_logit_err:.3e}, decisions the oracle takes "
+          f"otherwise {fol.exceptions}/{fol.decisions}, rounds {rounds}")
     kg.close()
 
 

@@ -427,3 +427,63 @@ def test_short_requests_and_call_order_on_a_bound_context():
         t += kg.accept(p)
     assert t[:20] == ref[:20]
     kg.close()
+
+
+@pytest.mark.parametrize("name,page", [("toy", 16), ("small_bf16", 64)])
+def test_nothing_beyond_the_committed_length_is_ever_read(name, page):
+    """Rollback only shortens lengths, so whatever the caches hold beyond the committed length must
+    never be read.  The KV pool (the caller's memory) is filled with NaN before the prefill and every
+    position >= base is overwritten with NaN again after each accept: rejected drafts' keys and
+    values, the run-ahead shallow step's, the tails of partly filled pages.  The oracle then follows
+    as usual; a single stale or masked-but-loaded value would turn logits into NaN."""
+    import torch
+    from tests import parity as P
+    shape = I.SHAPES[name]
+    hs = 25.0 if name == "toy" else 16.0
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=hs)
+    kg = P.load_model(shape, W, 128, gamma_max=6, kv_page_tokens=page)
+    kg.set_page_order(np.random.default_rng(1).permutation(128 // page))
+    kg.kv.view(torch.float32 if shape.kv_dtype == "f32" else torch.bfloat16).fill_(float("nan"))
+
+    def poison(k):
+        base, alen, _, _ = k.state()
+        assert alen <= base
+        P.poison_kv_tail(k, base)
+
+    fol = P.Follow(tol_for(shape, hs))
+    out, rounds = P.follow_kangaroo(kg, _oracle(shape, W, 128), I.gen_prompt(shape.vocab, 21), 40, 6, 0.6, fol,
+                                    after_commit=poison)
+    assert any(n < k for k, n in rounds) and any(n == k for k, n in rounds)     # rejections and full accepts both occurred
+    assert np.isfinite(kg.read_logits(1, 0)).all()
+    kg.close()
+
+
+def test_plain_step_after_rounds_continues_the_committed_sequence():
+    """kg_plain_step is allowed after kg_accept: it must run at the pending token's position (the
+    committed length), not at the prompt's end.  After some rounds, forcing the pending token through
+    plain steps must give the tokens plain decoding gives there, and the logits of a fresh context
+    that decoded the same sequence plainly."""
+    from paper_2404_18911_amd import binding as B
+    from tests import parity as P
+    shape = I.SHAPES["toy_bf16"]
+    W = I.gen_weights(shape, seed=1, alpha=0.05, head_scale=25.0)
+    prompt = I.gen_prompt(shape.vocab, 14)
+    p, _ = B.make_params(eta=0.6, gamma=4)
+    kg = P.load_model(shape, W, 96, kv_page_tokens=16)
+    ref, _ = kg.decode_plain(p, prompt, 40)
+    ref_logits = kg.read_logits(1, 0)            # the row that produced ref[39]
+    out = [kg.prefill(p, prompt)]
+    for _ in range(3):
+        while not kg.draft_step(p)[2]:
+            pass
+        kg.verify(p)
+        out += kg.accept(p)
+    assert out == ref[:len(out)] and len(out) > 3
+    while len(out) < 40:
+        out.append(kg.plain_step(p, out[-1]))
+    assert out == ref
+    np.testing.assert_array_equal(kg.read_logits(1, 0), ref_logits)
+    with pytest.raises(B.KangarooError) as ei:      # the adapter's cache is behind now
+        kg.draft_step(p)
+    assert ei.value.code == B.KG_ESTATE
+    kg.close()

@@ -235,3 +235,21 @@ def test_the_mlp_adapter_keeps_no_state():
     whole = m.adapter(f, 0)
     for i in (4, 0, 2):
         np.testing.assert_array_equal(new().adapter(f[i:i + 1], 17), whole[i:i + 1])
+
+
+def test_chunked_prefill_is_the_prefill(toy_shape, toy_weights):
+    """Feeding the prompt through in pieces changes nothing: same logits, pending token and caches,
+    bit for bit (a row's arithmetic does not depend on the rows that travel with it)."""
+    prompt = I.gen_prompt(toy_shape.vocab, 23)
+    a = O.KangarooDecoder(O.OracleModel(toy_shape, toy_weights, 40))
+    b = O.KangarooDecoder(O.OracleModel(toy_shape, toy_weights, 40))
+    seen = []
+    ta, tb = a.prefill(prompt), b.prefill(prompt, chunk=5, progress=seen.append)
+    assert ta == tb and seen == [5, 10, 15, 20, 23]
+    assert np.array_equal(a.prefill_logits, b.prefill_logits)
+    for slot in range(toy_shape.n_layers + 1):
+        for pos in (0, 7, 22):
+            ka, va = a.m.kv_read(slot, pos)
+            kb, vb = b.m.kv_read(slot, pos)
+            assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+    assert a.round() == b.round()
