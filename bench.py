@@ -27,17 +27,37 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+TRAFFIC_PROFILE = os.path.join("profiles", "gemv_bf16_attn_7b_kangaroo_decode.txt")
+
+
+def kernel_source_digest():
+    """Digest of the library's sources: the committed counter summary names the digest it was
+    measured with, so that a traffic figure that outlived a kernel change is reported as stale."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in ("paper_2404_18911_amd/csrc/kernels.hip.h", "paper_2404_18911_amd/csrc/kangaroo.hip"):
+        h.update(open(os.path.join(ROOT, rel), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def profiled_traffic():
     """HBM bytes per projection launch from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE runs of this very command, scaled by a copy of known size), or None."""
-    path = os.path.join(ROOT, "profiles", "gemv_bf16_attn_7b_kangaroo_decode.txt")
+    WRITE_SIZE runs of this very command, scaled by a copy of known size), or None; with where the
+    figure comes from and whether the kernels have changed since it was measured.  It is not measured
+    by this run: counters need a profiler pass of their own."""
+    traffic = digest = None
     try:
-        for line in open(path):
-            if line.strip().startswith("TRAFFIC_BYTES_PER_PROJECTION_LAUNCH"):
-                return float(line.split()[1])
+        for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
+            f = line.split()
+            if len(f) >= 2 and f[0] == "TRAFFIC_BYTES_PER_PROJECTION_LAUNCH":
+                traffic = float(f[1])
+            if len(f) >= 2 and f[0] == "KERNEL_SOURCE_DIGEST":
+                digest = f[1]
     except OSError:
         pass
-    return None
+    now = kernel_source_digest()
+    return traffic, {"from": TRAFFIC_PROFILE + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes of this command, committed)",
+                     "measured_with_kernel_digest": digest, "kernel_digest_now": now, "stale": digest != now}
 
 
 def log(*a):
@@ -49,7 +69,7 @@ def forward_bytes(shape, ctx=0):
     `ctx` positions once per attention layer of the forward."""
     b = shape.bytes_per_weight()
     d, f, V = shape.d_model, shape.d_ffn, shape.vocab
-    kv = 2 * d * (2 if shape.kv_dtype == "bf16" else 4) * ctx          # one layer's cache
+    kv = 2 * d * (4 if shape.kv_dtype == "f32" else 2) * ctx          # one layer's cache
     from paper_2404_18911_amd import inputs as I
     layer = (4 * d * d + 3 * d * f) * b
     head = d * V * b
@@ -351,6 +371,154 @@ def train_demo(args, kg, shape, T):
     return res
 
 
+def run_micro(args):
+    """Microbenchmarks that bound what a decode forward can reach on this device, through the
+    library's own stand-alone ops (one JSON object; not the benchmark line):
+      * the streaming-read ceiling on a buffer far larger than the caches;
+      * a dependency-free stream of exactly one projection's weight bytes, launched back to back, for
+        the four projection shapes of the configured model: what a launch of that size costs when it
+        does nothing but read (fixed cost per launch + bytes / bandwidth), against
+      * the projection kernel itself on that shape (kg_op_linear on random weights), one row and
+        KG_MAX_ROWS rows;
+      * the fixed cost per launch and the asymptotic bandwidth fitted to stream launches of 8 sizes."""
+    import numpy as np
+    import torch
+    from paper_2404_18911_amd import binding as B
+    from paper_2404_18911_amd import inputs as I
+    L = B.lib()
+    dev = torch.device("cuda:0")
+    st = torch.cuda.current_stream(dev)
+    shape = I.SHAPES[args.shape]
+    d, f, V = shape.d_model, shape.d_ffn, shape.vocab
+    shapes = {"q,k,v": (3 * d, d), "o_proj": (d, d), "gate+up": (2 * f, d), "down_proj": (d, f), "lm_head": (V, d)}
+    buf = torch.empty(3 << 30, dtype=torch.uint8, device=dev)
+    buf.zero_()
+    work = torch.zeros(4096, dtype=torch.uint8, device=dev)
+
+    def timed(fn, reps):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = 1e9
+        for _ in range(3):
+            e0.record(st)
+            for i in range(reps):
+                fn(i)
+            e1.record(st)
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e-3 / reps)
+        return best
+
+    out = {"micro": True, "shape": args.shape, "stream_read_ceiling_GBs": B.op_stream_read_GBs(), "projections": {}}
+    # a stream of exactly the projection's bytes, each launch on another part of a 3 GiB buffer (cold)
+    for name, (N, K) in shapes.items():
+        nbytes = N * K * 2
+        span = (len(buf) - nbytes) // 256 * 256
+        t_stream = timed(lambda i=0: L.kg_op_stream_read(buf.data_ptr() + (i * 201326592) % span // 256 * 256, nbytes, work.data_ptr(),
+                                                         st.cuda_stream), 64)
+        rng = np.random.default_rng(N + K)
+        n_copies = max(1, min(8, (2 << 30) // nbytes))          # rotate over several copies so that no launch finds its weights cached
+        packed = torch.empty(n_copies * L.kg_op_packed_bytes(1, N, K), dtype=torch.uint8, device=dev)
+        per = L.kg_op_packed_bytes(1, N, K)
+        wsrc = torch.from_numpy(I.f32_to_bf16_bits((rng.standard_normal((N, K)) * 0.02).astype(np.float32)).view(np.int16)).to(dev)
+        for c in range(n_copies):
+            assert L.kg_op_pack(1, wsrc.data_ptr(), N, K, packed.data_ptr() + c * per, st.cuda_stream) == 0
+        wk = torch.empty(L.kg_op_work_bytes(K), dtype=torch.uint8, device=dev)
+        res = {"bytes": nbytes, "stream_only_us": 1e6 * t_stream, "stream_only_GBs": nbytes / t_stream / 1e9}
+        for M in (1, B.KG_MAX_ROWS):
+            x = torch.randn(M, K, dtype=torch.float32, device=dev)
+            y = torch.empty(M, N, dtype=torch.float32, device=dev)
+            t = timed(lambda i=0: L.kg_op_linear(1, packed.data_ptr() + (i % n_copies) * per, N, K, x.data_ptr(), M, y.data_ptr(),
+                                                 wk.data_ptr(), st.cuda_stream), 64)
+            # kg_op_linear = clear + pack of the rows + the projection: subtract what the two small launches cost alone
+            res[f"linear_M{M}_us_with_row_packing"] = 1e6 * t
+        # the projection alone at one row, matrix units against vector ALUs (same tiles, same launch shape):
+        # kg_op_linear's row packing is a fixed cost of its own, measured by packing without multiplying
+        x1 = torch.randn(1, K, dtype=torch.float32, device=dev)
+        y1 = torch.empty(1, N, dtype=torch.float32, device=dev)
+        t_valu = timed(lambda i=0: L.kg_op_linear_valu(packed.data_ptr() + (i % n_copies) * per, N, K, x1.data_ptr(), y1.data_ptr(),
+                                                       st.cuda_stream), 64)
+        res["valu_M1_us"] = 1e6 * t_valu
+        res["valu_M1_GBs"] = nbytes / t_valu / 1e9
+        out["projections"][name] = res
+        del packed, wsrc
+        log(f"[micro] {name}: {res}")
+    # fixed cost per launch and asymptotic bandwidth: t(S) = a + S / bw over stream launches of several sizes
+    sizes = [8 << 20, 16 << 20, 32 << 20, 64 << 20, 96 << 20, 128 << 20, 192 << 20, 256 << 20]
+    ts = []
+    for sz in sizes:
+        span = (len(buf) - sz) // 256 * 256
+        ts.append(timed(lambda i=0: L.kg_op_stream_read(buf.data_ptr() + (i * 335544320) % span // 256 * 256, sz, work.data_ptr(),
+                                                        st.cuda_stream), 48))
+    A = np.vstack([np.ones(len(sizes)), np.array(sizes, dtype=np.float64)]).T
+    (a, b), *_ = np.linalg.lstsq(A, np.array(ts), rcond=None)
+    out["stream_launch_fit"] = {"sizes_MB": [s_ >> 20 for s_ in sizes], "us": [1e6 * t for t in ts],
+                                "fixed_us_per_launch": 1e6 * a, "asymptotic_GBs": 1.0 / b / 1e9}
+    print(json.dumps(out), flush=True)
+
+
+def trace_summary(path):
+    """Per-layer timeline of the plain decode forwards found in a rocprofv3 kernel trace
+    (`rocprofv3 --kernel-trace --output-format csv -d DIR -- python3 bench.py ...`; path = DIR or the
+    *_kernel_trace.csv): for every kernel slot of a layer (q,k,v / attention / o_proj / gate+up /
+    down_proj) the mean duration and the mean idle gap before it, over all layers of all one-row
+    forwards in the trace, plus the forward's span against the sum of its kernels."""
+    import collections
+    import csv
+    import glob
+    if os.path.isdir(path):
+        path = sorted(glob.glob(os.path.join(path, "**", "*_kernel_trace.csv"), recursive=True))[-1]
+    rows = [r for r in csv.DictReader(open(path))]
+    rows.sort(key=lambda r: int(r["Start_Timestamp"]))
+
+    def short(r):
+        n = r["Kernel_Name"]
+        if n.startswith("gemv_bf16"):
+            return "gemv[%d]" % (int(r["Grid_Size_X"]) // 512)           # row tiles of the projection
+        return n.split("(")[0].replace("void ", "")[:40]
+    names = [short(r) for r in rows]
+    # a plain forward: pack_rows, then (gemv attn gemv gemv gemv) x L, gemv (head), head_final
+    fw = []
+    i = 0
+    while i < len(rows):
+        if names[i].startswith("pack_rows"):
+            j = i + 1
+            while j < len(rows) and not names[j].startswith("head_final") and not names[j].startswith("pack_rows"):
+                j += 1
+            if j < len(rows) and names[j].startswith("head_final"):
+                body = list(range(i + 1, j - 1))
+                if len(body) >= 10 and len(body) % 5 == 0 and all(names[body[k]].startswith("attn_kernel") for k in range(1, len(body), 5)):
+                    fw.append((i, j))
+            i = j
+        else:
+            i += 1
+    print(f"# {os.path.basename(path)}: {len(rows)} dispatches, {len(fw)} one-token whole-model forwards")
+    if not fw:
+        return
+    dur = collections.defaultdict(list)
+    gap = collections.defaultdict(list)
+    spans, busys = [], []
+    for i, j in fw:
+        t0, t1 = int(rows[i]["Start_Timestamp"]), int(rows[j]["End_Timestamp"])
+        spans.append(t1 - t0)
+        busys.append(sum(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]) for k in range(i, j + 1)))
+        for k in range(i + 1, j - 1):
+            slot = ((k - i - 1) % 5, names[k])
+            dur[slot].append(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]))
+            gap[slot].append(int(rows[k]["Start_Timestamp"]) - int(rows[k - 1]["End_Timestamp"]))
+        for k, tag in ((i, "first: pack_rows"), (j - 1, "last: lm head"), (j, "last: head_final")):
+            dur[(9, tag)].append(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]))
+            gap[(9, tag)].append(int(rows[k]["Start_Timestamp"]) - int(rows[k - 1]["End_Timestamp"]) if k > i else 0)
+    mean = lambda v: sum(v) / len(v) / 1e3
+    print(f"forward span {mean(spans):.1f} us, sum of kernel durations {mean(busys):.1f} us, idle between kernels {mean(spans) - mean(busys):.1f} us")
+    print("slot  kernel                                     launches  mean us  gap before, us")
+    layer = 0.0
+    for slot in sorted(dur):
+        print(f"{slot[0]:>4}  {slot[1]:<42} {len(dur[slot]):>8} {mean(dur[slot]):>8.2f} {mean(gap[slot]):>10.2f}")
+        if slot[0] < 5:
+            layer += mean(dur[slot]) + mean(gap[slot])
+    print(f"one layer (5 kernels + gaps): {layer:.2f} us")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -373,9 +541,14 @@ def main():
     ap.add_argument("--streams", type=int, default=16)
     ap.add_argument("--train-head-scale", type=float, default=1.0, help="LM-head multiplier of --train (sharpens the target distribution)")
     ap.add_argument("--lr", type=float, default=2e-5)
+    ap.add_argument("--micro", action="store_true", help="stream / projection microbenchmarks of the configured shape (not the benchmark line)")
+    ap.add_argument("--trace-summary", default="", help="summarise a rocprofv3 kernel trace (directory or csv) as a per-layer timeline; needs no GPU")
     ap.add_argument("--prefill-only", type=int, default=0,
                     help="run only this many prompt passes (for profiling the MFMA prompt kernels) and print their timing")
     args = ap.parse_args()
+    if args.trace_summary:
+        trace_summary(args.trace_summary)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -396,6 +569,9 @@ def main():
     if args.train:
         run_train(args)
         return
+    if args.micro:
+        run_micro(args)
+        return
     threads = min(16, os.cpu_count() or 8)
     shape = I.SHAPES[args.shape]
     gamma, eta = 6, 0.6
@@ -409,10 +585,10 @@ def main():
             W[(kind, layer)] = a
     log(f"[bench] weights generated and loaded in {time.time() - t0:.1f}s")
     prompt = I.gen_prompt(shape.vocab, args.prompt)
-    # --sample: speculative rejection sampling (and plain sampling for the baseline) with seeded uniforms
-    U = I.gen_uniforms(args.prompt + args.new + gamma + 8, seed=3) if args.sample else None
+    # --sample: speculative rejection sampling (and plain sampling for the baseline); the uniform numbers
+    # come from the library's device generator keyed by the seed
     mode = 1 if args.sample else 0
-    p, _keep_u = B.make_params(mode=mode, temperature=args.temperature, eta=eta, gamma=gamma, uniforms=U)
+    p, _keep_u = B.make_params(mode=mode, temperature=args.temperature, eta=eta, gamma=gamma, seed=3)
 
     def sync():
         torch.cuda.synchronize()
@@ -479,9 +655,10 @@ def main():
         kg.set_profiling(False)
         g_bytes, g_s, g_n = pr.bytes[0], pr.seconds[0], pr.launches[0]
         ach = g_bytes / g_s / 1e9
+        traffic, traffic_src = profiled_traffic() if args.shape == "7b" and args.prompt == 256 and not args.sample else (None, None)
         res["roofline"] = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                            "frac": ach / HBM_PEAK_GBS,
-                           "traffic": profiled_traffic() if args.shape == "7b" else None,
+                           "traffic": traffic, "traffic_source": traffic_src,
                            "kernel": "gemv_bf16_kernel", "launches": int(g_n),
                            "avg_launch_us": 1e6 * g_s / g_n, "avg_launch_bytes": g_bytes / g_n}
         res["device_time_share"] = {"projections": pr.seconds[0], "attention": pr.seconds[1], "other": pr.seconds[2],
@@ -512,12 +689,14 @@ def main():
         res["speedup_vs_plain"] = value / res["plain_tokens_per_s"]
         res["plain_forward_GBs"] = fb["plain"] * st_p.plain_steps / st_p.t_total_s / 1e9
         res["per_forward"]["plain"] = fwd(fb["plain"], st_p.t_total_s / st_p.plain_steps)
+        # whole forwards next to the dominant kernel's figure: fraction of the 8 TB/s peak per forward type
+        res["roofline"]["forward_frac"] = {k: v["frac_of_peak"] for k, v in res["per_forward"].items()}
         res["lossless_on_gpu"] = None if args.sample else bool(out_p == out)   # sampled streams differ by construction
         # whole-forward bandwidth of the Kangaroo loop: bytes of all forwards / decode wall-clock
         kang_bytes = stats.draft_steps * fb["draft"] + stats.verify_calls * (fb["shallow"] + fb["verify"])
         res["kangaroo_forward_GBs"] = kang_bytes / stats.t_total_s / 1e9
         res["kangaroo_forward_frac_of_peak"] = res["kangaroo_forward_GBs"] / HBM_PEAK_GBS
-        p0, _keep_u0 = B.make_params(mode=mode, temperature=args.temperature, eta=0.0, gamma=gamma, uniforms=U)
+        p0, _keep_u0 = B.make_params(mode=mode, temperature=args.temperature, eta=0.0, gamma=gamma, seed=3)
         out0, st0 = kg.generate(p0, prompt, args.new)
         res["eta0"] = {"tokens_per_s": (len(out0) - 1) / st0.t_total_s, "rounds": st0.rounds,
                        "acceptance_rate": st0.accepted / max(1, st0.drafted),

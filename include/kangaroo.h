@@ -47,7 +47,8 @@ typedef struct kg_config {
     int n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
     int exit_layer;
     int dtype;          /* storage type of the weights: 0 = float32, 1 = bfloat16 */
-    int kv_dtype;       /* storage type of the KV cache (rotated keys, values): 0 = float32, 1 = bfloat16 */
+    int kv_dtype;       /* storage type of the KV cache (rotated keys, values): 0 = float32, 1 = bfloat16,
+                           2 = float16 (IEEE half); 1 and 2 need dtype = 1 */
     float rms_eps, rope_theta;
     int max_seq;        /* token capacity of the caches: prompt + generated + gamma_max + 1 */
     int gamma_max;      /* largest draft length gamma that will be used (<= KG_MAX_ROWS - 1) */
@@ -96,9 +97,14 @@ typedef enum kg_tensor_kind {
  * stops after a token whose top-1 probability is < eta (Eq. 4; eta = 0 gives fixed-step
  * drafting).  mode 0 accepts drafts while they equal the target's top-1 token; mode 1 is
  * speculative rejection sampling at the given temperature, which keeps the target's sampling
- * distribution.  In mode 1 `uniforms` (host, float[n_uniform_positions][3], each in [0,1)) gives,
- * per absolute token position, the numbers used to draw a draft token [0], to test its
- * acceptance [1], and to draw a resampled / bonus / first token [2]. */
+ * distribution.  Mode 1 uses one uniform number in [0,1) per (absolute token position, purpose):
+ * purpose 0 draws the draft token of that position, 1 tests its acceptance, 2 draws a resampled /
+ * bonus / first / plain token there.  With uniforms == NULL the kernels generate the number on the
+ * device: Philox4x32-10 with key (seed mod 2^32, seed >> 32) and counter (position, purpose, 0, 0),
+ * u = (first output word >> 8) * 2^-24; the stream of a request is then a function of (weights,
+ * prompt, seed) alone, whatever the control flow.  With uniforms != NULL (host,
+ * float[n_uniform_positions][3], indexed [position][purpose]) those numbers are used instead and
+ * seed is ignored: a hook for tests that need to choose the numbers. */
 typedef struct kg_params {
     int mode;
     float temperature;
@@ -106,15 +112,24 @@ typedef struct kg_params {
     int gamma;
     const float *uniforms;
     int n_uniform_positions;
+    uint64_t seed;
 } kg_params;
 
 /* Counters of one kg_generate / kg_decode_plain call.  s_hist[s] counts the rounds that emitted
- * s tokens (the list S of Section 3; compression rate, Eq. 1, is emitted_in_rounds / rounds). */
+ * s tokens (the list S of Section 3; compression rate, Eq. 1, is emitted_in_rounds / rounds).
+ * bytes_*: algorithmic device traffic of the decode loop (Section 1: decoding is bound by reading the
+ * weights): weight bytes streamed plus cached key / value bytes read, by what the forward belongs to:
+ * draft = the self-draft model's steps (shallow layers, adapter, head), shallow = the shallow-only
+ * passes (the stopped token's next early feature, Figure 2), verify = the remaining layers and the
+ * head over the unit (or the whole model in plain decoding).  The prompt pass is not included.
+ * There is no wall-clock for the shallow-only pass: it is launched ahead, inside the draft step, while
+ * the host waits for that step's token, so its time is part of t_draft_s. */
 typedef struct kg_stats {
     int rounds, drafted, accepted, emitted;
     int s_hist[KG_MAX_ROWS + 1];
     int draft_steps, verify_calls, plain_steps;
     double t_draft_s, t_verify_s, t_total_s; /* host wall-clock spent in each phase */
+    double bytes_draft, bytes_shallow, bytes_verify;
 } kg_stats;
 
 /* Metrics of Section 3 from the counters of a run: compression rate CR = mean tokens emitted per
@@ -311,6 +326,23 @@ size_t kg_op_work_bytes(int K);
 int kg_op_pack(int dtype, const void *src_dev, int N, int K, void *packed_dev, void *hip_stream);
 int kg_op_linear(int dtype, const void *packed_dev, int N, int K, const float *x_dev, int M, float *y_dev,
                  void *work_dev, void *hip_stream);
+
+/*
+ * The one-row product y[N] = W . x[K] of kg_op_linear (bf16 tiles from kg_op_pack, x and y fp32 on the
+ * device) computed on the vector ALUs instead of the matrix units: the same launch shape and memory
+ * stream, another arithmetic unit.  It exists for the A/B measurement behind the choice of the matrix
+ * units for the weight-streaming projections (Section 1: the projections are bound by reading the
+ * weights, so the unit that multiplies should not matter; measured, it does not).  K % 16 == 0.
+ * Launches on `hip_stream`, does not synchronise.
+ */
+int kg_op_linear_valu(const void *packed_dev, int N, int K, const float *x_dev, float *y_dev, void *hip_stream);
+
+/*
+ * The generator of sampling mode on its own (kernel-level tests): out_dev[i] = first output word of
+ * Philox4x32-10 for key (seed mod 2^32, seed >> 32) and counter (pos0 + i, purpose, 0, 0), i < n.
+ * Launches on `hip_stream`, does not synchronise.
+ */
+int kg_op_philox_words(uint64_t seed, uint32_t pos0, uint32_t purpose, int n, uint32_t *out_dev, void *hip_stream);
 
 /*
  * Measured ceiling for a weight stream (Section 1: decoding is bound by reading the weights): one

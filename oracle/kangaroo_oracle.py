@@ -62,7 +62,7 @@ def build(force: bool = False, out: Optional[str] = None, extra_flags: Sequence[
 
 class _Cfg(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn",
-                                            "vocab", "exit_layer", "wdtype", "max_seq", "kv_bf16",
+                                            "vocab", "exit_layer", "wdtype", "max_seq", "kv_round",
                                             "adapter_kind")] + \
                [("rms_eps", ctypes.c_double), ("rope_theta", ctypes.c_double)]
 
@@ -98,6 +98,8 @@ def lib():
         _lib.ko_attend.argtypes = [dp, dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp]
         _lib.ko_round_bf16.restype = ctypes.c_double
         _lib.ko_round_bf16.argtypes = [ctypes.c_double]
+        _lib.ko_round_f16.restype = ctypes.c_double
+        _lib.ko_round_f16.argtypes = [ctypes.c_double]
         _lib.ko_matvec.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp,
                                    ctypes.c_int, dp]
         u32p = ctypes.POINTER(ctypes.c_uint32)
@@ -114,7 +116,10 @@ def _dp(a: np.ndarray):
 class OracleModel:
     """The model of kangaroo_ref.c bound to a set of weights (borrowed numpy arrays)."""
 
-    def __init__(self, shape, weights: Dict[Tuple[int, int], np.ndarray], max_seq: int):
+    def __init__(self, shape, weights: Dict[Tuple[int, int], np.ndarray], max_seq: int, exact_cache: bool = True):
+        """exact_cache (the default): keys and values are cached as computed, the plain definition.
+        With exact_cache=False the cache holds them rounded to the shape's cache storage type
+        (bfloat16 or IEEE half), which is how one studies what such a storage format costs."""
         self.shape = shape
         self.L, self.d, self.V, self.l = shape.n_layers, shape.d_model, shape.vocab, shape.exit_layer
         self.max_seq = max_seq
@@ -123,7 +128,8 @@ class OracleModel:
         for a in weights.values():
             assert a.flags["C_CONTIGUOUS"] and a.dtype == (np.float32 if wd == 0 else np.uint16)
         cfg = _Cfg(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
-                   shape.exit_layer, wd, max_seq, 1 if getattr(shape, "kv_dtype", shape.dtype) == "bf16" else 0,
+                   shape.exit_layer, wd, max_seq,
+                   0 if exact_cache else {"f32": 0, "bf16": 1, "f16": 2}[getattr(shape, "kv_dtype", shape.dtype)],
                    getattr(shape, "adapter", 0), shape.rms_eps, shape.rope_theta)
         w = _W()
 

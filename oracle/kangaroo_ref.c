@@ -18,10 +18,11 @@
  *     (attention, post norm, feed-forward, both residuals), last norm, shared head; 3 "MLP Only" =
  *     input norm, two d x d linear maps, last norm, own head.
  *
- * The key/value cache is a storage format of the configuration, like the weights' type: the
- * bf16 configurations budget 2 bytes per cached element (16 KB per token and layer at d = 4096),
- * so with kv_bf16 set the cache holds rotated keys and values rounded to bfloat16 and attention
- * reads those; with it clear the cache is exact.
+ * The key/value cache is exact by default (kv_round = 0): that is the plain definition every GPU
+ * result is compared with.  A device keeps the cache in 2 bytes per element (16 KB per token and
+ * layer at d = 4096); to study what such a storage format costs, kv_round = 1 holds the rotated keys
+ * and the values rounded to bfloat16 and kv_round = 2 rounded to IEEE half precision, and attention
+ * reads the rounded numbers.
  *
  * Readings where the paper is silent: rotate-half RoPE pairing (i, i+hd/2), base theta, no
  * biases, residual connection around the adapter's attention, early feature = residual stream
@@ -43,7 +44,7 @@ typedef struct {
     int exit_layer;
     int wdtype;            /* 0 = float32, 1 = bfloat16 bit patterns */
     int max_seq;
-    int kv_bf16;           /* 1: the cache stores rotated keys and values rounded to bfloat16 */
+    int kv_round;          /* cache storage: 0 exact, 1 rounded to bfloat16, 2 rounded to IEEE half */
     int adapter_kind;      /* Table 2: 0 attention, 1 attention + own head, 2 decoder block, 3 two linear maps + own head */
     double rms_eps, rope_theta;
 } ko_config;
@@ -83,6 +84,26 @@ static inline double round_bf16(double x)
     u &= 0xFFFF0000u;
     memcpy(&f, &u, 4);
     return (double)f;
+}
+
+/* value as an IEEE half-precision cache would hold it: to float (nearest), then to the nearest
+ * number with 11 significant bits in the half range (ties to even; subnormal spacing 2^-24 below
+ * 2^-14; beyond the largest half, 65504, rounds to infinity from 65520 on) */
+static inline double round_f16(double x)
+{
+    double f = (double)(float)x;
+    if (f == 0.0 || isnan(f) || isinf(f)) return f;
+    int e;
+    (void)frexp(f, &e);                      /* |f| = m 2^e, 0.5 <= m < 1 */
+    int ulp_exp = (e - 1 < -14 ? -14 : e - 1) - 10;
+    double r = ldexp(nearbyint(ldexp(f, -ulp_exp)), ulp_exp);   /* nearbyint: ties to even */
+    if (fabs(r) > 65504.0) return r > 0 ? INFINITY : -INFINITY;
+    return r;
+}
+
+static inline double round_kv(const ko_config *c, double x)
+{
+    return c->kv_round == 1 ? round_bf16(x) : c->kv_round == 2 ? round_f16(x) : x;
 }
 
 ko_model *ko_create(const ko_config *c, const ko_weights *w)
@@ -209,10 +230,10 @@ static void attn_sublayer(ko_model *mo, int slot, const void *g, const void *wq,
             ko_rope(q + (size_t)m * d + h * hd, hd, pos, c->rope_theta);
             ko_rope(k + (size_t)m * d + h * hd, hd, pos, c->rope_theta);
         }
-        if (c->kv_bf16)
+        if (c->kv_round)
             for (int i = 0; i < d; i++) {
-                k[(size_t)m * d + i] = round_bf16(k[(size_t)m * d + i]);
-                v[(size_t)m * d + i] = round_bf16(v[(size_t)m * d + i]);
+                k[(size_t)m * d + i] = round_kv(c, k[(size_t)m * d + i]);
+                v[(size_t)m * d + i] = round_kv(c, v[(size_t)m * d + i]);
             }
         memcpy(Kc + (size_t)pos * d, k + (size_t)m * d, sizeof(double) * d);
         memcpy(Vc + (size_t)pos * d, v + (size_t)m * d, sizeof(double) * d);
@@ -333,10 +354,14 @@ void ko_kv_poison(ko_model *mo, int from)
             }
 }
 
-/* the cache's rounding (exposed so that tests can pin ties and the double -> float step) */
+/* the cache roundings (exposed so that tests can pin ties and the double -> float step) */
 double ko_round_bf16(double x)
 {
     return round_bf16(x);
+}
+double ko_round_f16(double x)
+{
+    return round_f16(x);
 }
 
 /* y = W x for a bare stored matrix (exposed so that tests can pin the widening and the loop) */

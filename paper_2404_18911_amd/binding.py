@@ -27,14 +27,15 @@ class kg_config(ctypes.Structure):
 class kg_params(ctypes.Structure):
     _fields_ = [("mode", ctypes.c_int), ("temperature", ctypes.c_float), ("eta", ctypes.c_float),
                 ("gamma", ctypes.c_int), ("uniforms", ctypes.POINTER(ctypes.c_float)),
-                ("n_uniform_positions", ctypes.c_int)]
+                ("n_uniform_positions", ctypes.c_int), ("seed", ctypes.c_uint64)]
 
 
 class kg_stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in ("rounds", "drafted", "accepted", "emitted")] + \
                [("s_hist", ctypes.c_int * (KG_MAX_ROWS + 1))] + \
                [(n, ctypes.c_int) for n in ("draft_steps", "verify_calls", "plain_steps")] + \
-               [(n, ctypes.c_double) for n in ("t_draft_s", "t_verify_s", "t_total_s")]
+               [(n, ctypes.c_double) for n in ("t_draft_s", "t_verify_s", "t_total_s", "bytes_draft", "bytes_shallow",
+                                               "bytes_verify")]
 
 
 class kg_profile(ctypes.Structure):
@@ -51,7 +52,7 @@ TRAIN_FEATURES, TRAIN_TARGET_LOGITS, TRAIN_DRAFT_LOGITS, TRAIN_GRADIENTS, TRAIN_
 SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "kg_bind", "kg_load_tensor", "kg_set_page_order", "kg_prefill",
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
-           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_stream_read",
+           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_linear_valu", "kg_op_philox_words", "kg_op_stream_read",
            "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_accumulate", "kg_train_apply", "kg_train_features", "kg_train_accumulate_features",
            "kg_train_read", "kg_op_gemm_f32", "kg_op_tile_pos"]
 
@@ -100,6 +101,8 @@ def lib() -> ctypes.CDLL:
     L.kg_op_work_bytes.restype = ctypes.c_size_t
     L.kg_op_pack.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, vp]
     L.kg_op_linear.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_int, vp, vp, vp]
+    L.kg_op_linear_valu.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, vp, vp]
+    L.kg_op_philox_words.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int, vp, vp]
     L.kg_op_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     L.kg_train_workspace_bytes.argtypes = [vp, ctypes.c_int, szp]
     L.kg_train_bind.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int]
@@ -139,15 +142,16 @@ class KangarooError(RuntimeError):
 
 def make_config(shape, max_seq: int, gamma_max: int = 6, kv_page_tokens: int = 128) -> kg_config:
     return kg_config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
-                     shape.exit_layer, 0 if shape.dtype == "f32" else 1, 0 if shape.kv_dtype == "f32" else 1,
+                     shape.exit_layer, 0 if shape.dtype == "f32" else 1, {"f32": 0, "bf16": 1, "f16": 2}[shape.kv_dtype],
                      shape.rms_eps, shape.rope_theta,
                      max_seq, gamma_max, kv_page_tokens, getattr(shape, "adapter", 0))
 
 
 def make_params(mode: int = 0, temperature: float = 1.0, eta: float = 0.6, gamma: int = 6,
-                uniforms: Optional[np.ndarray] = None) -> Tuple[kg_params, object]:
-    """Returns (params, keepalive)."""
-    p = kg_params(mode, temperature, eta, gamma, None, 0)
+                uniforms: Optional[np.ndarray] = None, seed: int = 0) -> Tuple[kg_params, object]:
+    """Returns (params, keepalive).  Sampling mode draws from the device generator keyed by `seed`
+    unless a table of uniform numbers is given."""
+    p = kg_params(mode, temperature, eta, gamma, None, 0, seed)
     keep = None
     if uniforms is not None:
         keep = np.ascontiguousarray(uniforms, dtype=np.float32)

@@ -46,7 +46,7 @@ struct kg_ctx {
     kg_config c;
     bool bf;
     int esz;                 // bytes per stored weight element
-    bool kvbf; int kvesz;    // KV cache element type
+    int kvt; int kvesz;      // KV cache element type (kg_config.kv_dtype) and its size
     int KSd, KSf;            // k-steps (32 features) of d_model and d_ffn
     int n_pages, logP;
     int n_cus = 256;         // compute units of the device (read at kg_bind)
@@ -84,6 +84,12 @@ struct kg_ctx {
     int n_target_rows = 0;
     int plain_len = 0;
     int spec_shallow = -1;   // index j of an early feature f_j already computed ahead of the host's decision
+    // algorithmic bytes (weights streamed + cached keys / values read) by what the launches belong to:
+    // 0 = self-draft model (shallow layers + adapter + head of a draft step), 1 = shallow-only pass
+    // (the stopped token's next early feature), 2 = verification / plain forward, 3 = prompt pass
+    double acct[4] = {0, 0, 0, 0};
+    int acct_phase = 3;
+    double spec_cost = 0;     // bytes of the run-ahead shallow pass still booked as shallow-only
     // adapter training (kg_train_*)
     char *tr = nullptr;
     TrainLayout tl;
@@ -292,6 +298,7 @@ int launch_gemv(kg_ctx *x, size_t w_off, int N, int K, const void *act, const Ep
 {
     if (N % 16) return fail(x, KG_EINVAL, "projection rows %d not a multiple of 16", N);
     ProfScope ps(x, 0, (double)N * K * x->esz);
+    x->acct[x->acct_phase] += (double)N * K * x->esz;
     if (x->bf)
         hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, x->stream,
                            at<const u32x4_t>(x->arena, w_off), (K + 31) / 32, e.M, (const u32x4_t *)act, e.ssq_in, e.nt_in,
@@ -333,7 +340,10 @@ void launch_attn_rows(const AttnArgs &a, dim3 grid, int rows, hipStream_t stream
 int launch_attn_args(kg_ctx *x, const AttnArgs &a, dim3 grid, int rows)
 {
     const int hd = x->c.head_dim;
-    if (x->bf && x->kvbf) {
+    if (x->bf && x->kvt == 2) {
+        if (hd == 128) launch_attn_rows<kvhalf_t, 128, true>(a, grid, rows, x->stream);
+        else launch_attn_rows<kvhalf_t, 64, true>(a, grid, rows, x->stream);
+    } else if (x->bf && x->kvt == 1) {
         if (hd == 128) launch_attn_rows<uint16_t, 128, true>(a, grid, rows, x->stream);
         else launch_attn_rows<uint16_t, 64, true>(a, grid, rows, x->stream);
     } else if (x->bf) {
@@ -369,7 +379,9 @@ int launch_attn(kg_ctx *x, int slot, int pos0, int M, int append_only)
     const kg_config &c = x->c;
     AttnArgs a = attn_args(x, slot, pos0, M);
     a.append_only = append_only;
-    ProfScope ps(x, 1, append_only ? 0.0 : (double)(pos0 + M) * 2 * c.d_model * x->kvesz);
+    const double kv_read = append_only ? 0.0 : (double)(pos0 + M) * 2 * c.d_model * x->kvesz;
+    ProfScope ps(x, 1, kv_read);
+    x->acct[x->acct_phase] += kv_read;
     return launch_attn_args(x, a, dim3(c.n_heads, a.S), M);
 }
 
@@ -449,8 +461,23 @@ int pf_block(kg_ctx *x, int slot, size_t qkv_off, size_t wo_off, size_t gu_off, 
         KGCHK(launch_attn_args(x, a, dim3(c.n_heads, 1, nb), KG_ROWS));
     }
     if (kv_only) return KG_OK;
-    a.append_only = 0; a.append_all = 0; a.preappended = 1;
-    {
+    if (x->kvt == 2) {
+        // half-precision cache: the prompt rows' attention runs on the matrix units
+        PfAttnArgs pa;
+        memset(&pa, 0, sizeof(pa));
+        pa.qkv = at<const float>(x->scr, x->s_pqkv);
+        pa.d = d; pa.H = c.n_heads; pa.T = T; pa.pos0 = pos0; pa.logP = x->logP;
+        pa.page_table = at<const int>(x->scr, x->s_pt);
+        pa.kv = (const kvhalf_t *)x->kv; pa.slot = slot; pa.n_slots = c.n_layers + 1;
+        pa.rope = at<const float2>(x->scr, x->s_rope);
+        pa.act_out = actA; pa.act_blk_bytes = act_bytes(d);
+        ProfScope ps(x, 1, 0.0);
+        const dim3 grid(c.n_heads, (T + 63) / 64);
+        if (c.head_dim == 128) hipLaunchKernelGGL(pf_attn_kernel<128>, grid, dim3(256), 0, x->stream, pa);
+        else hipLaunchKernelGGL(pf_attn_kernel<64>, grid, dim3(256), 0, x->stream, pa);
+        KGCHK(check_launch(x, "prompt attention"));
+    } else {
+        a.append_only = 0; a.append_all = 0; a.preappended = 1;
         ProfScope ps(x, 1, 0.0);
         KGCHK(launch_attn_args(x, a, dim3(c.n_heads, a.S, nb), KG_ROWS));
     }
@@ -562,7 +589,7 @@ int run_layers(kg_ctx *x, int lo, int hi, int M, int pos0, const float *x_first,
 // arg-max and top-1 probability of rows 0..n_out-1 into the device tok/conf arrays.
 // u: per-row uniform numbers for sampling (mode 1), stat: where the rows' (max, sum exp) go.
 int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float inv_temp, int mode = 0,
-             const float *u = nullptr, float *stat = nullptr, bool draft = false)
+             const USrc *us = nullptr, int purpose = 0, float *stat = nullptr, bool draft = false)
 {
     // the draft head is the adapter's own where its architecture has one (Table 2), else the shared LM head
     const size_t head_off = (draft && x->a_head) ? x->a_head : x->head;
@@ -571,22 +598,33 @@ int run_head(kg_ctx *x, int M, int row_shift, float *logits, int n_out, float in
     e.hstat = at<float>(x->scr, x->s_hstat); e.inv_temp = inv_temp;
     KGCHK(launch_gemv(x, head_off, x->c.vocab, x->c.d_model, x->scr + x->s_actX, e));
     ProfScope ps(x, 2, 0.0);
-    F8 uu;
-    for (int i = 0; i < KG_ROWS; i++) uu.v[i] = (u && i < n_out) ? u[i] : 0.f;
+    USrc uu;
+    if (us) uu = *us; else memset(&uu, 0, sizeof(uu));
     hipLaunchKernelGGL(head_final_kernel, dim3(n_out), dim3(1024), 0, x->stream, at<const float>(x->scr, x->s_hstat),
-                       x->c.vocab / 16, (const float *)logits, x->c.vocab, inv_temp, mode, uu, at<int>(x->scr, x->s_tok),
+                       x->c.vocab / 16, (const float *)logits, x->c.vocab, inv_temp, mode, uu, purpose, at<int>(x->scr, x->s_tok),
                        at<float>(x->scr, x->s_conf), stat ? stat : at<float>(x->scr, x->s_tstat));
     return check_launch(x, "head_final");
 }
 
-// uniform number of (absolute position, purpose) for sampling mode
-int uniform_at(kg_ctx *x, const kg_params *p, int pos, int purpose, float *out)
+// Sampling mode: row `row` of a launch decides the token at absolute position pos.  With a table
+// of uniform numbers from the caller its entries for up to two purposes are copied into the launch's
+// arguments; otherwise the kernels evaluate the generator at (seed; position, purpose) themselves.
+int usrc_row(kg_ctx *x, const kg_params *p, USrc &us, int row, int pos, int purpose0, int purpose1 = -1)
 {
-    if (p->mode != 1) { *out = 0.f; return KG_OK; }
-    if (pos < 0 || pos >= p->n_uniform_positions) return fail(x, KG_EINVAL, "uniforms cover %d positions, position %d needed", p->n_uniform_positions, pos);
-    float u = p->uniforms[(size_t)pos * 3 + purpose];
-    if (!(u >= 0.f && u < 1.f)) return fail(x, KG_EINVAL, "uniform number outside [0,1)");
-    *out = u;
+    us.pos[row] = pos;
+    if (p->mode != 1) return KG_OK;
+    us.from_seed = p->uniforms ? 0 : 1;
+    us.k0 = (uint32_t)p->seed; us.k1 = (uint32_t)(p->seed >> 32);
+    if (pos < 0) return fail(x, KG_EINVAL, "negative position");
+    if (!p->uniforms) return KG_OK;
+    if (pos >= p->n_uniform_positions) return fail(x, KG_EINVAL, "uniforms cover %d positions, position %d needed", p->n_uniform_positions, pos);
+    const int pu[2] = {purpose0, purpose1};
+    for (int w = 0; w < 2; w++) {
+        if (pu[w] < 0) continue;
+        const float u = p->uniforms[(size_t)pos * 3 + pu[w]];
+        if (!(u >= 0.f && u < 1.f)) return fail(x, KG_EINVAL, "uniform number outside [0,1)");
+        (w ? us.u1 : us.u0)[row] = u;
+    }
     return KG_OK;
 }
 
@@ -684,7 +722,7 @@ int check_params(kg_ctx *x, const kg_params *p)
     if (p->mode != 0 && p->mode != 1) return fail(x, KG_EINVAL, "mode %d is neither 0 (greedy) nor 1 (sampling)", p->mode);
     if (p->mode == 1) {
         if (!(p->temperature > 0.f)) return fail(x, KG_EINVAL, "temperature must be > 0");
-        if (!p->uniforms) return fail(x, KG_EINVAL, "sampling mode needs uniforms");
+        if (p->uniforms && p->n_uniform_positions < 1) return fail(x, KG_EINVAL, "empty table of uniform numbers");
     }
     if (!(p->eta >= 0.f)) return fail(x, KG_EINVAL, "eta must be >= 0");
     return KG_OK;
@@ -752,8 +790,8 @@ int kg_create(const kg_config *cfg, kg_ctx **out)
     if (c.d_model % 16 || c.d_ffn % 8 || c.vocab % 16 || c.d_model > 8192) return KG_EINVAL;
     if (c.exit_layer < 1 || c.exit_layer > c.n_layers) return KG_EINVAL;
     if (c.dtype != 0 && c.dtype != 1) return KG_EINVAL;
-    if (c.kv_dtype != 0 && c.kv_dtype != 1) return KG_EINVAL;
-    if (c.dtype == 0 && c.kv_dtype == 1) return KG_EINVAL;   // fp32 weights keep an fp32 cache
+    if (c.kv_dtype < 0 || c.kv_dtype > 2) return KG_EINVAL;
+    if (c.dtype == 0 && c.kv_dtype != 0) return KG_EINVAL;   // fp32 weights keep an fp32 cache
     if (c.gamma_max < 1 || c.gamma_max > KG_MAX_ROWS - 1) return KG_EINVAL;
     if (c.kv_page_tokens < 16 || c.kv_page_tokens > 128 || (c.kv_page_tokens & (c.kv_page_tokens - 1))) return KG_EINVAL;
     if ((c.max_seq + c.kv_page_tokens - 1) / c.kv_page_tokens > 128) return KG_EINVAL;   // at most 128 KV pages
@@ -765,8 +803,8 @@ int kg_create(const kg_config *cfg, kg_ctx **out)
     x->akind = c.adapter_kind;
     x->bf = c.dtype == 1;
     x->esz = x->bf ? 2 : 4;
-    x->kvbf = c.kv_dtype == 1;
-    x->kvesz = x->kvbf ? 2 : 4;
+    x->kvt = c.kv_dtype;
+    x->kvesz = x->kvt ? 2 : 4;
     x->KSd = (c.d_model + 31) / 32;
     x->KSf = (c.d_ffn + 31) / 32;
     x->logP = ilog2(c.kv_page_tokens);
@@ -943,9 +981,11 @@ int kg_prefill(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n, int3
     if (n + 1 + p->gamma + 1 > c.max_seq) return fail(x, KG_ENOSPC, "prompt of %d tokens does not fit max_seq %d", n, c.max_seq);
     for (int i = 0; i < n; i++)
         if (prompt[i] < 0 || prompt[i] >= c.vocab) return fail(x, KG_EINVAL, "prompt token %d out of range", prompt[i]);
-    float u_first = 0.f;
-    KGCHK(uniform_at(x, p, n, 2, &u_first));
+    USrc u_first;
+    memset(&u_first, 0, sizeof(u_first));
+    KGCHK(usrc_row(x, p, u_first, 0, n, 2));
     KGCHK(kg_reset(x));
+    x->acct_phase = 3;
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     if (x->pf_rows > 0) {
         // bf16 weights: the prompt goes through the MFMA projections, pf_rows rows per pass
@@ -958,7 +998,7 @@ int kg_prefill(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n, int3
                 // target distribution of the first new token: final norm + LM head on the last row
                 KGCHK(launch_pack_rows(x, nullptr, x_last + (size_t)(T - 1) * c.d_model, 1, at<const float>(x->arena, x->gfinal),
                                        nullptr, x->scr + x->s_actX, at<float>(x->scr, x->s_ssq0)));
-                KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first));
+                KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first, 2));
             }
         }
     } else {
@@ -967,7 +1007,7 @@ int kg_prefill(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n, int3
             KGCHK(run_shallow(x, prompt + pos0, M, pos0, 0));
             KGCHK(run_adapter(x, 1, M, pos0, false));
             KGCHK(run_deep(x, M, pos0));
-            if (pos0 + M == n) KGCHK(run_head(x, M, -(M - 1), at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first));
+            if (pos0 + M == n) KGCHK(run_head(x, M, -(M - 1), at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_first, 2));
         }
     }
     KGCHK(fetch_results(x, 1));
@@ -992,9 +1032,13 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     if (x->base + j + 2 >= x->c.max_seq) return fail(x, KG_ENOSPC, "sequence would exceed max_seq");
     const int tok = j == 0 ? x->pending : x->drafts[j - 1];
     const int pos = x->base + j;
-    float u_draft = 0.f;
-    KGCHK(uniform_at(x, p, pos + 1, 0, &u_draft));
+    USrc u_draft;
+    memset(&u_draft, 0, sizeof(u_draft));
+    KGCHK(usrc_row(x, p, u_draft, 0, pos + 1, 0));
+    // a run-ahead pass that becomes this step's shallow pass was booked as shallow-only: move it
+    x->acct_phase = 0;
     if (x->spec_shallow != j) KGCHK(run_shallow(x, &tok, 1, pos, j));
+    else { x->acct[1] -= x->spec_cost; x->acct[0] += x->spec_cost; }
     x->spec_shallow = -1;
     int M = 1;
     if (j == 0 && x->lag && x->akind != KG_ADAPTER_MLP) {   // adapter catches up on [lagged f, f_0] (Figure 2)
@@ -1005,7 +1049,7 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     }
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     float *dl = at<float>(x->scr, x->s_dlog) + (size_t)j * x->c.vocab;
-    KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t, p->mode, &u_draft, at<float>(x->scr, x->s_dstat) + 2 * j, true));
+    KGCHK(run_head(x, M, -(M - 1), dl, 1, inv_t, p->mode, &u_draft, 0, at<float>(x->scr, x->s_dstat) + 2 * j, true));
     // The draft token's early feature is needed whatever the host decides next (one more draft
     // step, or verification): compute it now, reading the token from device memory, so that the
     // GPU keeps working while the host waits for the token and its confidence.  The results are
@@ -1013,7 +1057,12 @@ int kg_draft_step(kg_ctx *x, const kg_params *p, int32_t *token, float *confiden
     HIPCHK(x, hipMemcpyAsync(x->h_tok, x->scr + x->s_tok, KG_ROWS * 8, hipMemcpyDeviceToHost, x->stream));
     hipEvent_t ev = x->ev_fetch;
     HIPCHK(x, hipEventRecord(ev, x->stream));
-    KGCHK(run_shallow(x, nullptr, 1, pos + 1, j + 1, at<const int>(x->scr, x->s_tok)));
+    {
+        x->acct_phase = 1;
+        const double before = x->acct[1];
+        KGCHK(run_shallow(x, nullptr, 1, pos + 1, j + 1, at<const int>(x->scr, x->s_tok)));
+        x->spec_cost = x->acct[1] - before;
+    }
     x->spec_shallow = j + 1;
     HIPCHK(x, hipEventSynchronize(ev));
     KGCHK(check_tokens(x, 1));
@@ -1039,8 +1088,10 @@ int kg_verify(kg_ctx *x, const kg_params *p, int32_t *target_tokens, int *k_plus
     const int k = x->n_drafts;
     if (x->base + k + 1 >= x->c.max_seq) return fail(x, KG_ENOSPC, "sequence would exceed max_seq");
     const int tok = x->drafts[k - 1];
+    x->acct_phase = 1;
     if (x->spec_shallow != k) KGCHK(run_shallow(x, &tok, 1, x->base + k, k));   // next early feature f_k; adapter not run
     x->spec_shallow = -1;
+    x->acct_phase = 2;
     KGCHK(run_deep(x, k + 1, x->base));
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
     KGCHK(run_head(x, k + 1, 0, at<float>(x->scr, x->s_tlog), k + 1, inv_t));
@@ -1066,17 +1117,16 @@ int kg_accept(kg_ctx *x, const kg_params *p, int32_t *emitted, int *n_emitted)
         emitted[n] = x->targets[n];
     } else {
         I8 dr;
-        F8 ua, ur;
-        for (int i = 0; i < KG_ROWS; i++) { dr.v[i] = i < k ? x->drafts[i] : 0; ua.v[i] = 0.f; ur.v[i] = 0.f; }
-        for (int i = 0; i <= k; i++) {             // row i decides the token at position base + i + 1
-            if (i < k) KGCHK(uniform_at(x, p, x->base + i + 1, 1, &ua.v[i]));
-            KGCHK(uniform_at(x, p, x->base + i + 1, 2, &ur.v[i]));
-        }
+        USrc us;
+        memset(&us, 0, sizeof(us));
+        for (int i = 0; i < KG_ROWS; i++) dr.v[i] = i < k ? x->drafts[i] : 0;
+        for (int i = 0; i <= k; i++)               // row i decides the token at position base + i + 1
+            KGCHK(usrc_row(x, p, us, i, x->base + i + 1, i < k ? 1 : -1, 2));
         {
             ProfScope ps(x, 2, 0.0);
             hipLaunchKernelGGL(accept_sample_kernel, dim3(1), dim3(1024), 0, x->stream, at<const float>(x->scr, x->s_tlog),
                                at<const float>(x->scr, x->s_dlog), at<const float>(x->scr, x->s_tstat),
-                               at<const float>(x->scr, x->s_dstat), x->c.vocab, k, 1.f / p->temperature, dr, ua, ur,
+                               at<const float>(x->scr, x->s_dstat), x->c.vocab, k, 1.f / p->temperature, dr, us,
                                at<int>(x->scr, x->s_acc));
             KGCHK(check_launch(x, "accept_sample"));
         }
@@ -1118,6 +1168,7 @@ int kg_generate(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n_prom
     memset(&s, 0, sizeof(s));
     int32_t tok;
     KGCHK(kg_prefill(x, p, prompt, n_prompt, &tok));
+    const double a0[3] = {x->acct[0], x->acct[1], x->acct[2]};
     double t0 = now_s();
     int n = 0;
     out[n++] = tok;
@@ -1141,6 +1192,7 @@ int kg_generate(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n_prom
     }
     s.emitted = n;
     s.t_total_s = now_s() - t0;
+    s.bytes_draft = x->acct[0] - a0[0]; s.bytes_shallow = x->acct[1] - a0[1]; s.bytes_verify = x->acct[2] - a0[2];
     *n_out = n;
     if (st) *st = s;
     return KG_OK;
@@ -1157,13 +1209,15 @@ int kg_plain_step(kg_ctx *x, const kg_params *p, int32_t token, int32_t *next_to
     const kg_config &c = x->c;
     float *x0 = at<float>(x->scr, x->s_x0);
     const int tok = token;
+    x->acct_phase = 2;
     KGCHK(launch_pack_rows(x, &tok, nullptr, 1, at<const float>(x->arena, x->lw[0].g1), x0, x->scr + x->s_actX,
                            at<float>(x->scr, x->s_ssq0)));
     KGCHK(run_layers(x, 0, c.n_layers, 1, x->plain_len, x0, x0, at<const float>(x->arena, x->gfinal)));
     float inv_t = p->mode == 1 ? 1.f / p->temperature : 1.f;
-    float u_next = 0.f;
-    KGCHK(uniform_at(x, p, x->plain_len + 1, 2, &u_next));
-    KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_next));
+    USrc u_next;
+    memset(&u_next, 0, sizeof(u_next));
+    KGCHK(usrc_row(x, p, u_next, 0, x->plain_len + 1, 2));
+    KGCHK(run_head(x, 1, 0, at<float>(x->scr, x->s_tlog), 1, inv_t, p->mode, &u_next, 2));
     KGCHK(fetch_results(x, 1));
     x->plain_len++;
     x->n_target_rows = 1;
@@ -1183,6 +1237,7 @@ int kg_decode_plain(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n_
     memset(&s, 0, sizeof(s));
     int32_t tok;
     KGCHK(kg_prefill(x, p, prompt, n_prompt, &tok));
+    const double a2 = x->acct[2];
     double t0 = now_s();
     int n = 0;
     out[n++] = tok;
@@ -1193,6 +1248,7 @@ int kg_decode_plain(kg_ctx *x, const kg_params *p, const int32_t *prompt, int n_
     }
     s.emitted = n;
     s.t_total_s = now_s() - t0;
+    s.bytes_verify = x->acct[2] - a2;
     *n_out = n;
     if (st) *st = s;
     return KG_OK;
@@ -1234,7 +1290,11 @@ int kg_read_kv(kg_ctx *x, int slot, int pos, float *k_host, float *v_host)
     if (slot < 0 || slot > c.n_layers || pos < 0 || pos >= c.max_seq) return fail(x, KG_EINVAL, "slot/pos out of range");
     float *tmp = at<float>(x->scr, x->s_misc);
     int n = c.d_model;
-    if (x->kvbf)
+    if (x->kvt == 2)
+        hipLaunchKernelGGL(kv_read_kernel<kvhalf_t>, dim3((n + 255) / 256), dim3(256), 0, x->stream, x->kv,
+                           at<const int>(x->scr, x->s_pt), slot, c.n_layers + 1, c.n_heads, c.head_dim,
+                           c.kv_page_tokens, x->logP, pos, tmp, tmp + n);
+    else if (x->kvt == 1)
         hipLaunchKernelGGL(kv_read_kernel<uint16_t>, dim3((n + 255) / 256), dim3(256), 0, x->stream, x->kv,
                            at<const int>(x->scr, x->s_pt), slot, c.n_layers + 1, c.n_heads, c.head_dim,
                            c.kv_page_tokens, x->logP, pos, tmp, tmp + n);
@@ -1847,20 +1907,22 @@ int kg_op_pack(int dtype, const void *src, int N, int K, void *packed, void *hip
     return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
 }
 
-int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, int M, float *yd, void *work,
-                 void *hip_stream)
+// Both entry points of the stand-alone projection: the activation staging area `work` comes from the
+// caller (cleared with a memset) or is the library's static array (cleared by a fill kernel, which a
+// stream capture can record).
+static int op_linear_launch(int dtype, const void *packed, int N, int K, const float *xd, int M, float *yd, void *work,
+                            hipStream_t s, bool clear_by_kernel)
 {
-    if (!packed || !xd || !yd || !work || N < 16 || N % 16 || K < 16 || K % 16 || M < 1 || M > KG_ROWS ||
-        (dtype != 0 && dtype != 1))
-        return KG_EINVAL;
-    hipStream_t s = (hipStream_t)hip_stream;
     Tok8 tk;
     memset(&tk, 0, sizeof(tk));
     Epi e;
     memset(&e, 0, sizeof(e));
     e.kind = EPI_PLAIN; e.M = M; e.N = N; e.out = yd;
     if (dtype == 1) {
-        if (hipMemsetAsync(work, 0, act_bytes(K), s) != hipSuccess) return KG_EHIP;
+        if (clear_by_kernel) {
+            const unsigned n16 = (unsigned)(act_bytes(K) / 16);
+            hipLaunchKernelGGL(fill_zero_kernel, dim3((n16 + 255) / 256), dim3(256), 0, s, (u32x4_t *)work, n16);
+        } else if (hipMemsetAsync(work, 0, act_bytes(K), s) != hipSuccess) return KG_EHIP;
         hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(K / 16), dim3(128), 0, s, (const void *)nullptr, tk, (const int *)nullptr, xd, K, M,
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
         hipLaunchKernelGGL(gemv_bf16_kernel, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, s, (const u32x4_t *)packed, (K + 31) / 32,
@@ -1870,6 +1932,35 @@ int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, i
                            (const float *)nullptr, (float *)nullptr, work, (float *)nullptr);
         hipLaunchKernelGGL(gemv_f32_kernel, dim3(N / 16), dim3(256), 0, s, (const float *)packed, K, (const float *)work, e);
     }
+    return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
+}
+
+static bool op_linear_args_ok(int dtype, const void *packed, int N, int K, const float *xd, int M, const float *yd)
+{
+    return packed && xd && yd && N >= 16 && N % 16 == 0 && K >= 16 && K % 16 == 0 && M >= 1 && M <= KG_ROWS &&
+           (dtype == 0 || dtype == 1);
+}
+
+int kg_op_linear(int dtype, const void *packed, int N, int K, const float *xd, int M, float *yd, void *work,
+                 void *hip_stream)
+{
+    if (!op_linear_args_ok(dtype, packed, N, K, xd, M, yd) || !work) return KG_EINVAL;
+    return op_linear_launch(dtype, packed, N, K, xd, M, yd, work, (hipStream_t)hip_stream, false);
+}
+
+int kg_op_linear_valu(const void *packed, int N, int K, const float *xd, float *yd, void *hip_stream)
+{
+    if (!packed || !xd || !yd || N < 16 || N % 16 || K < 16 || K % 16) return KG_EINVAL;
+    hipLaunchKernelGGL(gemv_bf16_valu_kernel, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, (hipStream_t)hip_stream,
+                       (const u32x4_t *)packed, (K + 31) / 32, xd, K, yd);
+    return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
+}
+
+int kg_op_philox_words(uint64_t seed, uint32_t pos0, uint32_t purpose, int n, uint32_t *out_dev, void *hip_stream)
+{
+    if (!out_dev || n < 1) return KG_EINVAL;
+    hipLaunchKernelGGL(philox_words_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), pos0, purpose, n, out_dev);
     return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
 }
 

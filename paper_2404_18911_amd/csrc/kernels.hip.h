@@ -365,6 +365,73 @@ __global__ __launch_bounds__(64 * GEMV_WAVES, 2) void gemv_bf16_kernel(const u32
     epilogue<true>(e, rt, yt, sc, sq, resv, gainv, true);
 }
 
+// The one-row projection on the vector ALUs instead of the matrix units, over the same weight tiles,
+// launch shape, k ranges and chunked, double-buffered loads as gemv_bf16_kernel: the comparison that
+// backs the choice of an MFMA per tile also at one row (where 7 of its 8 row columns are idle).  A
+// lane holds 8 consecutive k of one weight row: it widens them and multiplies by the row's fp32
+// activations, the four lanes of a row are added at the end of the wave's range, the waves through LDS.
+// y[n] = sum_k W[n][k] x[k], plain fp32 output; used by kg_op_linear_valu only.
+__global__ __launch_bounds__(64 * GEMV_WAVES, 2) void gemv_bf16_valu_kernel(const u32x4_t *__restrict__ W, int KS,
+                                                                        const float *__restrict__ x, int K, float *y)
+{
+    __shared__ float part[GEMV_WAVES][16];
+    const int rt = blockIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int ks0 = (wave * KS) / GEMV_WAVES, ks1 = ((wave + 1) * KS) / GEMV_WAVES;
+    const int q = KS >> 3, n_long = KS - 8 * q;
+    const bool long_range = ks1 - ks0 > q;
+    const u32x4_t *wbase = W + (size_t)rt * KS * 64 + lane;
+    const u32x4_t *wp = wbase + (size_t)(n_long + wave) * 64;
+    const int g8 = (lane >> 4) * 8;
+    int ks = ks0 + (long_range ? 1 : 0);
+    float acc = 0.f;
+    auto mac = [&](const u32x4_t &a, int kstep) {
+        const int k0 = kstep * 32 + g8;
+        float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0;
+        if (k0 + 8 <= K) { x0 = *(const float4 *)(x + k0); x1 = *(const float4 *)(x + k0 + 4); }
+        acc = fmaf(__uint_as_float(a[0] << 16), x0.x, acc); acc = fmaf(__uint_as_float(a[0] & 0xFFFF0000u), x0.y, acc);
+        acc = fmaf(__uint_as_float(a[1] << 16), x0.z, acc); acc = fmaf(__uint_as_float(a[1] & 0xFFFF0000u), x0.w, acc);
+        acc = fmaf(__uint_as_float(a[2] << 16), x1.x, acc); acc = fmaf(__uint_as_float(a[2] & 0xFFFF0000u), x1.y, acc);
+        acc = fmaf(__uint_as_float(a[3] << 16), x1.z, acc); acc = fmaf(__uint_as_float(a[3] & 0xFFFF0000u), x1.w, acc);
+    };
+    if (long_range) {
+        const u32x4_t ax = __builtin_nontemporal_load(wbase + (size_t)(ks0 - wave * q) * 64);
+        mac(ax, ks0);
+    }
+    int n = q;
+    u32x4_t a0[4], a1[4];
+    int rem = n >> 2;
+    n &= 3;
+#define LDV(A) { _Pragma("unroll") for (int u = 0; u < 4; u++) A[u] = __builtin_nontemporal_load(wp + u * 512); wp += 2048; }
+#define MACV(A) { _Pragma("unroll") for (int u = 0; u < 4; u++) mac(A[u], ks + u); ks += 4; }
+    if (rem) LDV(a0)
+    while (rem >= 2) {
+        LDV(a1)
+        MACV(a0)
+        if (rem > 2) LDV(a0)
+        MACV(a1)
+        rem -= 2;
+    }
+    if (rem == 1) MACV(a0)
+#undef LDV
+#undef MACV
+    for (; n > 0; n--) {
+        const u32x4_t a = __builtin_nontemporal_load(wp);
+        wp += 512;
+        mac(a, ks++);
+    }
+    acc += __shfl_xor(acc, 16);
+    acc += __shfl_xor(acc, 32);
+    if (lane < 16) part[wave][lane] = acc;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        float v = part[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < GEMV_WAVES; w++) v += part[w][threadIdx.x];
+        y[rt * 16 + threadIdx.x] = v;
+    }
+}
+
 // Projection, fp32 weights (row-major [N][K]) and fp32 activations [8][K]: 16 threads per row.
 // Only the small fp32 correctness configuration uses it.
 __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__ W, int K,
@@ -831,15 +898,28 @@ struct AttnArgs {
     int append_all;     // with append_only: write every row of the block to its own page (grid.y = 1)
 };
 
+// Element types of the KV cache: float, uint16_t (bfloat16 bit patterns), kvhalf_t (IEEE half bit
+// patterns).  Keys and values are O(1) numbers, far inside the half range; half keeps three more
+// significant bits than bfloat16 in the same two bytes.
+// A half only ever exists as an integer bit pattern in memory, registers and aggregates here, and is
+// converted at the point of use (arrays of structs with a _Float16 member that are filled
+// conditionally came out of the compiler with every second element undefined).
+struct kvhalf_t { uint16_t bits; };
+static_assert(sizeof(kvhalf_t) == 2, "two-byte cache element");
+__device__ __forceinline__ float half_bits_to_f32(uint32_t low16) { return (float)__builtin_bit_cast(_Float16, (uint16_t)low16); }
+__device__ __forceinline__ uint16_t f32_to_half_bits(float v) { return __builtin_bit_cast(uint16_t, (_Float16)v); }
 template <typename T> __device__ __forceinline__ float kv_ld(const T *p);
 template <> __device__ __forceinline__ float kv_ld<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float kv_ld<uint16_t>(const uint16_t *p) { return bf2f(*p); }
+template <> __device__ __forceinline__ float kv_ld<kvhalf_t>(const kvhalf_t *p) { return half_bits_to_f32(p->bits); }
 template <typename T> __device__ __forceinline__ float kv_round(float v);     // value as the cache type holds it
 template <> __device__ __forceinline__ float kv_round<float>(float v) { return v; }
 template <> __device__ __forceinline__ float kv_round<uint16_t>(float v) { return bf2f(f2bf(v)); }
+template <> __device__ __forceinline__ float kv_round<kvhalf_t>(float v) { return half_bits_to_f32(f32_to_half_bits(rounded(v))); }
 template <typename T> __device__ __forceinline__ void kv_st(T *p, float v);
 template <> __device__ __forceinline__ void kv_st<float>(float *p, float v) { *p = v; }
 template <> __device__ __forceinline__ void kv_st<uint16_t>(uint16_t *p, float v) { *p = f2bf(v); }
+template <> __device__ __forceinline__ void kv_st<kvhalf_t>(kvhalf_t *p, float v) { p->bits = f32_to_half_bits(v); }
 
 template <typename T, int N8> struct KvVec;           // N8 groups of 8 cache elements, loaded as 16-byte pieces
 template <int N8> struct KvVec<uint16_t, N8> {
@@ -853,6 +933,19 @@ template <int N8> struct KvVec<uint16_t, N8> {
     {
         uint32_t w = r[i >> 3][(i >> 1) & 3];
         return __uint_as_float((i & 1) ? (w & 0xFFFF0000u) : (w << 16));
+    }
+};
+template <int N8> struct KvVec<kvhalf_t, N8> {
+    u32x4_t r[N8];
+    __device__ __forceinline__ void load(const kvhalf_t *p)
+    {
+#pragma unroll
+        for (int i = 0; i < N8; i++) r[i] = *(const u32x4_t *)(p + 8 * i);
+    }
+    __device__ __forceinline__ float get(int i) const
+    {
+        const uint32_t w = r[i >> 3][(i >> 1) & 3];
+        return half_bits_to_f32((i & 1) ? (w >> 16) : (w & 0xFFFFu));
     }
 };
 template <int N8> struct KvVec<float, N8> {
@@ -880,6 +973,16 @@ template <> struct KvLane<uint16_t, 1> {
     uint16_t r;
     __device__ __forceinline__ void load(const uint16_t *p) { r = *p; }
     __device__ __forceinline__ float get(int) const { return bf2f(r); }
+};
+template <> struct KvLane<kvhalf_t, 2> {
+    uint32_t r;
+    __device__ __forceinline__ void load(const kvhalf_t *p) { r = *(const uint32_t *)p; }
+    __device__ __forceinline__ float get(int e) const { return half_bits_to_f32(e ? (r >> 16) : (r & 0xFFFFu)); }
+};
+template <> struct KvLane<kvhalf_t, 1> {
+    uint32_t r;
+    __device__ __forceinline__ void load(const kvhalf_t *p) { r = p->bits; }
+    __device__ __forceinline__ float get(int) const { return half_bits_to_f32(r); }
 };
 template <> struct KvLane<float, 2> {
     float2 r;
@@ -1237,22 +1340,288 @@ __global__ __launch_bounds__(512, (sizeof(T) == 2 ? 6 : 1)) void attn_kernel(con
 }
 
 // ---------------------------------------------------------------------------------------------
+// Attention of the prompt rows (prefill) on the matrix units, for a half-precision KV cache.
+// One workgroup (4 waves) per head and block of 64 query rows; a wave owns 16 rows.  The keys and
+// values of all rows of this pass are already in the cache (appended by an earlier launch), so the
+// block walks the cache in tiles of 128 positions up to its own last row:
+//   S^T = K Q^T   per 16-position tile: A = keys from LDS (as stored: one position's 8 consecutive
+//         dimensions per lane), B = the rotated, scaled queries held in registers as half hi + lo
+//         parts (two MFMAs per step, fp32-grade scores); the result has a lane's query row in its
+//         column and four positions in its registers;
+//   row softmax   running maximum and sum per query row (flash-attention recurrence), reductions
+//         over a lane's own registers and two lane exchanges;
+//   O = P V       A = the probabilities straight from the score registers, rounded to half (the
+//         contraction index may be enumerated in any order as long as both operands agree: k-slot
+//         j of lane group g is position 32 u + 16 (j / 4) + 4 g + j % 4), B = V^T from LDS, where the
+//         values were transposed on the way in and laid out in exactly that order.
+// Rows are masked causally; rows beyond the pass are computed and dropped.  The output goes to the
+// activation tiles of the output projection (hi + lo bf16 parts per 8-row block), like the decode
+// kernel's.  Numerically the rows differ from the decode kernel's in the order of the sums and in
+// the half-precision probabilities (relative 2^-12), far inside the logit tolerance.
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+
+struct PfAttnArgs {
+    const float *qkv;        // [T][3d] rows of this pass: q | k | v, RMS-scaled projections, not rotated
+    int d, H, T, pos0, logP;
+    const int *page_table;
+    const kvhalf_t *kv;      // pool: [phys page][slot][head][K|V][P][hd]
+    int slot, n_slots;
+    const float2 *rope;      // [max_seq][hd/2]
+    void *act_out;           // activation tiles of the output projection, one per 8-row block
+    size_t act_blk_bytes;
+};
+
+template <int HD>
+__global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
+{
+    constexpr int KS = HD / 32;                 // contraction steps of Q.K^T
+    constexpr int DT = HD / 16;                 // 16-wide tiles of the head dimension
+    constexpr int HH = HD / 2;
+    constexpr int KROW = HD + 8;                // halves per key row in LDS (16 bytes of padding: conflict-free 16-byte reads)
+    constexpr int VROW = 128 + 8;               // halves per dimension row of V^T in LDS
+    __shared__ __align__(16) uint16_t Ks[128 * KROW];
+    __shared__ __align__(16) uint16_t Vt[HD * VROW];
+    const int h = blockIdx.x, t = threadIdx.x;
+    const int rb = (int)gridDim.y - 1 - (int)blockIdx.y;        // late row blocks (most tiles) are scheduled first
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
+    const int q16 = lane & 15, g = lane >> 4;
+    const int P = 1 << a.logP, d = a.d;
+    const int row = rb * 64 + wave * 16 + q16;                  // the query row this lane's column stands for
+    const int qpos = a.pos0 + row;
+    const bool row_ok = row < a.T;
+    const int last_pos = a.pos0 + min(a.T, rb * 64 + 64) - 1;   // last position any row of the block attends to
+    const int n_tiles = (last_pos >> 7) + 1;
+    const int wave_last = a.pos0 + min(a.T - 1, rb * 64 + wave * 16 + 15);
+    const size_t unit = (size_t)2 * P * HD;
+
+    // queries: rotate, scale, split into half hi + lo, in B-operand order (8 consecutive dimensions per lane and step)
+    f16x8_t qhi[KS], qlo[KS];
+    {
+        const float *q = a.qkv + (size_t)min(row, a.T - 1) * 3 * d + h * HD;
+        const float qscale = rsqrtf((float)HD);
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const int dim = 32 * ks + 8 * g + e, i = dim % HH;
+                const float2 cs = a.rope[(size_t)min(qpos, a.pos0 + a.T - 1) * HH + i];
+                const float x0 = q[i], x1 = q[i + HH];
+                const float v = rounded((dim < HH ? rot_lo(x0, x1, cs) : rot_hi(x0, x1, cs)) * qscale);
+                const _Float16 hi = (_Float16)v;
+                qhi[ks][e] = hi;
+                qlo[ks][e] = (_Float16)(v - (float)hi);
+            }
+        }
+    }
+    f32x4_t o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; dt++) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;       // running maximum of the row (same in its four lanes), this lane's share of the sum
+
+    for (int kt = 0; kt < n_tiles; kt++) {
+        const int tile0 = kt << 7;
+        __syncthreads();                        // the previous tile has been consumed
+        // keys as stored: thread -> (position, 8 dimensions); positions beyond the block's reach are zero
+#pragma unroll
+        for (int i = 0; i < HD / 16; i++) {
+            const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
+            const int ap = tile0 + pos;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (ap <= last_pos) {
+                const kvhalf_t *Kp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit;
+                v = *(const u32x4_t *)(Kp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
+            }
+            *(u32x4_t *)&Ks[pos * KROW + 8 * dq] = v;
+        }
+        // values, transposed: thread -> (8 dimensions, position = lane-consecutive); two neighbouring positions are
+        // packed into one 32-bit LDS write by the even lane
+#pragma unroll
+        for (int i = 0; i < HD / 16; i++) {
+            const int pc = t + 256 * i, pos = pc & 127, dq = pc >> 7;
+            const int ap = tile0 + pos;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (ap <= last_pos) {
+                const kvhalf_t *Vp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit + (size_t)P * HD;
+                v = *(const u32x4_t *)(Vp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
+            }
+            // column of position pos inside a dimension row: [u = pos / 32][g = (pos % 16) / 4][j = 4 ((pos / 16) % 2) + pos % 4]
+            const int col = (pos >> 5) * 32 + ((pos & 15) >> 2) * 8 + ((pos >> 4) & 1) * 4 + (pos & 3);
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                const uint32_t mine = v[w];
+                const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xB1, 0xF, 0xF, false);   // lane ^ 1
+                if ((lane & 1) == 0) {
+                    *(uint32_t *)&Vt[(8 * dq + 2 * w) * VROW + col] = (mine & 0xFFFFu) | (other << 16);
+                    *(uint32_t *)&Vt[(8 * dq + 2 * w + 1) * VROW + col] = (mine >> 16) | (other & 0xFFFF0000u);
+                }
+            }
+        }
+        __syncthreads();
+        if (tile0 > wave_last) continue;        // nothing of this tile is visible to the wave's rows (uniform in the wave)
+
+        // scores of 128 positions x 16 query rows
+        f32x4_t s[8];
+#pragma unroll
+        for (int pt = 0; pt < 8; pt++) {
+            s[pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) {
+                const f16x8_t kk = __builtin_bit_cast(f16x8_t, *(const u32x4_t *)&Ks[(16 * pt + q16) * KROW + 32 * ks + 8 * g]);
+                s[pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kk, qhi[ks], s[pt], 0, 0, 0);
+                s[pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kk, qlo[ks], s[pt], 0, 0, 0);
+            }
+        }
+        // causal mask, tile maximum of the row
+        float mx = -INFINITY;
+#pragma unroll
+        for (int pt = 0; pt < 8; pt++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const int ap = tile0 + 16 * pt + 4 * g + r;
+                const float v = (row_ok && ap <= qpos) ? s[pt][r] : -INFINITY;
+                s[pt][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float scale = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);     // m_run = -inf gives 0
+        float psum = 0.f;
+        f16x8_t pa[4];
+#pragma unroll
+        for (int pt = 0; pt < 8; pt++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const float p = (s[pt][r] == -INFINITY) ? 0.f : __expf(s[pt][r] - m_new);
+                psum += p;
+                pa[pt >> 1][4 * (pt & 1) + r] = (_Float16)p;
+            }
+        l_run = l_run * scale + psum;
+        m_run = m_new;
+        // rescale the output rows 4 g + r by the factor of their query row, then add P.V
+        float sc[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) sc[r] = __shfl(scale, 4 * g + r);
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++) {
+#pragma unroll
+            for (int r = 0; r < 4; r++) o[dt][r] *= sc[r];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const f16x8_t vv = __builtin_bit_cast(f16x8_t, *(const u32x4_t *)&Vt[(16 * dt + q16) * VROW + 32 * u + 8 * g]);
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[u], vv, o[dt], 0, 0, 0);
+            }
+        }
+    }
+    // normalise and store: lane holds dimension 16 dt + q16 of query rows 4 g + r
+    float l = l_run + __shfl_xor(l_run, 16);
+    l += __shfl_xor(l, 32);
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        const float ir = __shfl(inv, 4 * g + r);
+        const int orow = rb * 64 + wave * 16 + 4 * g + r;
+        if (orow < a.T) {
+            void *blk = (char *)a.act_out + (size_t)(orow >> 3) * a.act_blk_bytes;
+#pragma unroll
+            for (int dt = 0; dt < DT; dt++) store_act<true>(blk, d, orow & 7, h * HD + 16 * dt + q16, o[dt][r] * ir);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Random numbers of sampling mode: Philox4x32-10 (Salmon et al., SC 2011), a counter-based generator,
+// so that the number for (absolute token position, purpose) can be produced by whichever kernel
+// needs it, with no state to carry and independent of the control flow that led there.
+// Ten rounds on the counter words (c0, c1, c2, c3) under the key (k0, k1):
+//   (c0, c1, c2, c3) <- (mulhi(B, c2) ^ c1 ^ k0, B * c2, mulhi(A, c0) ^ c3 ^ k1, A * c0),
+// A = 0xD2511F53, B = 0xCD9E8D57, products mod 2^32; the key grows by (0x9E3779B9, 0xBB67AE85)
+// between rounds.  Returns the first word of the block for counter (position, purpose, 0, 0).
+__device__ __forceinline__ uint32_t philox_word(uint32_t k0, uint32_t k1, uint32_t position, uint32_t purpose)
+{
+    uint32_t a = position, b = purpose, c = 0u, d = 0u;
+#pragma unroll
+    for (int r = 0; r < 10; r++) {
+        const uint32_t ha = __umulhi(0xD2511F53u, a), la = 0xD2511F53u * a;
+        const uint32_t hc = __umulhi(0xCD9E8D57u, c), lc = 0xCD9E8D57u * c;
+        a = hc ^ b ^ (k0 + (uint32_t)r * 0x9E3779B9u);
+        c = ha ^ d ^ (k1 + (uint32_t)r * 0xBB67AE85u);
+        b = lc;
+        d = la;
+    }
+    return a;
+}
+// uniform number in [0, 1) with 24 random bits
+__device__ __forceinline__ float philox_uniform(uint32_t k0, uint32_t k1, uint32_t position, uint32_t purpose)
+{
+    return (float)(philox_word(k0, k1, position, purpose) >> 8) * (1.f / 16777216.f);
+}
+
+__global__ void philox_words_kernel(uint32_t k0, uint32_t k1, uint32_t pos0, uint32_t purpose, int n, uint32_t *out)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = philox_word(k0, k1, pos0 + (uint32_t)i, purpose);
+}
+
+// Where the uniform numbers of a launch's rows come from: the generator keyed by the seed, evaluated
+// at the absolute position each row decides, or numbers the caller supplied (a test hook).
+struct USrc {
+    int from_seed;
+    uint32_t k0, k1;
+    int pos[KG_ROWS];
+    float u0[KG_ROWS], u1[KG_ROWS];     // caller's numbers for the launch's first / second purpose
+};
+__device__ __forceinline__ float row_uniform(const USrc &s, int row, int purpose, int which)
+{
+    // constant indices only: the argument block stays in scalar registers
+    float tv = 0.f;
+    int pv = 0;
+#pragma unroll
+    for (int i = 0; i < KG_ROWS; i++)
+        if (i == row) { tv = which ? s.u1[i] : s.u0[i]; pv = s.pos[i]; }
+    return s.from_seed ? philox_uniform(s.k0, s.k1, (uint32_t)pv, (uint32_t)purpose) : tv;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Block-wide inverse-CDF draw (1024 threads): smallest index n with w(0) + .. + w(n) > u * total,
 // walking ascending indices; weights are accumulated in double.  Returns -1 when total == 0.
-// All threads must call it; all get the result.
-struct F8 { float v[KG_ROWS]; };
+// All threads must call it; all get the result.  The weight of index i is w(za[i], zb[i]) (zb may be
+// null: its value is then 0).
+// Up to 32768 indices every thread owns 32 consecutive ones: it fetches them with 16-byte loads,
+// computes their weights once and keeps them in registers for the sum, the walk and the fallback;
+// larger index sets are walked in chunks with the weights recomputed.
 struct I8 { int v[KG_ROWS]; };
 
 template <class F>
-__device__ int block_inverse_cdf(F w, int V, float u)
+__device__ int block_inverse_cdf(const float *za, const float *zb, F w, int V, float u)
 {
     __shared__ double wsum[16];
     __shared__ int found, lastpos;
     const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
-    const int chunk = (V + 1023) >> 10;
+    const bool in_regs = V <= 32768 && (V & 3) == 0;
+    const int chunk = in_regs ? 32 : (V + 1023) >> 10;
     const int i0 = min(V, t * chunk), i1 = min(V, i0 + chunk);
+    float wv[32];
     double local = 0.0;
-    for (int i = i0; i < i1; i++) local += (double)w(i);
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < 32; j += 4) {
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            const bool in = i0 + j < i1;                       // V % 4 == 0: a group of four is all in or all out
+            if (in) {
+                a = *(const float4 *)(za + i0 + j);
+                if (zb) b = *(const float4 *)(zb + i0 + j);
+            }
+            wv[j] = in ? w(a.x, b.x) : 0.f;
+            wv[j + 1] = in ? w(a.y, b.y) : 0.f;
+            wv[j + 2] = in ? w(a.z, b.z) : 0.f;
+            wv[j + 3] = in ? w(a.w, b.w) : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 32; j++) local += (double)wv[j];
+    } else {
+        for (int i = i0; i < i1; i++) local += (double)w(za[i], zb ? zb[i] : 0.f);
+    }
     double incl = local;                                   // inclusive scan inside the wave
     for (int o = 1; o < 64; o <<= 1) {
         double v = __shfl_up(incl, o);
@@ -1271,16 +1640,31 @@ __device__ int block_inverse_cdf(F w, int V, float u)
     const double excl = base + incl - local;
     if (excl <= thr && excl + local > thr) {
         double acc = excl;
-        for (int i = i0; i < i1; i++) {
-            acc += (double)w(i);
-            if (acc > thr) { found = i; break; }
+        if (in_regs) {
+            int f = -1;
+#pragma unroll
+            for (int j = 0; j < 32; j++) {
+                acc += (double)wv[j];
+                if (f < 0 && acc > thr) f = i0 + j;
+            }
+            if (f >= 0) found = f;
+        } else {
+            for (int i = i0; i < i1; i++) {
+                acc += (double)w(za[i], zb ? zb[i] : 0.f);
+                if (acc > thr) { found = i; break; }
+            }
         }
     }
     __syncthreads();
     if (found >= 0) return found;
     // u * total landed beyond the accumulated mass by rounding: last index with weight
     int lp = -1;
-    for (int i = i0; i < i1; i++) if (w(i) > 0.f) lp = i;
+    if (in_regs) {
+#pragma unroll
+        for (int j = 0; j < 32; j++) if (wv[j] > 0.f) lp = i0 + j;
+    } else {
+        for (int i = i0; i < i1; i++) if (w(za[i], zb ? zb[i] : 0.f) > 0.f) lp = i;
+    }
     if (lp >= 0) atomicMax(&lastpos, lp);
     __syncthreads();
     return lastpos;
@@ -1288,10 +1672,11 @@ __device__ int block_inverse_cdf(F w, int V, float u)
 
 // Final reduction of the per-tile LM-head statistics for one row per block: arg-max (lowest index
 // among equal maxima) and top-1 probability of softmax(z / T) = 1 / sum exp((z - max) / T).
-// mode 1 additionally draws the token from softmax(z / T) with the row's uniform number.
+// mode 1 additionally draws the token from softmax(z / T) with the row's uniform number (of the
+// given purpose: 0 a draft token, 2 a first / plain token).
 // stat_out[row] = (max of z/T, sum exp(z/T - max)).
 __global__ __launch_bounds__(1024) void head_final_kernel(const float *hstat, int n_tiles, const float *logits,
-                                                          int V, float inv_temp, int mode, F8 u, int *tok_out,
+                                                          int V, float inv_temp, int mode, USrc us, int purpose, int *tok_out,
                                                           float *conf_out, float *stat_out)
 {
     __shared__ float bm[16], bs[16];
@@ -1340,7 +1725,8 @@ __global__ __launch_bounds__(1024) void head_final_kernel(const float *hstat, in
     __syncthreads();
     const float mx = fin[0];
     const float *z = logits + (size_t)m * V;
-    int tok = block_inverse_cdf([&](int i) { return __expf(z[i] * inv_temp - mx); }, V, u.v[m]);
+    int tok = block_inverse_cdf(z, nullptr, [&](float zv, float) { return __expf(zv * inv_temp - mx); }, V,
+                                row_uniform(us, m, purpose, 0));
     if (t == 0) tok_out[m] = tok < 0 ? fin_i : tok;
 }
 
@@ -1348,11 +1734,13 @@ __global__ __launch_bounds__(1024) void head_final_kernel(const float *hstat, in
 // rest; the sampling distribution of the target is preserved).  Draft d_i ~ q_i is kept while
 // u_acc[i] < min(1, p_i(d_i) / q_i(d_i)); the first rejected position is redrawn from
 // normalize(max(0, p_i - q_i)); if all k are kept a bonus token is drawn from p_k.
+// Row i decides the token at us.pos[i]; its acceptance number has purpose 1 (us.u0), its redraw /
+// bonus number purpose 2 (us.u1).
 // zt: target logits [k+1][V], zd: draft logits [k][V]; tstat/dstat: (max, sum exp) per row of z/T.
 // out[0] = number of accepted drafts, out[1] = the redrawn / bonus token.
 __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *zt, const float *zd, const float *tstat,
                                                              const float *dstat, int V, int k, float inv_temp,
-                                                             I8 drafts, F8 u_acc, F8 u_res, int *out)
+                                                             I8 drafts, USrc us, int *out)
 {
     __shared__ int n_acc;
     const int t = threadIdx.x;
@@ -1363,7 +1751,7 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *zt, co
             float pp = __expf(zt[(size_t)n * V + dd] * inv_temp - tstat[2 * n]) / tstat[2 * n + 1];
             float qq = __expf(zd[(size_t)n * V + dd] * inv_temp - dstat[2 * n]) / dstat[2 * n + 1];
             float a = fminf(1.f, pp / qq);
-            if (u_acc.v[n] < a) n++;
+            if (row_uniform(us, n, 1, 0) < a) n++;
             else break;
         }
         n_acc = n;
@@ -1377,11 +1765,12 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *zt, co
         const float *zq = zd + (size_t)n * V;
         const float qm = dstat[2 * n], qs = 1.f / dstat[2 * n + 1];
         tok = block_inverse_cdf(
-            [&](int i) { return fmaxf(0.f, __expf(zp[i] * inv_temp - pm) * ps - __expf(zq[i] * inv_temp - qm) * qs); }, V,
-            u_res.v[n]);
+            zp, zq, [&](float a, float b) { return fmaxf(0.f, __expf(a * inv_temp - pm) * ps - __expf(b * inv_temp - qm) * qs); }, V,
+            row_uniform(us, n, 2, 1));
         __syncthreads();
     }
-    if (tok < 0) tok = block_inverse_cdf([&](int i) { return __expf(zp[i] * inv_temp - pm) * ps; }, V, u_res.v[n]);
+    if (tok < 0)
+        tok = block_inverse_cdf(zp, nullptr, [&](float a, float) { return __expf(a * inv_temp - pm) * ps; }, V, row_uniform(us, n, 2, 1));
     if (t == 0) { out[0] = n; out[1] = tok; }
 }
 
@@ -1408,6 +1797,13 @@ __global__ __launch_bounds__(512, 2) void stream_read_kernel(const u32x4_t *__re
     }
     for (int o = 32; o >= 1; o >>= 1) x ^= __shfl_xor(x, o);
     if (lane == 0) atomicXor(&out[blockIdx.x], x);
+}
+
+// Zero n16 16-byte pieces (a launch that a stream capture can record, unlike a memset node).
+__global__ void fill_zero_kernel(u32x4_t *p, unsigned n16)
+{
+    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n16) p[i] = u32x4_t{0u, 0u, 0u, 0u};
 }
 
 // Copy cached k and v rows of one position, widened to float (test / debug access).

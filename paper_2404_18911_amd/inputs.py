@@ -73,12 +73,12 @@ class ModelShape:
     dtype: str = "bf16"          # storage type of the weights: "f32" | "bf16"
     rms_eps: float = 1e-6
     rope_theta: float = 10000.0
-    kv: str = ""                 # storage type of the key/value cache; "" = same as dtype
+    kv: str = ""                 # storage type of the key/value cache: "f32" | "bf16" | "f16"; "" = f32 for f32 weights, f16 otherwise
     adapter: int = 0             # adapter architecture (Table 2): ADAPTER_ATTN .. ADAPTER_MLP
 
     @property
     def kv_dtype(self) -> str:
-        return self.kv or self.dtype
+        return self.kv or ("f32" if self.dtype == "f32" else "f16")
 
     def layer_params(self) -> int:
         d, f = self.d_model, self.d_ffn

@@ -127,7 +127,7 @@ def generate(name: str, threads: int, log=print) -> dict:
     log(f"[{name}] decode of {n_new} tokens in {time.time() - t0:.1f}s, {len(rounds)} rounds")
 
     meta = dict(format=FORMAT, name=name, **cfg, weight_seed=1, prompt_seed=2, probe_len=PROBE_LEN,
-                kv=shape.kv_dtype, dtype=shape.dtype)
+                oracle_cache="exact", dtype=shape.dtype)
     tp = sorted(T)
     dp = sorted(D)
     out = dict(

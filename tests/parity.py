@@ -70,7 +70,10 @@ def follow_kangaroo(kg, model, prompt, n_new, gamma, eta, fol: Follow, after_com
             if stop != ostop:   # only legitimate when the confidence sits on the threshold
                 assert abs(oconf - eta) <= 3 * fol.conf_tol * max(oconf, 1e-3) + 1e-6, (conf, oconf, eta)
                 dec.stopped = stop
-            np.testing.assert_allclose(kg.read_feature(j), dec.F[j], rtol=0, atol=fol.tol)
+            # early features are not logits: the stated tolerance is taken relative to their size (it is a
+            # bound for numbers of standard deviation about 1; the residual stream of the wide models is larger)
+            np.testing.assert_allclose(kg.read_feature(j), dec.F[j], rtol=0,
+                                       atol=fol.tol * max(1.0, float(np.sqrt(np.mean(dec.F[j] ** 2)))))
             if stop:
                 break
         tg = kg.verify(p)
@@ -99,7 +102,7 @@ def poison_kv_tail(kg, frm):
     c = kg.cfg
     P, hd, H, slots = c.kv_page_tokens, c.head_dim, c.n_heads, c.n_layers + 1
     n_pages = (c.max_seq + P - 1) // P
-    dt = torch.bfloat16 if c.kv_dtype == 1 else torch.float32
+    dt = {0: torch.float32, 1: torch.bfloat16, 2: torch.float16}[c.kv_dtype]
     n = n_pages * slots * H * 2 * P * hd
     pool = kg.kv.view(dt)[:n].view(n_pages, slots, H, 2, P, hd)
     for lp in range(frm // P, n_pages):
@@ -133,13 +136,18 @@ def _cdf_valid(p, tok, u, ctol):
     return (lo - ctol <= u < c[tok] + ctol) and (p[tok] > 0.0 or ctol > 0.0)
 
 
-def follow_kangaroo_sampling(kg, model, prompt, n_new, gamma, eta, temperature, U, fol: Follow, ctol, chunk=None):
+def follow_kangaroo_sampling(kg, model, prompt, n_new, gamma, eta, temperature, U, fol: Follow, ctol, chunk=None,
+                             gpu_seed=None):
     """Sampling mode (speculative rejection sampling) with the oracle following.  Every GPU decision
     is checked against the oracle's quantities for the same uniform numbers: a drawn token must be
     the inverse-CDF result up to ctol on the cumulative sums, an accept / reject must be on the
     right side of min(1, p/q) up to ctol.  Counts the decisions where the oracle itself would have
-    decided otherwise (possible only inside the tolerance)."""
-    p, keep = B.make_params(mode=1, temperature=temperature, eta=eta, gamma=gamma, uniforms=U)
+    decided otherwise (possible only inside the tolerance).  With gpu_seed the GPU draws its numbers
+    from its own generator keyed by that seed (U must then be the oracle's table for the same seed)."""
+    if gpu_seed is None:
+        p, keep = B.make_params(mode=1, temperature=temperature, eta=eta, gamma=gamma, uniforms=U)
+    else:
+        p, keep = B.make_params(mode=1, temperature=temperature, eta=eta, gamma=gamma, seed=gpu_seed)
     dec = O.KangarooDecoder(model, gamma=gamma, eta=eta, mode="sample", temperature=temperature, uniforms=U)
     t = kg.prefill(p, prompt)
     own = dec.prefill(prompt, chunk=chunk)

@@ -37,7 +37,7 @@ def test_create_validates_the_configuration():
     assert rc == B.KG_OK and h.value
     B.lib().kg_destroy(h)
     for bad in (dict(exit_layer=0), dict(exit_layer=5), dict(head_dim=48), dict(n_heads=3), dict(gamma_max=8),
-                dict(kv_page_tokens=24), dict(kv_page_tokens=256), dict(dtype=2), dict(dtype=0, kv_dtype=1),
+                dict(kv_page_tokens=24), dict(kv_page_tokens=256), dict(dtype=2), dict(dtype=0, kv_dtype=1), dict(dtype=0, kv_dtype=2), dict(kv_dtype=3),
                 dict(vocab=1000), dict(max_seq=1), dict(max_seq=16 * 129), dict(adapter_kind=4), dict(adapter_kind=-1)):
         rc, h = _create(shape, **bad)
         assert rc == B.KG_EINVAL and not h.value, bad

@@ -21,7 +21,7 @@ def _w64(shape, W, kind, layer=-1):
     return torch.from_numpy(np.asarray(a, dtype=np.float64))
 
 
-def torch_forward(shape, W, tokens, lo_hi=None, with_adapter=False):
+def torch_forward(shape, W, tokens, lo_hi=None, with_adapter=False, cache=None):
     """Whole-sequence forward without a cache, written from the textbook definitions with
     torch fp64 matmul / softmax.  Returns (early features, final hidden, target logits,
     draft logits)."""
@@ -44,9 +44,9 @@ def torch_forward(shape, W, tokens, lo_hi=None, with_adapter=False):
         q = rope((a @ wq.T).view(T, H, hd)).transpose(0, 1)          # [H, T, hd]
         k = rope((a @ wk.T).view(T, H, hd)).transpose(0, 1)
         v = (a @ wv.T).view(T, H, hd).transpose(0, 1)
-        if shape.kv_dtype == "bf16":        # the cache stores rotated keys and values as bfloat16
-            k = k.to(torch.float32).to(torch.bfloat16).to(torch.float64)
-            v = v.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+        if cache is not None:               # a cache that stores rotated keys and values in 2 bytes
+            k = k.to(torch.float32).to(cache).to(torch.float64)
+            v = v.to(torch.float32).to(cache).to(torch.float64)
         s = q @ k.transpose(1, 2) / np.sqrt(hd)
         s = s.masked_fill(torch.triu(torch.ones(T, T, dtype=torch.bool), 1), float("-inf"))
         o = (torch.softmax(s, -1) @ v).transpose(0, 1).reshape(T, d)
@@ -81,15 +81,18 @@ def torch_forward(shape, W, tokens, lo_hi=None, with_adapter=False):
     return f.numpy(), x.numpy(), logits.numpy(), dlogits.numpy()
 
 
-@pytest.mark.parametrize("name,kv,adapter", [("toy", "", 0), ("toy_bf16", "", 0), ("toy_bf16", "f32", 0),
+@pytest.mark.parametrize("name,kv,adapter", [("toy", "", 0), ("toy_bf16", "", 0), ("toy_bf16", "bf16", 0), ("toy_bf16", "f16", 0),
                                              ("toy", "", 1), ("toy", "", 2), ("toy", "", 3),
-                                             ("toy_bf16", "", 2), ("toy_bf16", "", 3)])
+                                             ("toy_bf16", "", 2), ("toy_bf16", "f16", 3)])
 def test_incremental_decode_matches_whole_sequence_library_forward(name, kv, adapter):
     """Oracle run token by token through its caches == library forward of the whole sequence.
     A dropped residual, a wrong RoPE pairing or sign, a transposed operand, a cache indexing
-    slip or a wrong widening of bf16 all break this."""
+    slip or a wrong widening of bf16 all break this.  kv = "": the exact cache of the plain
+    definition; "bf16" / "f16": the oracle's optional rounding of cached keys and values against
+    the same rounding applied inside the library forward."""
     import dataclasses
     shape = dataclasses.replace(I.SHAPES[name], kv=kv, adapter=adapter)
+    cache = {"": None, "bf16": torch.bfloat16, "f16": torch.float16}[kv]
     # non-trivial gains so that a missing or misplaced gain is caught too; an own head that is not
     # the model's, so that a draft head read from the wrong matrix is caught
     W = I.gen_weights(shape, seed=5, alpha=0.7, own_head_copy=False)
@@ -100,8 +103,8 @@ def test_incremental_decode_matches_whole_sequence_library_forward(name, kv, ada
             g = (1.0 + 0.3 * rng.standard_normal(a.shape)).astype(np.float32)
             W[(k, l)] = g if shape.dtype == "f32" else I.f32_to_bf16_bits(g)
     toks = I.gen_prompt(shape.vocab, 11, seed=9)
-    f_ref, x_ref, z_ref, dz_ref = torch_forward(shape, W, toks)
-    m = O.OracleModel(shape, W, 32)
+    f_ref, x_ref, z_ref, dz_ref = torch_forward(shape, W, toks, cache=cache)
+    m = O.OracleModel(shape, W, 32, exact_cache=cache is None)
     # mixed row counts: 4 rows, then 1, 1, 3, 2
     cuts = [0, 4, 5, 6, 9, 11]
     fs, xs, hs = [], [], []
@@ -160,6 +163,23 @@ def test_cache_rounding_is_nearest_with_ties_to_even():
     # a double just above a float tie: float conversion comes first and lands on the tie (2^-40 is
     # below float resolution at 1), which then goes to even
     assert r(1.0 + e / 2 + 2.0 ** -40) == 1.0
+
+
+def test_half_precision_cache_rounding_is_the_library_conversion():
+    """The oracle's optional rounding of cached values to IEEE half precision (written from the
+    format's definition: 11 significant bits, subnormals below 2^-14, ties to even) against numpy's
+    float32 -> float16 conversion on random, tie, subnormal, tiny and near-overflow values."""
+    r = O.lib().ko_round_f16
+    rng = np.random.default_rng(8)
+    vals = np.concatenate([rng.standard_normal(4000) * 3.0, rng.standard_normal(500) * 1e-5, rng.standard_normal(500) * 2e4,
+                           [0.0, 1.0, -1.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 2.0 ** -22,
+                            2.0 ** -14, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25, 2.0 ** -26, 65504.0, 65519.9, -65519.9]])
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float32).astype(np.float16).astype(np.float64)
+    got = np.array([r(float(v)) for v in vals])
+    np.testing.assert_array_equal(got, want)
+    assert r(1.0 + 2.0 ** -11) == 1.0 and r(1.0 + 3 * 2.0 ** -11) == 1.0 + 2.0 ** -9      # ties to even
+    assert r(65520.0) == np.inf and r(-70000.0) == -np.inf
 
 
 def test_rmsnorm_unit_gain_gives_unit_rms():

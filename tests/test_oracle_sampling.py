@@ -267,3 +267,77 @@ def test_draft_confidence_is_taken_from_the_tempered_draft_distribution():
                 assert abs(r["conf"][0] - 1.0 / 16) < 0.02
     assert set(ks[1.0e4]) == {1}
     assert max(ks[1.0]) > 1
+
+
+# ----------------------------------------------------------------------------- Philox4x32-10
+
+def _philox_invert(out, key, rounds=10):
+    """Undo `rounds` rounds of the published round function, from its definition: a round maps
+    (c0, c1, c2, c3) to (hi(B c2) ^ c1 ^ k0, lo(B c2), hi(A c0) ^ c3 ^ k1, lo(A c0)), so c2 and c0 come
+    back through the inverses of the odd multipliers mod 2^32, c1 and c3 through the xors.  The key
+    of round r is key + r * (W0, W1) with the Weyl constants taken from their closed forms."""
+    import math
+    A, B, M = 0xD2511F53, 0xCD9E8D57, 1 << 32
+    W0 = (math.isqrt(5 << 64) - (1 << 32)) >> 1           # floor(2^32 (sqrt(5) - 1) / 2), the golden ratio
+    W1 = math.isqrt(3 << 64) - (1 << 32)                  # floor(2^32 (sqrt(3) - 1))
+    Ai, Bi = pow(A, -1, M), pow(B, -1, M)
+    o = list(out)
+    for r in reversed(range(rounds)):
+        k0, k1 = (key[0] + r * W0) % M, (key[1] + r * W1) % M
+        c2 = (o[1] * Bi) % M
+        c0 = (o[3] * Ai) % M
+        c1 = o[0] ^ ((B * c2) >> 32) ^ k0
+        c3 = o[2] ^ ((A * c0) >> 32) ^ k1
+        o = [c0, c1, c2, c3]
+    return o
+
+
+def test_philox_is_the_ten_round_bijection_of_its_definition():
+    """Ten published rounds, undone one by one, give the counter back: every xor partner, both
+    multipliers, the word order, the round count and the key schedule (Weyl constants from their
+    closed forms) have to be right for that."""
+    rng = np.random.default_rng(9)
+    cases = [([0, 0, 0, 0], [0, 0]), ([0xFFFFFFFF] * 4, [0xFFFFFFFF] * 2)]
+    cases += [(rng.integers(0, 1 << 32, 4).tolist(), rng.integers(0, 1 << 32, 2).tolist()) for _ in range(200)]
+    for ctr, key in cases:
+        assert _philox_invert(O.philox4x32_10(ctr, key), key) == ctr
+    # nine or eleven rounds do not invert it
+    ctr, key = cases[5]
+    assert _philox_invert(O.philox4x32_10(ctr, key), key, rounds=9) != ctr
+    assert _philox_invert(O.philox4x32_10(ctr, key), key, rounds=11) != ctr
+
+
+def test_philox_words_avalanche_and_are_uniform():
+    """A counter or key bit flipped changes about half of the 128 output bits; 2^20 uniform numbers
+    of consecutive positions fill 256 bins evenly (chi-square), have the moments of U[0,1) and no
+    correlation between neighbouring positions or between the purposes of one position."""
+    rng = np.random.default_rng(10)
+    flips = []
+    for _ in range(300):
+        ctr, key = rng.integers(0, 1 << 32, 4).tolist(), rng.integers(0, 1 << 32, 2).tolist()
+        a = O.philox4x32_10(ctr, key)
+        bit = int(rng.integers(0, 192))
+        c2, k2 = list(ctr), list(key)
+        if bit < 128:
+            c2[bit // 32] ^= 1 << (bit % 32)
+        else:
+            k2[(bit - 128) // 32] ^= 1 << (bit % 32)
+        b = O.philox4x32_10(c2, k2)
+        flips.append(sum(bin(x ^ y).count("1") for x, y in zip(a, b)))
+    assert 60 < np.mean(flips) < 68 and min(flips) > 30
+    n = 1 << 20
+    U = O.philox_uniforms(12345, n).astype(np.float64)
+    assert U.min() >= 0.0 and U.max() < 1.0
+    for purpose in range(3):
+        u = U[:, purpose]
+        counts = np.bincount((u * 256).astype(int), minlength=256)
+        chi2 = ((counts - n / 256) ** 2 / (n / 256)).sum()
+        assert chi2 < 255 + 5 * np.sqrt(2 * 255), chi2            # mean 255, sd 22.6
+        assert abs(u.mean() - 0.5) < 5 / np.sqrt(12 * n) and abs(u.var() - 1 / 12) < 1e-3
+        assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 5 / np.sqrt(n)
+    assert abs(np.corrcoef(U[:, 0], U[:, 1])[0, 1]) < 5 / np.sqrt(n)
+    # the table is the generator: u[pos][purpose] = (word >> 8) 2^-24 of counter (pos, purpose, 0, 0)
+    w = O.philox_words(12345, 1000, 2, 16)
+    assert np.array_equal((w >> 8).astype(np.float64) * 2.0 ** -24, U[1000:1016, 2])
+    assert w[3] == O.philox4x32_10([1003, 2, 0, 0], [12345, 0])[0]
+    assert O.philox_words((7 << 32) | 5, 0, 0, 1)[0] == O.philox4x32_10([0, 0, 0, 0], [5, 7])[0]
