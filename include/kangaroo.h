@@ -338,6 +338,23 @@ int kg_op_linear(int dtype, const void *packed_dev, int N, int K, const float *x
 int kg_op_linear_valu(const void *packed_dev, int N, int K, const float *x_dev, float *y_dev, void *hip_stream);
 
 /*
+ * kg_op_linear for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same product, same kernels
+ * and bit-identical results; the activation staging area is a static device array inside the library
+ * (KG_OP_STATIC_MAX_K * KG_MAX_ROWS * 4 bytes = 512 KB per GPU, held until the process ends) instead of
+ * work_dev.  Allocates nothing (no hipMalloc / hipFree, no memset node: the area is cleared by a
+ * kernel), launches on `hip_stream`, does not synchronise.  The device address of the array is looked
+ * up on the first call on each device (the current device must be the one the pointers live on).
+ * Errors: KG_EINVAL as kg_op_linear, or a device ordinal >= KG_OP_STATIC_MAX_DEVICES; KG_ENOSPC for
+ * K > KG_OP_STATIC_MAX_K; KG_EHIP.  Every call on one GPU shares that GPU's array: calls that overlap
+ * on one GPU (different streams or threads) race; calls ordered on one stream do not.
+ */
+#define KG_OP_STATIC_MAX_K 16384
+#define KG_OP_STATIC_MAX_DEVICES 64
+int kg_op_linear_static(int dtype, const void *packed_dev, int N, int K, const float *x_dev, int M, float *y_dev,
+                        void *hip_stream);
+
+/*
  * The generator of sampling mode on its own (kernel-level tests): out_dev[i] = first output word of
  * Philox4x32-10 for key (seed mod 2^32, seed >> 32) and counter (pos0 + i, purpose, 0, 0), i < n.
  * Launches on `hip_stream`, does not synchronise.

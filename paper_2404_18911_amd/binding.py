@@ -52,7 +52,7 @@ TRAIN_FEATURES, TRAIN_TARGET_LOGITS, TRAIN_DRAFT_LOGITS, TRAIN_GRADIENTS, TRAIN_
 SYMBOLS = ["kg_stats_cr", "kg_stats_ctar", "kg_create", "kg_workspace_bytes", "kg_bind", "kg_load_tensor", "kg_set_page_order", "kg_prefill",
            "kg_draft_step", "kg_verify", "kg_accept", "kg_generate", "kg_decode_plain", "kg_plain_step",
            "kg_read_logits", "kg_read_feature", "kg_read_kv", "kg_get_state", "kg_set_profiling", "kg_get_profile", "kg_reset", "kg_last_error",
-           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_linear_valu", "kg_op_philox_words", "kg_op_stream_read",
+           "kg_destroy", "kg_op_packed_bytes", "kg_op_work_bytes", "kg_op_pack", "kg_op_linear", "kg_op_linear_static", "kg_op_linear_valu", "kg_op_philox_words", "kg_op_stream_read",
            "kg_train_workspace_bytes", "kg_train_bind", "kg_train_step", "kg_train_accumulate", "kg_train_apply", "kg_train_features", "kg_train_accumulate_features",
            "kg_train_read", "kg_op_gemm_f32", "kg_op_tile_pos"]
 
@@ -101,6 +101,7 @@ def lib() -> ctypes.CDLL:
     L.kg_op_work_bytes.restype = ctypes.c_size_t
     L.kg_op_pack.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, vp]
     L.kg_op_linear.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_int, vp, vp, vp]
+    L.kg_op_linear_static.argtypes = [ctypes.c_int, vp, ctypes.c_int, ctypes.c_int, vp, ctypes.c_int, vp, vp]
     L.kg_op_linear_valu.argtypes = [vp, ctypes.c_int, ctypes.c_int, vp, vp, vp]
     L.kg_op_philox_words.argtypes = [ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_int, vp, vp]
     L.kg_op_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]

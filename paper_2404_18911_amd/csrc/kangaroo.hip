@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "kangaroo.h"
@@ -1954,6 +1955,33 @@ int kg_op_linear_valu(const void *packed, int N, int K, const float *xd, float *
     hipLaunchKernelGGL(gemv_bf16_valu_kernel, dim3(N / 16), dim3(64 * GEMV_WAVES), 0, (hipStream_t)hip_stream,
                        (const u32x4_t *)packed, (K + 31) / 32, xd, K, yd);
     return hipGetLastError() == hipSuccess ? KG_OK : KG_EHIP;
+}
+
+// The staging area of kg_op_linear_static: one array per GPU, held until the process ends.  Host code
+// never uses the array's name as an address: the device address is asked for once per device.
+static __device__ __align__(256) unsigned char scratch[KG_OP_STATIC_MAX_K * KG_ROWS * 4];
+static_assert(sizeof(scratch) >= (size_t)KG_OP_STATIC_MAX_K / 32 * 1024, "bf16 staging fits");
+static std::mutex static_scratch_lock;
+static void *static_scratch_ptr[KG_OP_STATIC_MAX_DEVICES];      // per device, NULL until first use
+
+int kg_op_linear_static(int dtype, const void *packed, int N, int K, const float *xd, int M, float *yd, void *hip_stream)
+{
+    if (!op_linear_args_ok(dtype, packed, N, K, xd, M, yd)) return KG_EINVAL;
+    if (K > KG_OP_STATIC_MAX_K) return KG_ENOSPC;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return KG_EHIP;
+    if (dev < 0 || dev >= KG_OP_STATIC_MAX_DEVICES) return KG_EINVAL;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> g(static_scratch_lock);
+        if (!static_scratch_ptr[dev]) {
+            void *q = nullptr;
+            if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return KG_EHIP;
+            static_scratch_ptr[dev] = q;
+        }
+        ptr = static_scratch_ptr[dev];
+    }
+    return op_linear_launch(dtype, packed, N, K, xd, M, yd, ptr, (hipStream_t)hip_stream, true);
 }
 
 int kg_op_philox_words(uint64_t seed, uint32_t pos0, uint32_t purpose, int n, uint32_t *out_dev, void *hip_stream)
