@@ -772,6 +772,188 @@ __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw2(PfArgs a, Epi e) 
 __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1_cb4(PfArgs a, Epi e) { gemm_prefill_body<1, 4>(a, e); }
 
 // ---------------------------------------------------------------------------------------------
+// Projection for long prompt passes: the same contraction as gemm_prefill_body for passes of 512 rows
+// and more, organised for reuse instead of for the one-token kernel's summation order (a prompt row
+// then differs from the same row decoded alone in the order of its sums only, far inside the logit
+// tolerance).  A workgroup owns 8 * TW weight tiles x 128 rows.  The hi and lo halves of the
+// activations are two B operands of 16 distinct rows each (two 8-row blocks) that are multiplied into
+// the SAME accumulator, so a wave's TW x 8 accumulators cover twice the rows that the hi | lo column
+// split covers, nothing is folded, and no per-range totals are kept: four times the outputs per
+// workgroup in the same registers, i.e. a weight tile fetched from the L2 serves 128 rows and an
+// activation tile serves up to 512 weight rows.  Movers / multipliers, the ring of 3 stage buffers
+// (one k-step per stage) and the exact wait counts are those of gemm_prefill_body; the movers gather
+// the B operands into MFMA lane order (lane = column c + 16 * k group: row block c / 8, row c % 8).
+template <int TW, int NB>
+__device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e)
+{
+    constexpr int NTW = 8 * TW;
+    constexpr int RB = 16;                                  // 8-row blocks per workgroup
+    __shared__ u32x4_t As[NB][NTW][64];                     // ring of NB stage buffers, one k-step each
+    __shared__ u32x4_t Bs[NB][RB / 2][2][64];
+    __shared__ float scs[RB][KG_ROWS];
+    const int t = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
+    const bool mover = wave >= 8;
+    const int nb = (a.T + 7) >> 3;
+    const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
+    const int gyi = (jj / a.gx) * 8 + xcd;
+    if (gyi >= a.gy) return;
+    const int b0 = (jj % a.gx) * RB;
+    const int nbw = min(RB, nb - b0);
+    const int KS = a.KS;
+    const int col = lane & 15, g4 = lane >> 4;
+
+    // RMS scales of the group's rows: one wave per row block (12 waves serve 16 blocks)
+    for (int blk = wave; blk < nbw; blk += 12) {
+        const Epi eb = pf_block_epi(e, a, b0 + blk);
+#pragma unroll
+        for (int m = 0; m < KG_ROWS; m++) {
+            float sv = 1.f;
+            if (eb.ssq_in) {
+                sv = 0.f;
+                for (int i = lane; i < eb.nt_in; i += 64) sv += (m < eb.M) ? eb.ssq_in[(size_t)i * KG_ROWS + m] : 0.f;
+                for (int o = 32; o >= 1; o >>= 1) sv += __shfl_xor(sv, o);
+                sv = rsqrtf(fmaf(sv, eb.inv_d, eb.eps));
+            }
+            if (lane == 0) scs[blk][m] = sv;
+        }
+    }
+
+    constexpr int TL = NTW + RB;                            // tile loads of a stage
+    constexpr int LPW = TL / 4;
+    static_assert(TL % 4 == 0, "tile loads spread evenly over the 4 mover waves");
+    auto issue = [&](int ks, int buf) {                     // movers: operands of k-step ks (clamped: late stages reload a valid one)
+        const int kk = min(ks, KS - 1);
+#pragma unroll
+        for (int i = 0; i < LPW; i++) {
+            const int j = (wave - 8) + 4 * i;               // uniform in the wave
+            if (j < NTW) {
+                const int rt = min(gyi * NTW + j, a.NT - 1);
+                const u32x4_t *src = a.W + ((size_t)rt * KS + tile_pos(kk, KS)) * 64 + lane;
+                __builtin_amdgcn_global_load_lds(src, &As[buf][j][0], 16, 0, 0);
+            } else {
+                const int jb = j - NTW, grp = jb >> 1, part = jb & 1;
+                const int blk = min(b0 + 2 * grp + (col >> 3), nb - 1);
+                const u32x4_t *src = a.act + (size_t)blk * a.act_blk + (size_t)kk * 64 + ((col & 7) * 8 + part * 4 + g4);
+                __builtin_amdgcn_global_load_lds(src, &Bs[buf][grp][part][0], 16, 0, 0);
+            }
+        }
+    };
+    auto meet = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // the movers run NB - 1 stages ahead: when stage ks is multiplied, stages ks + 1 .. ks + NB - 1 are on
+    // their way or have landed; after issuing one more, at most NB - 2 stages may still be in flight
+    // for the next stage to be complete
+    static_assert((NB - 2) * LPW <= 63, "the wait count must fit the instruction's field");
+    int buf = 0;
+    if (mover) {
+#pragma unroll
+        for (int s0 = 0; s0 < NB - 1; s0++) issue(s0, s0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NB - 2) * LPW) : "memory");
+        __syncthreads();
+        for (int ks = 0; ks < KS; ks++) {
+            issue(ks + NB - 1, buf >= 1 ? buf - 1 : NB - 1);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NB - 2) * LPW) : "memory");
+            meet();
+            buf = buf == NB - 1 ? 0 : buf + 1;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return;
+    }
+    f32x4_t acc[TW][RB / 2];
+#pragma unroll
+    for (int tw = 0; tw < TW; tw++)
+#pragma unroll
+        for (int gq = 0; gq < RB / 2; gq++) acc[tw][gq] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    __syncthreads();
+    for (int ks = 0; ks < KS; ks++) {
+        bf16x8_t av[TW];
+#pragma unroll
+        for (int tw = 0; tw < TW; tw++) av[tw] = __builtin_bit_cast(bf16x8_t, As[buf][wave * TW + tw][lane]);
+#pragma unroll
+        for (int gq = 0; gq < RB / 2; gq++) {
+            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, Bs[buf][gq][0][lane]);
+            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, Bs[buf][gq][1][lane]);
+#pragma unroll
+            for (int tw = 0; tw < TW; tw++) {
+                acc[tw][gq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tw], bh, acc[tw][gq], 0, 0, 0);
+                acc[tw][gq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tw], bl, acc[tw][gq], 0, 0, 0);
+            }
+        }
+        meet();
+        buf = buf == NB - 1 ? 0 : buf + 1;
+    }
+
+    // Epilogue from the accumulators: lane (column c, group g4) holds weight rows 4 g4 .. 4 g4 + 3 of a
+    // tile for row c % 8 of block b0 + 2 gq + c / 8.
+#pragma unroll
+    for (int tw = 0; tw < TW; tw++) {
+        const int rt = gyi * NTW + wave * TW + tw;
+        const bool valid = rt < a.NT;
+        const int n0 = rt * 16 + 4 * g4;
+#pragma unroll
+        for (int gq = 0; gq < RB / 2; gq++) {
+            const int blk = 2 * gq + (col >> 3), m = col & 7;
+            const bool in_group = blk < nbw;
+            const Epi eb = pf_block_epi(e, a, b0 + min(blk, nbw - 1));
+            const bool live = valid && in_group && m < eb.M;
+            const f32x4_t y = acc[tw][gq];
+            if (e.kind == EPI_RESID) {
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
+                if (live) {
+                    const float4 rv = *(const float4 *)(eb.res + (size_t)m * eb.N + n0);
+                    v[0] = rv.x + y[0]; v[1] = rv.y + y[1]; v[2] = rv.z + y[2]; v[3] = rv.w + y[3];
+                    *(float4 *)(eb.xout + (size_t)m * eb.N + n0) = make_float4(v[0], v[1], v[2], v[3]);
+                    if (eb.act_out) {
+                        const float4 gv = eb.gain ? *(const float4 *)(eb.gain + n0) : make_float4(1.f, 1.f, 1.f, 1.f);
+                        const float gq4[4] = {gv.x, gv.y, gv.z, gv.w};
+                        uint16_t hi[4], lo[4];
+#pragma unroll
+                        for (int r = 0; r < 4; r++) {
+                            const float xv = rounded(v[r] * gq4[r]);
+                            hi[r] = f2bf(xv);
+                            lo[r] = f2bf(xv - bf2f(hi[r]));
+                        }
+                        uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(n0 >> 5) * 512 + (size_t)(m * 8 + ((n0 >> 3) & 3)) * 8 + (n0 & 7);
+                        *(uint2 *)pa = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                        *(uint2 *)(pa + 32) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                    }
+                }
+                if (e.ssq_out) {                 // sum of squares of the tile's 16 outputs per row: 4 in the lane, then the 4 lane groups
+                    float sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                    sq += __shfl_xor(sq, 16);
+                    sq += __shfl_xor(sq, 32);
+                    if (live && g4 == 0) eb.ssq_out[(size_t)rt * KG_ROWS + m] = sq;
+                }
+            } else if (live) {
+                const float sc = scs[blk][m];
+                if (e.kind == EPI_PLAIN) {
+                    *(float4 *)(eb.out + (size_t)m * eb.N + n0) = make_float4(y[0] * sc, y[1] * sc, y[2] * sc, y[3] * sc);
+                } else {                          // EPI_SWIGLU: rows (2i, 2i+1) = (gate, up) of feature rt*8 + i
+                    uint16_t hi[2], lo[2];
+#pragma unroll
+                    for (int i = 0; i < 2; i++) {
+                        const float gt = y[2 * i] * sc, up = y[2 * i + 1] * sc;
+                        const float av2 = rounded(gt / (1.f + __expf(-gt)) * up);
+                        hi[i] = f2bf(av2);
+                        lo[i] = f2bf(av2 - bf2f(hi[i]));
+                    }
+                    const int k0 = rt * 8 + 2 * g4;
+                    uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(k0 >> 5) * 512 + (size_t)(m * 8 + ((k0 >> 3) & 3)) * 8 + (k0 & 7);
+                    *(uint32_t *)pa = hi[0] | ((uint32_t)hi[1] << 16);
+                    *(uint32_t *)(pa + 32) = lo[0] | ((uint32_t)lo[1] << 16);
+                }
+            }
+        }
+    }
+}
+__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw1(PfArgs a, Epi e) { gemm_prefill2_body<1, 6>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw2(PfArgs a, Epi e) { gemm_prefill2_body<2, 4>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw4(PfArgs a, Epi e) { gemm_prefill2_body<4, 3>(a, e); }
+
+// ---------------------------------------------------------------------------------------------
 // Rows -> activation for the first projection of a stack: x[m] = E[tok[m]] (emb != null) or the
 // given fp32 rows; writes xout (optional), act = x * gain (hi/lo), ssq[tile][m].  One block per
 // 16 features.
@@ -1421,29 +1603,34 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
     for (int kt = 0; kt < n_tiles; kt++) {
         const int tile0 = kt << 7;
         __syncthreads();                        // the previous tile has been consumed
-        // keys as stored: thread -> (position, 8 dimensions); positions beyond the block's reach are zero
+        // keys as stored: thread -> (position, 8 dimensions); positions beyond the block's reach are zero.
+        // All loads of a tile are issued before the first one is used.
+        u32x4_t kreg[HD / 16], vreg[HD / 16];
 #pragma unroll
         for (int i = 0; i < HD / 16; i++) {
             const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
-            const int ap = tile0 + pos;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ap <= last_pos) {
-                const kvhalf_t *Kp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit;
-                v = *(const u32x4_t *)(Kp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
-            }
-            *(u32x4_t *)&Ks[pos * KROW + 8 * dq] = v;
+            const int ap = min(tile0 + pos, last_pos);
+            const kvhalf_t *Kp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit;
+            kreg[i] = *(const u32x4_t *)(Kp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
+        }
+#pragma unroll
+        for (int i = 0; i < HD / 16; i++) {
+            const int pc = t + 256 * i, pos = pc & 127, dq = pc >> 7;
+            const int ap = min(tile0 + pos, last_pos);
+            const kvhalf_t *Vp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit + (size_t)P * HD;
+            vreg[i] = *(const u32x4_t *)(Vp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
+        }
+#pragma unroll
+        for (int i = 0; i < HD / 16; i++) {
+            const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
+            *(u32x4_t *)&Ks[pos * KROW + 8 * dq] = (tile0 + pos <= last_pos) ? kreg[i] : u32x4_t{0u, 0u, 0u, 0u};
         }
         // values, transposed: thread -> (8 dimensions, position = lane-consecutive); two neighbouring positions are
         // packed into one 32-bit LDS write by the even lane
 #pragma unroll
         for (int i = 0; i < HD / 16; i++) {
             const int pc = t + 256 * i, pos = pc & 127, dq = pc >> 7;
-            const int ap = tile0 + pos;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (ap <= last_pos) {
-                const kvhalf_t *Vp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit + (size_t)P * HD;
-                v = *(const u32x4_t *)(Vp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
-            }
+            const u32x4_t v = (tile0 + pos <= last_pos) ? vreg[i] : u32x4_t{0u, 0u, 0u, 0u};
             // column of position pos inside a dimension row: [u = pos / 32][g = (pos % 16) / 4][j = 4 ((pos / 16) % 2) + pos % 4]
             const int col = (pos >> 5) * 32 + ((pos & 15) >> 2) * 8 + ((pos >> 4) & 1) * 4 + (pos & 3);
 #pragma unroll
