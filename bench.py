@@ -491,32 +491,36 @@ def trace_summary(path):
             i = j
         else:
             i += 1
-    print(f"# {os.path.basename(path)}: {len(rows)} dispatches, {len(fw)} one-token whole-model forwards")
-    if not fw:
-        return
-    dur = collections.defaultdict(list)
-    gap = collections.defaultdict(list)
-    spans, busys = [], []
-    for i, j in fw:
-        t0, t1 = int(rows[i]["Start_Timestamp"]), int(rows[j]["End_Timestamp"])
-        spans.append(t1 - t0)
-        busys.append(sum(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]) for k in range(i, j + 1)))
-        for k in range(i + 1, j - 1):
-            slot = ((k - i - 1) % 5, names[k])
-            dur[slot].append(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]))
-            gap[slot].append(int(rows[k]["Start_Timestamp"]) - int(rows[k - 1]["End_Timestamp"]))
-        for k, tag in ((i, "first: pack_rows"), (j - 1, "last: lm head"), (j, "last: head_final")):
-            dur[(9, tag)].append(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]))
-            gap[(9, tag)].append(int(rows[k]["Start_Timestamp"]) - int(rows[k - 1]["End_Timestamp"]) if k > i else 0)
+    print(f"# {os.path.basename(path)}: {len(rows)} dispatches, {len(fw)} forwards of the form pack_rows, layers x (q,k,v / attention / "
+          f"o_proj / gate+up / down_proj), lm head, head_final")
     mean = lambda v: sum(v) / len(v) / 1e3
-    print(f"forward span {mean(spans):.1f} us, sum of kernel durations {mean(busys):.1f} us, idle between kernels {mean(spans) - mean(busys):.1f} us")
-    print("slot  kernel                                     launches  mean us  gap before, us")
-    layer = 0.0
-    for slot in sorted(dur):
-        print(f"{slot[0]:>4}  {slot[1]:<42} {len(dur[slot]):>8} {mean(dur[slot]):>8.2f} {mean(gap[slot]):>10.2f}")
-        if slot[0] < 5:
-            layer += mean(dur[slot]) + mean(gap[slot])
-    print(f"one layer (5 kernels + gaps): {layer:.2f} us")
+    kinds = collections.defaultdict(list)          # (layers, attention instantiation) -> forwards
+    for i, j in fw:
+        kinds[((j - i - 2) // 5, names[i + 2])].append((i, j))
+    for (layers, attn), group in sorted(kinds.items(), key=lambda kv: -len(kv[1])):
+        dur = collections.defaultdict(list)
+        gap = collections.defaultdict(list)
+        spans, busys = [], []
+        for i, j in group:
+            t0, t1 = int(rows[i]["Start_Timestamp"]), int(rows[j]["End_Timestamp"])
+            spans.append(t1 - t0)
+            busys.append(sum(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]) for k in range(i, j + 1)))
+            for k in range(i + 1, j - 1):
+                slot = ((k - i - 1) % 5, names[k])
+                dur[slot].append(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]))
+                gap[slot].append(int(rows[k]["Start_Timestamp"]) - int(rows[k - 1]["End_Timestamp"]))
+            for k, tag in ((i, "first: pack_rows"), (j - 1, "last: lm head"), (j, "last: head_final")):
+                dur[(9, tag)].append(int(rows[k]["End_Timestamp"]) - int(rows[k]["Start_Timestamp"]))
+                gap[(9, tag)].append(int(rows[k]["Start_Timestamp"]) - int(rows[k - 1]["End_Timestamp"]) if k > i else 0)
+        print(f"\n## {len(group)} forwards over {layers} layers with {attn}")
+        print(f"forward span {mean(spans):.1f} us, sum of kernel durations {mean(busys):.1f} us, idle between kernels {mean(spans) - mean(busys):.1f} us")
+        print("slot  kernel                                     launches  mean us  gap before, us")
+        layer = 0.0
+        for slot in sorted(dur):
+            print(f"{slot[0]:>4}  {slot[1]:<42} {len(dur[slot]):>8} {mean(dur[slot]):>8.2f} {mean(gap[slot]):>10.2f}")
+            if slot[0] < 5:
+                layer += mean(dur[slot]) + mean(gap[slot])
+        print(f"one layer (5 kernels + gaps): {layer:.2f} us")
 
 
 def main():

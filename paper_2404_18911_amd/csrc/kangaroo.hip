@@ -419,31 +419,36 @@ int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T
     a.ssq_in_blk = ssq_in ? sq : 0; a.ssq_out_blk = ssq_out ? sq : 0;
     a.act_out_blk = act_out_K ? act_bytes(act_out_K) : 0;
     const int nb = (T + KG_ROWS - 1) / KG_ROWS;
-    if (T >= 512 && x->kvt == 2) {
-        // long pass with the half-precision cache (whose prompt rows are not bit-identical to decoded rows
-        // anyway): workgroups of 8 * TW weight tiles x 128 rows (gemm_prefill2_body).  These launches are
-        // bound by the operand traffic from the L2 into LDS, so TW is the one with the least of it: per
+    if (T >= 256 && x->kvt == 2) {
+        // longer passes with the half-precision cache (whose prompt rows are not bit-identical to decoded
+        // rows anyway): workgroups of 8 * TW weight tiles x 128 rows (gemm_prefill2_body).  These launches
+        // are bound by the operand traffic from the L2 into LDS, so TW is the one with the least of it: per
         // k-step every row group fetches all NT weight tiles and every workgroup its 16 activation tiles,
         // and a last round of workgroups that fills only part of the device costs a whole round
         // (measured at the 7B shape, 1024 rows: q,k,v 272 / 242 / 192 us for TW 1 / 2 / 4, gate+up
-        // 522 / 376 / 406, o_proj and down_proj 164 / 196 / 319; the model picks 4, 2 and 1)
-        a.gx = (nb + 15) / 16;
+        // 522 / 376 / 406, o_proj and down_proj 164 / 196 / 319; the model picks 4, 2 and 1).  Where even
+        // TW = 1 leaves more than half of the compute units without a workgroup (o_proj and down_proj
+        // at 256 rows: 132 us against 84 us) the smaller row groups below are used.
+        const int gx2 = (nb + 15) / 16;
         int best_tw = 1;
-        double best_cost = -1.0;
+        double best_cost = -1.0, best_wgs = 0.0;
         for (int tw = 4; tw >= 1; tw >>= 1) {
             const int gy = (a.NT + 8 * tw - 1) / (8 * tw);
-            const double wgs = (double)a.gx * gy;
+            const double wgs = (double)gx2 * gy;
             const double rounds = std::ceil(wgs / x->n_cus);
-            const double cost = ((double)a.NT * a.gx + 16.0 * wgs) * rounds * x->n_cus / wgs;
-            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_tw = tw; }
+            const double cost = ((double)a.NT * gx2 + 16.0 * wgs) * rounds * x->n_cus / wgs;
+            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_tw = tw; best_wgs = wgs; }
         }
-        a.gy = (a.NT + 8 * best_tw - 1) / (8 * best_tw);
-        const int groups = a.gx * 8 * ((a.gy + 7) / 8);
-        ProfScope ps(x, 3, 2.0 * T * (double)N * K);
-        if (best_tw == 4) hipLaunchKernelGGL(gemm_prefill2_kernel_tw4, dim3(groups), dim3(768), 0, x->stream, a, e);
-        else if (best_tw == 2) hipLaunchKernelGGL(gemm_prefill2_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e);
-        else hipLaunchKernelGGL(gemm_prefill2_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e);
-        return check_launch(x, "prompt projection");
+        if (best_wgs >= 0.45 * x->n_cus) {
+            a.gx = gx2;
+            a.gy = (a.NT + 8 * best_tw - 1) / (8 * best_tw);
+            const int groups = a.gx * 8 * ((a.gy + 7) / 8);
+            ProfScope ps(x, 3, 2.0 * T * (double)N * K);
+            if (best_tw == 4) hipLaunchKernelGGL(gemm_prefill2_kernel_tw4, dim3(groups), dim3(768), 0, x->stream, a, e);
+            else if (best_tw == 2) hipLaunchKernelGGL(gemm_prefill2_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e);
+            else hipLaunchKernelGGL(gemm_prefill2_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e);
+            return check_launch(x, "prompt projection");
+        }
     }
     // two weight tiles per multiplying wave where that still leaves enough workgroups for the device
     const int tw = a.NT >= 512 ? 2 : 1;
