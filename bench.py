@@ -456,6 +456,55 @@ def run_micro(args):
     print(json.dumps(out), flush=True)
 
 
+def profile_tables(dirs):
+    """Reduce rocprofv3 csv output (`--kernel-trace --stats` and `--pmc` runs of this file's commands) to
+    short tables: kernel statistics, duration per launch shape, counter means per launch shape, and
+    from FETCH_SIZE / WRITE_SIZE runs the HBM bytes per projection launch, each counter scaled by what
+    it reads for the 1 GiB device-to-device copy that every run of this file issues first."""
+    import collections
+    import csv
+    import glob
+
+    def short(n, w=60):
+        return n.replace("void ", "")[:w]
+    print(f"KERNEL_SOURCE_DIGEST {kernel_source_digest()}   (sha256 prefix of the two kernel sources the run was built from)")
+    counters = collections.defaultdict(list)                     # (kernel, grid, counter) -> per-dispatch values
+    for d in dirs:
+        for f in sorted(glob.glob(os.path.join(d, "**", "*_kernel_stats.csv"), recursive=True)):
+            print(f"\n== kernel statistics, {os.path.relpath(f, d)} ==")
+            for r in csv.DictReader(open(f)):
+                print(f"{short(r['Name']):60s} calls {r['Calls']:>8s} total_ns {r['TotalDurationNs']:>14s} "
+                      f"avg_ns {float(r['AverageNs']):12.1f} pct {float(r['Percentage']):.3f}")
+        for f in sorted(glob.glob(os.path.join(d, "**", "*_kernel_trace.csv"), recursive=True)):
+            agg = collections.defaultdict(list)
+            for r in csv.DictReader(open(f)):
+                agg[(short(r["Kernel_Name"], 44), r["Grid_Size_X"], r["Grid_Size_Y"])].append(
+                    int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+            print("\n== duration per launch shape (kernel, grid x, grid y): calls, mean / min / max ns ==")
+            for k, v in sorted(agg.items(), key=lambda kv: -sum(kv[1]))[:32]:
+                print(f"{k[0]:44s} {k[1]:>9s} {k[2]:>4s}  calls {len(v):>7d}  mean {sum(v) / len(v):10.1f}  min {min(v):>8d}  max {max(v):>8d}")
+        for f in sorted(glob.glob(os.path.join(d, "**", "*_counter_collection.csv"), recursive=True)):
+            for r in csv.DictReader(open(f)):
+                counters[(short(r["Kernel_Name"], 44), r.get("Grid_Size", ""), r["Counter_Name"])].append(float(r["Counter_Value"]))
+    if counters:
+        print("\n== counters per (kernel, grid, counter): dispatches, mean, max ==")
+        for k, v in sorted(counters.items(), key=lambda kv: (kv[0][2], -sum(kv[1])))[:400]:
+            print(f"{k[0]:44s} {k[1]:>9s} {k[2]:<22s} n {len(v):>7d}  mean {sum(v) / len(v):14.1f}  max {max(v):14.1f}")
+    # HBM bytes per projection launch: FETCH_SIZE / WRITE_SIZE count KiB per dispatch; the copy moves 2^20 KiB each way
+    scale, per_launch = {}, {}
+    for name in ("FETCH_SIZE", "WRITE_SIZE"):
+        cal = [max(v) for k, v in counters.items() if k[2] == name and k[0].startswith("__amd_rocclr_copyBuffer")]
+        gem = [x for k, v in counters.items() if k[2] == name and k[0].startswith("gemv_bf16_kernel") for x in v]
+        if cal and gem and max(cal) > 0:
+            scale[name] = float(1 << 20) / max(cal)
+            per_launch[name] = 1024.0 * scale[name] * sum(gem) / len(gem)
+            print(f"\n{name}: the 1 GiB copy reads {max(cal):.1f} -> factor {scale[name]:.4f}; gemv_bf16_kernel over {len(gem)} "
+                  f"launches: {per_launch[name] / 1e6:.3f} MB per launch")
+    if len(per_launch) == 2:
+        print(f"TRAFFIC_BYTES_PER_PROJECTION_LAUNCH {per_launch['FETCH_SIZE'] + per_launch['WRITE_SIZE']:.0f}   "
+              f"(bench.py reports it as roofline.traffic while KERNEL_SOURCE_DIGEST matches the sources)")
+
+
 def trace_summary(path):
     """Per-layer timeline of the plain decode forwards found in a rocprofv3 kernel trace
     (`rocprofv3 --kernel-trace --output-format csv -d DIR -- python3 bench.py ...`; path = DIR or the
@@ -466,7 +515,10 @@ def trace_summary(path):
     import csv
     import glob
     if os.path.isdir(path):
-        path = sorted(glob.glob(os.path.join(path, "**", "*_kernel_trace.csv"), recursive=True))[-1]
+        found = sorted(glob.glob(os.path.join(path, "**", "*_kernel_trace.csv"), recursive=True))
+        if not found:
+            return
+        path = found[-1]
     rows = [r for r in csv.DictReader(open(path))]
     rows.sort(key=lambda r: int(r["Start_Timestamp"]))
 
@@ -546,12 +598,17 @@ def main():
     ap.add_argument("--train-head-scale", type=float, default=1.0, help="LM-head multiplier of --train (sharpens the target distribution)")
     ap.add_argument("--lr", type=float, default=2e-5)
     ap.add_argument("--micro", action="store_true", help="stream / projection microbenchmarks of the configured shape (not the benchmark line)")
-    ap.add_argument("--trace-summary", default="", help="summarise a rocprofv3 kernel trace (directory or csv) as a per-layer timeline; needs no GPU")
+    ap.add_argument("--trace-summary", default="",
+                    help="reduce rocprofv3 csv output (comma-separated directories of --kernel-trace --stats and --pmc runs) to "
+                         "short tables and a per-layer timeline of the one-row forwards; needs no GPU")
     ap.add_argument("--prefill-only", type=int, default=0,
                     help="run only this many prompt passes (for profiling the MFMA prompt kernels) and print their timing")
     args = ap.parse_args()
     if args.trace_summary:
-        trace_summary(args.trace_summary)
+        dirs = [d for d in args.trace_summary.split(",") if d]
+        profile_tables(dirs)
+        for d in dirs:
+            trace_summary(d)
         return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)

@@ -1158,7 +1158,8 @@ int kg_accept(kg_ctx *x, const kg_params *p, int32_t *emitted, int *n_emitted)
             ProfScope ps(x, 2, 0.0);
             hipLaunchKernelGGL(accept_sample_kernel, dim3(1), dim3(1024), 0, x->stream, at<const float>(x->scr, x->s_tlog),
                                at<const float>(x->scr, x->s_dlog), at<const float>(x->scr, x->s_tstat),
-                               at<const float>(x->scr, x->s_dstat), x->c.vocab, k, 1.f / p->temperature, dr, us,
+                               at<const float>(x->scr, x->s_dstat), at<const float>(x->scr, x->s_hstat), x->c.vocab, k,
+                               1.f / p->temperature, dr, us,
                                at<int>(x->scr, x->s_acc));
             KGCHK(check_launch(x, "accept_sample"));
         }

@@ -38,7 +38,8 @@ struct Epi {
     float *out;
     int row_shift;
     // EPI_HEAD: as EPI_PLAIN, plus per-tile statistics of z * inv_temp for the rows kept:
-    // hstat[(tile * 8 + row) * 4 + {0,1,2}] = max, sum exp(. - max), arg-max index (as float bits)
+    // hstat[(row * N / 16 + tile) * 4 + {0,1,2}] = max, sum exp(. - max), arg-max index (as float bits):
+    // the statistics of one row lie together, for the block that reduces them
     float *hstat;
     float inv_temp;
     // EPI_RESID: x = res[m][n] + y; xout[m][n] = x; act_out <- x * gain[n]; ssq_out[tile][m] = sum x^2
@@ -176,7 +177,7 @@ __device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_RO
                     if (sq[r][t] > best) { best = sq[r][t]; bi = r; }
                 float sum = 0.f;
                 for (int r = 0; r < 16; r++) sum += __expf(sq[r][t] - best);
-                float *hs = e.hstat + ((size_t)rt * KG_ROWS + mo) * 4;
+                float *hs = e.hstat + ((size_t)mo * (e.N >> 4) + rt) * 4;
                 hs[0] = best;
                 hs[1] = sum;
                 hs[2] = __int_as_float(rt * 16 + bi);
@@ -1857,6 +1858,76 @@ __device__ int block_inverse_cdf(const float *za, const float *zb, F w, int V, f
     return lastpos;
 }
 
+// Block-wide inverse-CDF draw from softmax(z / T) through the LM head's per-tile statistics (1024
+// threads): tile i (16 consecutive tokens) weighs s_i exp(m_i - mx), so the tile that holds u * total is
+// found from n_tiles numbers, and only its 16 logits are looked at.  Walks ascending token indices;
+// sums in double.  Returns -1 when the total is not positive.  All threads must call it; all get the result.
+// hs: statistics of the row, tile i at hs[4 i] = (max of z / T, sum exp(z / T - max), ..).
+__device__ int tile_inverse_cdf(const float *hs, int n_tiles, const float *z, float inv_temp, float mx, float u)
+{
+    __shared__ double wsum[16];
+    __shared__ int cand[16];
+    __shared__ int found;
+    const int t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const int chunk = (n_tiles + 1023) >> 10;
+    const int i0 = min(n_tiles, t * chunk), i1 = min(n_tiles, i0 + chunk);
+    auto weight = [&](int i) {
+        const float2 ms = *(const float2 *)(hs + (size_t)i * 4);
+        return (double)(ms.y * __expf(ms.x - mx));
+    };
+    double local = 0.0;
+    for (int i = i0; i < i1; i++) local += weight(i);
+    double incl = local;                                   // inclusive scan inside the wave
+    for (int o = 1; o < 64; o <<= 1) {
+        double v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    if (t == 0) found = -1;
+    __syncthreads();
+    double base = 0.0, total = 0.0;
+    for (int k = 0; k < 16; k++) {
+        if (k < wave) base += wsum[k];
+        total += wsum[k];
+    }
+    if (!(total > 0.0)) return -1;
+    const double thr = (double)u * total;                  // u < 1: below the total
+    const double excl = base + incl - local;
+    // the stretch that holds the threshold: the last one that starts at or below it
+    const unsigned long long starts_below = __ballot(i0 < i1 && excl <= thr);
+    if (lane == 0) cand[wave] = starts_below ? wave * 64 + 63 - __builtin_clzll(starts_below) : -1;
+    __syncthreads();
+    int owner = -1;
+    for (int k = 0; k < 16; k++) owner = max(owner, cand[k]);
+    if (t == owner) {
+        double acc = excl;
+        int tile = -1;
+        for (int i = i0; i < i1; i++) {
+            const double wt = weight(i);
+            if (wt > 0.0) {
+                if (tile >= 0) acc += weight(tile);        // pass the tile before: the threshold lies beyond it
+                tile = i;
+                if (acc + wt > thr) break;
+            }
+        }
+        // (a stretch whose sums fall short of the threshold by rounding ends at its last tile with weight)
+        if (tile >= 0) {
+            // inside the tile the 16 weights are recomputed; if their sum misses the tile's own by rounding,
+            // the tile's last token with weight is the draw
+            int f = -1, lastw = -1;
+            for (int j = 0; j < 16; j++) {
+                const float wj = __expf(z[tile * 16 + j] * inv_temp - mx);
+                acc += (double)wj;
+                if (wj > 0.f) lastw = tile * 16 + j;
+                if (f < 0 && acc > thr) f = tile * 16 + j;
+            }
+            found = f >= 0 ? f : lastw;
+        }
+    }
+    __syncthreads();
+    return found;
+}
+
 // Final reduction of the per-tile LM-head statistics for one row per block: arg-max (lowest index
 // among equal maxima) and top-1 probability of softmax(z / T) = 1 / sum exp((z - max) / T).
 // mode 1 additionally draws the token from softmax(z / T) with the row's uniform number (of the
@@ -1874,9 +1945,9 @@ __global__ __launch_bounds__(1024) void head_final_kernel(const float *hstat, in
     float best = -INFINITY, sum = 0.f;
     int idx = 0x7FFFFFFF;
     for (int i = t; i < n_tiles; i += 1024) {
-        const float *hs = hstat + ((size_t)i * KG_ROWS + m) * 4;
-        float mx = hs[0], sm = hs[1];
-        int id = __float_as_int(hs[2]);
+        const float4 hs = *(const float4 *)(hstat + ((size_t)m * n_tiles + i) * 4);
+        float mx = hs.x, sm = hs.y;
+        int id = __float_as_int(hs.z);
         if (mx > best) { sum = sum * __expf(best - mx) + sm; best = mx; idx = id; }
         else { sum += sm * __expf(mx - best); if (mx == best && id < idx) idx = id; }
     }
@@ -1910,10 +1981,8 @@ __global__ __launch_bounds__(1024) void head_final_kernel(const float *hstat, in
     }
     if (mode == 0) return;
     __syncthreads();
-    const float mx = fin[0];
-    const float *z = logits + (size_t)m * V;
-    int tok = block_inverse_cdf(z, nullptr, [&](float zv, float) { return __expf(zv * inv_temp - mx); }, V,
-                                row_uniform(us, m, purpose, 0));
+    const int tok = tile_inverse_cdf(hstat + (size_t)m * n_tiles * 4, n_tiles, logits + (size_t)m * V, inv_temp, fin[0],
+                                     row_uniform(us, m, purpose, 0));
     if (t == 0) tok_out[m] = tok < 0 ? fin_i : tok;
 }
 
@@ -1926,22 +1995,29 @@ __global__ __launch_bounds__(1024) void head_final_kernel(const float *hstat, in
 // zt: target logits [k+1][V], zd: draft logits [k][V]; tstat/dstat: (max, sum exp) per row of z/T.
 // out[0] = number of accepted drafts, out[1] = the redrawn / bonus token.
 __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *zt, const float *zd, const float *tstat,
-                                                             const float *dstat, int V, int k, float inv_temp,
-                                                             I8 drafts, USrc us, int *out)
+                                                             const float *dstat, const float *hstat_t, int V, int k,
+                                                             float inv_temp, I8 drafts, USrc us, int *out)
 {
     __shared__ int n_acc;
     const int t = threadIdx.x;
-    if (t == 0) {
-        int n = 0;
-        while (n < k) {
-            int dd = drafts.v[n];
-            float pp = __expf(zt[(size_t)n * V + dd] * inv_temp - tstat[2 * n]) / tstat[2 * n + 1];
-            float qq = __expf(zd[(size_t)n * V + dd] * inv_temp - dstat[2 * n]) / dstat[2 * n + 1];
-            float a = fminf(1.f, pp / qq);
-            if (row_uniform(us, n, 1, 0) < a) n++;
-            else break;
+    // the k acceptance tests are independent: lane n tests draft n, the first failure ends the run
+    if (t < 64) {
+        bool keep = true;
+        if (t < k) {
+            int dd = 0;
+#pragma unroll
+            for (int i = 0; i < KG_ROWS; i++)
+                if (i == t) dd = drafts.v[i];
+            const float pp = __expf(zt[(size_t)t * V + dd] * inv_temp - tstat[2 * t]) / tstat[2 * t + 1];
+            const float qq = __expf(zd[(size_t)t * V + dd] * inv_temp - dstat[2 * t]) / dstat[2 * t + 1];
+            float uv = 0.f;
+#pragma unroll
+            for (int i = 0; i < KG_ROWS; i++)
+                if (i == t) uv = row_uniform(us, i, 1, 0);
+            keep = uv < fminf(1.f, pp / qq);
         }
-        n_acc = n;
+        const unsigned long long rejected = __ballot(!keep);
+        if (t == 0) n_acc = rejected ? min(k, __builtin_ctzll(rejected)) : k;
     }
     __syncthreads();
     const int n = n_acc;
@@ -1956,8 +2032,8 @@ __global__ __launch_bounds__(1024) void accept_sample_kernel(const float *zt, co
             row_uniform(us, n, 2, 1));
         __syncthreads();
     }
-    if (tok < 0)
-        tok = block_inverse_cdf(zp, nullptr, [&](float a, float) { return __expf(a * inv_temp - pm) * ps; }, V, row_uniform(us, n, 2, 1));
+    // all drafts kept (or an empty residual): the bonus token from p_n, through the target head's tile statistics
+    if (tok < 0) tok = tile_inverse_cdf(hstat_t + (size_t)n * (V / 16) * 4, V / 16, zp, inv_temp, pm, row_uniform(us, n, 2, 1));
     if (t == 0) { out[0] = n; out[1] = tok; }
 }
 
