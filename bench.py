@@ -380,7 +380,9 @@ def run_micro(args):
         does nothing but read (fixed cost per launch + bytes / bandwidth), against
       * the projection kernel itself on that shape (kg_op_linear on random weights), one row and
         KG_MAX_ROWS rows;
-      * the fixed cost per launch and the asymptotic bandwidth fitted to stream launches of 8 sizes."""
+      * the fixed cost per launch and the asymptotic bandwidth fitted to stream launches of 8 sizes;
+      * a 128 MB stream over the same buffer every time (resident in the memory-side cache) against
+        the rotating one."""
     import numpy as np
     import torch
     from paper_2404_18911_amd import binding as B
@@ -453,6 +455,9 @@ def run_micro(args):
     (a, b), *_ = np.linalg.lstsq(A, np.array(ts), rcond=None)
     out["stream_launch_fit"] = {"sizes_MB": [s_ >> 20 for s_ in sizes], "us": [1e6 * t for t in ts],
                                 "fixed_us_per_launch": 1e6 * a, "asymptotic_GBs": 1.0 / b / 1e9}
+    # the same 128 MB read again and again (it fits the 256 MB memory-side cache) against the rotating reads above
+    t_same = timed(lambda i=0: L.kg_op_stream_read(buf.data_ptr(), 128 << 20, work.data_ptr(), st.cuda_stream), 48)
+    out["reread_128MB"] = {"same_buffer_us": 1e6 * t_same, "rotating_us": 1e6 * ts[sizes.index(128 << 20)]}
     print(json.dumps(out), flush=True)
 
 

@@ -216,8 +216,8 @@ def test_no_matrix_instruction_sits_in_an_exec_masked_region_without_a_skip_bran
     exec-masked region: an `if` on a per-lane copy of a wave-uniform condition that holds nothing
     but an MFMA then runs it also in the waves where the condition is false, on registers they never
     loaded (this once put NaNs into a few logits).  Scan the generated gfx950 code of every kernel:
-    walking back from each MFMA, a branch, a label or the end of a masked region must come before
-    any instruction that narrows EXEC."""
+    walking back from each MFMA through the listing (across labels and across branches on scc / vcc),
+    a branch on EXEC or the end of a masked region must come before any instruction that narrows EXEC."""
     import re
     import shutil
     if shutil.which("hipcc") is None:
@@ -238,6 +238,45 @@ def test_no_matrix_instruction_sits_in_an_exec_masked_region_without_a_skip_bran
             for kk in range(k - 1, -1, -1):
                 p = lines[kk]
                 assert not p.startswith(("s_and_saveexec", "s_andn2_saveexec", "s_or_saveexec")), (name, k, p)
-                if p.startswith(("s_cbranch", "s_branch", "s_or_b64 exec", "s_endpgm")) or p.endswith(":"):
+                # what ends the walk: a branch on EXEC itself (the skip branch of a masked region, or the
+                # back edge of a divergent loop), or EXEC being restored / set outright.  Branches on scc
+                # or vcc, unconditional branches and labels do not: a region masked before them is
+                # still masked after them.
+                if p.startswith(("s_cbranch_execz", "s_cbranch_execnz", "s_or_b64 exec", "s_mov_b64 exec", "s_endpgm")):
                     break
     assert n_mfma > 20
+
+
+def test_the_attention_merge_exchanges_its_partials_with_device_coherent_accesses(tmp_path):
+    """The page merge of the decode attention passes partial results between workgroups of one launch
+    without a fence: it relies on (1) the partials being stored with agent-scope (sc1, write-through)
+    stores, (2) every such store being acknowledged (s_waitcnt vmcnt(0)) before the workgroup bumps the
+    head's counter with an atomic add that returns the old value, and (3) the last workgroup reading the
+    partials with agent-scope (sc1, cache-bypassing) loads issued after that atomic.  These are properties
+    of the generated instructions, not of the source's memory orders, so they are checked on the
+    generated gfx950 code of every instantiation."""
+    import re
+    import shutil
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not available")
+    from paper_2404_18911_amd import build as BLD
+    asm = open(BLD.device_asm(str(tmp_path / "kangaroo.s"))).read()
+    kernels = [k for k in re.findall(r"^(_Z\w+):", asm, flags=re.M) if "attn_kernel" in k and "pf_attn" not in k]
+    assert len(kernels) >= 6
+    for name in kernels:
+        i = asm.index(name + ":")
+        j = asm.find(".Lfunc_end", i)
+        lines = [l.strip() for l in asm[i:j].split("\n") if l.strip() and not l.strip().startswith(";")]
+        adds = [k for k, l in enumerate(lines) if l.startswith("global_atomic_add")]
+        assert len(adds) == 1 and lines[adds[0]].endswith("sc0"), (name, [lines[k] for k in adds])   # returns the old count
+        ia = adds[0]
+        stores = [k for k in range(ia) if lines[k].startswith("global_store_dword") and lines[k].endswith("sc1")]
+        assert len(stores) >= 3, (name, "partials, maxima and sums are stored with sc1")
+        waits = [k for k in range(stores[-1] + 1, ia) if lines[k].startswith("s_waitcnt") and "vmcnt(0)" in lines[k]]
+        assert waits, (name, "no wait for the stores between the last of them and the counter's atomic")
+        # nothing between that wait and the atomic may store partials again
+        assert not [k for k in range(waits[-1], ia) if lines[k].startswith("global_store")], name
+        loads = [k for k in range(ia, len(lines)) if lines[k].startswith("global_load_dword") and lines[k].endswith("sc1")]
+        assert len(loads) >= 3, (name, "the merge reads partials, maxima and sums with sc1")
+        # the counter is handed back to zero with the same kind of store
+        assert [k for k in range(ia, len(lines)) if lines[k].startswith("global_store_dword") and lines[k].endswith("sc1")], name
