@@ -280,3 +280,49 @@ def test_the_attention_merge_exchanges_its_partials_with_device_coherent_accesse
         assert len(loads) >= 3, (name, "the merge reads partials, maxima and sums with sc1")
         # the counter is handed back to zero with the same kind of store
         assert [k for k in range(ia, len(lines)) if lines[k].startswith("global_store_dword") and lines[k].endswith("sc1")], name
+
+
+def test_profile_reducer_of_bench_reads_rocprof_csv(tmp_path):
+    """bench.py --trace-summary on a hand-made rocprofv3 csv tree: per-shape durations, counter means, the
+    calibration by the 1 GiB copy, the bytes per projection launch and the per-layer timeline."""
+    import subprocess
+    import sys
+    d = tmp_path / "t" / "vm"
+    d.mkdir(parents=True)
+    rows = ["Kernel_Name,Grid_Size_X,Grid_Size_Y,Grid_Size_Z,Start_Timestamp,End_Timestamp"]
+    t = 1000
+
+    def k(name, gx, dur, gy=1, gap=0):
+        nonlocal t
+        t += gap
+        rows.append(f'"{name}",{gx},{gy},1,{t},{t + dur}')
+        t += dur
+    for _ in range(2):                                   # two forwards of two layers
+        k("void pack_rows_kernel<true>(void const*)", 32768, 4000)
+        for _ in range(2):
+            k("gemv_bf16_kernel(unsigned int)", 393216, 17000, gap=100)
+            k("void attn_kernel<kvhalf_t, 128, true, 1>(AttnArgs)", 16384, 7000, gy=3)
+            k("gemv_bf16_kernel(unsigned int)", 131072, 8000)
+            k("gemv_bf16_kernel(unsigned int)", 704512, 30000)
+            k("gemv_bf16_kernel(unsigned int)", 131072, 16000)
+        k("gemv_bf16_kernel(unsigned int)", 1024000, 41000)
+        k("head_final_kernel(float const*)", 1024, 5000)
+    (d / "1_kernel_trace.csv").write_text("\n".join(rows) + "\n")
+    c = tmp_path / "c" / "vm"
+    c.mkdir(parents=True)
+    crow = ["Kernel_Name,Grid_Size,Counter_Name,Counter_Value"]
+    for name, v in (("FETCH_SIZE", 524288.0), ("WRITE_SIZE", 1048576.0)):
+        crow.append(f'"__amd_rocclr_copyBuffer",131072,{name},{v}')
+    for v in (50000.0, 52000.0):
+        crow.append(f'"gemv_bf16_kernel(unsigned int)",393216,FETCH_SIZE,{v}')
+        crow.append(f'"gemv_bf16_kernel(unsigned int)",393216,WRITE_SIZE,100.0')
+    (c / "2_counter_collection.csv").write_text("\n".join(crow) + "\n")
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--trace-summary", f"{tmp_path / 't'},{tmp_path / 'c'}"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    out = r.stdout
+    assert "KERNEL_SOURCE_DIGEST" in out and "2 forwards" in out and "over 2 layers" in out
+    assert "one layer (5 kernels + gaps): 78.10 us" in out            # 17 + 7 + 8 + 30 + 16 us and the 0.1 us gap before q,k,v
+    # FETCH x 2.0 (the copy reads half of its KiB), WRITE x 1.0: (51000 * 2 + 100) KiB per launch
+    line = [l for l in out.splitlines() if l.startswith("TRAFFIC_BYTES_PER_PROJECTION_LAUNCH")][0]
+    assert abs(float(line.split()[1]) - (51000 * 2 + 100) * 1024) < 1.0
