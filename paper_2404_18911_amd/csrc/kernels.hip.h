@@ -470,7 +470,9 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(const float *__restrict__
 // MFMA, exactly as in decoding), so every output is computed by the same instruction sequence as
 // in gemv_bf16_kernel: per output tile the k-steps are split into the same 8 ranges, each range is
 // accumulated in order by MFMA, hi and lo are folded, and the 8 range sums are added in order.
-// A prefilled cache is therefore bit-identical to one written token by token.
+// A cache prefilled by this kernel and the 8-row attention is therefore bit-identical to one written
+// token by token (the bfloat16 / float32 cache options; with the half-precision cache long passes use
+// gemm_prefill2_body and pf_attn_kernel below, which sum in another order).
 //   A workgroup handles a group of CBW row blocks (CBW = 8: 64 rows) and a group of 8 * TW weight tiles.
 //   It has 12 waves: waves 8..11 only move data, waves 0..7 only multiply.  The movers bring the
 //   weight tiles and the activation tiles of a stage (PF_KC k-steps) straight from memory into LDS
@@ -773,15 +775,15 @@ __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw2(PfArgs a, Epi e) 
 __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1_cb4(PfArgs a, Epi e) { gemm_prefill_body<1, 4>(a, e); }
 
 // ---------------------------------------------------------------------------------------------
-// Projection for long prompt passes: the same contraction as gemm_prefill_body for passes of 512 rows
-// and more, organised for reuse instead of for the one-token kernel's summation order (a prompt row
+// Projection for long prompt passes: the same contraction as gemm_prefill_body for passes of 256 rows
+// and more (where the launch fills at least 45 % of the compute units), organised for reuse instead of for the one-token kernel's summation order (a prompt row
 // then differs from the same row decoded alone in the order of its sums only, far inside the logit
 // tolerance).  A workgroup owns 8 * TW weight tiles x 128 rows.  The hi and lo halves of the
 // activations are two B operands of 16 distinct rows each (two 8-row blocks) that are multiplied into
 // the SAME accumulator, so a wave's TW x 8 accumulators cover twice the rows that the hi | lo column
 // split covers, nothing is folded, and no per-range totals are kept: four times the outputs per
 // workgroup in the same registers, i.e. a weight tile fetched from the L2 serves 128 rows and an
-// activation tile serves up to 512 weight rows.  Movers / multipliers, the ring of 3 stage buffers
+// activation tile serves up to 512 weight rows.  Movers / multipliers, the ring of NB stage buffers
 // (one k-step per stage) and the exact wait counts are those of gemm_prefill_body; the movers gather
 // the B operands into MFMA lane order (lane = column c + 16 * k group: row block c / 8, row c % 8).
 template <int TW, int NB>
