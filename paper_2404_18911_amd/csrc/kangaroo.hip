@@ -390,6 +390,9 @@ Epi epi_base(kg_ctx *x, int kind, int M, int N);
 
 // ---- prompt pass (dense MFMA projections over many 8-row blocks) ---------------------------------
 
+enum { PF_PLAN_TW1_RB8 = 17 };     // pf_gemm_plan: TW 1 with workgroups of 64 rows
+int pf_gemm_plan(const kg_ctx *x, int N, int K, int T);
+
 int launch_pf_pack(kg_ctx *x, const int *tok_dev, const float *rows, int T, const float *gain, float *xout)
 {
     const int d = x->c.d_model, nb = (T + KG_ROWS - 1) / KG_ROWS;
@@ -398,14 +401,48 @@ int launch_pf_pack(kg_ctx *x, const int *tok_dev, const float *rows, int T, cons
     tk.vocab = x->c.vocab;
     const void *emb = tok_dev ? (const void *)(x->arena + x->embed) : nullptr;
     ProfScope ps(x, 2, 0.0);
+    // the rows feed a q,k,v projection: stored in the layout its kernel reads
     hipLaunchKernelGGL(pack_rows_kernel<true>, dim3(d / 16, nb), dim3(128), 0, x->stream, emb, tk, tok_dev, rows, d, T, gain,
                        xout, (void *)(x->scr + x->s_pactX), at<float>(x->scr, x->s_pssq0), act_bytes(d),
-                       (d / 16) * KG_ROWS);
+                       (d / 16) * KG_ROWS, pf_gemm_plan(x, 3 * d, d, T) ? 1 : 0);
     return check_launch(x, "prompt pack_rows");
 }
 
 // Y[T][N] = X[T][K] . W^T with the epilogue e applied per 8-row block; in/out block strides follow
 // the prompt buffers (activation tiles of K features per block, d/16 tile sums per block)
+// Which kernel multiplies a prompt pass of T rows by a matrix [N][K]: 0 = the 8-row-block kernels
+// (gemm_prefill_body: rows bit-identical to one-token decoding), else the TW of gemm_prefill2_body.
+// The answer also fixes the layout in which the producer of the projection's input has to store it
+// (pf_act_ptr: the pair layout for gemm_prefill2_body).
+int pf_gemm_plan(const kg_ctx *x, int N, int K, int T)
+{
+    // long passes with the half-precision cache only (its prompt rows are not bit-identical to decoded rows anyway)
+    if (T < 256 || x->kvt != 2 || (K + 31) / 32 > PF2_KS_MAX) return 0;
+    // Workgroups of 8 * TW weight tiles x 128 rows.  TW is the one with the least operand traffic: per
+    // k-step every row group fetches all NT weight tiles and every workgroup its 16 activation tiles,
+    // and a last round of workgroups that fills only part of the device costs a whole round; beside the
+    // traffic, the kernels that read the next k-step's operands under the current one's multiplications
+    // (TW 1 and 2) take 0.95 and 1.0 of the model's time and TW 4 takes 1.2.  Measured at the 7B shape,
+    // microseconds per launch for TW 1 / 2 / 4: 1024 rows: q,k,v 236 / 217 / 190, gate+up 454 / 335 / 406,
+    // o_proj and down_proj 116 / 157 / -; 512 rows: q,k,v 145 / 107 / -, gate+up 224 / 219 / 205; 256 rows:
+    // q,k,v 75 / - / -, gate+up 149 / 108 / - (a dash: under 45 % of the compute units would get a workgroup).
+    const int NT = N / 16, nb = (T + KG_ROWS - 1) / KG_ROWS, gx2 = (nb + 15) / 16;
+    int best_tw = 1;
+    double best_cost = -1.0, best_wgs = 0.0;
+    for (int tw = 4; tw >= 1; tw >>= 1) {
+        const int gy = (NT + 8 * tw - 1) / (8 * tw);
+        const double wgs = (double)gx2 * gy;
+        const double rounds = std::ceil(wgs / x->n_cus);
+        const double cost = ((double)NT * gx2 + 16.0 * wgs) * rounds * x->n_cus / wgs * (tw == 4 ? 1.2 : tw == 2 ? 1.0 : 0.95);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_tw = tw; best_wgs = wgs; }
+    }
+    if (best_wgs >= 0.45 * x->n_cus) return best_tw;
+    // few weight tiles (o_proj and down_proj at 256 rows: 64 workgroups of 128 rows): workgroups of 64 rows
+    // where those reach that fill (84 -> 73 us per launch against the 8-row-block kernel), else that kernel
+    const double wgs8 = (double)((nb + 7) / 8) * ((NT + 7) / 8);
+    return wgs8 >= 0.45 * x->n_cus ? PF_PLAN_TW1_RB8 : 0;
+}
+
 int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T, const Epi &e, bool ssq_in, bool ssq_out,
                    int act_out_K)
 {
@@ -419,36 +456,17 @@ int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T
     a.ssq_in_blk = ssq_in ? sq : 0; a.ssq_out_blk = ssq_out ? sq : 0;
     a.act_out_blk = act_out_K ? act_bytes(act_out_K) : 0;
     const int nb = (T + KG_ROWS - 1) / KG_ROWS;
-    if (T >= 256 && x->kvt == 2) {
-        // longer passes with the half-precision cache (whose prompt rows are not bit-identical to decoded
-        // rows anyway): workgroups of 8 * TW weight tiles x 128 rows (gemm_prefill2_body).  These launches
-        // are bound by the operand traffic from the L2 into LDS, so TW is the one with the least of it: per
-        // k-step every row group fetches all NT weight tiles and every workgroup its 16 activation tiles,
-        // and a last round of workgroups that fills only part of the device costs a whole round
-        // (measured at the 7B shape, 1024 rows: q,k,v 272 / 242 / 192 us for TW 1 / 2 / 4, gate+up
-        // 522 / 376 / 406, o_proj and down_proj 164 / 196 / 319; the model picks 4, 2 and 1).  Where even
-        // TW = 1 leaves more than half of the compute units without a workgroup (o_proj and down_proj
-        // at 256 rows: 132 us against 84 us) the smaller row groups below are used.
-        const int gx2 = (nb + 15) / 16;
-        int best_tw = 1;
-        double best_cost = -1.0, best_wgs = 0.0;
-        for (int tw = 4; tw >= 1; tw >>= 1) {
-            const int gy = (a.NT + 8 * tw - 1) / (8 * tw);
-            const double wgs = (double)gx2 * gy;
-            const double rounds = std::ceil(wgs / x->n_cus);
-            const double cost = ((double)a.NT * gx2 + 16.0 * wgs) * rounds * x->n_cus / wgs;
-            if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_tw = tw; best_wgs = wgs; }
-        }
-        if (best_wgs >= 0.45 * x->n_cus) {
-            a.gx = gx2;
-            a.gy = (a.NT + 8 * best_tw - 1) / (8 * best_tw);
-            const int groups = a.gx * 8 * ((a.gy + 7) / 8);
-            ProfScope ps(x, 3, 2.0 * T * (double)N * K);
-            if (best_tw == 4) hipLaunchKernelGGL(gemm_prefill2_kernel_tw4, dim3(groups), dim3(768), 0, x->stream, a, e);
-            else if (best_tw == 2) hipLaunchKernelGGL(gemm_prefill2_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e);
-            else hipLaunchKernelGGL(gemm_prefill2_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e);
-            return check_launch(x, "prompt projection");
-        }
+    if (const int plan = pf_gemm_plan(x, N, K, T)) {
+        const int best_tw = plan == PF_PLAN_TW1_RB8 ? 1 : plan;
+        a.gx = plan == PF_PLAN_TW1_RB8 ? (nb + 7) / 8 : (nb + 15) / 16;
+        a.gy = (a.NT + 8 * best_tw - 1) / (8 * best_tw);
+        const int groups = a.gx * 8 * ((a.gy + 7) / 8);
+        ProfScope ps(x, 3, 2.0 * T * (double)N * K);
+        if (plan == PF_PLAN_TW1_RB8) hipLaunchKernelGGL(gemm_prefill2_kernel_tw1_rb8, dim3(groups), dim3(768), 0, x->stream, a, e);
+        else if (best_tw == 4) hipLaunchKernelGGL(gemm_prefill2_kernel_tw4, dim3(groups), dim3(768), 0, x->stream, a, e);
+        else if (best_tw == 2) hipLaunchKernelGGL(gemm_prefill2_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e);
+        else hipLaunchKernelGGL(gemm_prefill2_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e);
+        return check_launch(x, "prompt projection");
     }
     // two weight tiles per multiplying wave where that still leaves enough workgroups for the device
     const int tw = a.NT >= 512 ? 2 : 1;
@@ -503,6 +521,7 @@ int pf_block(kg_ctx *x, int slot, size_t qkv_off, size_t wo_off, size_t gu_off, 
         pa.kv = (const kvhalf_t *)x->kv; pa.slot = slot; pa.n_slots = c.n_layers + 1;
         pa.rope = at<const float2>(x->scr, x->s_rope);
         pa.act_out = actA; pa.act_blk_bytes = act_bytes(d);
+        pa.act_pair = pf_gemm_plan(x, d, d, T) ? 1 : 0;               // read by the output projection
         ProfScope ps(x, 1, 0.0);
         const dim3 grid(c.n_heads, (T + 63) / 64);
         if (c.head_dim == 128) hipLaunchKernelGGL(pf_attn_kernel<128>, grid, dim3(256), 0, x->stream, pa);
@@ -516,15 +535,18 @@ int pf_block(kg_ctx *x, int slot, size_t qkv_off, size_t wo_off, size_t gu_off, 
 
     e = epi_base(x, EPI_RESID, KG_ROWS, d);
     e.res = x_in; e.xout = x_mid; e.act_out = actX; e.act_K = d; e.gain = g2; e.ssq_out = ssq1;
+    e.act_pair = pf_gemm_plan(x, 2 * f, d, T) ? 1 : 0;                // read by gate+up
     KGCHK(launch_pf_gemm(x, wo_off, d, d, actA, T, e, false, true, d));
 
     e = epi_base(x, EPI_SWIGLU, KG_ROWS, 2 * f);
     e.ssq_in = ssq1; e.act_out = actF; e.act_K = f;
+    e.act_pair = pf_gemm_plan(x, d, f, T) ? 1 : 0;                    // read by down_proj
     KGCHK(launch_pf_gemm(x, gu_off, 2 * f, d, actX, T, e, true, false, f));
 
     e = epi_base(x, EPI_RESID, KG_ROWS, d);
     e.res = x_mid; e.xout = x_out; e.act_out = next_gain ? actX : nullptr; e.act_K = d; e.gain = next_gain;
     e.ssq_out = ssq0;
+    e.act_pair = pf_gemm_plan(x, 3 * d, d, T) ? 1 : 0;                // read by the next block's q,k,v
     KGCHK(launch_pf_gemm(x, wd_off, d, f, actF, T, e, false, true, next_gain ? d : 0));
     return KG_OK;
 }

@@ -48,6 +48,7 @@ struct Epi {
     // EPI_SILU: act_out <- silu(y * scale) at K index n (the first map of the two-linear-map adapter)
     // EPI_RESID / EPI_SWIGLU: activation for the next projection (K index = n, or tile*8+i for SwiGLU)
     void *act_out;
+    int act_pair;       // prompt passes: layout of act_out, see pf_act_ptr (0 = the 8-row layout above)
     int act_K;
     const float *gain;
     float *ssq_out;
@@ -153,6 +154,34 @@ __device__ __forceinline__ void compute_scale(const Epi &e, float *sc)
 }
 
 // Epilogue on a finished tile: yt[16][8] in LDS (row in tile, batch row), all 256 threads call it.
+// Prompt passes: where the producer of a projection's input puts row m of 8-row block b, feature k.
+// Returns the address of the hi part; the lo part lies lo_off elements further.
+// pair = 0: the block's own tiles [k/32][row m][hi|lo][k%32/8][k%8], what the 8-row kernels read.
+// pair = 1: tiles of two blocks, [k/32][hi|lo][lane (8 (b % 2) + m) + 16 (k%32/8)][k%8]: the B operand of a
+// 16-row MFMA as one contiguous KB, which a mover wave fetches with one coalesced access per four lanes
+// (gathered from the 8-row layout the same tile costs one access per lane: neighbouring lanes then
+// read 128 bytes apart).
+__device__ __forceinline__ uint16_t *pf_act_ptr(void *base, size_t blk_bytes, int b, int m, int k, int pair, int &lo_off)
+{
+    uint16_t *p = (uint16_t *)base;
+    if (pair) {
+        lo_off = 512;
+        return p + (size_t)(b >> 1) * blk_bytes + (size_t)(k >> 5) * 1024 + (size_t)(((b & 1) * 8 + m) + 16 * ((k >> 3) & 3)) * 8 + (k & 7);
+    }
+    lo_off = 32;
+    return p + (size_t)b * (blk_bytes >> 1) + (size_t)(k >> 5) * 512 + (size_t)(m * 8 + ((k >> 3) & 3)) * 8 + (k & 7);
+}
+// one value, split as store_act splits it
+__device__ __forceinline__ void store_act_pf(void *base, size_t blk_bytes, int b, int m, int k, float v, int pair)
+{
+    int lo_off;
+    uint16_t *p = pf_act_ptr(base, blk_bytes, b, m, k, pair, lo_off);
+    v = rounded(v);
+    const uint16_t hi = f2bf(v);
+    p[0] = hi;
+    p[lo_off] = f2bf(v - bf2f(hi));
+}
+
 template <bool BF>
 __device__ __forceinline__ void epilogue(const Epi &e, int rt, float (*yt)[KG_ROWS], const float *sc,
                                          float (*sq)[KG_ROWS], float resv = 0.f, float gainv = 1.f,
@@ -586,20 +615,41 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
 #pragma unroll
     for (int tw = 0; tw < PF_TW; tw++) valid[tw] = rt0 + tw < a.NT;
     const int bsl = b_slot(lane);
+    // movers: the address of every tile of the wave at k-step 0 is computed once (tile j = wave - 8 + 4 i is
+    // uniform in the wave; the first PF_KC * NTW tiles of a stage are weight tiles [kk][tile], the others
+    // activation tiles [kk][row block]); a stage then adds the position of its k-steps
+    const u32x4_t *src0[LPW];
+    if (mover) {
+#pragma unroll
+        for (int i = 0; i < LPW; i++) {
+            const int j = (wave - 8) + 4 * i;
+            if (j < PF_KC * NTW) {
+                const int rt = min(gyi * NTW + j % NTW, a.NT - 1);
+                src0[i] = a.W + (size_t)rt * KS * 64 + lane;
+            } else {
+                const int cb = (j - PF_KC * NTW) % CBW;
+                src0[i] = a.act + (size_t)(b0 + min(cb, nbw - 1)) * a.act_blk + bsl;
+            }
+        }
+    }
     auto issue = [&](const PfStage &sg, int buf) {         // movers: loads of stage sg into ring slot buf
         const int k0 = sg.r < 8 ? sg.k : 0, n = sg.r < 8 ? sg.n : 0;
+        int wpos[PF_KC], apos[PF_KC];
+#pragma unroll
+        for (int kk = 0; kk < PF_KC; kk++) {
+            const int ks = k0 + (kk < n ? kk : 0);
+            wpos[kk] = tile_pos_in_range(sg.r < 8 ? sg.r : 0, ks, KS) * 64;
+            apos[kk] = ks * 64;
+        }
 #pragma unroll
         for (int i = 0; i < LPW; i++) {
             const int j = (wave - 8) + 4 * i;              // uniform in the wave
             if (j < PF_KC * NTW) {
                 const int kk = j / NTW, tile = j % NTW;
-                const int rt = min(gyi * NTW + tile, a.NT - 1);
-                const u32x4_t *src = a.W + ((size_t)rt * KS + tile_pos_in_range(sg.r < 8 ? sg.r : 0, k0 + (kk < n ? kk : 0), KS)) * 64 + lane;
-                __builtin_amdgcn_global_load_lds(src, &As[buf][kk][tile][0], 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(src0[i] + wpos[kk], &As[buf][kk][tile][0], 16, 0, 0);
             } else {
                 const int jb = j - PF_KC * NTW, kk = jb / CBW, cb = jb % CBW;
-                const u32x4_t *src = a.act + (size_t)(b0 + min(cb, nbw - 1)) * a.act_blk + (size_t)(k0 + (kk < n ? kk : 0)) * 64 + bsl;
-                __builtin_amdgcn_global_load_lds(src, &Bs[buf][kk][cb][0], 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(src0[i] + apos[kk], &Bs[buf][kk][cb][0], 16, 0, 0);
             }
         }
     };
@@ -718,9 +768,10 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
                             hi[r] = f2bf(x);
                             lo[r] = f2bf(x - bf2f(hi[r]));
                         }
-                        uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(n0 >> 5) * 512 + (size_t)(col * 8 + ((n0 >> 3) & 3)) * 8 + (n0 & 7);
+                        int lo_off;
+                        uint16_t *pa = pf_act_ptr(e.act_out, a.act_out_blk, b0 + cb, col, n0, e.act_pair, lo_off);
                         *(uint2 *)pa = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-                        *(uint2 *)(pa + 32) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                        *(uint2 *)(pa + lo_off) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
                     }
                 }
                 if (eb.ssq_out) {
@@ -759,9 +810,10 @@ __device__ __forceinline__ void gemm_prefill_body(const PfArgs &a, const Epi &e)
                         lo[i] = f2bf(av - bf2f(hi[i]));
                     }
                     const int k0 = rt * 8 + 2 * g4;
-                    uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(k0 >> 5) * 512 + (size_t)(col * 8 + ((k0 >> 3) & 3)) * 8 + (k0 & 7);
+                    int lo_off;
+                    uint16_t *pa = pf_act_ptr(e.act_out, a.act_out_blk, b0 + cb, col, k0, e.act_pair, lo_off);
                     *(uint32_t *)pa = hi[0] | ((uint32_t)hi[1] << 16);
-                    *(uint32_t *)(pa + 32) = lo[0] | ((uint32_t)lo[1] << 16);
+                    *(uint32_t *)(pa + lo_off) = lo[0] | ((uint32_t)lo[1] << 16);
                 }
             }
         }
@@ -776,24 +828,35 @@ __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1_cb4(PfArgs a, Epi
 
 // ---------------------------------------------------------------------------------------------
 // Projection for long prompt passes: the same contraction as gemm_prefill_body for passes of 256 rows
-// and more (where the launch fills at least 45 % of the compute units), organised for reuse instead of for the one-token kernel's summation order (a prompt row
-// then differs from the same row decoded alone in the order of its sums only, far inside the logit
-// tolerance).  A workgroup owns 8 * TW weight tiles x 128 rows.  The hi and lo halves of the
-// activations are two B operands of 16 distinct rows each (two 8-row blocks) that are multiplied into
-// the SAME accumulator, so a wave's TW x 8 accumulators cover twice the rows that the hi | lo column
-// split covers, nothing is folded, and no per-range totals are kept: four times the outputs per
-// workgroup in the same registers, i.e. a weight tile fetched from the L2 serves 128 rows and an
-// activation tile serves up to 512 weight rows.  Movers / multipliers, the ring of NB stage buffers
-// (one k-step per stage) and the exact wait counts are those of gemm_prefill_body; the movers gather
-// the B operands into MFMA lane order (lane = column c + 16 * k group: row block c / 8, row c % 8).
-template <int TW, int NB>
+// and more (where the launch fills at least 45 % of the compute units), organised for reuse instead of
+// for the one-token kernel's summation order (a prompt row then differs from the same row decoded alone
+// in the order of its sums only, far inside the logit tolerance).  A workgroup owns 8 * TW weight tiles
+// x 128 rows.  The hi and lo halves of the activations are two B operands of 16 distinct rows each (two
+// 8-row blocks) that are multiplied into the SAME accumulator, so nothing is folded and no per-range
+// totals are kept: a weight tile fetched from the L2 serves 128 rows and an activation tile serves up to
+// 512 weight rows.  The activations arrive in the pair layout of pf_act_ptr (a B operand = one KB).
+//   12 waves: waves 8..11 move, waves 0..7 multiply.  The movers bring the operand tiles of a k-step
+// straight into an LDS ring of NB stage buffers (global_load_lds), NB - 1 stages ahead, and wait with
+// exact counts; their loop holds nothing but the loads: every tile's address at k-step 0 is computed
+// once, the position of k-step ks inside a row tile (tile_pos) comes from a table filled at the start.
+//   PIPE (TW 1, 2): the multiplying waves are arranged 4 x 2, a wave owns 2 TW weight tiles x 4 pairs of
+// row blocks (2 TW + 8 operand reads from LDS per 16 TW multiplications instead of TW + 16), all reads
+// of a k-step are issued together, the hi halves are multiplied into every accumulator before the lo
+// halves, and the operands of k-step ks + 1 are read under the second half of step ks (two register
+// sets).  Without PIPE (TW 4, whose 128 accumulator registers leave no room for a second set) a wave
+// owns TW weight tiles x all 8 pairs.
+#define PF2_KS_MAX 1024
+template <int TW, int NB, bool PIPE, int RB = 16>            // RB = 8-row blocks per workgroup: 16, or 8 for launches with few weight tiles
 __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e)
 {
     constexpr int NTW = 8 * TW;
-    constexpr int RB = 16;                                  // 8-row blocks per workgroup
+    static_assert(RB == 16 || (RB == 8 && PIPE), "128 rows, or 64 with the 4 x 2 wave arrangement");
+    constexpr int WA = PIPE ? 2 * TW : TW;                  // weight tiles of a multiplying wave
+    constexpr int WP = PIPE ? RB / 4 : RB / 2;              // its pairs of row blocks (hi and lo operand each)
     __shared__ u32x4_t As[NB][NTW][64];                     // ring of NB stage buffers, one k-step each
     __shared__ u32x4_t Bs[NB][RB / 2][2][64];
     __shared__ float scs[RB][KG_ROWS];
+    __shared__ uint16_t tpos[PF2_KS_MAX];
     const int t = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
     const bool mover = wave >= 8;
     const int nb = (a.T + 7) >> 3;
@@ -804,8 +867,10 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
     const int nbw = min(RB, nb - b0);
     const int KS = a.KS;
     const int col = lane & 15, g4 = lane >> 4;
+    const int a0 = PIPE ? (wave & 3) * WA : wave * TW;      // first weight tile and first pair of a multiplying wave
+    const int g0 = PIPE ? ((wave >> 2) & 1) * WP : 0;
 
-    // RMS scales of the group's rows: one wave per row block (12 waves serve 16 blocks)
+    // RMS scales of the group's rows: one wave per row block (12 waves serve 16 blocks); the table of tile positions
     for (int blk = wave; blk < nbw; blk += 12) {
         const Epi eb = pf_block_epi(e, a, b0 + blk);
 #pragma unroll
@@ -820,27 +885,12 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
             if (lane == 0) scs[blk][m] = sv;
         }
     }
+    for (int i = t; i < KS; i += 768) tpos[i] = (uint16_t)tile_pos(i, KS);
+    __syncthreads();
 
     constexpr int TL = NTW + RB;                            // tile loads of a stage
     constexpr int LPW = TL / 4;
-    static_assert(TL % 4 == 0, "tile loads spread evenly over the 4 mover waves");
-    auto issue = [&](int ks, int buf) {                     // movers: operands of k-step ks (clamped: late stages reload a valid one)
-        const int kk = min(ks, KS - 1);
-#pragma unroll
-        for (int i = 0; i < LPW; i++) {
-            const int j = (wave - 8) + 4 * i;               // uniform in the wave
-            if (j < NTW) {
-                const int rt = min(gyi * NTW + j, a.NT - 1);
-                const u32x4_t *src = a.W + ((size_t)rt * KS + tile_pos(kk, KS)) * 64 + lane;
-                __builtin_amdgcn_global_load_lds(src, &As[buf][j][0], 16, 0, 0);
-            } else {
-                const int jb = j - NTW, grp = jb >> 1, part = jb & 1;
-                const int blk = min(b0 + 2 * grp + (col >> 3), nb - 1);
-                const u32x4_t *src = a.act + (size_t)blk * a.act_blk + (size_t)kk * 64 + ((col & 7) * 8 + part * 4 + g4);
-                __builtin_amdgcn_global_load_lds(src, &Bs[buf][grp][part][0], 16, 0, 0);
-            }
-        }
-    };
+    static_assert(TL % 4 == 0 && NTW % 4 == 0, "tile loads spread evenly over the 4 mover waves, weight tiles first");
     auto meet = [&]() {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
@@ -852,6 +902,29 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
     static_assert((NB - 2) * LPW <= 63, "the wait count must fit the instruction's field");
     int buf = 0;
     if (mover) {
+        const u32x4_t *src0[LPW];                           // the wave's tiles at k-step 0 (tile j = wave - 8 + 4 i: uniform in the wave)
+#pragma unroll
+        for (int i = 0; i < LPW; i++) {
+            const int j = (wave - 8) + 4 * i;
+            if (i < NTW / 4) {
+                const int rt = min(gyi * NTW + j, a.NT - 1);
+                src0[i] = a.W + (size_t)rt * KS * 64 + lane;
+            } else {
+                const int jb = j - NTW, grp = jb >> 1, part = jb & 1;
+                const int pr = min((b0 >> 1) + grp, (nb - 1) >> 1);
+                src0[i] = a.act + (size_t)pr * 2 * a.act_blk + part * 64 + lane;
+            }
+        }
+        auto issue = [&](int ks, int bf) {                  // operands of k-step ks (clamped: late stages reload a valid one)
+            const int kk = min(ks, KS - 1);
+            const int wpos = __builtin_amdgcn_readfirstlane((int)tpos[kk]) * 64, apos = kk * 128;
+#pragma unroll
+            for (int i = 0; i < LPW; i++) {
+                const int j = (wave - 8) + 4 * i;
+                if (i < NTW / 4) __builtin_amdgcn_global_load_lds(src0[i] + wpos, &As[bf][j][0], 16, 0, 0);
+                else __builtin_amdgcn_global_load_lds(src0[i] + apos, &Bs[bf][(j - NTW) >> 1][(j - NTW) & 1][0], 16, 0, 0);
+            }
+        };
 #pragma unroll
         for (int s0 = 0; s0 < NB - 1; s0++) issue(s0, s0);
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NB - 2) * LPW) : "memory");
@@ -865,44 +938,85 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         return;
     }
-    f32x4_t acc[TW][RB / 2];
+    f32x4_t acc[WA][WP];
 #pragma unroll
-    for (int tw = 0; tw < TW; tw++)
+    for (int ta = 0; ta < WA; ta++)
 #pragma unroll
-        for (int gq = 0; gq < RB / 2; gq++) acc[tw][gq] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    __syncthreads();
-    for (int ks = 0; ks < KS; ks++) {
-        bf16x8_t av[TW];
+        for (int gb = 0; gb < WP; gb++) acc[ta][gb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    if (PIPE) {
+        struct Frag { bf16x8_t av[WA], bh[WP], bl[WP]; };
+        auto fetch = [&](Frag &f, int bf) {
 #pragma unroll
-        for (int tw = 0; tw < TW; tw++) av[tw] = __builtin_bit_cast(bf16x8_t, As[buf][wave * TW + tw][lane]);
+            for (int ta = 0; ta < WA; ta++) f.av[ta] = __builtin_bit_cast(bf16x8_t, As[bf][a0 + ta][lane]);
 #pragma unroll
-        for (int gq = 0; gq < RB / 2; gq++) {
-            const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, Bs[buf][gq][0][lane]);
-            const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, Bs[buf][gq][1][lane]);
+            for (int gb = 0; gb < WP; gb++) f.bh[gb] = __builtin_bit_cast(bf16x8_t, Bs[bf][g0 + gb][0][lane]);
 #pragma unroll
-            for (int tw = 0; tw < TW; tw++) {
-                acc[tw][gq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tw], bh, acc[tw][gq], 0, 0, 0);
-                acc[tw][gq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tw], bl, acc[tw][gq], 0, 0, 0);
-            }
+            for (int gb = 0; gb < WP; gb++) f.bl[gb] = __builtin_bit_cast(bf16x8_t, Bs[bf][g0 + gb][1][lane]);
+        };
+        // Between the halves of a step: the barrier after which stage ks + 1 has landed (and no wave still
+        // reads the stage before), and the reads of that stage.
+        auto step = [&](const Frag &cur, Frag &nxt) {
+#pragma unroll
+            for (int gb = 0; gb < WP; gb++)
+#pragma unroll
+                for (int ta = 0; ta < WA; ta++)
+                    acc[ta][gb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.av[ta], cur.bh[gb], acc[ta][gb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            meet();
+            buf = buf == NB - 1 ? 0 : buf + 1;
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(nxt, buf);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int gb = 0; gb < WP; gb++)
+#pragma unroll
+                for (int ta = 0; ta < WA; ta++)
+                    acc[ta][gb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.av[ta], cur.bl[gb], acc[ta][gb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        __syncthreads();
+        Frag fa, fb;
+        fetch(fa, 0);
+        // (the reads after the last step's barrier fetch a stage the movers filled with a valid, unused k-step)
+        for (int ks = 0; ks < KS; ks += 2) {
+            step(fa, fb);
+            if (ks + 1 < KS) step(fb, fa);
         }
-        meet();
-        buf = buf == NB - 1 ? 0 : buf + 1;
+    } else {
+        __syncthreads();
+        for (int ks = 0; ks < KS; ks++) {
+            bf16x8_t av[WA];
+#pragma unroll
+            for (int ta = 0; ta < WA; ta++) av[ta] = __builtin_bit_cast(bf16x8_t, As[buf][a0 + ta][lane]);
+#pragma unroll
+            for (int gb = 0; gb < WP; gb++) {
+                const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, Bs[buf][g0 + gb][0][lane]);
+                const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, Bs[buf][g0 + gb][1][lane]);
+#pragma unroll
+                for (int ta = 0; ta < WA; ta++) {
+                    acc[ta][gb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[ta], bh, acc[ta][gb], 0, 0, 0);
+                    acc[ta][gb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[ta], bl, acc[ta][gb], 0, 0, 0);
+                }
+            }
+            meet();
+            buf = buf == NB - 1 ? 0 : buf + 1;
+        }
     }
 
     // Epilogue from the accumulators: lane (column c, group g4) holds weight rows 4 g4 .. 4 g4 + 3 of a
-    // tile for row c % 8 of block b0 + 2 gq + c / 8.
+    // tile for row c % 8 of block b0 + 2 (g0 + gb) + c / 8.
 #pragma unroll
-    for (int tw = 0; tw < TW; tw++) {
-        const int rt = gyi * NTW + wave * TW + tw;
+    for (int ta = 0; ta < WA; ta++) {
+        const int rt = gyi * NTW + a0 + ta;
         const bool valid = rt < a.NT;
         const int n0 = rt * 16 + 4 * g4;
 #pragma unroll
-        for (int gq = 0; gq < RB / 2; gq++) {
-            const int blk = 2 * gq + (col >> 3), m = col & 7;
+        for (int gb = 0; gb < WP; gb++) {
+            const int blk = 2 * (g0 + gb) + (col >> 3), m = col & 7;
             const bool in_group = blk < nbw;
             const Epi eb = pf_block_epi(e, a, b0 + min(blk, nbw - 1));
             const bool live = valid && in_group && m < eb.M;
-            const f32x4_t y = acc[tw][gq];
+            const f32x4_t y = acc[ta][gb];
             if (e.kind == EPI_RESID) {
                 float v[4] = {0.f, 0.f, 0.f, 0.f};
                 if (live) {
@@ -919,9 +1033,10 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
                             hi[r] = f2bf(xv);
                             lo[r] = f2bf(xv - bf2f(hi[r]));
                         }
-                        uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(n0 >> 5) * 512 + (size_t)(m * 8 + ((n0 >> 3) & 3)) * 8 + (n0 & 7);
+                        int lo_off;
+                        uint16_t *pa = pf_act_ptr(e.act_out, a.act_out_blk, b0 + blk, m, n0, e.act_pair, lo_off);
                         *(uint2 *)pa = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-                        *(uint2 *)(pa + 32) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                        *(uint2 *)(pa + lo_off) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
                     }
                 }
                 if (e.ssq_out) {                 // sum of squares of the tile's 16 outputs per row: 4 in the lane, then the 4 lane groups
@@ -944,17 +1059,19 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
                         lo[i] = f2bf(av2 - bf2f(hi[i]));
                     }
                     const int k0 = rt * 8 + 2 * g4;
-                    uint16_t *pa = (uint16_t *)eb.act_out + (size_t)(k0 >> 5) * 512 + (size_t)(m * 8 + ((k0 >> 3) & 3)) * 8 + (k0 & 7);
+                    int lo_off;
+                    uint16_t *pa = pf_act_ptr(e.act_out, a.act_out_blk, b0 + blk, m, k0, e.act_pair, lo_off);
                     *(uint32_t *)pa = hi[0] | ((uint32_t)hi[1] << 16);
-                    *(uint32_t *)(pa + 32) = lo[0] | ((uint32_t)lo[1] << 16);
+                    *(uint32_t *)(pa + lo_off) = lo[0] | ((uint32_t)lo[1] << 16);
                 }
             }
         }
     }
 }
-__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw1(PfArgs a, Epi e) { gemm_prefill2_body<1, 6>(a, e); }
-__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw2(PfArgs a, Epi e) { gemm_prefill2_body<2, 4>(a, e); }
-__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw4(PfArgs a, Epi e) { gemm_prefill2_body<4, 3>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw1(PfArgs a, Epi e) { gemm_prefill2_body<1, 6, true>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw2(PfArgs a, Epi e) { gemm_prefill2_body<2, 4, true>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw4(PfArgs a, Epi e) { gemm_prefill2_body<4, 3, false>(a, e); }
+__global__ __launch_bounds__(768) void gemm_prefill2_kernel_tw1_rb8(PfArgs a, Epi e) { gemm_prefill2_body<1, 8, true, 8>(a, e); }
 
 // ---------------------------------------------------------------------------------------------
 // Rows -> activation for the first projection of a stack: x[m] = E[tok[m]] (emb != null) or the
@@ -966,12 +1083,13 @@ template <bool BF>
 __global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 tok, const int *tok_dev,
                                                         const float *rows, int d, int M, const float *gain,
                                                         float *xout, void *act, float *ssq,
-                                                        size_t act_blk_bytes = 0, int ssq_blk = 0)
+                                                        size_t act_blk_bytes = 0, int ssq_blk = 0, int act_pair = 0)
 {
     __shared__ float sq[16][KG_ROWS];
     // blockIdx.y selects a block of 8 rows (prefill passes many blocks in one launch; M is then the
     // total row count and every per-row pointer advances by 8 rows per block)
     const int blk = blockIdx.y;
+    void *const act_base = act;
     if (blk) {
         M -= 8 * blk;
         if (tok_dev) tok_dev += 8 * blk;
@@ -996,7 +1114,8 @@ __global__ __launch_bounds__(128) void pack_rows_kernel(const void *emb, Tok8 to
             v = rows[(size_t)m * d + n];
         }
         if (xout) xout[(size_t)m * d + n] = v;
-        store_act<BF>(act, d, m, n, gain ? v * gain[n] : v);
+        if (BF && act_pair) store_act_pf(act_base, act_blk_bytes, blk, m, n, gain ? v * gain[n] : v, 1);
+        else store_act<BF>(act, d, m, n, gain ? v * gain[n] : v);
     }
     sq[row][m] = v * v;
     __syncthreads();
@@ -1554,6 +1673,7 @@ struct PfAttnArgs {
     const float2 *rope;      // [max_seq][hd/2]
     void *act_out;           // activation tiles of the output projection, one per 8-row block
     size_t act_blk_bytes;
+    int act_pair;            // layout of act_out (pf_act_ptr)
 };
 
 template <int HD>
@@ -1712,9 +1832,9 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
         const float ir = __shfl(inv, 4 * g + r);
         const int orow = rb * 64 + wave * 16 + 4 * g + r;
         if (orow < a.T) {
-            void *blk = (char *)a.act_out + (size_t)(orow >> 3) * a.act_blk_bytes;
 #pragma unroll
-            for (int dt = 0; dt < DT; dt++) store_act<true>(blk, d, orow & 7, h * HD + 16 * dt + q16, o[dt][r] * ir);
+            for (int dt = 0; dt < DT; dt++)
+                store_act_pf(a.act_out, a.act_blk_bytes, orow >> 3, orow & 7, h * HD + 16 * dt + q16, o[dt][r] * ir, a.act_pair);
         }
     }
 }
