@@ -438,7 +438,7 @@ int pf_gemm_plan(const kg_ctx *x, int N, int K, int T)
     }
     if (best_wgs >= 0.45 * x->n_cus) return best_tw;
     // few weight tiles (o_proj and down_proj at 256 rows: 64 workgroups of 128 rows): workgroups of 64 rows
-    // where those reach that fill (84 -> 73 us per launch against the 8-row-block kernel), else that kernel
+    // where those reach that fill (70 us per launch against 84 us of the 8-row-block kernel), else that kernel
     const double wgs8 = (double)((nb + 7) / 8) * ((NT + 7) / 8);
     return wgs8 >= 0.45 * x->n_cus ? PF_PLAN_TW1_RB8 : 0;
 }
