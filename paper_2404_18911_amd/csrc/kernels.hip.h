@@ -837,8 +837,10 @@ __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1_cb4(PfArgs a, Epi
 // 512 weight rows.  The activations arrive in the pair layout of pf_act_ptr (a B operand = one KB).
 //   12 waves: waves 8..11 move, waves 0..7 multiply.  The movers bring the operand tiles of a k-step
 // straight into an LDS ring of NB stage buffers (global_load_lds), NB - 1 stages ahead, and wait with
-// exact counts; their loop holds nothing but the loads: every tile's address at k-step 0 is computed
-// once, the position of k-step ks inside a row tile (tile_pos) comes from a table filled at the start.
+// exact counts; their loop holds nothing but the loads: every tile's address at step 0 is computed
+// once, and the k loop walks a row tile's weight tiles in the order they are stored (contiguous memory;
+// the sum over k may take any order here) and takes the k-step each one holds from a table, the inverse
+// of tile_pos filled at the start, to pick the matching activation tile.
 //   PIPE (TW 1, 2): the multiplying waves are arranged 4 x 2, a wave owns 2 TW weight tiles x 4 pairs of
 // row blocks (2 TW + 8 operand reads from LDS per 16 TW multiplications instead of TW + 16), all reads
 // of a k-step are issued together, the hi halves are multiplied into every accumulator before the lo
@@ -856,7 +858,7 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
     __shared__ u32x4_t As[NB][NTW][64];                     // ring of NB stage buffers, one k-step each
     __shared__ u32x4_t Bs[NB][RB / 2][2][64];
     __shared__ float scs[RB][KG_ROWS];
-    __shared__ uint16_t tpos[PF2_KS_MAX];
+    __shared__ uint16_t kstep_at[PF2_KS_MAX];               // k-step held by the tile at position p of a row tile
     const int t = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
     const bool mover = wave >= 8;
     const int nb = (a.T + 7) >> 3;
@@ -870,7 +872,7 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
     const int a0 = PIPE ? (wave & 3) * WA : wave * TW;      // first weight tile and first pair of a multiplying wave
     const int g0 = PIPE ? ((wave >> 2) & 1) * WP : 0;
 
-    // RMS scales of the group's rows: one wave per row block (12 waves serve 16 blocks); the table of tile positions
+    // RMS scales of the group's rows: one wave per row block (12 waves serve 16 blocks); the table of k-steps by position
     for (int blk = wave; blk < nbw; blk += 12) {
         const Epi eb = pf_block_epi(e, a, b0 + blk);
 #pragma unroll
@@ -885,7 +887,7 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
             if (lane == 0) scs[blk][m] = sv;
         }
     }
-    for (int i = t; i < KS; i += 768) tpos[i] = (uint16_t)tile_pos(i, KS);
+    for (int i = t; i < KS; i += 768) kstep_at[tile_pos(i, KS)] = (uint16_t)i;
     __syncthreads();
 
     constexpr int TL = NTW + RB;                            // tile loads of a stage
@@ -915,9 +917,9 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
                 src0[i] = a.act + (size_t)pr * 2 * a.act_blk + part * 64 + lane;
             }
         }
-        auto issue = [&](int ks, int bf) {                  // operands of k-step ks (clamped: late stages reload a valid one)
+        auto issue = [&](int ks, int bf) {                  // operands of step ks (clamped: late stages reload a valid one)
             const int kk = min(ks, KS - 1);
-            const int wpos = __builtin_amdgcn_readfirstlane((int)tpos[kk]) * 64, apos = kk * 128;
+            const int wpos = kk * 64, apos = __builtin_amdgcn_readfirstlane((int)kstep_at[kk]) * 128;
 #pragma unroll
             for (int i = 0; i < LPW; i++) {
                 const int j = (wave - 8) + 4 * i;
