@@ -18,7 +18,12 @@
 namespace {
 
 constexpr size_t ALIGN = 256;
-constexpr int PF_ROWS_MAX = 1024;     // prompt rows handled per pass of the prompt kernels
+// Prompt rows handled per pass of the prompt kernels.  With the half-precision cache the projections
+// run in workgroups of 128 rows x 8 TW weight tiles, one per compute unit at a time: a pass of 1024
+// rows gives some launches 0.75 or 2.7 rounds of workgroups, a pass of 4096 rows 3 .. 11 rounds (a
+// 4096-token prompt at the 7B shape: 122 ms in passes of 1024 rows, 109 in passes of 2048, 105 in one).
+// The other cache types keep the 8-row-block kernels, whose attention needs page partials per block.
+constexpr int PF_ROWS_MAX = 1024, PF_ROWS_MAX_HALF = 4096;
 inline size_t up(size_t x, size_t a = ALIGN) { return (x + a - 1) / a * a; }
 
 struct LayerW {
@@ -208,8 +213,9 @@ void layout(kg_ctx *x)
     x->s_ptok = take((size_t)c.max_seq * 4);
     x->pf_rows = 0;
     if (x->bf) {
-        x->pf_rows = std::min(PF_ROWS_MAX, (c.max_seq + KG_ROWS - 1) / KG_ROWS * KG_ROWS);
-        const size_t R = x->pf_rows, nb = R / KG_ROWS;
+        const bool half = x->kvt == 2;          // prompt attention on the matrix units: no page partials
+        x->pf_rows = std::min(half ? PF_ROWS_MAX_HALF : PF_ROWS_MAX, (c.max_seq + KG_ROWS - 1) / KG_ROWS * KG_ROWS);
+        const size_t R = x->pf_rows, nb = R / KG_ROWS, nbp = half ? 1 : nb;
         x->s_px0 = take(R * d * 4);
         x->s_px1 = take(R * d * 4);
         x->s_pF = take(R * d * 4);
@@ -219,9 +225,9 @@ void layout(kg_ctx *x)
         x->s_pactF = take(nb * act_bytes(f));
         x->s_pssq0 = take(nb * (d / 16) * KG_ROWS * 4);
         x->s_pssq1 = take(nb * (d / 16) * KG_ROWS * 4);
-        x->s_popart = take(nb * c.n_heads * x->n_pages * KG_ROWS * c.head_dim * 4);
-        x->s_pmxs = take(nb * c.n_heads * x->n_pages * KG_ROWS * 4);
-        x->s_psms = take(nb * c.n_heads * x->n_pages * KG_ROWS * 4);
+        x->s_popart = take(nbp * c.n_heads * x->n_pages * KG_ROWS * c.head_dim * 4);
+        x->s_pmxs = take(nbp * c.n_heads * x->n_pages * KG_ROWS * 4);
+        x->s_psms = take(nbp * c.n_heads * x->n_pages * KG_ROWS * 4);
         x->s_pcnt = take(nb * c.n_heads * 4);
     }
     x->scratch_bytes = o;

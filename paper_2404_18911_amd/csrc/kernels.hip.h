@@ -1688,6 +1688,7 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
     constexpr int VROW = 128 + 8;               // halves per dimension row of V^T in LDS
     __shared__ __align__(16) uint16_t Ks[128 * KROW];
     __shared__ __align__(16) uint16_t Vt[HD * VROW];
+    __shared__ int pages[128];                  // the page table (a context has at most 128 pages)
     const int h = blockIdx.x, t = threadIdx.x;
     const int rb = (int)gridDim.y - 1 - (int)blockIdx.y;        // late row blocks (most tiles) are scheduled first
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
@@ -1695,25 +1696,64 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
     const int P = 1 << a.logP, d = a.d;
     const int row = rb * 64 + wave * 16 + q16;                  // the query row this lane's column stands for
     const int qpos = a.pos0 + row;
-    const bool row_ok = row < a.T;
     const int last_pos = a.pos0 + min(a.T, rb * 64 + 64) - 1;   // last position any row of the block attends to
     const int n_tiles = (last_pos >> 7) + 1;
     const int wave_last = a.pos0 + min(a.T - 1, rb * 64 + wave * 16 + 15);
     const size_t unit = (size_t)2 * P * HD;
+    if (t <= (last_pos >> a.logP) && t < 128) pages[t] = a.page_table[t];
+    __syncthreads();
+
+    // keys as stored: thread -> (position, 8 dimensions); values: thread -> (8 dimensions, position =
+    // lane-consecutive).  A tile's loads are issued one tile ahead, into registers, and stay in flight
+    // under the multiplications of the tile before.
+    u32x4_t kreg[HD / 16], vreg[HD / 16];
+    const size_t page_stride = (size_t)a.n_slots * a.H * unit;              // elements per physical page
+    const kvhalf_t *kv_head = a.kv + ((size_t)a.slot * a.H + h) * unit;     // this layer's and head's keys in physical page 0
+    auto load_tile = [&](int tile0) {       // (positions beyond the block's reach repeat the last one: finite, and masked below)
+#pragma unroll
+        for (int i = 0; i < HD / 16; i++) {
+            const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
+            const int ap = min(tile0 + pos, last_pos);
+            kreg[i] = *(const u32x4_t *)(kv_head + (size_t)pages[ap >> a.logP] * page_stride + ((ap & (P - 1)) * HD + 8 * dq));
+        }
+        {
+            const int ap = min(tile0 + (t & 127), last_pos);                // one position per thread, HD / 16 chunks of it
+            const kvhalf_t *Vp = kv_head + (size_t)pages[ap >> a.logP] * page_stride + ((P + (ap & (P - 1))) * HD + 8 * (t >> 7));
+#pragma unroll
+            for (int i = 0; i < HD / 16; i++) vreg[i] = *(const u32x4_t *)(Vp + 16 * i);
+        }
+    };
+    load_tile(0);                               // under the preparation of the queries
 
     // queries: rotate, scale, split into half hi + lo, in B-operand order (8 consecutive dimensions per lane and step)
     f16x8_t qhi[KS], qlo[KS];
     {
         const float *q = a.qkv + (size_t)min(row, a.T - 1) * 3 * d + h * HD;
+        const float2 *rp = a.rope + (size_t)min(qpos, a.pos0 + a.T - 1) * HH;
         const float qscale = rsqrtf((float)HD);
+        // all loads first (8 consecutive dimensions: 16-byte loads), then the arithmetic
+        float4 x0v[KS][2], x1v[KS][2], csv[KS][4];
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
+            const int i0 = (32 * ks + 8 * g) % HH;
+#pragma unroll
+            for (int j = 0; j < 2; j++) {
+                x0v[ks][j] = *(const float4 *)(q + i0 + 4 * j);
+                x1v[ks][j] = *(const float4 *)(q + i0 + HH + 4 * j);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; j++) csv[ks][j] = *(const float4 *)(rp + i0 + 2 * j);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            const float x0a[8] = {x0v[ks][0].x, x0v[ks][0].y, x0v[ks][0].z, x0v[ks][0].w, x0v[ks][1].x, x0v[ks][1].y, x0v[ks][1].z, x0v[ks][1].w};
+            const float x1a[8] = {x1v[ks][0].x, x1v[ks][0].y, x1v[ks][0].z, x1v[ks][0].w, x1v[ks][1].x, x1v[ks][1].y, x1v[ks][1].z, x1v[ks][1].w};
 #pragma unroll
             for (int e = 0; e < 8; e++) {
-                const int dim = 32 * ks + 8 * g + e, i = dim % HH;
-                const float2 cs = a.rope[(size_t)min(qpos, a.pos0 + a.T - 1) * HH + i];
-                const float x0 = q[i], x1 = q[i + HH];
-                const float v = rounded((dim < HH ? rot_lo(x0, x1, cs) : rot_hi(x0, x1, cs)) * qscale);
+                const int dim = 32 * ks + 8 * g + e;
+                const float4 c4 = csv[ks][e >> 1];
+                const float2 cs = (e & 1) ? make_float2(c4.z, c4.w) : make_float2(c4.x, c4.y);
+                const float v = rounded((dim < HH ? rot_lo(x0a[e], x1a[e], cs) : rot_hi(x0a[e], x1a[e], cs)) * qscale);
                 const _Float16 hi = (_Float16)v;
                 qhi[ks][e] = hi;
                 qlo[ks][e] = (_Float16)(v - (float)hi);
@@ -1725,50 +1765,38 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
     for (int dt = 0; dt < DT; dt++) o[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;       // running maximum of the row (same in its four lanes), this lane's share of the sum
 
+    // column of position pos inside a dimension row of V^T: [u = pos / 32][g = (pos % 16) / 4][j = 4 ((pos / 16) % 2) + pos % 4]
+    uint16_t *vt_lane;
+    uint32_t vt_sel;
+    {
+        const int pos = t & 127, odd = pos & 1;
+        const int col = (pos >> 5) * 32 + ((pos & 15) >> 2) * 8 + ((pos >> 4) & 1) * 4 + (pos & 3);
+        vt_lane = &Vt[(8 * (t >> 7) + odd) * VROW + (col & ~1)];
+        vt_sel = odd ? 0x03020706u : 0x05040100u;   // (hi of other, hi of mine) : (lo of mine, lo of other)
+    }
+    const int wave_first = a.pos0 + rb * 64 + wave * 16;        // position of the wave's first row
     for (int kt = 0; kt < n_tiles; kt++) {
         const int tile0 = kt << 7;
         __syncthreads();                        // the previous tile has been consumed
-        // keys as stored: thread -> (position, 8 dimensions); positions beyond the block's reach are zero.
-        // All loads of a tile are issued before the first one is used.
-        u32x4_t kreg[HD / 16], vreg[HD / 16];
 #pragma unroll
         for (int i = 0; i < HD / 16; i++) {
             const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
-            const int ap = min(tile0 + pos, last_pos);
-            const kvhalf_t *Kp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit;
-            kreg[i] = *(const u32x4_t *)(Kp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
+            *(u32x4_t *)&Ks[pos * KROW + 8 * dq] = kreg[i];
         }
+        // values, transposed: a 32-bit word of the thread holds dimensions (2 j, 2 j + 1) of its position; with the
+        // neighbouring lane's word (position ^ 1) the even lane forms the pair of positions of dimension 2 j and
+        // the odd lane that of dimension 2 j + 1: one byte permutation and one 32-bit LDS write per word
 #pragma unroll
         for (int i = 0; i < HD / 16; i++) {
-            const int pc = t + 256 * i, pos = pc & 127, dq = pc >> 7;
-            const int ap = min(tile0 + pos, last_pos);
-            const kvhalf_t *Vp = a.kv + (((size_t)a.page_table[ap >> a.logP] * a.n_slots + a.slot) * a.H + h) * unit + (size_t)P * HD;
-            vreg[i] = *(const u32x4_t *)(Vp + (size_t)(ap & (P - 1)) * HD + 8 * dq);
-        }
-#pragma unroll
-        for (int i = 0; i < HD / 16; i++) {
-            const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
-            *(u32x4_t *)&Ks[pos * KROW + 8 * dq] = (tile0 + pos <= last_pos) ? kreg[i] : u32x4_t{0u, 0u, 0u, 0u};
-        }
-        // values, transposed: thread -> (8 dimensions, position = lane-consecutive); two neighbouring positions are
-        // packed into one 32-bit LDS write by the even lane
-#pragma unroll
-        for (int i = 0; i < HD / 16; i++) {
-            const int pc = t + 256 * i, pos = pc & 127, dq = pc >> 7;
-            const u32x4_t v = (tile0 + pos <= last_pos) ? vreg[i] : u32x4_t{0u, 0u, 0u, 0u};
-            // column of position pos inside a dimension row: [u = pos / 32][g = (pos % 16) / 4][j = 4 ((pos / 16) % 2) + pos % 4]
-            const int col = (pos >> 5) * 32 + ((pos & 15) >> 2) * 8 + ((pos >> 4) & 1) * 4 + (pos & 3);
 #pragma unroll
             for (int w = 0; w < 4; w++) {
-                const uint32_t mine = v[w];
+                const uint32_t mine = vreg[i][w];
                 const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xB1, 0xF, 0xF, false);   // lane ^ 1
-                if ((lane & 1) == 0) {
-                    *(uint32_t *)&Vt[(8 * dq + 2 * w) * VROW + col] = (mine & 0xFFFFu) | (other << 16);
-                    *(uint32_t *)&Vt[(8 * dq + 2 * w + 1) * VROW + col] = (mine >> 16) | (other & 0xFFFF0000u);
-                }
+                *(uint32_t *)(vt_lane + (16 * i + 2 * w) * VROW) = __builtin_amdgcn_perm(other, mine, vt_sel);
             }
         }
         __syncthreads();
+        if (kt + 1 < n_tiles) load_tile(tile0 + 128);
         if (tile0 > wave_last) continue;        // nothing of this tile is visible to the wave's rows (uniform in the wave)
 
         // scores of 128 positions x 16 query rows
@@ -1783,28 +1811,32 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
                 s[pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kk, qlo[ks], s[pt], 0, 0, 0);
             }
         }
-        // causal mask, tile maximum of the row
+        // causal mask (only a tile that reaches beyond the wave's first row needs it), tile maximum of the row.
+        // Every row sees position 0, so its maximum is finite from the first tile on; rows beyond the pass are
+        // computed like the others (on the last row's queries) and dropped.
+        if (tile0 + 127 > wave_first) {
+#pragma unroll
+            for (int pt = 0; pt < 8; pt++)
+#pragma unroll
+                for (int r = 0; r < 4; r++)
+                    s[pt][r] = (tile0 + 16 * pt + 4 * g + r <= qpos) ? s[pt][r] : -INFINITY;
+        }
         float mx = -INFINITY;
 #pragma unroll
         for (int pt = 0; pt < 8; pt++)
 #pragma unroll
-            for (int r = 0; r < 4; r++) {
-                const int ap = tile0 + 16 * pt + 4 * g + r;
-                const float v = (row_ok && ap <= qpos) ? s[pt][r] : -INFINITY;
-                s[pt][r] = v;
-                mx = fmaxf(mx, v);
-            }
+            for (int r = 0; r < 4; r++) mx = fmaxf(mx, s[pt][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);
-        const float scale = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);     // m_run = -inf gives 0
+        const float scale = __expf(m_run - m_new);              // 0 in the first tile (m_run = -inf)
         float psum = 0.f;
         f16x8_t pa[4];
 #pragma unroll
         for (int pt = 0; pt < 8; pt++)
 #pragma unroll
             for (int r = 0; r < 4; r++) {
-                const float p = (s[pt][r] == -INFINITY) ? 0.f : __expf(s[pt][r] - m_new);
+                const float p = __expf(s[pt][r] - m_new);       // 0 for a masked score
                 psum += p;
                 pa[pt >> 1][4 * (pt & 1) + r] = (_Float16)p;
             }

@@ -78,8 +78,8 @@ def test_33b_shape():
 
 
 def test_long_context_attention_follows_oracle():
-    """1100-token prompt on a 7B-wide, two-layer model: nine KV pages, cross-page merge, prefill in
-    8-row chunks, then greedy rounds and sampled rounds, against the oracle."""
+    """1100-token prompt on a 7B-wide, two-layer model: nine KV pages, cross-page merge, one prompt
+    pass of 1100 rows, then greedy rounds and sampled rounds, against the oracle."""
     from oracle import kangaroo_oracle as O
     from tests import parity as P
     shape = dataclasses.replace(I.with_layers(I.SHAPES["7b"], 2), exit_layer=1)
