@@ -531,9 +531,16 @@ int pf_block(kg_ctx *x, int slot, size_t qkv_off, size_t wo_off, size_t gu_off, 
         pa.act_out = actA; pa.act_blk_bytes = act_bytes(d);
         pa.act_pair = pf_gemm_plan(x, d, d, T) ? 1 : 0;               // read by the output projection
         ProfScope ps(x, 1, 0.0);
-        const dim3 grid(c.n_heads, (T + 63) / 64);
-        if (c.head_dim == 128) hipLaunchKernelGGL(pf_attn_kernel<128>, grid, dim3(256), 0, x->stream, pa);
-        else hipLaunchKernelGGL(pf_attn_kernel<64>, grid, dim3(256), 0, x->stream, pa);
+        // workgroups of 128 rows (8 waves, a compute unit each) where those alone fill the device, else of 64 rows
+        if ((size_t)c.n_heads * ((T + 127) / 128) >= (size_t)x->n_cus) {
+            const dim3 grid(c.n_heads, (T + 127) / 128);
+            if (c.head_dim == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 8>), grid, dim3(512), 0, x->stream, pa);
+            else hipLaunchKernelGGL((pf_attn_kernel<64, 8>), grid, dim3(512), 0, x->stream, pa);
+        } else {
+            const dim3 grid(c.n_heads, (T + 63) / 64);
+            if (c.head_dim == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 4>), grid, dim3(256), 0, x->stream, pa);
+            else hipLaunchKernelGGL((pf_attn_kernel<64, 4>), grid, dim3(256), 0, x->stream, pa);
+        }
         KGCHK(check_launch(x, "prompt attention"));
     } else {
         a.append_only = 0; a.append_all = 0; a.preappended = 1;

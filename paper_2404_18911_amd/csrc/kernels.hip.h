@@ -1647,9 +1647,11 @@ __global__ __launch_bounds__(512, (sizeof(T) == 2 ? 6 : 1)) void attn_kernel(con
 
 // ---------------------------------------------------------------------------------------------
 // Attention of the prompt rows (prefill) on the matrix units, for a half-precision KV cache.
-// One workgroup (4 waves) per head and block of 64 query rows; a wave owns 16 rows.  The keys and
-// values of all rows of this pass are already in the cache (appended by an earlier launch), so the
-// block walks the cache in tiles of 128 positions up to its own last row:
+// One workgroup per head and block of 64 query rows (4 waves, two workgroups per compute unit) or of
+// 128 query rows (8 waves, a compute unit alone, two tiles of K and V in LDS: half the staging per row
+// and one barrier per tile; for passes whose blocks of 128 rows fill the device); a wave owns 16 rows.
+// The keys and values of all rows of this pass are already in the cache (appended by an earlier
+// launch), so the block walks the cache in tiles of 128 positions up to its own last row:
 //   S^T = K Q^T   per 16-position tile: A = keys from LDS (as stored: one position's 8 consecutive
 //         dimensions per lane), B = the rotated, scaled queries held in registers as half hi + lo
 //         parts (two MFMAs per step, fp32-grade scores); the result has a lane's query row in its
@@ -1678,27 +1680,31 @@ struct PfAttnArgs {
     int act_pair;            // layout of act_out (pf_act_ptr)
 };
 
-template <int HD>
-__global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
+template <int HD, int NW>     // NW waves: 16 NW query rows per workgroup
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : 2) void pf_attn_kernel(const PfAttnArgs a)
 {
+    constexpr int NT = 64 * NW, ROWS = 16 * NW;
+    constexpr int NBUF = NW == 8 ? 2 : 1;       // tiles of K and V^T in LDS (two workgroups of 4 waves share a compute unit instead)
+    constexpr int CH = 16 * HD / NT;            // 16-byte chunks of a K tile (and of a V tile) per thread
+    constexpr int VSTEP = NT / 128;             // chunk index step of a thread's V chunks
     constexpr int KS = HD / 32;                 // contraction steps of Q.K^T
     constexpr int DT = HD / 16;                 // 16-wide tiles of the head dimension
     constexpr int HH = HD / 2;
     constexpr int KROW = HD + 8;                // halves per key row in LDS (16 bytes of padding: conflict-free 16-byte reads)
     constexpr int VROW = 128 + 8;               // halves per dimension row of V^T in LDS
-    __shared__ __align__(16) uint16_t Ks[128 * KROW];
-    __shared__ __align__(16) uint16_t Vt[HD * VROW];
+    __shared__ __align__(16) uint16_t Ks[NBUF][128 * KROW];
+    __shared__ __align__(16) uint16_t Vt[NBUF][HD * VROW];
     __shared__ int pages[128];                  // the page table (a context has at most 128 pages)
     const int h = blockIdx.x, t = threadIdx.x;
     const int rb = (int)gridDim.y - 1 - (int)blockIdx.y;        // late row blocks (most tiles) are scheduled first
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63;
     const int q16 = lane & 15, g = lane >> 4;
     const int P = 1 << a.logP, d = a.d;
-    const int row = rb * 64 + wave * 16 + q16;                  // the query row this lane's column stands for
+    const int row = rb * ROWS + wave * 16 + q16;                  // the query row this lane's column stands for
     const int qpos = a.pos0 + row;
-    const int last_pos = a.pos0 + min(a.T, rb * 64 + 64) - 1;   // last position any row of the block attends to
+    const int last_pos = a.pos0 + min(a.T, rb * ROWS + ROWS) - 1;   // last position any row of the block attends to
     const int n_tiles = (last_pos >> 7) + 1;
-    const int wave_last = a.pos0 + min(a.T - 1, rb * 64 + wave * 16 + 15);
+    const int wave_last = a.pos0 + min(a.T - 1, rb * ROWS + wave * 16 + 15);
     const size_t unit = (size_t)2 * P * HD;
     if (t <= (last_pos >> a.logP) && t < 128) pages[t] = a.page_table[t];
     __syncthreads();
@@ -1706,21 +1712,21 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
     // keys as stored: thread -> (position, 8 dimensions); values: thread -> (8 dimensions, position =
     // lane-consecutive).  A tile's loads are issued one tile ahead, into registers, and stay in flight
     // under the multiplications of the tile before.
-    u32x4_t kreg[HD / 16], vreg[HD / 16];
+    u32x4_t kreg[CH], vreg[CH];
     const size_t page_stride = (size_t)a.n_slots * a.H * unit;              // elements per physical page
     const kvhalf_t *kv_head = a.kv + ((size_t)a.slot * a.H + h) * unit;     // this layer's and head's keys in physical page 0
     auto load_tile = [&](int tile0) {       // (positions beyond the block's reach repeat the last one: finite, and masked below)
 #pragma unroll
-        for (int i = 0; i < HD / 16; i++) {
-            const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
+        for (int i = 0; i < CH; i++) {
+            const int pc = t + NT * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
             const int ap = min(tile0 + pos, last_pos);
             kreg[i] = *(const u32x4_t *)(kv_head + (size_t)pages[ap >> a.logP] * page_stride + ((ap & (P - 1)) * HD + 8 * dq));
         }
         {
-            const int ap = min(tile0 + (t & 127), last_pos);                // one position per thread, HD / 16 chunks of it
+            const int ap = min(tile0 + (t & 127), last_pos);                // one position per thread, CH chunks of it
             const kvhalf_t *Vp = kv_head + (size_t)pages[ap >> a.logP] * page_stride + ((P + (ap & (P - 1))) * HD + 8 * (t >> 7));
 #pragma unroll
-            for (int i = 0; i < HD / 16; i++) vreg[i] = *(const u32x4_t *)(Vp + 16 * i);
+            for (int i = 0; i < CH; i++) vreg[i] = *(const u32x4_t *)(Vp + 8 * VSTEP * i);
         }
     };
     load_tile(0);                               // under the preparation of the queries
@@ -1771,90 +1777,108 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
     {
         const int pos = t & 127, odd = pos & 1;
         const int col = (pos >> 5) * 32 + ((pos & 15) >> 2) * 8 + ((pos >> 4) & 1) * 4 + (pos & 3);
-        vt_lane = &Vt[(8 * (t >> 7) + odd) * VROW + (col & ~1)];
+        vt_lane = &Vt[0][(8 * (t >> 7) + odd) * VROW + (col & ~1)];
         vt_sel = odd ? 0x03020706u : 0x05040100u;   // (hi of other, hi of mine) : (lo of mine, lo of other)
     }
-    const int wave_first = a.pos0 + rb * 64 + wave * 16;        // position of the wave's first row
-    for (int kt = 0; kt < n_tiles; kt++) {
-        const int tile0 = kt << 7;
-        __syncthreads();                        // the previous tile has been consumed
+    const int wave_first = a.pos0 + rb * ROWS + wave * 16;        // position of the wave's first row
+    // tile in registers -> LDS buffer bf: keys as stored; values transposed: a 32-bit word of the thread holds
+    // dimensions (2 j, 2 j + 1) of its position; with the neighbouring lane's word (position ^ 1) the even lane
+    // forms the pair of positions of dimension 2 j and the odd lane that of dimension 2 j + 1: one byte
+    // permutation and one 32-bit LDS write per word
+    auto write_tile = [&](int bf) {
 #pragma unroll
-        for (int i = 0; i < HD / 16; i++) {
-            const int pc = t + 256 * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
-            *(u32x4_t *)&Ks[pos * KROW + 8 * dq] = kreg[i];
+        for (int i = 0; i < CH; i++) {
+            const int pc = t + NT * i, pos = pc / (HD / 8), dq = pc % (HD / 8);
+            *(u32x4_t *)&Ks[bf][pos * KROW + 8 * dq] = kreg[i];
         }
-        // values, transposed: a 32-bit word of the thread holds dimensions (2 j, 2 j + 1) of its position; with the
-        // neighbouring lane's word (position ^ 1) the even lane forms the pair of positions of dimension 2 j and
-        // the odd lane that of dimension 2 j + 1: one byte permutation and one 32-bit LDS write per word
 #pragma unroll
-        for (int i = 0; i < HD / 16; i++) {
+        for (int i = 0; i < CH; i++) {
 #pragma unroll
             for (int w = 0; w < 4; w++) {
                 const uint32_t mine = vreg[i][w];
                 const uint32_t other = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mine, 0xB1, 0xF, 0xF, false);   // lane ^ 1
-                *(uint32_t *)(vt_lane + (16 * i + 2 * w) * VROW) = __builtin_amdgcn_perm(other, mine, vt_sel);
+                *(uint32_t *)(vt_lane + bf * (HD * VROW) + (8 * VSTEP * i + 2 * w) * VROW) = __builtin_amdgcn_perm(other, mine, vt_sel);
             }
         }
+    };
+    // One tile in LDS: barrier, write, barrier, then the next tile's loads fly under this tile's multiplications.
+    // Two tiles in LDS: the next tile is written into the other buffer after this tile's multiplications (no wave
+    // reads that buffer any more: its tile was finished before the last barrier), one barrier per tile.
+    if (NBUF == 2) {
+        write_tile(0);
         __syncthreads();
-        if (kt + 1 < n_tiles) load_tile(tile0 + 128);
-        if (tile0 > wave_last) continue;        // nothing of this tile is visible to the wave's rows (uniform in the wave)
-
-        // scores of 128 positions x 16 query rows
-        f32x4_t s[8];
-#pragma unroll
-        for (int pt = 0; pt < 8; pt++) {
-            s[pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ks++) {
-                const f16x8_t kk = __builtin_bit_cast(f16x8_t, *(const u32x4_t *)&Ks[(16 * pt + q16) * KROW + 32 * ks + 8 * g]);
-                s[pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kk, qhi[ks], s[pt], 0, 0, 0);
-                s[pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kk, qlo[ks], s[pt], 0, 0, 0);
-            }
+    }
+    for (int kt = 0; kt < n_tiles; kt++) {
+        const int tile0 = kt << 7, bf = NBUF == 2 ? (kt & 1) : 0;
+        const bool more = kt + 1 < n_tiles;
+        if (NBUF == 1) {
+            __syncthreads();                    // the previous tile has been consumed
+            write_tile(0);
+            __syncthreads();
         }
-        // causal mask (only a tile that reaches beyond the wave's first row needs it), tile maximum of the row.
-        // Every row sees position 0, so its maximum is finite from the first tile on; rows beyond the pass are
-        // computed like the others (on the last row's queries) and dropped.
-        if (tile0 + 127 > wave_first) {
+        if (more) load_tile(tile0 + 128);
+        if (tile0 <= wave_last) {               // else nothing of this tile is visible to the wave's rows (uniform in the wave)
+            // scores of 128 positions x 16 query rows
+            f32x4_t s[8];
+#pragma unroll
+            for (int pt = 0; pt < 8; pt++) {
+                s[pt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ks++) {
+                    const f16x8_t kk = __builtin_bit_cast(f16x8_t, *(const u32x4_t *)&Ks[bf][(16 * pt + q16) * KROW + 32 * ks + 8 * g]);
+                    s[pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kk, qhi[ks], s[pt], 0, 0, 0);
+                    s[pt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kk, qlo[ks], s[pt], 0, 0, 0);
+                }
+            }
+            // causal mask (only a tile that reaches beyond the wave's first row needs it), tile maximum of the row.
+            // Every row sees position 0, so its maximum is finite from the first tile on; rows beyond the pass are
+            // computed like the others (on the last row's queries) and dropped.
+            if (tile0 + 127 > wave_first) {
+#pragma unroll
+                for (int pt = 0; pt < 8; pt++)
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        s[pt][r] = (tile0 + 16 * pt + 4 * g + r <= qpos) ? s[pt][r] : -INFINITY;
+            }
+            float mx = -INFINITY;
 #pragma unroll
             for (int pt = 0; pt < 8; pt++)
 #pragma unroll
-                for (int r = 0; r < 4; r++)
-                    s[pt][r] = (tile0 + 16 * pt + 4 * g + r <= qpos) ? s[pt][r] : -INFINITY;
+                for (int r = 0; r < 4; r++) mx = fmaxf(mx, s[pt][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            const float scale = __expf(m_run - m_new);              // 0 in the first tile (m_run = -inf)
+            float psum = 0.f;
+            f16x8_t pa[4];
+#pragma unroll
+            for (int pt = 0; pt < 8; pt++)
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const float p = __expf(s[pt][r] - m_new);       // 0 for a masked score
+                    psum += p;
+                    pa[pt >> 1][4 * (pt & 1) + r] = (_Float16)p;
+                }
+            l_run = l_run * scale + psum;
+            m_run = m_new;
+            // rescale the output rows 4 g + r by the factor of their query row, then add P.V
+            float sc[4];
+#pragma unroll
+            for (int r = 0; r < 4; r++) sc[r] = __shfl(scale, 4 * g + r);
+#pragma unroll
+            for (int dt = 0; dt < DT; dt++) {
+#pragma unroll
+                for (int r = 0; r < 4; r++) o[dt][r] *= sc[r];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const f16x8_t vv = __builtin_bit_cast(f16x8_t, *(const u32x4_t *)&Vt[bf][(16 * dt + q16) * VROW + 32 * u + 8 * g]);
+                    o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[u], vv, o[dt], 0, 0, 0);
+                }
+            }
         }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int pt = 0; pt < 8; pt++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) mx = fmaxf(mx, s[pt][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float scale = __expf(m_run - m_new);              // 0 in the first tile (m_run = -inf)
-        float psum = 0.f;
-        f16x8_t pa[4];
-#pragma unroll
-        for (int pt = 0; pt < 8; pt++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) {
-                const float p = __expf(s[pt][r] - m_new);       // 0 for a masked score
-                psum += p;
-                pa[pt >> 1][4 * (pt & 1) + r] = (_Float16)p;
-            }
-        l_run = l_run * scale + psum;
-        m_run = m_new;
-        // rescale the output rows 4 g + r by the factor of their query row, then add P.V
-        float sc[4];
-#pragma unroll
-        for (int r = 0; r < 4; r++) sc[r] = __shfl(scale, 4 * g + r);
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++) {
-#pragma unroll
-            for (int r = 0; r < 4; r++) o[dt][r] *= sc[r];
-#pragma unroll
-            for (int u = 0; u < 4; u++) {
-                const f16x8_t vv = __builtin_bit_cast(f16x8_t, *(const u32x4_t *)&Vt[(16 * dt + q16) * VROW + 32 * u + 8 * g]);
-                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(pa[u], vv, o[dt], 0, 0, 0);
-            }
+        if (NBUF == 2) {
+            if (more) write_tile(bf ^ 1);
+            __syncthreads();
         }
     }
     // normalise and store: lane holds dimension 16 dt + q16 of query rows 4 g + r
@@ -1864,7 +1888,7 @@ __global__ __launch_bounds__(256, 2) void pf_attn_kernel(const PfAttnArgs a)
 #pragma unroll
     for (int r = 0; r < 4; r++) {
         const float ir = __shfl(inv, 4 * g + r);
-        const int orow = rb * 64 + wave * 16 + 4 * g + r;
+        const int orow = rb * ROWS + wave * 16 + 4 * g + r;
         if (orow < a.T) {
 #pragma unroll
             for (int dt = 0; dt < DT; dt++)

@@ -389,6 +389,22 @@ def test_the_largest_page_count_follows_oracle():
     kg.close()
 
 
+def test_prompt_attention_with_many_narrow_heads_follows_oracle():
+    """16 heads of 64 dimensions, 2100-token prompt: the prompt rows' attention runs in workgroups of
+    128 rows (two tiles of keys and values in LDS) at the narrow head size, with a ragged last block
+    (52 rows) and a last tile of 52 positions; then a few draft-and-verify rounds, against the
+    oracle."""
+    from tests import parity as P
+    shape = I.ModelShape("narrow", 2, 1024, 16, 64, 2752, 1024, 1, "bf16")
+    W = I.gen_weights(shape, seed=2, alpha=0.1)
+    n_prompt = 2100
+    kg = P.load_model(shape, W, n_prompt + 64, gamma_max=6, kv_page_tokens=128)
+    fol = P.Follow(TOL["bf16"])
+    P.follow_kangaroo(kg, _oracle(shape, W, n_prompt + 64), I.gen_prompt(shape.vocab, n_prompt), 8, 6, 0.6, fol)
+    print(f"narrow heads: max logit err {fol.max_logit_err:.3e}, near-tie exceptions {fol.exceptions}/{fol.decisions}")
+    kg.close()
+
+
 @pytest.mark.parametrize("n_prompt", [1, 15, 16, 17])
 def test_degenerate_prompts_follow_oracle(n_prompt):
     """A one-token prompt, and prompts that end just before, on and just after a KV page boundary
