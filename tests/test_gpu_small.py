@@ -210,12 +210,12 @@ def test_sampling_plain_decoding_follows_oracle():
 
 @pytest.mark.parametrize("kv", ["f16", "bf16"])
 @pytest.mark.parametrize("name,n_prompt,page", [("toy_bf16", 300, 32), ("small_bf16", 77, 64), ("small_bf16", 264, 128),
-                                                ("toy_bf16", 1100, 128), ("toy_bf16", 4200, 128)])
+                                                ("toy_bf16", 1100, 128), ("toy_bf16", 4200, 128), ("toy_bf16", 4097, 64)])
 def test_prompt_pass_agrees_with_one_token_decoding(name, n_prompt, page, kv):
     """The prompt goes through the dense MFMA projections in passes of up to 4096 rows with the
     half-precision cache and up to 1024 rows with the bfloat16 cache (groups of 128 or 64 rows, blocks
     of 8, ragged tails and an odd number of block pairs here; the 1100-token case takes two passes with
-    the bfloat16 cache, the 4200-token case two and five).  Against the same
+    the bfloat16 cache, the 4200-token case two and five, the 4097-token case ends in a pass of one row).  Against the same
     prompt fed token by token through the one-token kernels: with the bfloat16 cache the prompt rows'
     attention runs the decode kernel per block of 8 rows and every row comes out bit for bit as the
     one-token kernels compute it; with the half-precision cache (the default) the attention of the
