@@ -69,7 +69,7 @@ struct kg_ctx {
     // prompt pass: device copy of the prompt and buffers for pf_rows rows at a time (bf16 weights)
     int pf_rows = 0;
     size_t s_ptok, s_px0, s_px1, s_pF, s_pqkv, s_pactX, s_pactA, s_pactF, s_pssq0, s_pssq1, s_popart, s_pmxs, s_psms,
-        s_pcnt;
+        s_pcnt, s_pscale;
     // bindings
     char *arena = nullptr, *kv = nullptr, *scr = nullptr;
     hipStream_t stream = nullptr;
@@ -229,6 +229,7 @@ void layout(kg_ctx *x)
         x->s_pmxs = take(nbp * c.n_heads * x->n_pages * KG_ROWS * 4);
         x->s_psms = take(nbp * c.n_heads * x->n_pages * KG_ROWS * 4);
         x->s_pcnt = take(nb * c.n_heads * 4);
+        x->s_pscale = take(R * 4);
     }
     x->scratch_bytes = o;
 }
@@ -469,11 +470,19 @@ int launch_pf_gemm(kg_ctx *x, size_t w_off, int N, int K, const void *act, int T
         a.gx = plan == PF_PLAN_TW1_RB8 ? (nb + 7) / 8 : (nb + 15) / 16;
         a.gy = (a.NT + 8 * best_tw - 1) / (8 * best_tw);
         const int groups = a.gx * 8 * ((a.gy + 7) / 8);
+        Epi e2 = e;
+        if (ssq_in) {       // the rows' RMS scales once per pass, not once per workgroup
+            float *scale = at<float>(x->scr, x->s_pscale);
+            hipLaunchKernelGGL(pf_rms_scale_kernel, dim3(nb), dim3(512), 0, x->stream, e.ssq_in, a.ssq_in_blk, e.nt_in, T, e.inv_d,
+                               e.eps, scale);
+            KGCHK(check_launch(x, "prompt row scales"));
+            e2.scale_in = scale;
+        }
         ProfScope ps(x, 3, 2.0 * T * (double)N * K);
-        if (plan == PF_PLAN_TW1_RB8) hipLaunchKernelGGL(gemm_prefill2_kernel_tw1_rb8, dim3(groups), dim3(768), 0, x->stream, a, e);
-        else if (best_tw == 4) hipLaunchKernelGGL(gemm_prefill2_kernel_tw4, dim3(groups), dim3(768), 0, x->stream, a, e);
-        else if (best_tw == 2) hipLaunchKernelGGL(gemm_prefill2_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e);
-        else hipLaunchKernelGGL(gemm_prefill2_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e);
+        if (plan == PF_PLAN_TW1_RB8) hipLaunchKernelGGL(gemm_prefill2_kernel_tw1_rb8, dim3(groups), dim3(768), 0, x->stream, a, e2);
+        else if (best_tw == 4) hipLaunchKernelGGL(gemm_prefill2_kernel_tw4, dim3(groups), dim3(768), 0, x->stream, a, e2);
+        else if (best_tw == 2) hipLaunchKernelGGL(gemm_prefill2_kernel_tw2, dim3(groups), dim3(768), 0, x->stream, a, e2);
+        else hipLaunchKernelGGL(gemm_prefill2_kernel_tw1, dim3(groups), dim3(768), 0, x->stream, a, e2);
         return check_launch(x, "prompt projection");
     }
     // two weight tiles per multiplying wave where that still leaves enough workgroups for the device

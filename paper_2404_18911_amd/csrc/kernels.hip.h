@@ -34,6 +34,7 @@ struct Epi {
     const float *ssq_in;
     int nt_in;
     float inv_d, eps;
+    const float *scale_in;  // prompt passes in 128-row workgroups: the scales themselves, one per row (pf_rms_scale_kernel)
     // EPI_PLAIN: out[(m + row_shift)][n] = y * scale, rows with m + row_shift < 0 are dropped
     float *out;
     int row_shift;
@@ -827,6 +828,30 @@ __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw2(PfArgs a, Epi e) 
 __global__ __launch_bounds__(768) void gemm_prefill_kernel_tw1_cb4(PfArgs a, Epi e) { gemm_prefill_body<1, 4>(a, e); }
 
 // ---------------------------------------------------------------------------------------------
+// RMSNorm scale of every row of a prompt pass: rsqrt(sum of the row's tile sums of squares / d + eps),
+// the sums taken in the order of the one-token kernels (a lane adds its tiles lane, lane + 64, .., then
+// the lanes are folded).  One workgroup per 8-row block, one wave per row; rows beyond the pass get the
+// scale of an all-zero row and are not used.
+__global__ __launch_bounds__(512) void pf_rms_scale_kernel(const float *ssq, int ssq_blk, int nt_in, int T, float inv_d,
+                                                           float eps, float *scale)
+{
+    const int b = blockIdx.x, m = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int M = min(KG_ROWS, T - KG_ROWS * b);
+    const float *p = ssq + (size_t)b * ssq_blk;
+    float pv[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        const int i = lane + 64 * j;
+        pv[j] = (m < M && i < nt_in) ? p[(size_t)i * KG_ROWS + m] : 0.f;
+    }
+    float sv = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) sv += pv[j];
+    for (int o = 32; o >= 1; o >>= 1) sv += __shfl_xor(sv, o);
+    if (lane == 0) scale[(size_t)b * KG_ROWS + m] = rsqrtf(fmaf(sv, inv_d, eps));
+}
+
+// ---------------------------------------------------------------------------------------------
 // Projection for long prompt passes: the same contraction as gemm_prefill_body for passes of 256 rows
 // and more (where the launch fills at least 45 % of the compute units), organised for reuse instead of
 // for the one-token kernel's summation order (a prompt row then differs from the same row decoded alone
@@ -872,21 +897,9 @@ __device__ __forceinline__ void gemm_prefill2_body(const PfArgs &a, const Epi &e
     const int a0 = PIPE ? (wave & 3) * WA : wave * TW;      // first weight tile and first pair of a multiplying wave
     const int g0 = PIPE ? ((wave >> 2) & 1) * WP : 0;
 
-    // RMS scales of the group's rows: one wave per row block (12 waves serve 16 blocks); the table of k-steps by position
-    for (int blk = wave; blk < nbw; blk += 12) {
-        const Epi eb = pf_block_epi(e, a, b0 + blk);
-#pragma unroll
-        for (int m = 0; m < KG_ROWS; m++) {
-            float sv = 1.f;
-            if (eb.ssq_in) {
-                sv = 0.f;
-                for (int i = lane; i < eb.nt_in; i += 64) sv += (m < eb.M) ? eb.ssq_in[(size_t)i * KG_ROWS + m] : 0.f;
-                for (int o = 32; o >= 1; o >>= 1) sv += __shfl_xor(sv, o);
-                sv = rsqrtf(fmaf(sv, eb.inv_d, eb.eps));
-            }
-            if (lane == 0) scs[blk][m] = sv;
-        }
-    }
+    // RMS scales of the group's rows (computed once per pass by pf_rms_scale_kernel: every workgroup summing
+    // the tile sums of its 128 rows again cost a tenth of a short pass); the table of k-steps by position
+    if (t < nbw * KG_ROWS) scs[t >> 3][t & 7] = e.scale_in ? e.scale_in[(size_t)b0 * KG_ROWS + t] : 1.f;
     for (int i = t; i < KS; i += 768) kstep_at[tile_pos(i, KS)] = (uint16_t)i;
     __syncthreads();
 
