@@ -50,5 +50,23 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+MICROBENCH = [os.path.join(_HERE, "csrc", "microbench", n) for n in ("mfma_rate.hip", "prompt_gemm_loop_model.hip")]
+
+
+def build_microbench(out_dir: str | None = None) -> list[str]:
+    """Compile the stand-alone measurement programs of csrc/microbench (nothing in the library or the
+    tests runs them; profiles/ holds what they printed on an MI355X)."""
+    out_dir = out_dir or os.path.join(_HERE, "csrc", "microbench")
+    outs = []
+    for src in MICROBENCH:
+        exe = os.path.join(out_dir, os.path.splitext(os.path.basename(src))[0])
+        res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                              "-o", exe, src], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+        outs.append(exe)
+    return outs
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
