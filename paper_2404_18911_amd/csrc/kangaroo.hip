@@ -445,10 +445,16 @@ int pf_gemm_plan(const kg_ctx *x, int N, int K, int T)
         const double cost = ((double)NT * gx2 + 16.0 * wgs) * rounds * x->n_cus / wgs * (tw == 4 ? 1.2 : tw == 2 ? 1.0 : 0.95);
         if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_tw = tw; best_wgs = wgs; }
     }
-    if (best_wgs >= 0.45 * x->n_cus) return best_tw;
     // few weight tiles (o_proj and down_proj at 256 rows: 64 workgroups of 128 rows): workgroups of 64 rows
-    // where those reach that fill (70 us per launch against 84 us of the 8-row-block kernel), else that kernel
+    // where those reach that fill (70 us per launch against 84 us of the 8-row-block kernel), else that kernel.
+    // A workgroup of 64 rows takes 0.55 of the time of one of 128 rows, so the 64-row kernel also wins where it
+    // needs no more rounds of workgroups than TW 1 does (o_proj and down_proj at 512 rows: 256 workgroups instead
+    // of 128, a 512-token prompt 15.9 -> 14.6 ms; at 768 rows 384 instead of 192: two rounds, no gain).
     const double wgs8 = (double)((nb + 7) / 8) * ((NT + 7) / 8);
+    if (best_wgs >= 0.45 * x->n_cus) {
+        if (best_tw == 1 && 0.55 * std::ceil(wgs8 / x->n_cus) < std::ceil(best_wgs / x->n_cus)) return PF_PLAN_TW1_RB8;
+        return best_tw;
+    }
     return wgs8 >= 0.45 * x->n_cus ? PF_PLAN_TW1_RB8 : 0;
 }
 
