@@ -429,12 +429,12 @@ int pf_gemm_plan(const kg_ctx *x, int N, int K, int T)
     // k-step every row group fetches all NT weight tiles and every workgroup its 16 activation tiles,
     // and a last round of workgroups that fills only part of the device costs a whole round; beside the
     // traffic, the kernels that read the next k-step's operands under the current one's multiplications
-    // (TW 1 and 2) take 0.95 and 1.0 of the model's time and TW 4 takes 1.2.  Measured at the 7B shape,
-    // microseconds per launch for TW 1 / 2 / 4: 1024 rows: q,k,v 236 / 217 / 190, gate+up 454 / 335 / 406,
-    // o_proj and down_proj 116 / 157 / -; 512 rows: q,k,v 145 / 107 / -, gate+up 224 / 219 / 205; 256 rows:
-    // q,k,v 75 / - / -, gate+up 149 / 108 / - (a dash: under 45 % of the compute units would get a workgroup).
+    // (TW 1 and 2) take 0.95 and 1.0 of the model's time and TW 4 takes 1.2.  Measured at the 7B shape under a
+    // kernel trace, microseconds per launch for TW 1 / 2 / 4: 1024 rows: q,k,v 190 / 191 / 180, gate+up 359 / 296 /
+    // 364, o_proj and down_proj 119 / 164 / 313; 2048 rows: q,k,v 390 / 323 / 367, gate+up 686 / 599 / 589, o_proj
+    // and down_proj 245 / 204 / 331 (the model picks the fastest of each); 256 rows: q,k,v TW 1 58, gate+up TW 2 91.
     // At 4096 rows the model picks TW 4 for every projection (3 .. 11 full rounds of workgroups): a 4096-token
-    // prompt takes 104.5 ms so, 108.4 ms with TW 2 for gate+up and 114.2 ms with TW 2 for q,k,v as well.
+    // prompt took 104.5 ms so, 108.4 ms with TW 2 for gate+up and 114.2 ms with TW 2 for q,k,v as well.
     const int NT = N / 16, nb = (T + KG_ROWS - 1) / KG_ROWS, gx2 = (nb + 15) / 16;
     int best_tw = 1;
     double best_cost = -1.0, best_wgs = 0.0;
